@@ -1,0 +1,148 @@
+"""CPU oracle for the DropCompute batched step-time computation (Python face of dc_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, the smoke check and the benchmark's
+CPU-baseline leg.  The GPU library never imports, links or calls anything here, and this
+package imports nothing of the GPU library.
+
+  simulate(lat, taus, comm, method)  -> (step_sum[K], done_sum[K])  exact int64 sums over trials
+      method="literal": the four nested loops of Appendix C.1 / Algorithm 2
+      method="sorted" : same numbers via one walk over sorted thresholds (for large inputs)
+  select_tau(step_sum, done_sum, taus, T, N, M, base_step_sum) -> (thr[K], s_eff[K], best_k)
+      throughput N*M~/(min{tau,T}+T^c) and S_eff (Section 4.4), argmax (Algorithm 2, last line)
+  per_step_speedup(lat, taus, comm) -> S_eff[K] as the mean of per-iteration ratios S_i(tau)
+      (Algorithm 2 exactly as printed; float64)
+"""
+from __future__ import annotations
+
+import ctypes
+import subprocess
+from concurrent.futures import ThreadPoolExecutor
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_LIB_PATH = _HERE / "libdc_oracle.so"
+_lib = None
+
+OK, ERR_INVALID_ARG, ERR_NEGATIVE_LATENCY = 0, 1, 2
+
+
+class OracleError(ValueError):
+    def __init__(self, code: int):
+        super().__init__({1: "invalid argument", 2: "negative latency"}.get(code, f"error {code}"))
+        self.code = code
+
+
+def build(verbose: bool = False) -> Path:
+    """Compile dc_oracle.c with gcc into oracle/libdc_oracle.so."""
+    cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+           "-o", str(_LIB_PATH), str(_HERE / "dc_oracle.c")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    global _lib
+    _lib = None
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            build()
+        lib = ctypes.CDLL(str(_LIB_PATH))
+        sig = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+               ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        for name in ("dc_oracle_simulate_literal", "dc_oracle_simulate_sorted"):
+            fn = getattr(lib, name)
+            fn.argtypes = sig
+            fn.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def simulate(lat: np.ndarray, taus, comm: int, method: str = "literal"):
+    """Exact step-time and completed-micro-batch sums per threshold.
+
+    lat: int32 [T][N][M] microseconds.  Returns (step_sum, done_sum), int64 [K] each.
+    """
+    lat = np.ascontiguousarray(lat, dtype=np.int32)
+    if lat.ndim != 3:
+        raise OracleError(ERR_INVALID_ARG)
+    T, N, M = lat.shape
+    taus = np.ascontiguousarray(taus, dtype=np.int64)
+    K = taus.size
+    step = np.zeros(K, dtype=np.int64)
+    done = np.zeros(K, dtype=np.int64)
+    fn = getattr(_load(), {"literal": "dc_oracle_simulate_literal", "sorted": "dc_oracle_simulate_sorted"}[method])
+    rc = fn(lat.ctypes.data, T, N, M, taus.ctypes.data, K, int(comm), step.ctypes.data, done.ctypes.data)
+    if rc != OK:
+        raise OracleError(rc)
+    return step, done
+
+
+def simulate_threaded(lat: np.ndarray, taus, comm: int, method: str = "sorted", threads: int = 1):
+    """simulate() with the trials split over threads; the per-trial sums simply add."""
+    T = lat.shape[0]
+    threads = max(1, min(threads, T))
+    if threads == 1:
+        return simulate(lat, taus, comm, method)
+    bounds = [T * i // threads for i in range(threads + 1)]
+    with ThreadPoolExecutor(threads) as ex:
+        parts = list(ex.map(lambda i: simulate(lat[bounds[i]:bounds[i + 1]], taus, comm, method), range(threads)))
+    return sum(p[0] for p in parts), sum(p[1] for p in parts)
+
+
+def select_tau(step_sum, done_sum, taus, T: int, N: int, M: int, base_step_sum: int = 0):
+    """Throughput, effective speedup and the best threshold.
+
+    thr[k]   = done_sum[k] / step_sum[k]         micro-batches per microsecond, all workers (Section 4.4)
+    s_eff[k] = thr[k] / (T*N*M / base_step_sum)  ratio to the no-drop throughput (Section 4.4, S_eff),
+               with base_step_sum = sum_i (T_i + T^c); NaN when base_step_sum == 0
+    best_k   = argmax_k thr[k], compared exactly as integer cross-products; among exact
+               ties the largest tau wins (fewest dropped micro-batches), then the lowest index.
+    """
+    step = [int(x) for x in step_sum]
+    done = [int(x) for x in done_sum]
+    tau = [int(x) for x in taus]
+    K = len(tau)
+    if K == 0 or any(s <= 0 for s in step):
+        raise OracleError(ERR_INVALID_ARG)
+    thr = np.array([d / s for d, s in zip(done, step)], dtype=np.float64)
+    if base_step_sum > 0:
+        seff = np.array([(d / s) * float(base_step_sum) / (float(T) * float(N) * float(M)) for d, s in zip(done, step)])
+    else:
+        seff = np.full(K, np.nan)
+    best = 0
+    for k in range(1, K):
+        lhs, rhs = done[k] * step[best], done[best] * step[k]      # Python ints: exact
+        if lhs > rhs or (lhs == rhs and tau[k] > tau[best]):
+            best = k
+    return thr, seff, best
+
+
+def per_step_speedup(lat: np.ndarray, taus, comm):
+    """Algorithm 2 as printed: S_i(tau) per iteration, then the mean over iterations.
+
+    comm may be a scalar or one value per iteration (T_i^c).  float64.
+    """
+    lat = np.asarray(lat, dtype=np.int64)
+    T, N, M = lat.shape
+    comm = np.broadcast_to(np.asarray(comm, dtype=np.float64), (T,))
+    out = np.zeros(len(taus), dtype=np.float64)
+    for k, tau in enumerate(taus):
+        acc = 0.0
+        for i in range(T):
+            completed = 0.0
+            slowest = 0
+            for n in range(N):
+                elapsed = 0
+                for m in range(M):
+                    elapsed += int(lat[i, n, m])
+                    if elapsed < tau:
+                        completed += 1.0 / N
+                slowest = max(slowest, elapsed)
+            acc += (slowest + comm[i]) / (min(int(tau), slowest) + comm[i]) * completed / M
+        out[k] = acc / T
+    return out

@@ -1,0 +1,274 @@
+"""Pins for the CPU oracle: what the paper's definitions and plain mathematics fix.
+
+None of these compares the oracle with itself: each expected value is a hand computation,
+a closed form, an independent formulation (sort + binary search) or an invariant that
+follows from the definitions in Sections 4.2-4.4 / Appendix C.1.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+from scipy.special import ndtr, ndtri
+
+import oracle
+from dc_workloads import host, spec
+
+METHODS = ("literal", "sorted")
+BIG = 1 << 40
+
+
+def read_golden(path):
+    out = {}
+    for line in path.read_text().splitlines():
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, *vals = line.split()
+        out[key] = [int(v) for v in vals]
+    return out
+
+
+def independent_counts(lat, taus, comm):
+    """Sort every completion time once, then count by binary search (strictly below tau)."""
+    P = np.cumsum(lat.astype(np.int64), axis=2)
+    flat = np.sort(P.reshape(-1))
+    done = np.searchsorted(flat, np.asarray(taus, dtype=np.int64), side="left")
+    tmax = P[:, :, -1].max(axis=1)
+    step = np.array([np.minimum(tmax, t).sum() + comm * lat.shape[0] for t in taus], dtype=np.int64)
+    return step, done.astype(np.int64)
+
+
+def iid_recipe(qfun, T, N, M, seed=1, clip_min=0):
+    return spec.Recipe("pin", T=T, N=N, M=M, K=1, comm=0, grid="minmax",
+                       value=spec.quantile_tables(qfun), seed=seed, clip_min=clip_min)
+
+
+# --- p5: hand-worked example --------------------------------------------------------------
+
+@pytest.mark.parametrize("method", METHODS)
+def test_hand_worked_example(golden_dir, method):
+    g = read_golden(golden_dir / "hand_example.txt")
+    T, N, M = g["T"][0], g["N"][0], g["M"][0]
+    lat = np.array(g["lat"], dtype=np.int32).reshape(T, N, M)
+    step, done = oracle.simulate(lat, g["taus"], g["comm"][0], method)
+    assert done.tolist() == g["done"]
+    assert step.tolist() == g["step"]
+
+
+# --- p1 / p2 / p3: limits and the strict inequality ---------------------------------------
+
+@pytest.mark.parametrize("method", METHODS)
+def test_threshold_above_everything(method):
+    rng = np.random.default_rng(3)
+    lat = rng.integers(0, 1000, size=(7, 5, 9), dtype=np.int32)
+    step, done = oracle.simulate(lat, [BIG], 17, method)
+    assert done[0] == 7 * 5 * 9
+    assert step[0] == int(lat.astype(np.int64).sum(axis=2).max(axis=1).sum()) + 7 * 17
+
+
+@pytest.mark.parametrize("method", METHODS)
+def test_threshold_below_everything(method):
+    rng = np.random.default_rng(4)
+    lat = rng.integers(50, 1000, size=(6, 4, 8), dtype=np.int32)
+    tau = int(lat[:, :, 0].min())
+    step, done = oracle.simulate(lat, [tau, 0], 11, method)
+    assert done.tolist() == [0, 0]
+    assert step.tolist() == [6 * (tau + 11), 6 * 11]
+
+
+@pytest.mark.parametrize("method", METHODS)
+def test_tie_is_not_completed(method):
+    lat = np.array([[[10, 20, 30, 40]]], dtype=np.int32)       # completion times 10 30 60 100
+    step, done = oracle.simulate(lat, [60, 61, 100, 101], 0, method)
+    assert done.tolist() == [2, 3, 3, 4]
+    assert step.tolist() == [60, 61, 100, 100]
+
+
+# --- p4: brute force on tiny inputs -------------------------------------------------------
+
+@pytest.mark.parametrize("method", METHODS)
+def test_exhaustive_small_alphabet(method):
+    taus = list(range(0, 8))
+    for vals in itertools.product((0, 1, 2), repeat=6):
+        lat = np.array(vals, dtype=np.int32).reshape(1, 2, 3)
+        step, done = oracle.simulate(lat, taus, 1, method)
+        estep, edone = independent_counts(lat, taus, 1)
+        assert done.tolist() == edone.tolist(), vals
+        assert step.tolist() == estep.tolist(), vals
+
+
+@pytest.mark.parametrize("method", METHODS)
+@pytest.mark.parametrize("shape", [(3, 4, 5), (2, 1, 7), (5, 3, 1), (1, 6, 2)])
+def test_random_small_vs_sort_and_search(method, shape):
+    rng = np.random.default_rng(hash(shape) % 1000)
+    lat = rng.integers(0, 50, size=shape, dtype=np.int32)
+    lat[rng.random(shape) < 0.2] = 0                       # zero latencies are legal
+    taus = rng.integers(0, 50 * shape[2] + 5, size=7)
+    taus[3] = taus[1]                                      # duplicate, unsorted thresholds
+    step, done = oracle.simulate(lat, taus, 9, method)
+    estep, edone = independent_counts(lat, taus, 9)
+    assert done.tolist() == edone.tolist()
+    assert step.tolist() == estep.tolist()
+
+
+def test_sorted_walk_equals_literal_loops():
+    rng = np.random.default_rng(11)
+    for T, N, M, K in [(4, 3, 16, 33), (9, 17, 5, 8), (2, 2, 64, 100)]:
+        lat = rng.integers(0, 2000, size=(T, N, M), dtype=np.int32)
+        totals = lat.sum(axis=2, dtype=np.int64)
+        taus = rng.integers(0, int(totals.max()) + 10, size=K)
+        a = oracle.simulate(lat, taus, 5, "literal")
+        b = oracle.simulate(lat, taus, 5, "sorted")
+        c = oracle.simulate_threaded(lat, taus, 5, "sorted", threads=3)
+        assert a[0].tolist() == b[0].tolist() == c[0].tolist()
+        assert a[1].tolist() == b[1].tolist() == c[1].tolist()
+
+
+# --- p6: M = 1, maximum of iid workers (order statistics of the iid-max density, Section 4.2) --
+
+def test_exponential_max_matches_harmonic_number():
+    T, N, mean = 40000, 16, 10000.0
+    lat = host.generate(iid_recipe(spec.q_exponential(mean), T, N, 1))
+    step, done = oracle.simulate(lat, [BIG], 0, "sorted")
+    H = sum(1.0 / j for j in range(1, N + 1))
+    sd = mean * math.sqrt(sum(1.0 / j ** 2 for j in range(1, N + 1)))
+    assert done[0] == T * N
+    assert abs(step[0] / T - mean * H) <= 4 * sd / math.sqrt(T) + 1.0
+
+
+def test_uniform_max_matches_closed_form():
+    T, N, a, b = 40000, 16, 50000.0, 150000.0
+    lat = host.generate(iid_recipe(spec.q_uniform(a, b), T, N, 1))
+    step, _ = oracle.simulate(lat, [BIG], 0, "literal")
+    sd = (b - a) * math.sqrt(N / ((N + 1) ** 2 * (N + 2)))
+    assert abs(step[0] / T - (a + (b - a) * N / (N + 1))) <= 4 * sd / math.sqrt(T) + 1.0
+
+
+# --- p7 / p8: normal latencies against the closed forms of Section 4.2-4.3 ----------------
+
+def test_completed_count_matches_normal_cdf_sum():
+    T, N, M, mu, sigma = 2000, 8, 32, 100000.0, 10000.0
+    lat = host.generate(iid_recipe(spec.q_normal(mu, sigma), T, N, M, clip_min=1))
+    taus = [int(mu * M * f) for f in (0.55, 0.8, 0.95, 0.99, 1.0, 1.01, 1.05)]
+    _, done = oracle.simulate(lat, taus, 0, "sorted")
+    m = np.arange(1, M + 1)
+    for tau, d in zip(taus, done):
+        expected = ndtr((tau - m * mu) / (sigma * np.sqrt(m))).sum()
+        assert abs(d / (T * N) - expected) <= 0.03, (tau, d / (T * N), expected)
+
+
+def test_mean_iteration_time_near_normal_max_approximation():
+    T, N, M, mu, sigma = 4000, 64, 32, 100000.0, 10000.0
+    lat = host.generate(iid_recipe(spec.q_normal(mu, sigma), T, N, M, clip_min=1))
+    step, _ = oracle.simulate(lat, [BIG], 0, "sorted")
+    gamma = 0.5772156649015329
+    z = (1 - gamma) * ndtri(1 - 1 / N) + gamma * ndtri(1 - 1 / (math.e * N))
+    measured = (step[0] / T - M * mu) / (sigma * math.sqrt(M))
+    assert abs(measured - z) <= 0.05, (measured, z)
+    # the slowest of more workers takes longer
+    fewer, _ = oracle.simulate(lat[:, :8, :], [BIG], 0, "sorted")
+    assert fewer[0] < step[0]
+
+
+# --- p9 - p12: invariants -----------------------------------------------------------------
+
+@pytest.fixture(scope="module")
+def sample():
+    rng = np.random.default_rng(21)
+    lat = rng.integers(0, 3000, size=(12, 10, 24), dtype=np.int32)
+    totals = lat.sum(axis=2, dtype=np.int64)
+    taus = np.sort(rng.integers(0, int(totals.max()) + 100, size=40))
+    return lat, taus
+
+
+@pytest.mark.parametrize("method", METHODS)
+def test_monotone_and_bounded(sample, method):
+    lat, taus = sample
+    T, N, M = lat.shape
+    step, done = oracle.simulate(lat, taus, 7, method)
+    assert np.all(np.diff(step) >= 0) and np.all(np.diff(done) >= 0)
+    assert np.all(step <= T * (taus + 7))
+    assert np.all(done <= T * N * M) and np.all(done >= 0)
+
+
+@pytest.mark.parametrize("method", METHODS)
+def test_additivity_and_permutations(sample, method):
+    lat, taus = sample
+    step, done = oracle.simulate(lat, taus, 7, method)
+    a = oracle.simulate(lat[:5], taus, 7, method)
+    b = oracle.simulate(lat[5:], taus, 7, method)
+    assert (a[0] + b[0]).tolist() == step.tolist() and (a[1] + b[1]).tolist() == done.tolist()
+    # splitting the workers: completed counts add
+    l = oracle.simulate(lat[:, :4], taus, 7, method)
+    r = oracle.simulate(lat[:, 4:], taus, 7, method)
+    assert (l[1] + r[1]).tolist() == done.tolist()
+    rng = np.random.default_rng(5)
+    shuffled = lat[rng.permutation(lat.shape[0])][:, rng.permutation(lat.shape[1])]
+    s2, d2 = oracle.simulate(shuffled, taus, 7, method)
+    assert s2.tolist() == step.tolist() and d2.tolist() == done.tolist()
+    # reversing the micro-batch order keeps every worker's total, hence the step times
+    s3, _ = oracle.simulate(lat[:, :, ::-1], taus, 7, method)
+    assert s3.tolist() == step.tolist()
+
+
+@pytest.mark.parametrize("method", METHODS)
+def test_comm_only_shifts_step_time(sample, method):
+    lat, taus = sample
+    s0, d0 = oracle.simulate(lat, taus, 0, method)
+    s1, d1 = oracle.simulate(lat, taus, 123, method)
+    assert (s1 - s0).tolist() == [123 * lat.shape[0]] * len(taus)
+    assert d0.tolist() == d1.tolist()
+
+
+def test_select_tau_identities(sample):
+    lat, taus = sample
+    T, N, M = lat.shape
+    taus = np.append(taus, BIG)
+    step, done = oracle.simulate(lat, taus, 50, "sorted")
+    thr, seff, best = oracle.select_tau(step, done, taus, T, N, M, base_step_sum=int(step[-1]))
+    assert seff[-1] == pytest.approx(1.0, abs=1e-12)             # no drops: speedup 1
+    assert np.allclose(thr, done / step, rtol=1e-15)
+    assert thr[best] == thr.max()
+    extra = M / (done / (T * N)) - 1                             # compensation factor R = M/M~ - 1
+    assert np.all(extra[done > 0] >= -1e-12)
+
+
+def test_select_tau_tie_prefers_largest_threshold():
+    # identical throughput 1/2 everywhere -> the largest tau (index 2) is chosen
+    thr, _, best = oracle.select_tau([4, 8, 16, 2], [2, 4, 8, 1], [10, 30, 40, 20], 1, 1, 8)
+    assert best == 2 and np.allclose(thr, 0.5)
+    # cross-products that differ only beyond float64 resolution are still ordered exactly
+    big = 3 * 10 ** 18
+    _, _, best = oracle.select_tau([big, big - 1], [big - 1, big - 2], [1, 2], 1, 1, 1)
+    assert best == 0
+
+
+def test_per_step_speedup_matches_hand_example(golden_dir):
+    g = read_golden(golden_dir / "hand_example.txt")
+    lat = np.array(g["lat"], dtype=np.int32).reshape(1, 2, 3)
+    s = oracle.per_step_speedup(lat, g["taus"], g["comm"][0])
+    # S_i = (T_i + T^c)/(min(tau,T_i) + T^c) * (completed/N)/M with T_i = 13, N*M = 6
+    expected = [14 / 6 * 3 / 6, 14 / 9 * 4 / 6, 14 / 14 * 5 / 6, 1.0]
+    assert np.allclose(s, expected, rtol=1e-14)
+
+
+# --- error behaviour ------------------------------------------------------------------------
+
+@pytest.mark.parametrize("method", METHODS)
+def test_negative_latency_is_rejected(method):
+    lat = np.array([[[5, -1, 3]]], dtype=np.int32)
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.simulate(lat, [4], 0, method)
+    assert e.value.code == oracle.ERR_NEGATIVE_LATENCY
+
+
+@pytest.mark.parametrize("method", METHODS)
+def test_invalid_arguments(method):
+    lat = np.ones((1, 1, 2), dtype=np.int32)
+    with pytest.raises(oracle.OracleError):
+        oracle.simulate(lat, [-1], 0, method)
+    with pytest.raises(oracle.OracleError):
+        oracle.simulate(lat, [1], -5, method)
+    step, done = oracle.simulate(lat, [], 0, method)
+    assert step.size == 0 and done.size == 0

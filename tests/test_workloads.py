@@ -1,0 +1,102 @@
+"""The synthetic latency generator: hash vectors, NumPy vs C agreement, distribution sanity."""
+import math
+
+import numpy as np
+import pytest
+
+from dc_workloads import CONFIG_NAMES, config, host, spec
+
+
+def test_mix64_matches_published_splitmix64_outputs():
+    # first three outputs of SplitMix64 seeded with 0 (Steele, Lea & Flood; Vigna's reference code)
+    got = [spec.mix64_int(spec.GOLDEN * i) for i in (1, 2, 3)]
+    assert got == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+    arr = host.mix64(np.array([spec.GOLDEN, (2 * spec.GOLDEN) & spec.MASK64], dtype=np.uint64))
+    assert [int(x) for x in arr] == got[:2]
+
+
+@pytest.mark.parametrize("name", CONFIG_NAMES)
+def test_c_generator_equals_numpy_reference(name):
+    r = config(name).with_shape(T=3)
+    n = min(r.elements, 150_000)
+    ref = host.generate_numpy(r, 0, n)
+    fast = host.generate(r).reshape(-1)[:n]
+    assert np.array_equal(ref, fast)
+    # an offset window equals the same window of the whole
+    off = 12_345 % max(1, n - 100)
+    assert np.array_equal(host.generate_numpy(r, off, 100), ref[off:off + 100])
+
+
+def test_tail_cells_are_exercised_and_agree():
+    # hashes whose top 16 bits fall in the refined cells at both ends
+    r = config("extrapolation2048")
+    h = np.array([0, 1 << 40, (15 << 48) | 0xFFFFFFFF0000, (16 << 48), (65519 << 48) | 0xFFFFFFFF0000,
+                  (65520 << 48), (65535 << 48), spec.MASK64], dtype=np.uint64)
+    q = host.draw_q8(h, r.value)
+    assert np.all(np.diff(q.astype(np.int64)) >= 0)
+    assert q[0] == r.value.lo[0] and q[3] == r.value.main[16] and q[5] == r.value.main[65520]
+    assert q[7] <= r.value.hi[-1]
+
+
+def test_generation_is_seeded_and_windowed():
+    r = config("tiny")
+    a = host.generate(r, 10, 20)
+    b = host.generate(r, 0, 30)[10:20]
+    assert np.array_equal(a, b)
+    assert not np.array_equal(host.generate(r.with_shape(seed=1), 0, 2), host.generate(r, 0, 2))
+
+
+@pytest.mark.parametrize("name,mean,sd", [
+    ("tiny", 110000.0, 10000.0),
+    ("lognormal64", 120000.0 * math.exp(0.005), 120000.0 * math.exp(0.005) * math.sqrt(math.exp(0.01) - 1)),
+    ("extrapolation2048", 100000.0, 10000.0),
+])
+def test_moments_of_iid_workloads(name, mean, sd):
+    r = config(name)
+    r = r.with_shape(T=max(1, 2_000_000 // (r.N * r.M)))
+    x = host.generate(r).astype(np.float64).reshape(-1)
+    assert abs(x.mean() - mean) <= 5 * sd / math.sqrt(x.size) + 0.5
+    assert abs(x.std() - sd) <= 0.01 * sd
+    assert x.min() >= 1
+
+
+def test_straggler_rate_and_size():
+    r = config("additive200").with_shape(T=100)
+    x = host.generate(r).reshape(-1)
+    frac = np.mean(x > 450000)
+    assert abs(frac - 0.01) <= 5 * math.sqrt(0.01 * 0.99 / x.size)
+    assert abs(np.median(x[x > 450000]) - 750000) < 2000
+
+
+def test_heterogeneous_workers_have_persistent_slowdown():
+    r = config("heterogeneous2048").with_shape(T=4)
+    s = host.worker_scale_q16(r).astype(np.float64) / 65536.0
+    assert s.min() >= 1.0 and abs(s.mean() - 1.05) < 5 * 0.05 / math.sqrt(r.N)
+    x = host.generate(r).astype(np.float64)
+    per_worker = np.median(x, axis=(0, 2))
+    assert np.corrcoef(per_worker, s)[0, 1] > 0.99
+
+
+def test_tau_grid_rules():
+    r = config("tiny")
+    lat = host.generate(r)
+    totals = host.worker_totals(lat)
+    g = host.tau_grid(r)
+    assert g.size == r.K and g[0] == totals.min() and g[-1] == totals.max()
+    assert np.all(np.diff(g) >= 0)
+    r2 = config("lognormal64").with_shape(T=200)
+    totals = np.sort(host.worker_totals(host.generate(r2)))
+    g2 = host.tau_grid(r2)
+    n = totals.size
+    assert g2[0] == totals[(n - 1) // 100] and g2[-1] == totals[(n - 1) * 999 // 1000]
+    k = 37
+    assert g2[k] == g2[0] + (int(g2[-1] - g2[0]) * k) // (r2.K - 1)
+
+
+def test_largest_latency_leaves_room_for_int32_worker_totals():
+    for name in CONFIG_NAMES:
+        r = config(name)
+        scale = host.worker_scale_q16(r)
+        smax = 65536 if scale is None else int(scale.max())
+        top = ((int(r.value.hi[-1]) * smax * r.spike_mul + (1 << 23)) >> 24) + r.add + r.spike_add
+        assert max(top, r.clip_min) <= (2 ** 31 - 1) // r.M, name
