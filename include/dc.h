@@ -1,0 +1,127 @@
+/* dc.h - C ABI of the DropCompute batched step-time simulator for AMD MI355X (gfx950).
+ *
+ * What is computed (DropCompute, arXiv 2306.10598):
+ *   lat[t][n][m]  compute latency of micro-batch m on worker n in iteration ("trial") t,
+ *                 the samples t_{i,n}^{(m)} that Algorithm 2 (Appendix C.1) takes as input;
+ *   P[t][n][m]  = sum_{j<=m} lat[t][n][j], the completion time T_n^{(m)} (Section 4.3);
+ *   a micro-batch is completed under threshold tau iff P < tau, strictly (Section 4.3,
+ *                 definition of M~; Algorithm 2, inner loop);
+ *   Tmax[t]     = max_n P[t][n][M-1], the iteration's compute time T (Section 4.2);
+ *   step time   = min{tau, Tmax[t]} + comm, comm = T^c, the serial latency that includes
+ *                 the all-reduce (Section 4.3);
+ *   the reduction over iterations and the choice of tau follow Section 4.4 and the last
+ *   lines of Algorithm 2.
+ *
+ * Units are integer microseconds; every sum is an exact integer, so results do not depend
+ * on the order of accumulation.
+ *
+ * General conventions
+ *   - Every function returns a dc_status (0 = DC_OK).  Nothing throws or aborts across this
+ *     boundary.  On any status other than DC_OK the output buffers hold unspecified values.
+ *   - Every pointer is owned by the caller.  "DEVICE" pointers are HIP device memory of the
+ *     current device; "HOST" pointers are ordinary host memory.
+ *   - lat must be 4-byte aligned; rows are contiguous with m fastest: element (t,n,m) is at
+ *     lat[(t*N + n)*M + m].  The fast kernels need lat 16-byte aligned and M in
+ *     {4,8,16,32,64,128,256}; every other M >= 1 (and any alignment) takes a slower kernel
+ *     with the same results.
+ *   - Preconditions on values, checked while streaming: every latency is >= 0
+ *     (else DC_ERR_NEGATIVE_LATENCY) and <= floor((2^31-1)/M) (else DC_ERR_RANGE), which
+ *     guarantees that no worker's total overflows 31 bits.
+ *   - Thresholds: 0 <= tau (else DC_ERR_INVALID_ARG), any order, duplicates allowed; a
+ *     threshold >= 2^31 is above every possible completion time.  1 <= T, N, M;
+ *     0 <= K <= DC_MAX_THRESHOLDS (K = 0 does nothing and returns DC_OK); comm >= 0;
+ *     T*N*M < 2^62.
+ */
+#ifndef DC_H
+#define DC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DC_OK = 0,
+    DC_ERR_INVALID_ARG = 1,       /* null pointer, size out of range, negative tau or comm, workspace too small */
+    DC_ERR_NEGATIVE_LATENCY = 2,  /* some lat < 0 */
+    DC_ERR_RANGE = 3,             /* some lat > floor((2^31-1)/M) */
+    DC_ERR_DEVICE = 4,            /* a HIP call failed (see dc_last_device_error) */
+    DC_ERR_NOMEM = 5              /* device or host allocation failed */
+} dc_status;
+
+#define DC_MAX_THRESHOLDS 65536
+
+/* Step-time and completed-micro-batch sums for K thresholds (Sections 4.2-4.3; the loops of
+ * Algorithm 2 with the per-iteration quantities kept as integers):
+ *   out_step[k] = sum_t ( min(taus[k], Tmax[t]) + comm )
+ *   out_done[k] = sum_t sum_n #{ m : P[t][n][m] < taus[k] }      ( = N * sum_t M~_t(taus[k]) )
+ * lat: DEVICE, int32 [T][N][M], read only.  taus: HOST, K int64.  out_step, out_done: HOST,
+ * K int64 each, in the caller's threshold order.
+ * Runs on the null stream of the current device and returns after the results are on the
+ * host.  Uses a workspace that the library allocates on first use, keeps per process and
+ * grows when needed (dc_shutdown frees it); calls from several threads are serialised. */
+int dc_simulate(const int32_t* lat, int64_t T, int64_t N, int64_t M,
+                const int64_t* taus, int64_t K, int64_t comm,
+                int64_t* out_step, int64_t* out_done);
+
+/* Bytes of DEVICE workspace that dc_simulate_async needs for these sizes (0 if they are invalid). */
+size_t dc_workspace_bytes(int64_t T, int64_t N, int64_t M, int64_t K);
+
+/* Same computation, enqueued on `stream` (a hipStream_t passed as void*; NULL = null stream)
+ * without synchronising and without allocating.  taus_dev, out_step_dev, out_done_dev: DEVICE,
+ * K int64 each.  workspace_dev: DEVICE, 256-byte aligned, at least dc_workspace_bytes(T,N,M,K)
+ * bytes, contents irrelevant on entry; it must not be used by another call until this one has
+ * finished on the stream.  The return value covers only what the host can check (arguments,
+ * launch errors); value errors found on the device (negative tau, negative or too large
+ * latency) are recorded in the workspace and read back with dc_workspace_status. */
+int dc_simulate_async(const int32_t* lat, int64_t T, int64_t N, int64_t M,
+                      const int64_t* taus_dev, int64_t K, int64_t comm,
+                      int64_t* out_step_dev, int64_t* out_done_dev,
+                      void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/* Waits for `stream` and returns the dc_status that the last dc_simulate_async using
+ * workspace_dev recorded on the device (DC_OK, DC_ERR_INVALID_ARG for a negative threshold,
+ * DC_ERR_NEGATIVE_LATENCY, DC_ERR_RANGE) or DC_ERR_DEVICE if the stream reports an error. */
+int dc_workspace_status(const void* workspace_dev, void* stream);
+
+/* Throughput, effective speedup and the best threshold (Section 4.4; Algorithm 2, last line).
+ * HOST only, no GPU work.  Inputs are dc_simulate's outputs for the same taus, T, N, M.
+ *   out_thr[k]  = done_sum[k] / step_sum[k]       completed micro-batches per microsecond over all
+ *                                                 workers, N*M~/(min{tau,T}+T^c) with iteration means
+ *   out_seff[k] = out_thr[k] * base_step_sum / (T*N*M)   S_eff(tau_k): ratio to the no-drop
+ *                 throughput N*M/(T+T^c); base_step_sum = sum_t (Tmax[t] + comm), i.e. out_step
+ *                 of any threshold above every worker total.  With base_step_sum = 0 the
+ *                 S_eff values are NaN.
+ *   *out_best_k = argmax_k out_thr[k], decided exactly by 128-bit integer cross-multiplication;
+ *                 among exact ties the largest tau wins (fewest dropped micro-batches), then the
+ *                 lowest index.
+ * out_thr and out_seff may be NULL.  K >= 1 and every step_sum[k] > 0, else DC_ERR_INVALID_ARG. */
+int dc_select_tau(const int64_t* step_sum, const int64_t* done_sum, const int64_t* taus, int64_t K,
+                  int64_t T, int64_t N, int64_t M, int64_t base_step_sum,
+                  double* out_thr, double* out_seff, int64_t* out_best_k);
+
+/* Optional kernel timing for benchmarks.  When enabled, every dc_simulate / dc_simulate_async
+ * brackets its streaming kernel (the single pass over lat) and the whole enqueued sequence with
+ * HIP events on the stream it runs on.  dc_last_kernel_ms waits for those events and returns the
+ * elapsed milliseconds of the last call (scan_ms: streaming kernel(s) only; total_ms: all
+ * kernels of the call).  Either pointer may be NULL.  DC_ERR_INVALID_ARG if timing is off or no
+ * call has been timed yet. */
+int dc_set_kernel_timing(int enable);
+int dc_last_kernel_ms(float* scan_ms, float* total_ms);
+
+/* Name of a status code; a static string, never NULL. */
+const char* dc_status_string(int status);
+
+/* Text of the last HIP error that made a call in this thread return DC_ERR_DEVICE or
+ * DC_ERR_NOMEM ("" if none).  Static storage, valid until the next failing call. */
+const char* dc_last_device_error(void);
+
+/* Frees everything the library holds (cached workspace, events).  Safe to call twice. */
+void dc_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DC_H */

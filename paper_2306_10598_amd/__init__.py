@@ -1,0 +1,167 @@
+"""Python binding of libdc (include/dc.h): argument marshalling only.
+
+Every step of the computation runs in the HIP kernels of libdc.so; nothing here computes on
+latencies, and there is no CPU fallback: importing works without the library (so that build
+tooling can import the package), but every call raises if libdc.so cannot be loaded.
+
+PyTorch is used only to hold device memory (`tensor.data_ptr()`) and to name a stream.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+LIB_PATH = _HERE / "libdc.so"
+
+DC_OK, DC_ERR_INVALID_ARG, DC_ERR_NEGATIVE_LATENCY, DC_ERR_RANGE, DC_ERR_DEVICE, DC_ERR_NOMEM = range(6)
+DC_MAX_THRESHOLDS = 65536
+
+EXPORTS = (
+    "dc_simulate", "dc_workspace_bytes", "dc_simulate_async", "dc_workspace_status", "dc_select_tau",
+    "dc_set_kernel_timing", "dc_last_kernel_ms", "dc_status_string", "dc_last_device_error", "dc_shutdown",
+)
+
+_lib = None
+
+
+class DcError(RuntimeError):
+    """A libdc call returned a status other than DC_OK."""
+
+    def __init__(self, status: int, where: str):
+        lib = _load()
+        text = lib.dc_status_string(status).decode()
+        detail = lib.dc_last_device_error().decode()
+        super().__init__(f"{where}: {text}" + (f" ({detail})" if detail and status >= DC_ERR_DEVICE else ""))
+        self.status = status
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not LIB_PATH.exists():
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = ctypes.CDLL(str(LIB_PATH))
+    i64, p, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    lib.dc_simulate.argtypes = [p, i64, i64, i64, p, i64, i64, p, p]
+    lib.dc_simulate.restype = ctypes.c_int
+    lib.dc_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    lib.dc_workspace_bytes.restype = sz
+    lib.dc_simulate_async.argtypes = [p, i64, i64, i64, p, i64, i64, p, p, p, sz, p]
+    lib.dc_simulate_async.restype = ctypes.c_int
+    lib.dc_workspace_status.argtypes = [p, p]
+    lib.dc_workspace_status.restype = ctypes.c_int
+    lib.dc_select_tau.argtypes = [p, p, p, i64, i64, i64, i64, i64, p, p, p]
+    lib.dc_select_tau.restype = ctypes.c_int
+    lib.dc_set_kernel_timing.argtypes = [ctypes.c_int]
+    lib.dc_set_kernel_timing.restype = ctypes.c_int
+    lib.dc_last_kernel_ms.argtypes = [p, p]
+    lib.dc_last_kernel_ms.restype = ctypes.c_int
+    lib.dc_status_string.argtypes = [ctypes.c_int]
+    lib.dc_status_string.restype = ctypes.c_char_p
+    lib.dc_last_device_error.argtypes = []
+    lib.dc_last_device_error.restype = ctypes.c_char_p
+    lib.dc_shutdown.argtypes = []
+    lib.dc_shutdown.restype = None
+    _lib = lib
+    return lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != DC_OK:
+        raise DcError(status, where)
+
+
+def _device_tensor(t, dtype_name: str, what: str):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what} must be a GPU tensor")
+    if t.dtype != getattr(torch, dtype_name) or not t.is_contiguous():
+        raise TypeError(f"{what} must be a contiguous {dtype_name} tensor")
+    return t
+
+
+def dc_status_string(status: int) -> str:
+    return _load().dc_status_string(int(status)).decode()
+
+
+def dc_workspace_bytes(T: int, N: int, M: int, K: int) -> int:
+    return int(_load().dc_workspace_bytes(T, N, M, K))
+
+
+def dc_simulate(lat, taus, comm: int):
+    """out_step[K], out_done[K] (NumPy int64) for a GPU int32 tensor lat[T][N][M] and host thresholds."""
+    lat = _device_tensor(lat, "int32", "lat")
+    if lat.dim() != 3:
+        raise TypeError("lat must have shape [T][N][M]")
+    T, N, M = lat.shape
+    taus = np.ascontiguousarray(taus, dtype=np.int64)
+    K = taus.size
+    out_step = np.empty(K, dtype=np.int64)
+    out_done = np.empty(K, dtype=np.int64)
+    rc = _load().dc_simulate(lat.data_ptr(), T, N, M, taus.ctypes.data, K, int(comm),
+                             out_step.ctypes.data, out_done.ctypes.data)
+    _check(rc, "dc_simulate")
+    return out_step, out_done
+
+
+def dc_simulate_async(lat, taus_dev, comm: int, out_step_dev, out_done_dev, workspace, stream=None) -> None:
+    """Enqueue the computation on `stream` (a torch.cuda.Stream, or None for the null stream)."""
+    lat = _device_tensor(lat, "int32", "lat")
+    if lat.dim() != 3:
+        raise TypeError("lat must have shape [T][N][M]")
+    T, N, M = lat.shape
+    taus_dev = _device_tensor(taus_dev, "int64", "taus_dev")
+    K = taus_dev.numel()
+    out_step_dev = _device_tensor(out_step_dev, "int64", "out_step_dev")
+    out_done_dev = _device_tensor(out_done_dev, "int64", "out_done_dev")
+    workspace = _device_tensor(workspace, "uint8", "workspace")
+    if out_step_dev.numel() < K or out_done_dev.numel() < K:
+        raise ValueError("output tensors are shorter than the threshold list")
+    handle = 0 if stream is None else int(stream.cuda_stream)
+    rc = _load().dc_simulate_async(lat.data_ptr(), T, N, M, taus_dev.data_ptr(), K, int(comm),
+                                   out_step_dev.data_ptr(), out_done_dev.data_ptr(),
+                                   workspace.data_ptr(), workspace.numel(), handle)
+    _check(rc, "dc_simulate_async")
+
+
+def dc_workspace_status(workspace, stream=None) -> int:
+    """Wait for the stream; return the status the device recorded in the workspace (no exception)."""
+    workspace = _device_tensor(workspace, "uint8", "workspace")
+    handle = 0 if stream is None else int(stream.cuda_stream)
+    return int(_load().dc_workspace_status(workspace.data_ptr(), handle))
+
+
+def dc_select_tau(step_sum, done_sum, taus, T: int, N: int, M: int, base_step_sum: int = 0):
+    """(thr[K], s_eff[K], best_k) from dc_simulate's outputs; host only."""
+    step_sum = np.ascontiguousarray(step_sum, dtype=np.int64)
+    done_sum = np.ascontiguousarray(done_sum, dtype=np.int64)
+    taus = np.ascontiguousarray(taus, dtype=np.int64)
+    K = taus.size
+    if step_sum.size != K or done_sum.size != K:
+        raise ValueError("step_sum, done_sum and taus must have the same length")
+    thr = np.empty(K, dtype=np.float64)
+    seff = np.empty(K, dtype=np.float64)
+    best = ctypes.c_int64(-1)
+    rc = _load().dc_select_tau(step_sum.ctypes.data, done_sum.ctypes.data, taus.ctypes.data, K, T, N, M,
+                               int(base_step_sum), thr.ctypes.data, seff.ctypes.data, ctypes.byref(best))
+    _check(rc, "dc_select_tau")
+    return thr, seff, int(best.value)
+
+
+def dc_set_kernel_timing(enable: bool) -> None:
+    _check(_load().dc_set_kernel_timing(1 if enable else 0), "dc_set_kernel_timing")
+
+
+def dc_last_kernel_ms():
+    """(scan_ms, total_ms) of the last timed call."""
+    a, b = ctypes.c_float(0), ctypes.c_float(0)
+    _check(_load().dc_last_kernel_ms(ctypes.byref(a), ctypes.byref(b)), "dc_last_kernel_ms")
+    return float(a.value), float(b.value)
+
+
+def dc_shutdown() -> None:
+    _load().dc_shutdown()

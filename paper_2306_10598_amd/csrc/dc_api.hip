@@ -1,0 +1,321 @@
+// C ABI of the DropCompute step-time simulator (see include/dc.h): argument checks, the plan of a
+// call (kernel choice, work units, workspace layout), kernel sequencing, and the host-only
+// threshold selection.  No computation on latencies happens on the host.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "dc.h"
+#include "dc_internal.h"
+
+namespace {
+
+thread_local char g_error_text[256] = "";
+
+int device_error(hipError_t e, const char* what, int status = DC_ERR_DEVICE) {
+    snprintf(g_error_text, sizeof(g_error_text), "%s: %s", what, hipGetErrorString(e));
+    return status;
+}
+
+#define DC_HIP(call)                                         \
+    do {                                                     \
+        hipError_t e_ = (call);                              \
+        if (e_ != hipSuccess) return device_error(e_, #call); \
+    } while (0)
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+uint32_t next_pow2_above(uint32_t n) {   // smallest power of two > n
+    uint32_t p = 2;
+    while (p <= n) p <<= 1;
+    return p;
+}
+
+bool vec4_shape(int64_t M) {
+    return M >= 4 && M <= 256 && (M & (M - 1)) == 0;
+}
+
+// Returns false when the sizes are outside what the library handles.
+bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::Plan* out) {
+    if (T < 1 || N < 1 || M < 1 || K < 1 || K > DC_MAX_THRESHOLDS) return false;
+    const int64_t lim = (int64_t)1 << 31;
+    if (T >= lim || N >= lim || M >= lim) return false;
+    if ((long double)T * (long double)N * (long double)M >= 4.6e18L) return false;   // < 2^62
+    dc::Plan p{};
+    p.T = (uint32_t)T; p.N = (uint32_t)N; p.M = (uint32_t)M; p.K = (uint32_t)K;
+    p.elements = (uint64_t)T * (uint64_t)N * (uint64_t)M;
+    p.vec4 = allow_vec4 && vec4_shape(M);
+    uint64_t upt;
+    if (p.vec4) {
+        const uint64_t rows_per_load = 64 / (M / 4);
+        const uint64_t loads_per_trial = ((uint64_t)N + rows_per_load - 1) / rows_per_load;
+        p.per_unit = 64;                                          // 64 KiB of contiguous rows
+        upt = (loads_per_trial + p.per_unit - 1) / p.per_unit;
+    } else {
+        uint64_t rows = 16384 / (4 * (uint64_t)M);                // about 16 KiB per unit
+        if (rows < 1) rows = 1;
+        if (rows > 64) rows = 64;
+        p.per_unit = (uint32_t)rows;
+        upt = ((uint64_t)N + rows - 1) / rows;
+    }
+    const uint64_t units = (uint64_t)T * upt;
+    if (units >= (uint64_t)lim) return false;
+    p.units_per_trial = (uint32_t)upt;
+    p.units = (uint32_t)units;
+    uint64_t grid = (units + DC_SCAN_WAVES - 1) / DC_SCAN_WAVES;
+    p.grid = (uint32_t)(grid < DC_MAX_SCAN_BLOCKS ? grid : DC_MAX_SCAN_BLOCKS);
+    p.chunk = p.K < DC_CHUNK_THRESHOLDS ? p.K : DC_CHUNK_THRESHOLDS;
+    p.p2 = next_pow2_above(p.chunk);
+    p.max_latency = (uint32_t)(2147483647ll / M);
+
+    size_t off = 0;
+    p.off_status = off;     off += 256;
+    p.off_tau_sorted = off; off += align256((size_t)K * 8);
+    p.off_tau_u32 = off;    off += align256((size_t)K * 4);
+    p.off_pos = off;        off += align256((size_t)K * 4);
+    p.off_bins = off;       off += align256((size_t)3 * p.p2 * 8);
+    p.off_chunk_out = off;  off += align256((size_t)2 * p.chunk * 8);
+    p.off_unit_max = off;   off += align256((size_t)p.units * 4);
+    p.off_hist_part = off;  off += align256((size_t)p.grid * p.p2 * 4);
+    p.bytes = off;
+    *out = p;
+    return true;
+}
+
+// ---- optional timing ---------------------------------------------------------------------------
+struct Timing {
+    bool enabled = false;
+    bool valid = false;
+    hipEvent_t begin = nullptr, end = nullptr;
+    std::vector<hipEvent_t> scan;      // pairs (before, after) per chunk
+    size_t used_pairs = 0;
+};
+Timing g_timing;
+std::mutex g_mutex;                     // guards g_timing and the cached workspace
+
+int ensure_events(size_t pairs) {
+    if (!g_timing.begin) {
+        DC_HIP(hipEventCreate(&g_timing.begin));
+        DC_HIP(hipEventCreate(&g_timing.end));
+    }
+    while (g_timing.scan.size() < 2 * pairs) {
+        hipEvent_t e;
+        DC_HIP(hipEventCreate(&e));
+        g_timing.scan.push_back(e);
+    }
+    return DC_OK;
+}
+
+// ---- the enqueued sequence ---------------------------------------------------------------------
+int enqueue(const dc::Plan& p, const int32_t* lat, const int64_t* taus_dev, int64_t comm, int64_t* out_step_dev,
+            int64_t* out_done_dev, unsigned char* ws, hipStream_t stream, bool timed) {
+    uint32_t* status = reinterpret_cast<uint32_t*>(ws + p.off_status);
+    int64_t* tau_sorted = reinterpret_cast<int64_t*>(ws + p.off_tau_sorted);
+    uint32_t* tau_u32 = reinterpret_cast<uint32_t*>(ws + p.off_tau_u32);
+    uint32_t* pos = reinterpret_cast<uint32_t*>(ws + p.off_pos);
+    unsigned long long* hist_total = reinterpret_cast<unsigned long long*>(ws + p.off_bins);
+    unsigned long long* trial_cnt = hist_total + p.p2;
+    unsigned long long* trial_sum = trial_cnt + p.p2;
+    int64_t* chunk_step = reinterpret_cast<int64_t*>(ws + p.off_chunk_out);
+    int64_t* chunk_done = chunk_step + p.chunk;
+    uint32_t* unit_max = reinterpret_cast<uint32_t*>(ws + p.off_unit_max);
+    uint32_t* hist_part = reinterpret_cast<uint32_t*>(ws + p.off_hist_part);
+
+    const uint32_t chunks = (p.K + p.chunk - 1) / p.chunk;
+    if (timed) {
+        int rc = ensure_events(chunks);
+        if (rc) return rc;
+        g_timing.used_pairs = chunks;
+        g_timing.valid = false;
+        DC_HIP(hipEventRecord(g_timing.begin, stream));
+    }
+    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, hist_total, 3 * p.p2, stream);
+    for (uint32_t c = 0; c < chunks; ++c) {
+        const uint32_t chunk0 = c * p.chunk;
+        const uint32_t kc = p.K - chunk0 < p.chunk ? p.K - chunk0 : p.chunk;
+        if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c], stream));
+        dc::launch_scan(p, lat, tau_u32 + chunk0, kc, unit_max, hist_part, status, stream);
+        if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c + 1], stream));
+        dc::launch_reduce(p, hist_part, hist_total, unit_max, tau_u32 + chunk0, kc, trial_cnt, trial_sum, stream);
+        dc::launch_finalize(p, hist_total, trial_cnt, trial_sum, kc, chunk0, tau_sorted, pos, comm, out_step_dev,
+                            out_done_dev, chunk_step, chunk_done, stream);
+    }
+    if (timed) {
+        DC_HIP(hipEventRecord(g_timing.end, stream));
+        g_timing.valid = true;
+    }
+    DC_HIP(hipGetLastError());
+    return DC_OK;
+}
+
+int flags_to_status(uint32_t flags) {
+    if (flags & DC_FLAG_NEGATIVE_TAU) return DC_ERR_INVALID_ARG;
+    if (flags & DC_FLAG_NEGATIVE_LATENCY) return DC_ERR_NEGATIVE_LATENCY;
+    if (flags & DC_FLAG_RANGE) return DC_ERR_RANGE;
+    return DC_OK;
+}
+
+bool sizes_ok(int64_t T, int64_t N, int64_t M, int64_t K, int64_t comm) {
+    return T >= 1 && N >= 1 && M >= 1 && K >= 0 && K <= DC_MAX_THRESHOLDS && comm >= 0;
+}
+
+// cached allocation of the synchronous entry point
+unsigned char* g_cache = nullptr;
+size_t g_cache_bytes = 0;
+int g_cache_device = -1;
+
+}  // namespace
+
+extern "C" {
+
+size_t dc_workspace_bytes(int64_t T, int64_t N, int64_t M, int64_t K) {
+    dc::Plan a{}, b{};
+    if (!make_plan(T, N, M, K, true, &a)) return 0;
+    if (!make_plan(T, N, M, K, false, &b)) return 0;
+    return a.bytes > b.bytes ? a.bytes : b.bytes;
+}
+
+int dc_simulate_async(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus_dev, int64_t K,
+                      int64_t comm, int64_t* out_step_dev, int64_t* out_done_dev, void* workspace_dev,
+                      size_t workspace_bytes, void* stream) {
+    if (!sizes_ok(T, N, M, K, comm) || !lat) return DC_ERR_INVALID_ARG;
+    if (K == 0) return DC_OK;
+    if (!taus_dev || !out_step_dev || !out_done_dev || !workspace_dev) return DC_ERR_INVALID_ARG;
+    if (((uintptr_t)lat & 3u) || ((uintptr_t)workspace_dev & 255u)) return DC_ERR_INVALID_ARG;
+    dc::Plan p{};
+    const bool aligned = ((uintptr_t)lat & 15u) == 0;
+    if (!make_plan(T, N, M, K, aligned, &p)) return DC_ERR_INVALID_ARG;
+    if (workspace_bytes < p.bytes) return DC_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    return enqueue(p, lat, taus_dev, comm, out_step_dev, out_done_dev, static_cast<unsigned char*>(workspace_dev),
+                   static_cast<hipStream_t>(stream), g_timing.enabled);
+}
+
+int dc_workspace_status(const void* workspace_dev, void* stream) {
+    if (!workspace_dev) return DC_ERR_INVALID_ARG;
+    DC_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    uint32_t flags = 0;
+    DC_HIP(hipMemcpy(&flags, workspace_dev, sizeof(flags), hipMemcpyDeviceToHost));
+    return flags_to_status(flags);
+}
+
+int dc_simulate(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus, int64_t K, int64_t comm,
+                int64_t* out_step, int64_t* out_done) {
+    if (!sizes_ok(T, N, M, K, comm) || !lat) return DC_ERR_INVALID_ARG;
+    if (K == 0) return DC_OK;
+    if (!taus || !out_step || !out_done || ((uintptr_t)lat & 3u)) return DC_ERR_INVALID_ARG;
+    for (int64_t k = 0; k < K; ++k)
+        if (taus[k] < 0) return DC_ERR_INVALID_ARG;
+    dc::Plan p{};
+    const bool aligned = ((uintptr_t)lat & 15u) == 0;
+    if (!make_plan(T, N, M, K, aligned, &p)) return DC_ERR_INVALID_ARG;
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int device = 0;
+    DC_HIP(hipGetDevice(&device));
+    const size_t io_bytes = align256((size_t)K * 8);
+    const size_t need = 3 * io_bytes + p.bytes;
+    if (device != g_cache_device || need > g_cache_bytes) {
+        if (g_cache) { (void)hipFree(g_cache); g_cache = nullptr; g_cache_bytes = 0; }
+        void* mem = nullptr;
+        hipError_t e = hipMalloc(&mem, need);
+        if (e != hipSuccess) return device_error(e, "hipMalloc(workspace)", DC_ERR_NOMEM);
+        g_cache = static_cast<unsigned char*>(mem);
+        g_cache_bytes = need;
+        g_cache_device = device;
+    }
+    int64_t* taus_dev = reinterpret_cast<int64_t*>(g_cache);
+    int64_t* step_dev = reinterpret_cast<int64_t*>(g_cache + io_bytes);
+    int64_t* done_dev = reinterpret_cast<int64_t*>(g_cache + 2 * io_bytes);
+    unsigned char* ws = g_cache + 3 * io_bytes;
+
+    hipStream_t stream = nullptr;
+    DC_HIP(hipMemcpy(taus_dev, taus, (size_t)K * 8, hipMemcpyHostToDevice));
+    int rc = enqueue(p, lat, taus_dev, comm, step_dev, done_dev, ws, stream, g_timing.enabled);
+    if (rc) return rc;
+    DC_HIP(hipStreamSynchronize(stream));
+    uint32_t flags = 0;
+    DC_HIP(hipMemcpy(&flags, ws + p.off_status, sizeof(flags), hipMemcpyDeviceToHost));
+    rc = flags_to_status(flags);
+    if (rc) return rc;
+    DC_HIP(hipMemcpy(out_step, step_dev, (size_t)K * 8, hipMemcpyDeviceToHost));
+    DC_HIP(hipMemcpy(out_done, done_dev, (size_t)K * 8, hipMemcpyDeviceToHost));
+    return DC_OK;
+}
+
+int dc_select_tau(const int64_t* step_sum, const int64_t* done_sum, const int64_t* taus, int64_t K, int64_t T,
+                  int64_t N, int64_t M, int64_t base_step_sum, double* out_thr, double* out_seff,
+                  int64_t* out_best_k) {
+    if (!step_sum || !done_sum || !taus || !out_best_k || K < 1 || T < 1 || N < 1 || M < 1 || base_step_sum < 0)
+        return DC_ERR_INVALID_ARG;
+    for (int64_t k = 0; k < K; ++k)
+        if (step_sum[k] <= 0 || done_sum[k] < 0) return DC_ERR_INVALID_ARG;
+    const double full = (double)T * (double)N * (double)M;
+    int64_t best = 0;
+    for (int64_t k = 0; k < K; ++k) {
+        const double thr = (double)done_sum[k] / (double)step_sum[k];
+        if (out_thr) out_thr[k] = thr;
+        if (out_seff) out_seff[k] = base_step_sum > 0 ? thr * (double)base_step_sum / full : NAN;
+        if (k == 0) continue;
+        // done[k]/step[k] > done[best]/step[best]  <=>  done[k]*step[best] > done[best]*step[k]
+        const unsigned __int128 lhs = (unsigned __int128)(uint64_t)done_sum[k] * (uint64_t)step_sum[best];
+        const unsigned __int128 rhs = (unsigned __int128)(uint64_t)done_sum[best] * (uint64_t)step_sum[k];
+        if (lhs > rhs || (lhs == rhs && taus[k] > taus[best])) best = k;
+    }
+    *out_best_k = best;
+    return DC_OK;
+}
+
+int dc_set_kernel_timing(int enable) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_timing.enabled = enable != 0;
+    g_timing.valid = false;
+    return DC_OK;
+}
+
+int dc_last_kernel_ms(float* scan_ms, float* total_ms) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (!g_timing.enabled || !g_timing.valid) return DC_ERR_INVALID_ARG;
+    DC_HIP(hipEventSynchronize(g_timing.end));
+    if (total_ms) DC_HIP(hipEventElapsedTime(total_ms, g_timing.begin, g_timing.end));
+    if (scan_ms) {
+        float acc = 0.f;
+        for (size_t c = 0; c < g_timing.used_pairs; ++c) {
+            float ms = 0.f;
+            DC_HIP(hipEventElapsedTime(&ms, g_timing.scan[2 * c], g_timing.scan[2 * c + 1]));
+            acc += ms;
+        }
+        *scan_ms = acc;
+    }
+    return DC_OK;
+}
+
+const char* dc_status_string(int status) {
+    switch (status) {
+        case DC_OK: return "ok";
+        case DC_ERR_INVALID_ARG: return "invalid argument";
+        case DC_ERR_NEGATIVE_LATENCY: return "negative latency";
+        case DC_ERR_RANGE: return "latency too large for 31-bit worker totals";
+        case DC_ERR_DEVICE: return "HIP error";
+        case DC_ERR_NOMEM: return "out of memory";
+        default: return "unknown status";
+    }
+}
+
+const char* dc_last_device_error(void) { return g_error_text; }
+
+void dc_shutdown(void) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (g_cache) { (void)hipFree(g_cache); g_cache = nullptr; g_cache_bytes = 0; g_cache_device = -1; }
+    if (g_timing.begin) { (void)hipEventDestroy(g_timing.begin); g_timing.begin = nullptr; }
+    if (g_timing.end) { (void)hipEventDestroy(g_timing.end); g_timing.end = nullptr; }
+    for (hipEvent_t e : g_timing.scan) (void)hipEventDestroy(e);
+    g_timing.scan.clear();
+    g_timing.valid = false;
+}
+
+}  // extern "C"

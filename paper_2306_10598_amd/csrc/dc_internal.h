@@ -1,0 +1,54 @@
+// Shared between dc_api.hip (host logic, C ABI) and dc_kernels.hip (device code).
+#ifndef DC_INTERNAL_H
+#define DC_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#define DC_SCAN_THREADS 256
+#define DC_SCAN_WAVES (DC_SCAN_THREADS / 64)
+#define DC_FINAL_THREADS 1024
+#define DC_MAX_SCAN_BLOCKS 2048u       // 256 compute units x 8 resident blocks
+#define DC_CHUNK_THRESHOLDS 4095u      // thresholds handled by one pass over lat (LDS-resident grid)
+#define DC_TAU_CLAMP 0x80000000u       // thresholds at or above 2^31 exceed every completion time
+
+#define DC_FLAG_NEGATIVE_TAU 1u
+#define DC_FLAG_NEGATIVE_LATENCY 2u
+#define DC_FLAG_RANGE 4u
+
+namespace dc {
+
+// Everything the host decides about one call: which streaming kernel, how the tensor is cut
+// into units, and where each array sits in the workspace.
+struct Plan {
+    uint32_t T, N, M, K;
+    uint64_t elements;          // T*N*M
+    bool vec4;                  // 16-byte loads with a segmented scan (M = 4*L, L a power of two <= 64)
+    uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; generic: rows per unit
+    uint32_t units_per_trial;
+    uint32_t units;             // T * units_per_trial
+    uint32_t grid;              // blocks of the streaming kernel (= histogram slots)
+    uint32_t chunk;             // thresholds per pass, <= DC_CHUNK_THRESHOLDS
+    uint32_t p2;                // power of two > chunk: padded length of the LDS threshold array
+    uint32_t max_latency;       // floor((2^31-1)/M)
+    // byte offsets into the workspace
+    size_t off_status, off_tau_sorted, off_tau_u32, off_pos, off_bins, off_chunk_out, off_unit_max, off_hist_part;
+    size_t bytes;
+};
+
+void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t* tau_u32, uint32_t* pos,
+                 uint32_t* status, unsigned long long* bins, uint32_t bins_words, hipStream_t stream);
+void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
+                 uint32_t* hist_part, uint32_t* status, hipStream_t stream);
+void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long* hist_total,
+                   const uint32_t* unit_max, const uint32_t* tau_chunk, uint32_t kc,
+                   unsigned long long* trial_cnt, unsigned long long* trial_sum, hipStream_t stream);
+void launch_finalize(const Plan& p, unsigned long long* hist_total, unsigned long long* trial_cnt,
+                     unsigned long long* trial_sum, uint32_t kc, uint32_t chunk0, const int64_t* tau_sorted,
+                     const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done, int64_t* chunk_step,
+                     int64_t* chunk_done, hipStream_t stream);
+size_t scan_lds_bytes(const Plan& p);
+
+}  // namespace dc
+#endif

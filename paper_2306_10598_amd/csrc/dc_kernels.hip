@@ -1,0 +1,487 @@
+// Device kernels of the DropCompute step-time simulator, written for gfx950 (wave64, DPP, LDS).
+//
+// Pipeline of one call (all on one stream):
+//   dc_prep_kernel       sort the K thresholds by rank, clamp them to 32 bits, clear accumulators
+//   dc_scan_vec4_kernel  the single pass over lat: completion times by a segmented wave scan,
+//     / dc_scan_generic  histogram of completion times over the threshold grid, per-unit maxima
+//   dc_reduce_kernel     add the per-block histograms; per-trial maximum -> binned count and sum
+//   dc_finalize_kernel   prefix sums over the bins -> out_step, out_done in the caller's order
+//
+// Counting rests on two facts.  Latencies are >= 0, so a worker's completion times
+// P[m] = sum_{j<=m} lat[j] (Section 4.3) are non-decreasing.  And "P < tau_k" (strict, Section 4.3)
+// for ascending thresholds means k >= b(P) with b(P) = #{k : tau_k <= P}.  So one histogram of b(P)
+// and one running sum over k replace the K comparisons per element of Algorithm 2's loops, and
+// elements below the smallest threshold (b = 0) need no work at all.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dc_internal.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------------------------
+// wave-level primitives
+// ---------------------------------------------------------------------------------------------
+
+// DPP controls (GCN3+/CDNA encoding)
+constexpr int DPP_ROW_SHR = 0x110;      // + n: lane i reads lane i-n of its 16-lane row
+constexpr int DPP_ROW_BCAST15 = 0x142;  // lane 15 of each row -> every lane of the next row
+constexpr int DPP_ROW_BCAST31 = 0x143;  // lane 31 -> every lane of rows 2 and 3
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+    // lanes whose source is outside the row, or that ROW_MASK disables, receive 0
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, true);
+}
+
+// Inclusive prefix sum over aligned groups of L consecutive lanes (L a power of two, 1..64).
+template <int L>
+__device__ __forceinline__ uint32_t segmented_inclusive_scan(uint32_t v, uint32_t lane) {
+    const uint32_t pos = lane & (L - 1);
+    if constexpr (L >= 2) {
+        uint32_t t = dpp_or_zero<DPP_ROW_SHR + 1, 0xf>(v);
+        if constexpr (L < 16) t = pos >= 1 ? t : 0u;
+        v += t;
+    }
+    if constexpr (L >= 4) {
+        uint32_t t = dpp_or_zero<DPP_ROW_SHR + 2, 0xf>(v);
+        if constexpr (L < 16) t = pos >= 2 ? t : 0u;
+        v += t;
+    }
+    if constexpr (L >= 8) {
+        uint32_t t = dpp_or_zero<DPP_ROW_SHR + 4, 0xf>(v);
+        if constexpr (L < 16) t = pos >= 4 ? t : 0u;
+        v += t;
+    }
+    if constexpr (L >= 16) v += dpp_or_zero<DPP_ROW_SHR + 8, 0xf>(v);
+    if constexpr (L >= 32) v += dpp_or_zero<DPP_ROW_BCAST15, 0xa>(v);
+    if constexpr (L >= 64) v += dpp_or_zero<DPP_ROW_BCAST31, 0xc>(v);
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        uint32_t o = (uint32_t)__shfl_xor((int)v, d, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// b(v) = #{i < n : a[i] <= v} for ascending a[0..p2-2], padded with 0xFFFFFFFF beyond the
+// real thresholds; p2 is a power of two.  Result is in [0, p2-1] for every v.
+__device__ __forceinline__ uint32_t bin_of(const uint32_t* a, uint32_t p2, uint32_t v) {
+    uint32_t b = 0;
+    for (uint32_t s = p2 >> 1; s >= 1; s >>= 1)
+        if (a[b + s - 1] <= v) b += s;
+    return b;
+}
+
+// Four values at once (independent searches interleaved to overlap the LDS reads).
+__device__ __forceinline__ void bin_of4(const uint32_t* a, uint32_t p2, uint4 v, uint32_t (&b)[4]) {
+    b[0] = b[1] = b[2] = b[3] = 0;
+    for (uint32_t s = p2 >> 1; s >= 1; s >>= 1) {
+        const uint32_t a0 = a[b[0] + s - 1], a1 = a[b[1] + s - 1], a2 = a[b[2] + s - 1], a3 = a[b[3] + s - 1];
+        if (a0 <= v.x) b[0] += s;
+        if (a1 <= v.y) b[1] += s;
+        if (a2 <= v.z) b[2] += s;
+        if (a3 <= v.w) b[3] += s;
+    }
+}
+
+// Per-wave state of the streaming pass.
+struct WaveState {
+    uint32_t lane_max;   // running maximum of completion times seen by this lane in the current unit
+    uint32_t check;      // running unsigned maximum of raw latencies (negative values show as >= 2^31)
+    uint32_t q_head;     // ring-buffer read position (wave-uniform)
+    uint32_t q_count;    // items waiting in the ring buffer (wave-uniform)
+};
+
+constexpr uint32_t QUEUE_ITEMS = 128;   // per wave; a push adds at most 64, a drain removes 64
+
+// Take up to 64 queued items (one per lane), bin their four completion times, add to the
+// block histogram.  Bin 0 (below every threshold) is never needed and is skipped.
+__device__ __forceinline__ void drain(WaveState& st, uint4* queue, const uint32_t* tau_s, uint32_t* hist,
+                                      uint32_t p2, uint32_t lane) {
+    const uint32_t n = st.q_count < 64u ? st.q_count : 64u;
+    if (lane < n) {
+        const uint4 item = queue[(st.q_head + lane) & (QUEUE_ITEMS - 1)];
+        uint32_t b[4];
+        bin_of4(tau_s, p2, item, b);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (b[i]) atomicAdd(&hist[b[i]], 1u);
+    }
+    st.q_head = (st.q_head + n) & (QUEUE_ITEMS - 1);
+    st.q_count -= n;
+}
+
+// One 16-byte load per lane: four consecutive latencies of one worker.  Lanes of a worker are
+// L consecutive lanes, so the wave holds 64/L whole rows.
+template <int L>
+__device__ __forceinline__ void process_load(WaveState& st, u32x4 x, bool valid, uint32_t tau0,
+                                             uint4* queue, const uint32_t* tau_s, uint32_t* hist,
+                                             uint32_t p2, uint32_t lane) {
+    st.check = umax(st.check, umax(umax(x.x, x.y), umax(x.z, x.w)));
+    const uint32_t p0 = x.x, p1 = p0 + x.y, p2v = p1 + x.z, p3 = p2v + x.w;
+    const uint32_t incl = segmented_inclusive_scan<L>(p3, lane);   // completion time of the lane's last element
+    st.lane_max = umax(st.lane_max, incl);
+    const bool active = valid && incl >= tau0;                      // some element of the lane reaches the grid
+    const uint64_t mask = __ballot(active);
+    if (mask) {
+        if (active) {
+            const uint32_t before = incl - p3;                      // completion time before the lane's first element
+            const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            queue[(st.q_head + st.q_count + rank) & (QUEUE_ITEMS - 1)] =
+                make_uint4(before + p0, before + p1, before + p2v, incl);
+        }
+        st.q_count += (uint32_t)__popcll(mask);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (st.q_count >= 64u) drain(st, queue, tau_s, hist, p2, lane);
+    }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// dc_prep_kernel: rank-sort the thresholds, clamp, validate, clear accumulators
+// ---------------------------------------------------------------------------------------------
+__global__ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
+                               int64_t* __restrict__ tau_sorted, uint32_t* __restrict__ tau_u32,
+                               uint32_t* __restrict__ pos, uint32_t* __restrict__ status,
+                               unsigned long long* __restrict__ bins, uint32_t bins_words) {
+    const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t stride = gridDim.x * blockDim.x;
+    if (j == 0) *status = 0u;                     // kernels that set flags run later on the stream
+    for (uint32_t i = j; i < bins_words; i += stride) bins[i] = 0ull;
+    if (j >= K) return;
+    const int64_t mine = taus[j];
+    uint32_t rank = 0;
+    for (uint32_t i = 0; i < K; ++i) {
+        const int64_t other = taus[i];
+        rank += (other < mine) || (other == mine && i < j);
+    }
+    pos[j] = rank;
+    tau_sorted[rank] = mine;
+    tau_u32[rank] = mine >= (int64_t)DC_TAU_CLAMP ? DC_TAU_CLAMP : (mine < 0 ? 0u : (uint32_t)mine);
+    if (mine < 0) atomicOr(status, DC_FLAG_NEGATIVE_TAU);
+}
+
+// ---------------------------------------------------------------------------------------------
+// dc_scan_vec4_kernel: the streaming pass, M = 4*L with L in {1,2,4,...,64}
+// ---------------------------------------------------------------------------------------------
+// A "load" is 1 KiB read by one wave (16 B per lane) = 64/L whole rows.  A "unit" is up to
+// loads_per_unit consecutive loads inside one trial; waves take units round-robin.  No
+// block-level synchronisation inside the loop: every wave owns its queue, and the histogram is
+// updated with LDS atomics.
+template <int L>
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t units, uint32_t units_per_trial,
+                         uint32_t loads_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
+                         uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
+                         uint32_t* __restrict__ status, uint32_t max_latency) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
+    uint32_t* tau_s = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);  // [p2]
+    uint32_t* hist = tau_s + p2;                                                        // [p2]
+
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) {
+        tau_s[i] = i < kc ? tau_chunk[i] : 0xFFFFFFFFu;
+        hist[i] = 0u;
+    }
+    __syncthreads();
+
+    constexpr uint32_t R = 64 / L;                 // rows per load
+    constexpr uint32_t M = 4 * L;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = threadIdx.x >> 6;
+    uint4* queue = queue_all + wave * QUEUE_ITEMS;
+    const uint32_t tau0 = tau_s[0];
+    const uint32_t total_waves = gridDim.x * DC_SCAN_WAVES;
+
+    WaveState st{0u, 0u, 0u, 0u};
+    for (uint32_t u = blockIdx.x * DC_SCAN_WAVES + wave; u < units; u += total_waves) {
+        const uint32_t t = u / units_per_trial;
+        const uint32_t j = u - t * units_per_trial;
+        const uint32_t row0 = j * loads_per_unit * R;
+        const uint32_t rows_left = N - row0;
+        const uint32_t rows = rows_left < loads_per_unit * R ? rows_left : loads_per_unit * R;
+        const uint32_t nfull = rows / R;
+        const uint32_t tail_rows = rows - nfull * R;
+        const u32x4* base = reinterpret_cast<const u32x4*>(lat + ((uint64_t)t * N + row0) * M) + lane;
+        st.lane_max = 0u;
+
+        uint32_t i = 0;
+        for (; i + 4 <= nfull; i += 4) {
+            const u32x4 x0 = __builtin_nontemporal_load(base + (uint64_t)(i + 0) * 64);
+            const u32x4 x1 = __builtin_nontemporal_load(base + (uint64_t)(i + 1) * 64);
+            const u32x4 x2 = __builtin_nontemporal_load(base + (uint64_t)(i + 2) * 64);
+            const u32x4 x3 = __builtin_nontemporal_load(base + (uint64_t)(i + 3) * 64);
+            process_load<L>(st, x0, true, tau0, queue, tau_s, hist, p2, lane);
+            process_load<L>(st, x1, true, tau0, queue, tau_s, hist, p2, lane);
+            process_load<L>(st, x2, true, tau0, queue, tau_s, hist, p2, lane);
+            process_load<L>(st, x3, true, tau0, queue, tau_s, hist, p2, lane);
+        }
+        for (; i < nfull; ++i) {
+            const u32x4 x = __builtin_nontemporal_load(base + (uint64_t)i * 64);
+            process_load<L>(st, x, true, tau0, queue, tau_s, hist, p2, lane);
+        }
+        if (tail_rows) {                            // last, partial load of the trial: rows beyond N belong to the next trial
+            const bool valid = lane < tail_rows * L;
+            u32x4 x = {0u, 0u, 0u, 0u};
+            if (valid) x = __builtin_nontemporal_load(base + (uint64_t)nfull * 64);
+            process_load<L>(st, x, valid, tau0, queue, tau_s, hist, p2, lane);
+        }
+        const uint32_t m = wave_max(st.lane_max);
+        if (lane == 0) unit_max[u] = m;
+    }
+    while (st.q_count) drain(st, queue, tau_s, hist, p2, lane);
+
+    const uint32_t worst = wave_max(st.check);
+    if (lane == 0 && worst > max_latency)
+        atomicOr(status, worst >= 0x80000000u ? DC_FLAG_NEGATIVE_LATENCY : DC_FLAG_RANGE);
+
+    __syncthreads();
+    uint32_t* out = hist_part + (uint64_t)blockIdx.x * p2;
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = hist[i];
+}
+
+// ---------------------------------------------------------------------------------------------
+// dc_scan_generic_kernel: any M >= 1, any 4-byte alignment.  One wave walks the rows of its unit,
+// 64 elements at a time, carrying the running completion time from strip to strip.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_scan_generic_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t M, uint32_t units,
+                            uint32_t units_per_trial, uint32_t rows_per_unit,
+                            const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
+                            uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
+                            uint32_t* __restrict__ status, uint32_t max_latency) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint32_t* tau_s = reinterpret_cast<uint32_t*>(smem);
+    uint32_t* hist = tau_s + p2;
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) {
+        tau_s[i] = i < kc ? tau_chunk[i] : 0xFFFFFFFFu;
+        hist[i] = 0u;
+    }
+    __syncthreads();
+
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t tau0 = tau_s[0];
+    const uint32_t total_waves = gridDim.x * DC_SCAN_WAVES;
+    uint32_t check = 0u;
+
+    for (uint32_t u = blockIdx.x * DC_SCAN_WAVES + wave; u < units; u += total_waves) {
+        const uint32_t t = u / units_per_trial;
+        const uint32_t j = u - t * units_per_trial;
+        const uint32_t row0 = j * rows_per_unit;
+        const uint32_t rows = (N - row0) < rows_per_unit ? (N - row0) : rows_per_unit;
+        uint32_t best = 0u;
+        for (uint32_t r = 0; r < rows; ++r) {
+            const int32_t* row = lat + ((uint64_t)t * N + row0 + r) * M;
+            uint32_t carry = 0u;                                   // completion time before this strip
+            for (uint32_t m0 = 0; m0 < M; m0 += 64) {
+                const bool valid = m0 + lane < M;
+                const uint32_t x = valid ? (uint32_t)row[m0 + lane] : 0u;
+                check = umax(check, x);
+                const uint32_t p = carry + segmented_inclusive_scan<64>(x, lane);
+                if (valid && p >= tau0) {
+                    const uint32_t b = bin_of(tau_s, p2, p);
+                    atomicAdd(&hist[b], 1u);
+                }
+                carry = (uint32_t)__builtin_amdgcn_readlane((int)p, 63);
+            }
+            best = umax(best, carry);                              // the worker's total
+        }
+        if (lane == 0) unit_max[u] = best;
+    }
+    const uint32_t worst = wave_max(check);
+    if (lane == 0 && worst > max_latency)
+        atomicOr(status, worst >= 0x80000000u ? DC_FLAG_NEGATIVE_LATENCY : DC_FLAG_RANGE);
+
+    __syncthreads();
+    uint32_t* out = hist_part + (uint64_t)blockIdx.x * p2;
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = hist[i];
+}
+
+// ---------------------------------------------------------------------------------------------
+// dc_reduce_kernel: (a) column sums of the per-block histograms, (b) per-trial maximum binned
+// over the chunk's thresholds.  Blocks [0, hist_blocks) do (a); the rest do (b).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256)
+void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t slots, uint32_t p2, uint32_t hist_blocks,
+                      unsigned long long* __restrict__ hist_total,
+                      const uint32_t* __restrict__ unit_max, uint32_t T, uint32_t units_per_trial,
+                      const uint32_t* __restrict__ tau_chunk, uint32_t kc,
+                      unsigned long long* __restrict__ trial_cnt, unsigned long long* __restrict__ trial_sum) {
+    if (blockIdx.x < hist_blocks) {
+        // 64 columns per block, 4 row groups; consecutive threads read consecutive columns
+        __shared__ unsigned long long part[4][64];
+        const uint32_t col = blockIdx.x * 64 + (threadIdx.x & 63u);
+        const uint32_t grp = threadIdx.x >> 6;
+        unsigned long long acc = 0ull;
+        if (col < p2)
+            for (uint32_t s = grp; s < slots; s += 4) acc += hist_part[(uint64_t)s * p2 + col];
+        part[grp][threadIdx.x & 63u] = acc;
+        __syncthreads();
+        if (grp == 0 && col < p2)
+            hist_total[col] = part[0][threadIdx.x] + part[1][threadIdx.x] + part[2][threadIdx.x] + part[3][threadIdx.x];
+        return;
+    }
+    const uint32_t t = (blockIdx.x - hist_blocks) * 256 + threadIdx.x;
+    if (t >= T) return;
+    const uint32_t* um = unit_max + (uint64_t)t * units_per_trial;
+    uint32_t tmax = 0u;
+    for (uint32_t j = 0; j < units_per_trial; ++j) tmax = umax(tmax, um[j]);
+    // b = #{i < kc : tau_i <= tmax}; the trial's step time is tmax for thresholds i >= b, tau_i below
+    uint32_t lo = 0, hi = kc;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (tau_chunk[mid] <= tmax) lo = mid + 1; else hi = mid;
+    }
+    atomicAdd(&trial_cnt[lo], 1ull);
+    atomicAdd(&trial_sum[lo], (unsigned long long)tmax);
+}
+
+// ---------------------------------------------------------------------------------------------
+// dc_finalize_kernel: one block.  Running sums over the bins give, for sorted threshold i of the
+// chunk: not_done[i] = sum_{b>i} hist[b];  below[i] = #{t : Tmax_t < tau_i} = sum_{b<=i} cnt[b];
+// below_sum[i] = sum_{b<=i} sum[b].  Then
+//   done[i] = T*N*M - not_done[i]
+//   step[i] = below_sum[i] + tau_i * (T - below[i]) + T*comm
+// and results go to the caller's positions.  The accumulators are cleared for the next chunk.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(DC_FINAL_THREADS)
+void dc_finalize_kernel(unsigned long long* __restrict__ hist_total, unsigned long long* __restrict__ trial_cnt,
+                        unsigned long long* __restrict__ trial_sum, uint32_t kc, uint32_t p2, uint32_t chunk0,
+                        const int64_t* __restrict__ tau_sorted, const uint32_t* __restrict__ pos, uint32_t K,
+                        unsigned long long T, unsigned long long elements, long long comm,
+                        long long* __restrict__ out_step, long long* __restrict__ out_done,
+                        long long* __restrict__ chunk_step, long long* __restrict__ chunk_done) {
+    __shared__ unsigned long long s_a[DC_FINAL_THREADS], s_b[DC_FINAL_THREADS], s_c[DC_FINAL_THREADS];
+    const uint32_t tid = threadIdx.x;
+    // each thread owns a contiguous run of bins; p2 <= 4096, so at most 4 bins per thread
+    const uint32_t per = (p2 + DC_FINAL_THREADS - 1) / DC_FINAL_THREADS;
+    const uint32_t b0 = tid * per;
+    unsigned long long h[4], c[4], s[4];
+    unsigned long long th = 0, tc = 0, ts = 0;
+    for (uint32_t i = 0; i < per; ++i) {
+        const uint32_t b = b0 + i;
+        h[i] = b < p2 ? hist_total[b] : 0ull;
+        c[i] = b <= kc ? trial_cnt[b] : 0ull;
+        s[i] = b <= kc ? trial_sum[b] : 0ull;
+        th += h[i]; tc += c[i]; ts += s[i];
+    }
+    s_a[tid] = th; s_b[tid] = tc; s_c[tid] = ts;
+    __syncthreads();
+    for (uint32_t d = 1; d < DC_FINAL_THREADS; d <<= 1) {            // inclusive scan over threads
+        unsigned long long xa = 0, xb = 0, xc = 0;
+        if (tid >= d) { xa = s_a[tid - d]; xb = s_b[tid - d]; xc = s_c[tid - d]; }
+        __syncthreads();
+        s_a[tid] += xa; s_b[tid] += xb; s_c[tid] += xc;
+        __syncthreads();
+    }
+    const unsigned long long all_hist = s_a[DC_FINAL_THREADS - 1];
+    unsigned long long run_h = s_a[tid] - th, run_c = s_b[tid] - tc, run_s = s_c[tid] - ts;   // exclusive
+    for (uint32_t i = 0; i < per; ++i) {
+        const uint32_t b = b0 + i;
+        run_h += h[i]; run_c += c[i]; run_s += s[i];                 // inclusive up to bin b
+        if (b < kc) {
+            const unsigned long long not_done = all_hist - run_h;
+            const long long tau = tau_sorted[chunk0 + b];
+            const unsigned long long tau_c = tau >= (long long)DC_TAU_CLAMP ? (unsigned long long)DC_TAU_CLAMP
+                                                                           : (unsigned long long)(tau < 0 ? 0 : tau);
+            chunk_done[b] = (long long)(elements - not_done);
+            chunk_step[b] = (long long)(run_s + tau_c * (T - run_c) + T * (unsigned long long)comm);
+        }
+    }
+    __syncthreads();
+    for (uint32_t b = tid; b < p2; b += DC_FINAL_THREADS) {
+        hist_total[b] = 0ull;
+        if (b <= kc) { trial_cnt[b] = 0ull; trial_sum[b] = 0ull; }
+    }
+    __threadfence_block();
+    __syncthreads();
+    for (uint32_t j = tid; j < K; j += DC_FINAL_THREADS) {
+        const uint32_t p = pos[j];
+        if (p >= chunk0 && p < chunk0 + kc) {
+            out_step[j] = chunk_step[p - chunk0];
+            out_done[j] = chunk_done[p - chunk0];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers (called from dc_api.hip)
+// ---------------------------------------------------------------------------------------------
+namespace dc {
+
+void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t* tau_u32, uint32_t* pos,
+                 uint32_t* status, unsigned long long* bins, uint32_t bins_words, hipStream_t stream) {
+    const uint32_t threads = 256;
+    uint32_t blocks = (K + threads - 1) / threads;
+    const uint32_t need = (bins_words + threads - 1) / threads;
+    if (blocks < need) blocks = need > 64 ? 64 : need;
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(dc_prep_kernel, dim3(blocks), dim3(threads), 0, stream, taus, K, tau_sorted, tau_u32, pos,
+                       status, bins, bins_words);
+}
+
+size_t scan_lds_bytes(const Plan& p) {
+    const size_t tables = (size_t)p.p2 * 8;
+    return p.vec4 ? tables + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4) : tables;
+}
+
+template <int L>
+static void launch_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
+                        uint32_t* unit_max, uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
+    hipLaunchKernelGGL(dc_scan_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
+                       p.N, p.units, p.units_per_trial, p.per_unit, tau_chunk, kc, p.p2, unit_max, hist_part, status,
+                       p.max_latency);
+}
+
+void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
+                 uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
+    if (!p.vec4) {
+        hipLaunchKernelGGL(dc_scan_generic_kernel, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
+                           lat, p.N, p.M, p.units, p.units_per_trial, p.per_unit, tau_chunk, kc, p.p2, unit_max,
+                           hist_part, status, p.max_latency);
+        return;
+    }
+    switch (p.M / 4) {
+        case 1:  launch_vec4<1>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+        case 2:  launch_vec4<2>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+        case 4:  launch_vec4<4>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+        case 8:  launch_vec4<8>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+        case 16: launch_vec4<16>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+        case 32: launch_vec4<32>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+        default: launch_vec4<64>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+    }
+}
+
+void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long* hist_total,
+                   const uint32_t* unit_max, const uint32_t* tau_chunk, uint32_t kc,
+                   unsigned long long* trial_cnt, unsigned long long* trial_sum, hipStream_t stream) {
+    const uint32_t hist_blocks = (p.p2 + 63) / 64;
+    const uint32_t trial_blocks = (p.T + 255) / 256;
+    hipLaunchKernelGGL(dc_reduce_kernel, dim3(hist_blocks + trial_blocks), dim3(256), 0, stream, hist_part, p.grid,
+                       p.p2, hist_blocks, hist_total, unit_max, p.T, p.units_per_trial, tau_chunk, kc, trial_cnt,
+                       trial_sum);
+}
+
+void launch_finalize(const Plan& p, unsigned long long* hist_total, unsigned long long* trial_cnt,
+                     unsigned long long* trial_sum, uint32_t kc, uint32_t chunk0, const int64_t* tau_sorted,
+                     const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done, int64_t* chunk_step,
+                     int64_t* chunk_done, hipStream_t stream) {
+    hipLaunchKernelGGL(dc_finalize_kernel, dim3(1), dim3(DC_FINAL_THREADS), 0, stream, hist_total, trial_cnt,
+                       trial_sum, kc, p.p2, chunk0, tau_sorted, pos, p.K, (unsigned long long)p.T,
+                       (unsigned long long)p.elements, (long long)comm, (long long*)out_step, (long long*)out_done,
+                       (long long*)chunk_step, (long long*)chunk_done);
+}
+
+}  // namespace dc
