@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the DropCompute step-time simulator on one MI355X.
+
+One "step" is one whole pass of the hot path over a latency tensor already resident in HBM:
+dc_simulate_async (thresholds sorted, the streaming scan over lat, reductions, finalize), the
+copy of the 2*K result sums to the host, and dc_select_tau.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBPS = 8000.0            # MI355X published HBM3E bandwidth
+METRIC = "worker*microbatch*tau evals/s at N=2048; achieved HBM GB/s vs MI355X peak"
+SCAN_KERNEL = "dc_scan_vec4_kernel"
+
+
+def ensure_built() -> None:
+    import paper_2306_10598_amd as dc
+    from dc_workloads import device as gen_device
+    if not dc.LIB_PATH.exists() or not gen_device._LIB_PATH.exists():
+        import __graft_entry__
+        __graft_entry__.build()
+
+
+def kernel_source_hash() -> str:
+    h = hashlib.sha256()
+    for name in ("dc_kernels.hip", "dc_internal.h", "dc_api.hip"):
+        h.update((ROOT / "paper_2306_10598_amd" / "csrc" / name).read_bytes())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(workload: str):
+    """HBM bytes per launch of the scan kernel from the committed rocprofv3 counter summary,
+    or None when there is none for this workload or the kernel sources changed since."""
+    path = ROOT / "profiles" / f"{SCAN_KERNEL}_{workload}_pmc.txt"
+    if not path.exists():
+        return None
+    fields = {}
+    for line in path.read_text().splitlines():
+        if ":" in line and not line.startswith("#"):
+            k, v = line.split(":", 1)
+            fields[k.strip()] = v.strip()
+    if fields.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    try:
+        return float(fields["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def cpu_baseline(r, taus, target_seconds: float = 12.0):
+    """The CPU oracle, as it stands, on the first trials of the same workload."""
+    import oracle
+    from dc_workloads import host
+    threads = host.cpu_threads()
+    per_trial = r.N * r.M
+    # calibrate on a small slab, then size the sample for about target_seconds
+    t_small = max(threads, min(r.T, (32 << 20) // per_trial))
+    lat = host.generate(r, 0, t_small, threads)
+    t0 = time.perf_counter()
+    oracle.simulate_threaded(lat, taus, r.comm, "sorted", threads)
+    dt = max(time.perf_counter() - t0, 1e-4)
+    trials = int(min(r.T, max(t_small, t_small * target_seconds / dt), (4 << 30) // (4 * per_trial)))
+    lat = host.generate(r, 0, trials, threads)
+    reps, dt = 0, 0.0
+    t0 = time.perf_counter()
+    while dt < target_seconds:                                 # repeat the same sample until the clock is long enough
+        oracle.simulate_threaded(lat, taus, r.comm, "sorted", threads)
+        reps += 1
+        dt = time.perf_counter() - t0
+    sorted_rate = reps * trials * per_trial * taus.size / dt
+    # the literal four-loop form on a slab small enough to finish in a few seconds
+    t_lit = max(1, min(trials, int(2.0e10 // (per_trial * taus.size))))
+    t0 = time.perf_counter()
+    oracle.simulate_threaded(lat[:t_lit], taus, r.comm, "literal", threads)
+    dl = time.perf_counter() - t0
+    return {
+        "value": sorted_rate, "unit": "evals/s", "cores": threads, "kind": "oracle",
+        "sample": f"first {trials} of {r.T} trials of {r.name} (N={r.N}, M={r.M}, K={taus.size}), "
+                  f"sorted-threshold oracle, {reps} passes in {dt:.2f} s; input generation not timed",
+        "literal_value": t_lit * per_trial * taus.size / dl,
+        "literal_sample": f"first {t_lit} trials, four-loop oracle, {dl:.2f} s",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="heterogeneous2048")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain 4 GiB device-to-device copy instead (scale factor for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    ensure_built()
+    import numpy as np
+    import torch
+
+    import paper_2306_10598_amd as dc
+    from dc_workloads import config, device
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.int32, device=dev)          # 4 GiB read + 4 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": 4 << 30, "calibrate_copy_bytes_written": 4 << 30, "copies": 3}))
+        return 0
+    r = config(args.workload)
+
+    lat = device.generate(r)                                   # resident in HBM before timing starts
+    taus = device.tau_grid(r, lat)
+    K = taus.size
+    taus_dev = torch.from_numpy(taus).to(dev)
+    out_step = torch.zeros(K, dtype=torch.int64, device=dev)
+    out_done = torch.zeros(K, dtype=torch.int64, device=dev)
+    host_out = torch.zeros((2, K), dtype=torch.int64).pin_memory()
+    ws = torch.empty(dc.dc_workspace_bytes(r.T, r.N, r.M, K), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+
+    def step():
+        dc.dc_simulate_async(lat, taus_dev, r.comm, out_step, out_done, ws, stream)
+        with torch.cuda.stream(stream):
+            host_out[0].copy_(out_step, non_blocking=True)
+            host_out[1].copy_(out_done, non_blocking=True)
+        stream.synchronize()
+        s, d = host_out[0].numpy(), host_out[1].numpy()
+        return dc.dc_select_tau(s, d, taus, r.T, r.N, r.M, 0)
+
+    dc.dc_set_kernel_timing(True)
+    for _ in range(args.warmup):
+        step()
+    if dc.dc_workspace_status(ws, stream) != dc.DC_OK:
+        print("device reported a value error", file=sys.stderr)
+        return 1
+    scan_ms = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        thr, _, best = step()
+        scan_ms.append(dc.dc_last_kernel_ms()[0])              # HIP events on the stream the kernel ran on
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dc.dc_set_kernel_timing(False)
+
+    ms_per_step = 1e3 * wall / args.steps
+    evals = float(r.elements) * K
+    scan_avg_ms = float(np.mean(scan_ms))
+    algo_bytes = 4.0 * r.elements                              # every latency read once, nothing written back
+    achieved = algo_bytes / (scan_avg_ms * 1e-3) / 1e9
+    line = {
+        "metric": METRIC, "value": evals / (wall / args.steps), "unit": "evals/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"{r.name}: T={r.T} N={r.N} M={r.M} K={K} comm={r.comm}us, {r.description}",
+                   "tensor_bytes": r.nbytes, "best_tau_us": int(taus[best]), "best_thr_per_us": float(thr[best])},
+        "roofline": {"bound": "hbm", "kernel": SCAN_KERNEL, "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": recorded_traffic(r.name),
+                     "kernel_ms": scan_avg_ms, "kernel_ms_min": float(np.min(scan_ms)),
+                     "algorithmic_bytes": algo_bytes},
+    }
+    if not args.no_cpu_baseline:
+        del lat
+        torch.cuda.empty_cache()
+        line["cpu_baseline"] = cpu_baseline(r, taus)
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
