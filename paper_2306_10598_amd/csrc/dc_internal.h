@@ -8,6 +8,8 @@
 
 #define DC_SCAN_THREADS 256
 #define DC_SCAN_WAVES (DC_SCAN_THREADS / 64)
+#define DC_SCAN_UNROLL 4                // 16-byte loads in flight per lane in the streaming kernel
+#define DC_REDUCE_SLOTS 64u             // per-block histograms added by one block of the reduce kernel
 #define DC_FINAL_THREADS 1024
 #define DC_MAX_SCAN_BLOCKS 2048u       // 256 compute units x 8 resident blocks
 #define DC_CHUNK_THRESHOLDS 4095u      // thresholds handled by one pass over lat (LDS-resident grid)

@@ -120,25 +120,25 @@ __device__ __forceinline__ void drain(WaveState& st, uint4* queue, const uint32_
     st.q_count -= n;
 }
 
-// One 16-byte load per lane: four consecutive latencies of one worker.  Lanes of a worker are
-// L consecutive lanes, so the wave holds 64/L whole rows.
+// One 16-byte load per lane holds four consecutive latencies of one worker; the lanes of a
+// worker are L consecutive lanes, so a wave holds 64/L whole rows.  Completion time of the lane's
+// last element:
 template <int L>
-__device__ __forceinline__ void process_load(WaveState& st, u32x4 x, bool valid, uint32_t tau0,
-                                             uint4* queue, const uint32_t* tau_s, uint32_t* hist,
-                                             uint32_t p2, uint32_t lane) {
-    st.check = umax(st.check, umax(umax(x.x, x.y), umax(x.z, x.w)));
-    const uint32_t p0 = x.x, p1 = p0 + x.y, p2v = p1 + x.z, p3 = p2v + x.w;
-    const uint32_t incl = segmented_inclusive_scan<L>(p3, lane);   // completion time of the lane's last element
-    st.lane_max = umax(st.lane_max, incl);
-    const bool active = valid && incl >= tau0;                      // some element of the lane reaches the grid
+__device__ __forceinline__ uint32_t lane_completion_time(u32x4 x, uint32_t lane) {
+    return segmented_inclusive_scan<L>(x.x + x.y + x.z + x.w, lane);
+}
+
+// Lanes whose last completion time reaches the smallest threshold put their four completion
+// times into the wave's queue (compaction: the histogram work is done 64 items at a time).
+__device__ __forceinline__ void enqueue_active(WaveState& st, u32x4 x, uint32_t incl, bool active, uint4* queue,
+                                               const uint32_t* tau_s, uint32_t* hist, uint32_t p2, uint32_t lane) {
     const uint64_t mask = __ballot(active);
     if (mask) {
         if (active) {
-            const uint32_t before = incl - p3;                      // completion time before the lane's first element
             const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
                                       __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-            queue[(st.q_head + st.q_count + rank) & (QUEUE_ITEMS - 1)] =
-                make_uint4(before + p0, before + p1, before + p2v, incl);
+            const uint32_t c2 = incl - x.w, c1 = c2 - x.z, c0 = c1 - x.y;
+            queue[(st.q_head + st.q_count + rank) & (QUEUE_ITEMS - 1)] = make_uint4(c0, c1, c2, incl);
         }
         st.q_count += (uint32_t)__popcll(mask);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -146,26 +146,61 @@ __device__ __forceinline__ void process_load(WaveState& st, u32x4 x, bool valid,
     }
 }
 
+template <int L, int U>
+__device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U], uint32_t tau0, uint4* queue,
+                                              const uint32_t* tau_s, uint32_t* hist, uint32_t p2, uint32_t lane) {
+    uint32_t incl[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) incl[k] = lane_completion_time<L>(x[k], lane);   // independent scans interleave
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+        st.check = umax(st.check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
+        st.lane_max = umax(st.lane_max, incl[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) enqueue_active(st, x[k], incl[k], incl[k] >= tau0, queue, tau_s, hist, p2, lane);
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
 // dc_prep_kernel: rank-sort the thresholds, clamp, validate, clear accumulators
 // ---------------------------------------------------------------------------------------------
-__global__ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
-                               int64_t* __restrict__ tau_sorted, uint32_t* __restrict__ tau_u32,
-                               uint32_t* __restrict__ pos, uint32_t* __restrict__ status,
-                               unsigned long long* __restrict__ bins, uint32_t bins_words) {
-    const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+__global__ __launch_bounds__(256)
+void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
+                    int64_t* __restrict__ tau_sorted, uint32_t* __restrict__ tau_u32,
+                    uint32_t* __restrict__ pos, uint32_t* __restrict__ status,
+                    unsigned long long* __restrict__ bins, uint32_t bins_words) {
+    // A block ranks 32 thresholds; the comparisons of each are split over 8 threads.
+    constexpr uint32_t TILE = 1024;
+    __shared__ int64_t tile[TILE];
+    __shared__ uint32_t partial[8][32];
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
     const uint32_t stride = gridDim.x * blockDim.x;
-    if (j == 0) *status = 0u;                     // kernels that set flags run later on the stream
-    for (uint32_t i = j; i < bins_words; i += stride) bins[i] = 0ull;
-    if (j >= K) return;
-    const int64_t mine = taus[j];
+    if (gid == 0) *status = 0u;                   // kernels that set flags run later on the stream
+    for (uint32_t i = gid; i < bins_words; i += stride) bins[i] = 0ull;
+    const uint32_t jj = threadIdx.x & 31u, part = threadIdx.x >> 5;
+    const uint32_t j = blockIdx.x * 32 + jj;
+    const int64_t mine = j < K ? taus[j] : 0;
+    // position in ascending order = number of thresholds that sort before mine (ties by index)
     uint32_t rank = 0;
-    for (uint32_t i = 0; i < K; ++i) {
-        const int64_t other = taus[i];
-        rank += (other < mine) || (other == mine && i < j);
+    for (uint32_t base = 0; base < K; base += TILE) {
+        const uint32_t n = K - base < TILE ? K - base : TILE;
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) tile[i] = taus[base + i];
+        __syncthreads();
+#pragma unroll 8
+        for (uint32_t i = part; i < n; i += 8) {
+            const int64_t other = tile[i];
+            rank += (other < mine) || (other == mine && base + i < j);
+        }
     }
+    partial[part][jj] = rank;
+    __syncthreads();
+    if (part != 0 || j >= K) return;
+    rank = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) rank += partial[q][jj];
     pos[j] = rank;
     tau_sorted[rank] = mine;
     tau_u32[rank] = mine >= (int64_t)DC_TAU_CLAMP ? DC_TAU_CLAMP : (mine < 0 ? 0u : (uint32_t)mine);
@@ -198,8 +233,9 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
 
     constexpr uint32_t R = 64 / L;                 // rows per load
     constexpr uint32_t M = 4 * L;
+    constexpr int U = DC_SCAN_UNROLL;              // loads in flight per lane
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction
     uint4* queue = queue_all + wave * QUEUE_ITEMS;
     const uint32_t tau0 = tau_s[0];
     const uint32_t total_waves = gridDim.x * DC_SCAN_WAVES;
@@ -217,25 +253,24 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
         st.lane_max = 0u;
 
         uint32_t i = 0;
-        for (; i + 4 <= nfull; i += 4) {
-            const u32x4 x0 = __builtin_nontemporal_load(base + (uint64_t)(i + 0) * 64);
-            const u32x4 x1 = __builtin_nontemporal_load(base + (uint64_t)(i + 1) * 64);
-            const u32x4 x2 = __builtin_nontemporal_load(base + (uint64_t)(i + 2) * 64);
-            const u32x4 x3 = __builtin_nontemporal_load(base + (uint64_t)(i + 3) * 64);
-            process_load<L>(st, x0, true, tau0, queue, tau_s, hist, p2, lane);
-            process_load<L>(st, x1, true, tau0, queue, tau_s, hist, p2, lane);
-            process_load<L>(st, x2, true, tau0, queue, tau_s, hist, p2, lane);
-            process_load<L>(st, x3, true, tau0, queue, tau_s, hist, p2, lane);
+        for (; i + U <= nfull; i += U) {
+            u32x4 x[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) x[k] = __builtin_nontemporal_load(base + (uint64_t)(i + k) * 64);
+            process_loads<L, U>(st, x, tau0, queue, tau_s, hist, p2, lane);
         }
         for (; i < nfull; ++i) {
-            const u32x4 x = __builtin_nontemporal_load(base + (uint64_t)i * 64);
-            process_load<L>(st, x, true, tau0, queue, tau_s, hist, p2, lane);
+            const u32x4 x[1] = {__builtin_nontemporal_load(base + (uint64_t)i * 64)};
+            process_loads<L, 1>(st, x, tau0, queue, tau_s, hist, p2, lane);
         }
         if (tail_rows) {                            // last, partial load of the trial: rows beyond N belong to the next trial
             const bool valid = lane < tail_rows * L;
             u32x4 x = {0u, 0u, 0u, 0u};
             if (valid) x = __builtin_nontemporal_load(base + (uint64_t)nfull * 64);
-            process_load<L>(st, x, valid, tau0, queue, tau_s, hist, p2, lane);
+            const uint32_t incl = lane_completion_time<L>(x, lane);
+            st.check = umax(st.check, umax(umax(x.x, x.y), umax(x.z, x.w)));
+            st.lane_max = umax(st.lane_max, incl);
+            enqueue_active(st, x, incl, valid && incl >= tau0, queue, tau_s, hist, p2, lane);
         }
         const uint32_t m = wave_max(st.lane_max);
         if (lane == 0) unit_max[u] = m;
@@ -311,41 +346,63 @@ void dc_scan_generic_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_
 
 // ---------------------------------------------------------------------------------------------
 // dc_reduce_kernel: (a) column sums of the per-block histograms, (b) per-trial maximum binned
-// over the chunk's thresholds.  Blocks [0, hist_blocks) do (a); the rest do (b).
+// over the chunk's thresholds.  Blocks [0, hist_blocks) do (a): block (c, g) adds slots
+// [g*DC_REDUCE_SLOTS, ...) of columns [64c, 64c+64) and adds its partial sums to hist_total
+// (cleared beforehand).  The remaining blocks do (b), one thread per trial.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256)
-void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t slots, uint32_t p2, uint32_t hist_blocks,
-                      unsigned long long* __restrict__ hist_total,
+void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t slots, uint32_t p2, uint32_t col_blocks,
+                      uint32_t hist_blocks, unsigned long long* __restrict__ hist_total,
                       const uint32_t* __restrict__ unit_max, uint32_t T, uint32_t units_per_trial,
                       const uint32_t* __restrict__ tau_chunk, uint32_t kc,
                       unsigned long long* __restrict__ trial_cnt, unsigned long long* __restrict__ trial_sum) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t grp = threadIdx.x >> 6;
     if (blockIdx.x < hist_blocks) {
-        // 64 columns per block, 4 row groups; consecutive threads read consecutive columns
         __shared__ unsigned long long part[4][64];
-        const uint32_t col = blockIdx.x * 64 + (threadIdx.x & 63u);
-        const uint32_t grp = threadIdx.x >> 6;
+        const uint32_t col = (blockIdx.x % col_blocks) * 64 + lane;       // consecutive lanes, consecutive columns
+        const uint32_t s0 = (blockIdx.x / col_blocks) * DC_REDUCE_SLOTS;
+        const uint32_t s1 = s0 + DC_REDUCE_SLOTS < slots ? s0 + DC_REDUCE_SLOTS : slots;
         unsigned long long acc = 0ull;
         if (col < p2)
-            for (uint32_t s = grp; s < slots; s += 4) acc += hist_part[(uint64_t)s * p2 + col];
-        part[grp][threadIdx.x & 63u] = acc;
+            for (uint32_t s = s0 + grp; s < s1; s += 4) acc += hist_part[(uint64_t)s * p2 + col];
+        part[grp][lane] = acc;
         __syncthreads();
-        if (grp == 0 && col < p2)
-            hist_total[col] = part[0][threadIdx.x] + part[1][threadIdx.x] + part[2][threadIdx.x] + part[3][threadIdx.x];
+        if (grp == 0 && col < p2) {
+            const unsigned long long sum = part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane];
+            if (sum) atomicAdd(&hist_total[col], sum);
+        }
         return;
     }
+    // (b) one thread per trial
     const uint32_t t = (blockIdx.x - hist_blocks) * 256 + threadIdx.x;
-    if (t >= T) return;
-    const uint32_t* um = unit_max + (uint64_t)t * units_per_trial;
+    const bool live = t < T;
     uint32_t tmax = 0u;
-    for (uint32_t j = 0; j < units_per_trial; ++j) tmax = umax(tmax, um[j]);
+    if (live) {
+        const uint32_t* um = unit_max + (uint64_t)t * units_per_trial;
+        for (uint32_t j = 0; j < units_per_trial; ++j) tmax = umax(tmax, um[j]);
+    }
     // b = #{i < kc : tau_i <= tmax}; the trial's step time is tmax for thresholds i >= b, tau_i below
     uint32_t lo = 0, hi = kc;
     while (lo < hi) {
         const uint32_t mid = (lo + hi) >> 1;
         if (tau_chunk[mid] <= tmax) lo = mid + 1; else hi = mid;
     }
-    atomicAdd(&trial_cnt[lo], 1ull);
-    atomicAdd(&trial_sum[lo], (unsigned long long)tmax);
+    // Trial maxima of one workload crowd into a few bins: when a whole wave agrees on the bin,
+    // it adds once instead of 64 times to the same address.
+    const uint32_t first = __builtin_amdgcn_readfirstlane(lo);
+    if (__all(live && lo == first)) {
+        unsigned long long sum = tmax;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
+        if (lane == 0) {
+            atomicAdd(&trial_cnt[first], 64ull);
+            atomicAdd(&trial_sum[first], sum);
+        }
+    } else if (live) {
+        atomicAdd(&trial_cnt[lo], 1ull);
+        atomicAdd(&trial_sum[lo], (unsigned long long)tmax);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -423,10 +480,8 @@ namespace dc {
 
 void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t* tau_u32, uint32_t* pos,
                  uint32_t* status, unsigned long long* bins, uint32_t bins_words, hipStream_t stream) {
-    const uint32_t threads = 256;
-    uint32_t blocks = (K + threads - 1) / threads;
-    const uint32_t need = (bins_words + threads - 1) / threads;
-    if (blocks < need) blocks = need > 64 ? 64 : need;
+    const uint32_t threads = 256;                 // 32 thresholds per block
+    uint32_t blocks = (K + 31) / 32;
     if (blocks == 0) blocks = 1;
     hipLaunchKernelGGL(dc_prep_kernel, dim3(blocks), dim3(threads), 0, stream, taus, K, tau_sorted, tau_u32, pos,
                        status, bins, bins_words);
@@ -467,11 +522,13 @@ void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, u
 void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long* hist_total,
                    const uint32_t* unit_max, const uint32_t* tau_chunk, uint32_t kc,
                    unsigned long long* trial_cnt, unsigned long long* trial_sum, hipStream_t stream) {
-    const uint32_t hist_blocks = (p.p2 + 63) / 64;
+    const uint32_t col_blocks = (p.p2 + 63) / 64;
+    const uint32_t slot_groups = (p.grid + DC_REDUCE_SLOTS - 1) / DC_REDUCE_SLOTS;
+    const uint32_t hist_blocks = col_blocks * slot_groups;
     const uint32_t trial_blocks = (p.T + 255) / 256;
     hipLaunchKernelGGL(dc_reduce_kernel, dim3(hist_blocks + trial_blocks), dim3(256), 0, stream, hist_part, p.grid,
-                       p.p2, hist_blocks, hist_total, unit_max, p.T, p.units_per_trial, tau_chunk, kc, trial_cnt,
-                       trial_sum);
+                       p.p2, col_blocks, hist_blocks, hist_total, unit_max, p.T, p.units_per_trial, tau_chunk, kc,
+                       trial_cnt, trial_sum);
 }
 
 void launch_finalize(const Plan& p, unsigned long long* hist_total, unsigned long long* trial_cnt,
