@@ -53,7 +53,7 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     if (p.vec4) {
         const uint64_t rows_per_load = 64 / (M / 4);
         const uint64_t loads_per_trial = ((uint64_t)N + rows_per_load - 1) / rows_per_load;
-        p.per_unit = 64;                                          // 64 KiB of contiguous rows
+        p.per_unit = DC_UNIT_LOADS;                               // 64 KiB of contiguous rows
         upt = (loads_per_trial + p.per_unit - 1) / p.per_unit;
     } else {
         uint64_t rows = 16384 / (4 * (uint64_t)M);                // about 16 KiB per unit

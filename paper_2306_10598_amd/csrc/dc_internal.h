@@ -6,12 +6,25 @@
 #include <stddef.h>
 #include <stdint.h>
 
+// Tuning knobs of the streaming kernel (overridable at build time with -D).
+#ifndef DC_SCAN_THREADS
 #define DC_SCAN_THREADS 256
+#endif
+#ifndef DC_SCAN_UNROLL
+#define DC_SCAN_UNROLL 4                // 16-byte loads in flight per lane
+#endif
+#ifndef DC_SCAN_PREFETCH
+#define DC_SCAN_PREFETCH 0               // 1: issue the next group of loads before processing the current one
+#endif
+#ifndef DC_MAX_SCAN_BLOCKS
+#define DC_MAX_SCAN_BLOCKS 2048u        // 256 compute units x 8 resident blocks
+#endif
+#ifndef DC_UNIT_LOADS
+#define DC_UNIT_LOADS 64u               // 1 KiB loads per work unit (64 KiB of contiguous rows)
+#endif
 #define DC_SCAN_WAVES (DC_SCAN_THREADS / 64)
-#define DC_SCAN_UNROLL 4                // 16-byte loads in flight per lane in the streaming kernel
 #define DC_REDUCE_SLOTS 64u             // per-block histograms added by one block of the reduce kernel
 #define DC_FINAL_THREADS 1024
-#define DC_MAX_SCAN_BLOCKS 2048u       // 256 compute units x 8 resident blocks
 #define DC_CHUNK_THRESHOLDS 4095u      // thresholds handled by one pass over lat (LDS-resident grid)
 #define DC_TAU_CLAMP 0x80000000u       // thresholds at or above 2^31 exceed every completion time
 

@@ -81,15 +81,43 @@ __device__ __forceinline__ uint32_t bin_of(const uint32_t* a, uint32_t p2, uint3
     return b;
 }
 
-// Four values at once (independent searches interleaved to overlap the LDS reads).
-__device__ __forceinline__ void bin_of4(const uint32_t* a, uint32_t p2, uint4 v, uint32_t (&b)[4]) {
-    b[0] = b[1] = b[2] = b[3] = 0;
-    for (uint32_t s = p2 >> 1; s >= 1; s >>= 1) {
-        const uint32_t a0 = a[b[0] + s - 1], a1 = a[b[1] + s - 1], a2 = a[b[2] + s - 1], a3 = a[b[3] + s - 1];
-        if (a0 <= v.x) b[0] += s;
-        if (a1 <= v.y) b[1] += s;
-        if (a2 <= v.z) b[2] += s;
-        if (a3 <= v.w) b[3] += s;
+// The threshold grid of one pass as the streaming kernel sees it, all in LDS:
+//   tau[p2]     ascending thresholds, padded with 0xFFFFFFFF
+//   lut[p2+1]   lut[c] = #{k : tau_k < tau0 + c*2^shift}: uniform cells over [tau0, tau_last], so that a
+//               completion time v in cell c has its bin in [lut[c], lut[c+1]] (a short search;
+//               one step or none when the thresholds are evenly spaced)
+//   hist[p2]    bin counts of the block
+struct GridView {
+    const uint32_t* tau;
+    const uint32_t* lut;
+    uint32_t* hist;
+    uint32_t p2;
+    uint32_t shift;
+    uint32_t tau0;
+};
+
+// Bins b(v) = #{k : tau_k <= v} of four values at once (the searches interleave their LDS reads).
+__device__ __forceinline__ void bins_of4(const GridView& g, uint4 v, uint32_t (&lo)[4]) {
+    const uint32_t val[4] = {v.x, v.y, v.z, v.w};
+    uint32_t hi[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t c = (val[i] - g.tau0) >> g.shift;
+        c = c < g.p2 - 1 ? c : g.p2 - 1;
+        lo[i] = g.lut[c];
+        hi[i] = g.lut[c + 1];
+        if (val[i] < g.tau0) lo[i] = hi[i] = 0u;               // below every threshold
+    }
+    while ((lo[0] < hi[0]) | (lo[1] < hi[1]) | (lo[2] < hi[2]) | (lo[3] < hi[3])) {
+        uint32_t t[4], mid[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { mid[i] = (lo[i] + hi[i]) >> 1; t[i] = g.tau[mid[i]]; }   // mid <= p2-1
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool open = lo[i] < hi[i], right = t[i] <= val[i];
+            lo[i] = open && right ? mid[i] + 1 : lo[i];
+            hi[i] = open && !right ? mid[i] : hi[i];
+        }
     }
 }
 
@@ -105,16 +133,15 @@ constexpr uint32_t QUEUE_ITEMS = 128;   // per wave; a push adds at most 64, a d
 
 // Take up to 64 queued items (one per lane), bin their four completion times, add to the
 // block histogram.  Bin 0 (below every threshold) is never needed and is skipped.
-__device__ __forceinline__ void drain(WaveState& st, uint4* queue, const uint32_t* tau_s, uint32_t* hist,
-                                      uint32_t p2, uint32_t lane) {
+__device__ __forceinline__ void drain(WaveState& st, uint4* queue, const GridView& g, uint32_t lane) {
     const uint32_t n = st.q_count < 64u ? st.q_count : 64u;
     if (lane < n) {
         const uint4 item = queue[(st.q_head + lane) & (QUEUE_ITEMS - 1)];
         uint32_t b[4];
-        bin_of4(tau_s, p2, item, b);
+        bins_of4(g, item, b);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (b[i]) atomicAdd(&hist[b[i]], 1u);
+            if (b[i]) atomicAdd(&g.hist[b[i]], 1u);
     }
     st.q_head = (st.q_head + n) & (QUEUE_ITEMS - 1);
     st.q_count -= n;
@@ -131,7 +158,7 @@ __device__ __forceinline__ uint32_t lane_completion_time(u32x4 x, uint32_t lane)
 // Lanes whose last completion time reaches the smallest threshold put their four completion
 // times into the wave's queue (compaction: the histogram work is done 64 items at a time).
 __device__ __forceinline__ void enqueue_active(WaveState& st, u32x4 x, uint32_t incl, bool active, uint4* queue,
-                                               const uint32_t* tau_s, uint32_t* hist, uint32_t p2, uint32_t lane) {
+                                               const GridView& g, uint32_t lane) {
     const uint64_t mask = __ballot(active);
     if (mask) {
         if (active) {
@@ -142,13 +169,13 @@ __device__ __forceinline__ void enqueue_active(WaveState& st, u32x4 x, uint32_t 
         }
         st.q_count += (uint32_t)__popcll(mask);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        if (st.q_count >= 64u) drain(st, queue, tau_s, hist, p2, lane);
+        if (st.q_count >= 64u) drain(st, queue, g, lane);
     }
 }
 
 template <int L, int U>
-__device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U], uint32_t tau0, uint4* queue,
-                                              const uint32_t* tau_s, uint32_t* hist, uint32_t p2, uint32_t lane) {
+__device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U], uint4* queue, const GridView& g,
+                                              uint32_t lane) {
     uint32_t incl[U];
 #pragma unroll
     for (int k = 0; k < U; ++k) incl[k] = lane_completion_time<L>(x[k], lane);   // independent scans interleave
@@ -158,7 +185,7 @@ __device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U]
         st.lane_max = umax(st.lane_max, incl[k]);
     }
 #pragma unroll
-    for (int k = 0; k < U; ++k) enqueue_active(st, x[k], incl[k], incl[k] >= tau0, queue, tau_s, hist, p2, lane);
+    for (int k = 0; k < U; ++k) enqueue_active(st, x[k], incl[k], incl[k] >= g.tau0, queue, g, lane);
 }
 
 }  // namespace
@@ -224,12 +251,28 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
     uint32_t* tau_s = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);  // [p2]
     uint32_t* hist = tau_s + p2;                                                        // [p2]
+    uint32_t* lut = hist + p2;                                                          // [p2 + 1]
 
     for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) {
         tau_s[i] = i < kc ? tau_chunk[i] : 0xFFFFFFFFu;
         hist[i] = 0u;
     }
     __syncthreads();
+    // uniform cells of width 2^shift from the smallest threshold; the largest lands in a cell < p2-1
+    const uint32_t tau_first = tau_s[0], tau_last = tau_s[kc - 1];
+    uint32_t shift = 0;
+    while (((uint64_t)(tau_last - tau_first) >> shift) >= p2 - 1) ++shift;
+    for (uint32_t c = threadIdx.x; c <= p2; c += DC_SCAN_THREADS) {
+        const uint64_t edge = (uint64_t)tau_first + ((uint64_t)c << shift);
+        uint32_t lo = 0, hi = kc;                              // #{k : tau_k < edge}
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if ((uint64_t)tau_s[mid] < edge) lo = mid + 1; else hi = mid;
+        }
+        lut[c] = lo;
+    }
+    __syncthreads();
+    const GridView g{tau_s, lut, hist, p2, shift, tau_first};
 
     constexpr uint32_t R = 64 / L;                 // rows per load
     constexpr uint32_t M = 4 * L;
@@ -237,7 +280,6 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction
     uint4* queue = queue_all + wave * QUEUE_ITEMS;
-    const uint32_t tau0 = tau_s[0];
     const uint32_t total_waves = gridDim.x * DC_SCAN_WAVES;
 
     WaveState st{0u, 0u, 0u, 0u};
@@ -253,15 +295,34 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
         st.lane_max = 0u;
 
         uint32_t i = 0;
+#if DC_SCAN_PREFETCH
+        // software pipeline: the next group's loads are issued before the current group is processed
+        if (nfull >= (uint32_t)U) {
+            u32x4 cur[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) cur[k] = __builtin_nontemporal_load(base + (uint64_t)k * 64);
+            for (; i + 2 * U <= nfull; i += U) {
+                u32x4 nxt[U];
+#pragma unroll
+                for (int k = 0; k < U; ++k) nxt[k] = __builtin_nontemporal_load(base + (uint64_t)(i + U + k) * 64);
+                process_loads<L, U>(st, cur, queue, g, lane);
+#pragma unroll
+                for (int k = 0; k < U; ++k) cur[k] = nxt[k];
+            }
+            process_loads<L, U>(st, cur, queue, g, lane);
+            i += U;
+        }
+#else
         for (; i + U <= nfull; i += U) {
             u32x4 x[U];
 #pragma unroll
             for (int k = 0; k < U; ++k) x[k] = __builtin_nontemporal_load(base + (uint64_t)(i + k) * 64);
-            process_loads<L, U>(st, x, tau0, queue, tau_s, hist, p2, lane);
+            process_loads<L, U>(st, x, queue, g, lane);
         }
+#endif
         for (; i < nfull; ++i) {
             const u32x4 x[1] = {__builtin_nontemporal_load(base + (uint64_t)i * 64)};
-            process_loads<L, 1>(st, x, tau0, queue, tau_s, hist, p2, lane);
+            process_loads<L, 1>(st, x, queue, g, lane);
         }
         if (tail_rows) {                            // last, partial load of the trial: rows beyond N belong to the next trial
             const bool valid = lane < tail_rows * L;
@@ -270,12 +331,12 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
             const uint32_t incl = lane_completion_time<L>(x, lane);
             st.check = umax(st.check, umax(umax(x.x, x.y), umax(x.z, x.w)));
             st.lane_max = umax(st.lane_max, incl);
-            enqueue_active(st, x, incl, valid && incl >= tau0, queue, tau_s, hist, p2, lane);
+            enqueue_active(st, x, incl, valid && incl >= g.tau0, queue, g, lane);
         }
         const uint32_t m = wave_max(st.lane_max);
         if (lane == 0) unit_max[u] = m;
     }
-    while (st.q_count) drain(st, queue, tau_s, hist, p2, lane);
+    while (st.q_count) drain(st, queue, g, lane);
 
     const uint32_t worst = wave_max(st.check);
     if (lane == 0 && worst > max_latency)
@@ -488,8 +549,9 @@ void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t*
 }
 
 size_t scan_lds_bytes(const Plan& p) {
-    const size_t tables = (size_t)p.p2 * 8;
-    return p.vec4 ? tables + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4) : tables;
+    const size_t tables = (size_t)p.p2 * 8;                       // thresholds + histogram
+    if (!p.vec4) return tables;
+    return tables + ((size_t)p.p2 + 1) * 4 + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);   // + cells + queues
 }
 
 template <int L>
