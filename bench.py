@@ -134,9 +134,10 @@ def main() -> int:
     taus = device.tau_grid(r, lat)
     K = taus.size
     taus_dev = torch.from_numpy(taus).to(dev)
-    out_step = torch.zeros(K, dtype=torch.int64, device=dev)
-    out_done = torch.zeros(K, dtype=torch.int64, device=dev)
+    out = torch.zeros((2, K), dtype=torch.int64, device=dev)     # out_step, out_done: one buffer, one copy back
+    out_step, out_done = out[0], out[1]
     host_out = torch.zeros((2, K), dtype=torch.int64).pin_memory()
+    host_step, host_done = host_out[0].numpy(), host_out[1].numpy()
     ws = torch.empty(dc.dc_workspace_bytes(r.T, r.N, r.M, K), dtype=torch.uint8, device=dev)
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
@@ -144,11 +145,9 @@ def main() -> int:
     def step():
         dc.dc_simulate_async(lat, taus_dev, r.comm, out_step, out_done, ws, stream)
         with torch.cuda.stream(stream):
-            host_out[0].copy_(out_step, non_blocking=True)
-            host_out[1].copy_(out_done, non_blocking=True)
+            host_out.copy_(out, non_blocking=True)
         stream.synchronize()
-        s, d = host_out[0].numpy(), host_out[1].numpy()
-        return dc.dc_select_tau(s, d, taus, r.T, r.N, r.M, 0)
+        return dc.dc_select_tau(host_step, host_done, taus, r.T, r.N, r.M, 0)
 
     dc.dc_set_kernel_timing(True)
     for _ in range(args.warmup):

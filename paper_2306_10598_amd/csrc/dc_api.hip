@@ -29,8 +29,8 @@ int device_error(hipError_t e, const char* what, int status = DC_ERR_DEVICE) {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-uint32_t next_pow2_above(uint32_t n) {   // smallest power of two > n
-    uint32_t p = 2;
+uint32_t next_pow2_above(uint32_t n) {   // smallest power of two > n, at least 4 (the lookup cells need p2 - 2 >= 2)
+    uint32_t p = 4;
     while (p <= n) p <<= 1;
     return p;
 }
@@ -110,9 +110,34 @@ int ensure_events(size_t pairs) {
     return DC_OK;
 }
 
+// ---- grid size of the streaming kernel --------------------------------------------------------------
+// The kernel splits the work statically over its waves, so every block must be resident at once (a
+// block that waits for a free slot would run alone at the end), and the same number of blocks must
+// sit on every compute unit.  Queried once per (device, kernel variant, LDS size).
+struct ResidentKey { int device; bool vec4; uint32_t M; uint32_t p2; int blocks; };
+std::vector<ResidentKey> g_resident;
+
+uint32_t resident_blocks(const dc::Plan& p) {
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return DC_MAX_SCAN_BLOCKS;
+    for (const ResidentKey& k : g_resident)
+        if (k.device == device && k.vec4 == p.vec4 && k.M == (p.vec4 ? p.M : 0) && k.p2 == p.p2) return (uint32_t)k.blocks;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1) cus = 256;
+    int per_cu = dc::scan_blocks_per_cu(p);                    // what fits
+    if (per_cu < 1) per_cu = 1;
+    if (per_cu > (int)DC_SCAN_BLOCKS_PER_CU) per_cu = DC_SCAN_BLOCKS_PER_CU;   // what streams best
+    const int blocks = cus * per_cu;
+    g_resident.push_back({device, p.vec4, p.vec4 ? p.M : 0, p.p2, blocks});
+    return (uint32_t)blocks;
+}
+
 // ---- the enqueued sequence ---------------------------------------------------------------------
-int enqueue(const dc::Plan& p, const int32_t* lat, const int64_t* taus_dev, int64_t comm, int64_t* out_step_dev,
+int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, int64_t comm, int64_t* out_step_dev,
             int64_t* out_done_dev, unsigned char* ws, hipStream_t stream, bool timed) {
+    dc::Plan p = plan;
+    const uint32_t resident = resident_blocks(p);
+    if (p.grid > resident) p.grid = resident;                   // the workspace was sized for the larger grid
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + p.off_status);
     int64_t* tau_sorted = reinterpret_cast<int64_t*>(ws + p.off_tau_sorted);
     uint32_t* tau_u32 = reinterpret_cast<uint32_t*>(ws + p.off_tau_u32);

@@ -11,13 +11,16 @@
 #define DC_SCAN_THREADS 256
 #endif
 #ifndef DC_SCAN_UNROLL
-#define DC_SCAN_UNROLL 4                // 16-byte loads in flight per lane
+#define DC_SCAN_UNROLL 8                // 16-byte loads in flight per lane
 #endif
 #ifndef DC_SCAN_PREFETCH
 #define DC_SCAN_PREFETCH 0               // 1: issue the next group of loads before processing the current one
 #endif
+#ifndef DC_SCAN_BLOCKS_PER_CU
+#define DC_SCAN_BLOCKS_PER_CU 2u        // measured best on MI355X: 8 waves per compute unit, 8 loads in flight each
+#endif
 #ifndef DC_MAX_SCAN_BLOCKS
-#define DC_MAX_SCAN_BLOCKS 2048u        // 256 compute units x 8 resident blocks
+#define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
 #endif
 #ifndef DC_UNIT_LOADS
 #define DC_UNIT_LOADS 64u               // 1 KiB loads per work unit (64 KiB of contiguous rows)
@@ -64,6 +67,7 @@ void launch_finalize(const Plan& p, unsigned long long* hist_total, unsigned lon
                      const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done, int64_t* chunk_step,
                      int64_t* chunk_done, hipStream_t stream);
 size_t scan_lds_bytes(const Plan& p);
+int scan_blocks_per_cu(const Plan& p);
 
 }  // namespace dc
 #endif

@@ -61,16 +61,19 @@ __device__ __forceinline__ uint32_t segmented_inclusive_scan(uint32_t v, uint32_
     return v;
 }
 
-__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        uint32_t o = (uint32_t)__shfl_xor((int)v, d, 64);
-        v = o > v ? o : v;
-    }
-    return v;
-}
-
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// Maximum over the 64 lanes, returned in every lane: a running maximum with the scan's DPP
+// steps (0 is the identity of an unsigned maximum), then lane 63 holds the result.
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
+    v = umax(v, dpp_or_zero<DPP_ROW_SHR + 1, 0xf>(v));
+    v = umax(v, dpp_or_zero<DPP_ROW_SHR + 2, 0xf>(v));
+    v = umax(v, dpp_or_zero<DPP_ROW_SHR + 4, 0xf>(v));
+    v = umax(v, dpp_or_zero<DPP_ROW_SHR + 8, 0xf>(v));
+    v = umax(v, dpp_or_zero<DPP_ROW_BCAST15, 0xa>(v));
+    v = umax(v, dpp_or_zero<DPP_ROW_BCAST31, 0xc>(v));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
 
 // b(v) = #{i < n : a[i] <= v} for ascending a[0..p2-2], padded with 0xFFFFFFFF beyond the
 // real thresholds; p2 is a power of two.  Result is in [0, p2-1] for every v.
@@ -83,9 +86,9 @@ __device__ __forceinline__ uint32_t bin_of(const uint32_t* a, uint32_t p2, uint3
 
 // The threshold grid of one pass as the streaming kernel sees it, all in LDS:
 //   tau[p2]     ascending thresholds, padded with 0xFFFFFFFF
-//   lut[p2+1]   lut[c] = #{k : tau_k < tau0 + c*2^shift}: uniform cells over [tau0, tau_last], so that a
-//               completion time v in cell c has its bin in [lut[c], lut[c+1]] (a short search;
-//               one step or none when the thresholds are evenly spaced)
+//   lut[p2]     lut[c] = #{k : tau_k < tau0 + c*2^shift}: p2-1 uniform cells from tau0 on, the last one
+//               open-ended and beyond tau_last, so that a completion time v in cell c has its bin in
+//               [lut[c], lut[c+1]] (a short search; one step or none for evenly spaced thresholds)
 //   hist[p2]    bin counts of the block
 struct GridView {
     const uint32_t* tau;
@@ -103,7 +106,7 @@ __device__ __forceinline__ void bins_of4(const GridView& g, uint4 v, uint32_t (&
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         uint32_t c = (val[i] - g.tau0) >> g.shift;
-        c = c < g.p2 - 1 ? c : g.p2 - 1;
+        c = c < g.p2 - 2 ? c : g.p2 - 2;
         lo[i] = g.lut[c];
         hi[i] = g.lut[c + 1];
         if (val[i] < g.tau0) lo[i] = hi[i] = 0u;               // below every threshold
@@ -251,18 +254,18 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
     uint32_t* tau_s = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);  // [p2]
     uint32_t* hist = tau_s + p2;                                                        // [p2]
-    uint32_t* lut = hist + p2;                                                          // [p2 + 1]
+    uint32_t* lut = hist + p2;                                                          // [p2]
 
     for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) {
         tau_s[i] = i < kc ? tau_chunk[i] : 0xFFFFFFFFu;
         hist[i] = 0u;
     }
     __syncthreads();
-    // uniform cells of width 2^shift from the smallest threshold; the largest lands in a cell < p2-1
+    // uniform cells of width 2^shift from the smallest threshold; the largest lands in a cell < p2-2
     const uint32_t tau_first = tau_s[0], tau_last = tau_s[kc - 1];
-    uint32_t shift = 0;
-    while (((uint64_t)(tau_last - tau_first) >> shift) >= p2 - 1) ++shift;
-    for (uint32_t c = threadIdx.x; c <= p2; c += DC_SCAN_THREADS) {
+    uint32_t shift = 0;                                        // p2 >= 4, so this stops at shift <= 31
+    while (shift < 31 && ((tau_last - tau_first) >> shift) >= p2 - 2) ++shift;
+    for (uint32_t c = threadIdx.x; c < p2; c += DC_SCAN_THREADS) {
         const uint64_t edge = (uint64_t)tau_first + ((uint64_t)c << shift);
         uint32_t lo = 0, hi = kc;                              // #{k : tau_k < edge}
         while (lo < hi) {
@@ -551,7 +554,33 @@ void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t*
 size_t scan_lds_bytes(const Plan& p) {
     const size_t tables = (size_t)p.p2 * 8;                       // thresholds + histogram
     if (!p.vec4) return tables;
-    return tables + ((size_t)p.p2 + 1) * 4 + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);   // + cells + queues
+    return tables + (size_t)p.p2 * 4 + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);   // + cells + queues
+}
+
+template <int L>
+static int resident_vec4(size_t lds) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_vec4_kernel<L>, DC_SCAN_THREADS, lds) != hipSuccess) n = 0;
+    return n;
+}
+
+// Blocks of the streaming kernel that one compute unit holds at a time (0 if the query fails).
+int scan_blocks_per_cu(const Plan& p) {
+    const size_t lds = scan_lds_bytes(p);
+    int n = 0;
+    if (!p.vec4) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_generic_kernel, DC_SCAN_THREADS, lds) != hipSuccess) n = 0;
+        return n;
+    }
+    switch (p.M / 4) {
+        case 1:  return resident_vec4<1>(lds);
+        case 2:  return resident_vec4<2>(lds);
+        case 4:  return resident_vec4<4>(lds);
+        case 8:  return resident_vec4<8>(lds);
+        case 16: return resident_vec4<16>(lds);
+        case 32: return resident_vec4<32>(lds);
+        default: return resident_vec4<64>(lds);
+    }
 }
 
 template <int L>
