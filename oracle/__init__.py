@@ -58,6 +58,9 @@ def _load():
             fn = getattr(lib, name)
             fn.argtypes = sig
             fn.restype = ctypes.c_int
+        lib.dc_oracle_per_step_speedup.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                                   ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        lib.dc_oracle_per_step_speedup.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -123,26 +126,19 @@ def select_tau(step_sum, done_sum, taus, T: int, N: int, M: int, base_step_sum: 
 
 
 def per_step_speedup(lat: np.ndarray, taus, comm):
-    """Algorithm 2 as printed: S_i(tau) per iteration, then the mean over iterations.
+    """Algorithm 2 as printed: S_i(tau) per iteration, then the mean over iterations (float64).
 
-    comm may be a scalar or one value per iteration (T_i^c).  float64.
+    comm may be a scalar or one value per iteration (T_i^c).
     """
-    lat = np.asarray(lat, dtype=np.int64)
+    lat = np.ascontiguousarray(lat, dtype=np.int32)
+    if lat.ndim != 3:
+        raise OracleError(ERR_INVALID_ARG)
     T, N, M = lat.shape
-    comm = np.broadcast_to(np.asarray(comm, dtype=np.float64), (T,))
-    out = np.zeros(len(taus), dtype=np.float64)
-    for k, tau in enumerate(taus):
-        acc = 0.0
-        for i in range(T):
-            completed = 0.0
-            slowest = 0
-            for n in range(N):
-                elapsed = 0
-                for m in range(M):
-                    elapsed += int(lat[i, n, m])
-                    if elapsed < tau:
-                        completed += 1.0 / N
-                slowest = max(slowest, elapsed)
-            acc += (slowest + comm[i]) / (min(int(tau), slowest) + comm[i]) * completed / M
-        out[k] = acc / T
+    taus = np.ascontiguousarray(taus, dtype=np.int64)
+    comm = np.ascontiguousarray(np.broadcast_to(np.asarray(comm, dtype=np.int64), (T,)))
+    out = np.zeros(taus.size, dtype=np.float64)
+    fn = _load().dc_oracle_per_step_speedup
+    rc = fn(lat.ctypes.data, T, N, M, taus.ctypes.data, taus.size, comm.ctypes.data, out.ctypes.data)
+    if rc != OK:
+        raise OracleError(rc)
     return out

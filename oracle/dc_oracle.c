@@ -119,3 +119,38 @@ int dc_oracle_simulate_sorted(const int32_t* lat, int64_t T, int64_t N, int64_t 
     free(order); free(done_sorted); free(step_sorted);
     return DCO_OK;
 }
+
+/* Algorithm 2 exactly as printed (Appendix C.1): for every threshold, the effective speedup of each
+ * iteration, S_i(tau) = (T_i + T_i^c) / (min(tau, T_i) + T_i^c) * M~_i(tau) / M, with M~_i(tau) built up in
+ * steps of 1/N, then the mean over the I iterations.  comm[i] is T_i^c (one value per iteration).
+ * float64 throughout, as a direct reading of the listing's real-valued quantities.
+ * Returns DCO_ERR_INVALID_ARG if some iteration has min(tau, T_i) + T_i^c = 0 (the ratio is undefined). */
+int dc_oracle_per_step_speedup(const int32_t* lat, int64_t T, int64_t N, int64_t M,
+                               const int64_t* taus, int64_t K, const int64_t* comm, double* s_eff) {
+    if (T < 1 || N < 1 || M < 1 || K < 0 || !lat || !comm || (K > 0 && (!taus || !s_eff))) return DCO_ERR_INVALID_ARG;
+    for (int64_t k = 0; k < K; ++k) if (taus[k] < 0) return DCO_ERR_INVALID_ARG;
+    for (int64_t i = 0; i < T; ++i) if (comm[i] < 0) return DCO_ERR_INVALID_ARG;
+    if (has_negative(lat, T * N * M)) return DCO_ERR_NEGATIVE_LATENCY;
+    for (int64_t k = 0; k < K; ++k) {
+        const int64_t tau = taus[k];
+        double total = 0.0;
+        for (int64_t i = 0; i < T; ++i) {
+            double completed = 0.0;         /* M~_i(tau) */
+            int64_t slowest = 0;            /* T_i */
+            for (int64_t n = 0; n < N; ++n) {
+                const int32_t* t = lat + (i * N + n) * M;
+                int64_t elapsed = 0;        /* T_{i,n} */
+                for (int64_t m = 0; m < M; ++m) {
+                    elapsed += t[m];
+                    if (elapsed < tau) completed += 1.0 / (double)N;
+                }
+                if (elapsed > slowest) slowest = elapsed;
+            }
+            const int64_t capped = tau < slowest ? tau : slowest;
+            if (capped + comm[i] == 0) return DCO_ERR_INVALID_ARG;
+            total += (double)(slowest + comm[i]) / (double)(capped + comm[i]) * completed / (double)M;
+        }
+        s_eff[k] = total / (double)T;
+    }
+    return DCO_OK;
+}

@@ -253,6 +253,30 @@ def test_per_step_speedup_matches_hand_example(golden_dir):
     assert np.allclose(s, expected, rtol=1e-14)
 
 
+def test_per_step_speedup_pins():
+    rng = np.random.default_rng(31)
+    lat = rng.integers(1, 3000, size=(9, 6, 12), dtype=np.int32)
+    totals = lat.sum(axis=2, dtype=np.int64)
+    taus = np.sort(rng.integers(1, int(totals.max()) + 100, size=25))
+    taus = np.append(taus, BIG)
+    # one iteration: the mean of ratios is the ratio itself, i.e. select_tau's S_eff from the integer sums
+    one = lat[:1]
+    step, done = oracle.simulate(one, taus, 70, "literal")
+    _, seff, _ = oracle.select_tau(step, done, taus, 1, 6, 12, int(step[-1]))
+    assert np.allclose(oracle.per_step_speedup(one, taus, 70), seff, rtol=1e-12)
+    # no drops: every iteration's speedup is exactly 1
+    assert oracle.per_step_speedup(lat, [BIG], 70)[0] == pytest.approx(1.0, abs=1e-12)
+    # mean over iterations = mean of the single-iteration values, also with per-iteration T^c
+    comm = rng.integers(0, 500, size=9)
+    whole = oracle.per_step_speedup(lat, taus, comm)
+    parts = np.mean([oracle.per_step_speedup(lat[i:i + 1], taus, comm[i:i + 1]) for i in range(9)], axis=0)
+    assert np.allclose(whole, parts, rtol=1e-12)
+    # S_i <= (T_i + c)/(min(tau,T_i) + c) and >= 0
+    assert np.all(whole >= 0) and np.all(whole[:-1] <= (totals.max() + comm.max()) / taus[:-1].clip(1))
+    with pytest.raises(oracle.OracleError):
+        oracle.per_step_speedup(np.zeros((1, 1, 2), dtype=np.int32), [5], 0)      # 0/0 step time
+
+
 # --- error behaviour ------------------------------------------------------------------------
 
 @pytest.mark.parametrize("method", METHODS)
