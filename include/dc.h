@@ -102,6 +102,34 @@ int dc_select_tau(const int64_t* step_sum, const int64_t* done_sum, const int64_
                   int64_t T, int64_t N, int64_t M, int64_t base_step_sum,
                   double* out_thr, double* out_seff, int64_t* out_best_k);
 
+/* Effective speedup exactly as Algorithm 2 (Appendix C.1) prints it: the mean over iterations of the
+ * per-iteration ratio
+ *   S_t(tau) = (Tmax[t] + c_t) / (min(tau, Tmax[t]) + c_t) * done_t(tau) / (N*M),
+ *   done_t(tau) = sum_n #{ m : P[t][n][m] < tau },          out_seff[k] = (1/T) sum_t S_t(taus[k]),
+ * with c_t = comm_per_trial[t] (the listing's per-iteration T_i^c) or, when comm_per_trial is NULL, the
+ * constant comm.  float64; the sum over iterations is taken in a fixed order, so repeated calls give
+ * identical bits.  (dc_select_tau's S_eff is the ratio of iteration means instead; the two differ by a
+ * covariance term of order N^-1/2, Appendix C.2.)
+ * lat: DEVICE int32 [T][N][M].  taus: HOST K int64.  comm_per_trial: HOST T int64 (each >= 0) or NULL.
+ * out_seff: HOST K doubles, caller's threshold order.  Extra preconditions: N*M < 2^31, and
+ * min(tau, Tmax[t]) + c_t > 0 for every iteration and threshold (else DC_ERR_INVALID_ARG: the ratio is
+ * undefined).  Same stream, workspace caching and error rules as dc_simulate. */
+int dc_speedup_per_step(const int32_t* lat, int64_t T, int64_t N, int64_t M,
+                        const int64_t* taus, int64_t K, int64_t comm, const int64_t* comm_per_trial,
+                        double* out_seff);
+
+/* Bytes of DEVICE workspace that dc_speedup_per_step_async needs (0 if the sizes are invalid). */
+size_t dc_speedup_workspace_bytes(int64_t T, int64_t N, int64_t M, int64_t K);
+
+/* Same, enqueued on `stream` without synchronising or allocating.  taus_dev: DEVICE K int64;
+ * comm_per_trial_dev: DEVICE T int64 or NULL; out_seff_dev: DEVICE K doubles; workspace as for
+ * dc_simulate_async (at least dc_speedup_workspace_bytes bytes); device-side value errors are read
+ * back with dc_workspace_status. */
+int dc_speedup_per_step_async(const int32_t* lat, int64_t T, int64_t N, int64_t M,
+                              const int64_t* taus_dev, int64_t K, int64_t comm,
+                              const int64_t* comm_per_trial_dev, double* out_seff_dev,
+                              void* workspace_dev, size_t workspace_bytes, void* stream);
+
 /* Optional kernel timing for benchmarks.  When enabled, every dc_simulate / dc_simulate_async
  * brackets its streaming kernel (the single pass over lat) and the whole enqueued sequence with
  * HIP events on the stream it runs on.  dc_last_kernel_ms waits for those events and returns the

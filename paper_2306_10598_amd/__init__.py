@@ -21,6 +21,7 @@ DC_MAX_THRESHOLDS = 65536
 
 EXPORTS = (
     "dc_simulate", "dc_workspace_bytes", "dc_simulate_async", "dc_workspace_status", "dc_select_tau",
+    "dc_speedup_per_step", "dc_speedup_workspace_bytes", "dc_speedup_per_step_async",
     "dc_set_kernel_timing", "dc_last_kernel_ms", "dc_status_string", "dc_last_device_error", "dc_shutdown",
 )
 
@@ -56,6 +57,12 @@ def _load():
     lib.dc_workspace_status.restype = ctypes.c_int
     lib.dc_select_tau.argtypes = [p, p, p, i64, i64, i64, i64, i64, p, p, p]
     lib.dc_select_tau.restype = ctypes.c_int
+    lib.dc_speedup_per_step.argtypes = [p, i64, i64, i64, p, i64, i64, p, p]
+    lib.dc_speedup_per_step.restype = ctypes.c_int
+    lib.dc_speedup_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    lib.dc_speedup_workspace_bytes.restype = sz
+    lib.dc_speedup_per_step_async.argtypes = [p, i64, i64, i64, p, i64, i64, p, p, p, sz, p]
+    lib.dc_speedup_per_step_async.restype = ctypes.c_int
     lib.dc_set_kernel_timing.argtypes = [ctypes.c_int]
     lib.dc_set_kernel_timing.restype = ctypes.c_int
     lib.dc_last_kernel_ms.argtypes = [p, p]
@@ -150,6 +157,52 @@ def dc_select_tau(step_sum, done_sum, taus, T: int, N: int, M: int, base_step_su
                                int(base_step_sum), thr.ctypes.data, seff.ctypes.data, ctypes.byref(best))
     _check(rc, "dc_select_tau")
     return thr, seff, int(best.value)
+
+
+def dc_speedup_workspace_bytes(T: int, N: int, M: int, K: int) -> int:
+    return int(_load().dc_speedup_workspace_bytes(T, N, M, K))
+
+
+def dc_speedup_per_step(lat, taus, comm: int = 0, comm_per_trial=None):
+    """S_eff[K] (NumPy float64) as the mean of per-iteration speedups; comm_per_trial: T host values or None."""
+    lat = _device_tensor(lat, "int32", "lat")
+    if lat.dim() != 3:
+        raise TypeError("lat must have shape [T][N][M]")
+    T, N, M = lat.shape
+    taus = np.ascontiguousarray(taus, dtype=np.int64)
+    per = None
+    if comm_per_trial is not None:
+        per = np.ascontiguousarray(comm_per_trial, dtype=np.int64)
+        if per.size != T:
+            raise ValueError("comm_per_trial needs one value per trial")
+    out = np.empty(taus.size, dtype=np.float64)
+    rc = _load().dc_speedup_per_step(lat.data_ptr(), T, N, M, taus.ctypes.data, taus.size, int(comm),
+                                     None if per is None else per.ctypes.data, out.ctypes.data)
+    _check(rc, "dc_speedup_per_step")
+    return out
+
+
+def dc_speedup_per_step_async(lat, taus_dev, comm: int, comm_per_trial_dev, out_seff_dev, workspace, stream=None) -> None:
+    lat = _device_tensor(lat, "int32", "lat")
+    if lat.dim() != 3:
+        raise TypeError("lat must have shape [T][N][M]")
+    T, N, M = lat.shape
+    taus_dev = _device_tensor(taus_dev, "int64", "taus_dev")
+    out_seff_dev = _device_tensor(out_seff_dev, "float64", "out_seff_dev")
+    workspace = _device_tensor(workspace, "uint8", "workspace")
+    per_ptr = None
+    if comm_per_trial_dev is not None:
+        per = _device_tensor(comm_per_trial_dev, "int64", "comm_per_trial_dev")
+        if per.numel() != T:
+            raise ValueError("comm_per_trial_dev needs one value per trial")
+        per_ptr = per.data_ptr()
+    if out_seff_dev.numel() < taus_dev.numel():
+        raise ValueError("output tensor is shorter than the threshold list")
+    handle = 0 if stream is None else int(stream.cuda_stream)
+    rc = _load().dc_speedup_per_step_async(lat.data_ptr(), T, N, M, taus_dev.data_ptr(), taus_dev.numel(), int(comm),
+                                           per_ptr, out_seff_dev.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                           handle)
+    _check(rc, "dc_speedup_per_step_async")
 
 
 def dc_set_kernel_timing(enable: bool) -> None:

@@ -86,6 +86,30 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     return true;
 }
 
+// Plan of the per-iteration speedup pass: one block per trial, float64 sums per block.
+bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::Plan* out) {
+    if (T < 1 || N < 1 || M < 1 || K < 1 || K > DC_MAX_THRESHOLDS) return false;
+    const int64_t lim = (int64_t)1 << 31;
+    if (T >= lim || N >= lim || M >= lim || N * M >= lim) return false;      // per-trial counts are 32-bit
+    dc::Plan p{};
+    p.T = (uint32_t)T; p.N = (uint32_t)N; p.M = (uint32_t)M; p.K = (uint32_t)K;
+    p.elements = (uint64_t)T * (uint64_t)N * (uint64_t)M;
+    p.vec4 = allow_vec4 && vec4_shape(M);
+    p.grid = (uint32_t)(T < (int64_t)DC_MAX_TRIAL_BLOCKS ? T : DC_MAX_TRIAL_BLOCKS);
+    p.chunk = p.K < DC_TRIAL_CHUNK_THRESHOLDS ? p.K : DC_TRIAL_CHUNK_THRESHOLDS;
+    p.p2 = next_pow2_above(p.chunk);
+    p.max_latency = (uint32_t)(2147483647ll / M);
+    size_t off = 0;
+    p.off_status = off;     off += 256;
+    p.off_tau_sorted = off; off += align256((size_t)K * 8);
+    p.off_tau_u32 = off;    off += align256((size_t)K * 4);
+    p.off_pos = off;        off += align256((size_t)K * 4);
+    p.off_partial = off;    off += align256((size_t)p.grid * p.p2 * 8);
+    p.bytes = off;
+    *out = p;
+    return true;
+}
+
 // ---- optional timing ---------------------------------------------------------------------------
 struct Timing {
     bool enabled = false;
@@ -177,8 +201,37 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
     return DC_OK;
 }
 
+int compute_units() {
+    int device = 0, cus = 0;
+    if (hipGetDevice(&device) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1) return 256;
+    return cus;
+}
+
+int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, int64_t comm,
+                    const int64_t* comm_per_trial_dev, double* out_seff_dev, unsigned char* ws, hipStream_t stream) {
+    dc::Plan p = plan;
+    const uint32_t want = (uint32_t)compute_units() * DC_SCAN_BLOCKS_PER_CU;   // always fits: <= 57 KiB LDS, 4 waves each
+    if (p.grid > want) p.grid = want;
+    uint32_t* status = reinterpret_cast<uint32_t*>(ws + p.off_status);
+    int64_t* tau_sorted = reinterpret_cast<int64_t*>(ws + p.off_tau_sorted);
+    uint32_t* tau_u32 = reinterpret_cast<uint32_t*>(ws + p.off_tau_u32);
+    uint32_t* pos = reinterpret_cast<uint32_t*>(ws + p.off_pos);
+    double* partial = reinterpret_cast<double*>(ws + p.off_partial);
+    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, nullptr, 0, stream);
+    const uint32_t chunks = (p.K + p.chunk - 1) / p.chunk;
+    for (uint32_t c = 0; c < chunks; ++c) {
+        const uint32_t chunk0 = c * p.chunk;
+        const uint32_t kc = p.K - chunk0 < p.chunk ? p.K - chunk0 : p.chunk;
+        dc::launch_trial_scan(p, lat, tau_u32 + chunk0, kc, comm_per_trial_dev, comm, partial, status, stream);
+        dc::launch_speedup_finalize(p, partial, kc, chunk0, pos, out_seff_dev, stream);
+    }
+    DC_HIP(hipGetLastError());
+    return DC_OK;
+}
+
 int flags_to_status(uint32_t flags) {
-    if (flags & DC_FLAG_NEGATIVE_TAU) return DC_ERR_INVALID_ARG;
+    if (flags & (DC_FLAG_NEGATIVE_TAU | DC_FLAG_ZERO_STEP)) return DC_ERR_INVALID_ARG;
     if (flags & DC_FLAG_NEGATIVE_LATENCY) return DC_ERR_NEGATIVE_LATENCY;
     if (flags & DC_FLAG_RANGE) return DC_ERR_RANGE;
     return DC_OK;
@@ -192,6 +245,21 @@ bool sizes_ok(int64_t T, int64_t N, int64_t M, int64_t K, int64_t comm) {
 unsigned char* g_cache = nullptr;
 size_t g_cache_bytes = 0;
 int g_cache_device = -1;
+
+// Grow (never shrink) the cached device allocation of the synchronous entry points.  Caller holds g_mutex.
+int ensure_cache(size_t need) {
+    int device = 0;
+    DC_HIP(hipGetDevice(&device));
+    if (device == g_cache_device && need <= g_cache_bytes) return DC_OK;
+    if (g_cache) { (void)hipFree(g_cache); g_cache = nullptr; g_cache_bytes = 0; }
+    void* mem = nullptr;
+    hipError_t e = hipMalloc(&mem, need);
+    if (e != hipSuccess) return device_error(e, "hipMalloc(workspace)", DC_ERR_NOMEM);
+    g_cache = static_cast<unsigned char*>(mem);
+    g_cache_bytes = need;
+    g_cache_device = device;
+    return DC_OK;
+}
 
 }  // namespace
 
@@ -240,18 +308,10 @@ int dc_simulate(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64
     if (!make_plan(T, N, M, K, aligned, &p)) return DC_ERR_INVALID_ARG;
 
     std::lock_guard<std::mutex> lock(g_mutex);
-    int device = 0;
-    DC_HIP(hipGetDevice(&device));
     const size_t io_bytes = align256((size_t)K * 8);
-    const size_t need = 3 * io_bytes + p.bytes;
-    if (device != g_cache_device || need > g_cache_bytes) {
-        if (g_cache) { (void)hipFree(g_cache); g_cache = nullptr; g_cache_bytes = 0; }
-        void* mem = nullptr;
-        hipError_t e = hipMalloc(&mem, need);
-        if (e != hipSuccess) return device_error(e, "hipMalloc(workspace)", DC_ERR_NOMEM);
-        g_cache = static_cast<unsigned char*>(mem);
-        g_cache_bytes = need;
-        g_cache_device = device;
+    {
+        int rc = ensure_cache(3 * io_bytes + p.bytes);
+        if (rc) return rc;
     }
     int64_t* taus_dev = reinterpret_cast<int64_t*>(g_cache);
     int64_t* step_dev = reinterpret_cast<int64_t*>(g_cache + io_bytes);
@@ -269,6 +329,60 @@ int dc_simulate(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64
     if (rc) return rc;
     DC_HIP(hipMemcpy(out_step, step_dev, (size_t)K * 8, hipMemcpyDeviceToHost));
     DC_HIP(hipMemcpy(out_done, done_dev, (size_t)K * 8, hipMemcpyDeviceToHost));
+    return DC_OK;
+}
+
+size_t dc_speedup_workspace_bytes(int64_t T, int64_t N, int64_t M, int64_t K) {
+    dc::Plan p{};
+    return make_trial_plan(T, N, M, K, true, &p) ? p.bytes : 0;
+}
+
+int dc_speedup_per_step_async(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus_dev, int64_t K,
+                              int64_t comm, const int64_t* comm_per_trial_dev, double* out_seff_dev,
+                              void* workspace_dev, size_t workspace_bytes, void* stream) {
+    if (!sizes_ok(T, N, M, K, comm) || !lat) return DC_ERR_INVALID_ARG;
+    if (K == 0) return DC_OK;
+    if (!taus_dev || !out_seff_dev || !workspace_dev) return DC_ERR_INVALID_ARG;
+    if (((uintptr_t)lat & 3u) || ((uintptr_t)workspace_dev & 255u)) return DC_ERR_INVALID_ARG;
+    dc::Plan p{};
+    if (!make_trial_plan(T, N, M, K, ((uintptr_t)lat & 15u) == 0, &p)) return DC_ERR_INVALID_ARG;
+    if (workspace_bytes < p.bytes) return DC_ERR_INVALID_ARG;
+    return enqueue_speedup(p, lat, taus_dev, comm, comm_per_trial_dev, out_seff_dev,
+                           static_cast<unsigned char*>(workspace_dev), static_cast<hipStream_t>(stream));
+}
+
+int dc_speedup_per_step(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus, int64_t K,
+                        int64_t comm, const int64_t* comm_per_trial, double* out_seff) {
+    if (!sizes_ok(T, N, M, K, comm) || !lat) return DC_ERR_INVALID_ARG;
+    if (K == 0) return DC_OK;
+    if (!taus || !out_seff || ((uintptr_t)lat & 3u)) return DC_ERR_INVALID_ARG;
+    for (int64_t k = 0; k < K; ++k)
+        if (taus[k] < 0) return DC_ERR_INVALID_ARG;
+    if (comm_per_trial)
+        for (int64_t t = 0; t < T; ++t)
+            if (comm_per_trial[t] < 0) return DC_ERR_INVALID_ARG;
+    dc::Plan p{};
+    if (!make_trial_plan(T, N, M, K, ((uintptr_t)lat & 15u) == 0, &p)) return DC_ERR_INVALID_ARG;
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const size_t tau_bytes = align256((size_t)K * 8), comm_bytes = comm_per_trial ? align256((size_t)T * 8) : 0;
+    int rc = ensure_cache(2 * tau_bytes + comm_bytes + p.bytes);
+    if (rc) return rc;
+    int64_t* taus_dev = reinterpret_cast<int64_t*>(g_cache);
+    double* seff_dev = reinterpret_cast<double*>(g_cache + tau_bytes);
+    int64_t* comm_dev = comm_per_trial ? reinterpret_cast<int64_t*>(g_cache + 2 * tau_bytes) : nullptr;
+    unsigned char* ws = g_cache + 2 * tau_bytes + comm_bytes;
+    hipStream_t stream = nullptr;
+    DC_HIP(hipMemcpy(taus_dev, taus, (size_t)K * 8, hipMemcpyHostToDevice));
+    if (comm_dev) DC_HIP(hipMemcpy(comm_dev, comm_per_trial, (size_t)T * 8, hipMemcpyHostToDevice));
+    rc = enqueue_speedup(p, lat, taus_dev, comm, comm_dev, seff_dev, ws, stream);
+    if (rc) return rc;
+    DC_HIP(hipStreamSynchronize(stream));
+    uint32_t flags = 0;
+    DC_HIP(hipMemcpy(&flags, ws + p.off_status, sizeof(flags), hipMemcpyDeviceToHost));
+    rc = flags_to_status(flags);
+    if (rc) return rc;
+    DC_HIP(hipMemcpy(out_seff, seff_dev, (size_t)K * 8, hipMemcpyDeviceToHost));
     return DC_OK;
 }
 

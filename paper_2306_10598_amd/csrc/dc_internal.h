@@ -29,11 +29,14 @@
 #define DC_REDUCE_SLOTS 64u             // per-block histograms added by one block of the reduce kernel
 #define DC_FINAL_THREADS 1024
 #define DC_CHUNK_THRESHOLDS 4095u      // thresholds handled by one pass over lat (LDS-resident grid)
+#define DC_TRIAL_CHUNK_THRESHOLDS 2047u // same for the per-iteration speedup pass (it also keeps float64 sums in LDS)
+#define DC_MAX_TRIAL_BLOCKS 1024u      // upper bound of that pass's grid (sizes its per-block sums in the workspace)
 #define DC_TAU_CLAMP 0x80000000u       // thresholds at or above 2^31 exceed every completion time
 
 #define DC_FLAG_NEGATIVE_TAU 1u
 #define DC_FLAG_NEGATIVE_LATENCY 2u
 #define DC_FLAG_RANGE 4u
+#define DC_FLAG_ZERO_STEP 8u             // some iteration has min(tau, Tmax) + comm = 0 (per-iteration speedup undefined)
 
 namespace dc {
 
@@ -52,6 +55,7 @@ struct Plan {
     uint32_t max_latency;       // floor((2^31-1)/M)
     // byte offsets into the workspace
     size_t off_status, off_tau_sorted, off_tau_u32, off_pos, off_bins, off_chunk_out, off_unit_max, off_hist_part;
+    size_t off_partial;         // per-iteration speedup pass: float64 [grid][p2]
     size_t bytes;
 };
 
@@ -66,6 +70,12 @@ void launch_finalize(const Plan& p, unsigned long long* hist_total, unsigned lon
                      unsigned long long* trial_sum, uint32_t kc, uint32_t chunk0, const int64_t* tau_sorted,
                      const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done, int64_t* chunk_step,
                      int64_t* chunk_done, hipStream_t stream);
+void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
+                       const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
+                       hipStream_t stream);
+void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, uint32_t chunk0, const uint32_t* pos,
+                             double* out_seff, hipStream_t stream);
+size_t trial_scan_lds_bytes(const Plan& p);
 size_t scan_lds_bytes(const Plan& p);
 int scan_blocks_per_cu(const Plan& p);
 

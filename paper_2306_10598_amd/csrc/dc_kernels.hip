@@ -238,6 +238,92 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
 }
 
 // ---------------------------------------------------------------------------------------------
+// shared pieces of the streaming kernels
+// ---------------------------------------------------------------------------------------------
+
+// Stage one pass's thresholds in LDS (tau[p2] | hist[p2] | lut[p2] at `tables`), clear the histogram
+// and build the lookup cells.  Every thread of the block must call it (it synchronises the block).
+__device__ __forceinline__ GridView stage_grid(uint32_t* tables, const uint32_t* __restrict__ tau_chunk,
+                                               uint32_t kc, uint32_t p2) {
+    uint32_t* tau_s = tables;
+    uint32_t* hist = tau_s + p2;
+    uint32_t* lut = hist + p2;
+    for (uint32_t i = threadIdx.x; i < p2; i += blockDim.x) {
+        tau_s[i] = i < kc ? tau_chunk[i] : 0xFFFFFFFFu;
+        hist[i] = 0u;
+    }
+    __syncthreads();
+    // uniform cells of width 2^shift from the smallest threshold; the largest lands in a cell < p2-2
+    const uint32_t tau_first = tau_s[0], tau_last = tau_s[kc - 1];
+    uint32_t shift = 0;                                        // p2 >= 4, so this stops at shift <= 31
+    while (shift < 31 && ((tau_last - tau_first) >> shift) >= p2 - 2) ++shift;
+    for (uint32_t c = threadIdx.x; c < p2; c += blockDim.x) {
+        const uint64_t edge = (uint64_t)tau_first + ((uint64_t)c << shift);
+        uint32_t lo = 0, hi = kc;                              // #{k : tau_k < edge}
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if ((uint64_t)tau_s[mid] < edge) lo = mid + 1; else hi = mid;
+        }
+        lut[c] = lo;
+    }
+    __syncthreads();
+    return GridView{tau_s, lut, hist, p2, shift, tau_first};
+}
+
+// One wave streams `nfull` consecutive full loads (1 KiB each, 64/L whole rows) starting at `base`
+// (already offset by the lane), then, if tail_rows > 0, one partial load holding tail_rows rows.
+template <int L>
+__device__ __forceinline__ void stream_rows(WaveState& st, const u32x4* base, uint32_t nfull, uint32_t tail_rows,
+                                            uint4* queue, const GridView& g, uint32_t lane) {
+    constexpr int U = DC_SCAN_UNROLL;              // loads in flight per lane
+    uint32_t i = 0;
+#if DC_SCAN_PREFETCH
+    // software pipeline: the next group's loads are issued before the current group is processed
+    if (nfull >= (uint32_t)U) {
+        u32x4 cur[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) cur[k] = __builtin_nontemporal_load(base + (uint64_t)k * 64);
+        for (; i + 2 * U <= nfull; i += U) {
+            u32x4 nxt[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) nxt[k] = __builtin_nontemporal_load(base + (uint64_t)(i + U + k) * 64);
+            process_loads<L, U>(st, cur, queue, g, lane);
+#pragma unroll
+            for (int k = 0; k < U; ++k) cur[k] = nxt[k];
+        }
+        process_loads<L, U>(st, cur, queue, g, lane);
+        i += U;
+    }
+#else
+    for (; i + U <= nfull; i += U) {
+        u32x4 x[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) x[k] = __builtin_nontemporal_load(base + (uint64_t)(i + k) * 64);
+        process_loads<L, U>(st, x, queue, g, lane);
+    }
+#endif
+    for (; i < nfull; ++i) {
+        const u32x4 x[1] = {__builtin_nontemporal_load(base + (uint64_t)i * 64)};
+        process_loads<L, 1>(st, x, queue, g, lane);
+    }
+    if (tail_rows) {                                // rows beyond the trial's last worker belong to the next trial
+        const bool valid = lane < tail_rows * L;
+        u32x4 x = {0u, 0u, 0u, 0u};
+        if (valid) x = __builtin_nontemporal_load(base + (uint64_t)nfull * 64);
+        const uint32_t incl = lane_completion_time<L>(x, lane);
+        st.check = umax(st.check, umax(umax(x.x, x.y), umax(x.z, x.w)));
+        st.lane_max = umax(st.lane_max, incl);
+        enqueue_active(st, x, incl, valid && incl >= g.tau0, queue, g, lane);
+    }
+}
+
+__device__ __forceinline__ void report_range(uint32_t check, uint32_t max_latency, uint32_t lane, uint32_t* status) {
+    const uint32_t worst = wave_max(check);
+    if (lane == 0 && worst > max_latency)
+        atomicOr(status, worst >= 0x80000000u ? DC_FLAG_NEGATIVE_LATENCY : DC_FLAG_RANGE);
+}
+
+// ---------------------------------------------------------------------------------------------
 // dc_scan_vec4_kernel: the streaming pass, M = 4*L with L in {1,2,4,...,64}
 // ---------------------------------------------------------------------------------------------
 // A "load" is 1 KiB read by one wave (16 B per lane) = 64/L whole rows.  A "unit" is up to
@@ -252,34 +338,10 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
                          uint32_t* __restrict__ status, uint32_t max_latency) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
-    uint32_t* tau_s = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);  // [p2]
-    uint32_t* hist = tau_s + p2;                                                        // [p2]
-    uint32_t* lut = hist + p2;                                                          // [p2]
-
-    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) {
-        tau_s[i] = i < kc ? tau_chunk[i] : 0xFFFFFFFFu;
-        hist[i] = 0u;
-    }
-    __syncthreads();
-    // uniform cells of width 2^shift from the smallest threshold; the largest lands in a cell < p2-2
-    const uint32_t tau_first = tau_s[0], tau_last = tau_s[kc - 1];
-    uint32_t shift = 0;                                        // p2 >= 4, so this stops at shift <= 31
-    while (shift < 31 && ((tau_last - tau_first) >> shift) >= p2 - 2) ++shift;
-    for (uint32_t c = threadIdx.x; c < p2; c += DC_SCAN_THREADS) {
-        const uint64_t edge = (uint64_t)tau_first + ((uint64_t)c << shift);
-        uint32_t lo = 0, hi = kc;                              // #{k : tau_k < edge}
-        while (lo < hi) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if ((uint64_t)tau_s[mid] < edge) lo = mid + 1; else hi = mid;
-        }
-        lut[c] = lo;
-    }
-    __syncthreads();
-    const GridView g{tau_s, lut, hist, p2, shift, tau_first};
+    const GridView g = stage_grid(reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS), tau_chunk, kc, p2);
 
     constexpr uint32_t R = 64 / L;                 // rows per load
     constexpr uint32_t M = 4 * L;
-    constexpr int U = DC_SCAN_UNROLL;              // loads in flight per lane
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction
     uint4* queue = queue_all + wave * QUEUE_ITEMS;
@@ -293,61 +355,18 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
         const uint32_t rows_left = N - row0;
         const uint32_t rows = rows_left < loads_per_unit * R ? rows_left : loads_per_unit * R;
         const uint32_t nfull = rows / R;
-        const uint32_t tail_rows = rows - nfull * R;
         const u32x4* base = reinterpret_cast<const u32x4*>(lat + ((uint64_t)t * N + row0) * M) + lane;
         st.lane_max = 0u;
-
-        uint32_t i = 0;
-#if DC_SCAN_PREFETCH
-        // software pipeline: the next group's loads are issued before the current group is processed
-        if (nfull >= (uint32_t)U) {
-            u32x4 cur[U];
-#pragma unroll
-            for (int k = 0; k < U; ++k) cur[k] = __builtin_nontemporal_load(base + (uint64_t)k * 64);
-            for (; i + 2 * U <= nfull; i += U) {
-                u32x4 nxt[U];
-#pragma unroll
-                for (int k = 0; k < U; ++k) nxt[k] = __builtin_nontemporal_load(base + (uint64_t)(i + U + k) * 64);
-                process_loads<L, U>(st, cur, queue, g, lane);
-#pragma unroll
-                for (int k = 0; k < U; ++k) cur[k] = nxt[k];
-            }
-            process_loads<L, U>(st, cur, queue, g, lane);
-            i += U;
-        }
-#else
-        for (; i + U <= nfull; i += U) {
-            u32x4 x[U];
-#pragma unroll
-            for (int k = 0; k < U; ++k) x[k] = __builtin_nontemporal_load(base + (uint64_t)(i + k) * 64);
-            process_loads<L, U>(st, x, queue, g, lane);
-        }
-#endif
-        for (; i < nfull; ++i) {
-            const u32x4 x[1] = {__builtin_nontemporal_load(base + (uint64_t)i * 64)};
-            process_loads<L, 1>(st, x, queue, g, lane);
-        }
-        if (tail_rows) {                            // last, partial load of the trial: rows beyond N belong to the next trial
-            const bool valid = lane < tail_rows * L;
-            u32x4 x = {0u, 0u, 0u, 0u};
-            if (valid) x = __builtin_nontemporal_load(base + (uint64_t)nfull * 64);
-            const uint32_t incl = lane_completion_time<L>(x, lane);
-            st.check = umax(st.check, umax(umax(x.x, x.y), umax(x.z, x.w)));
-            st.lane_max = umax(st.lane_max, incl);
-            enqueue_active(st, x, incl, valid && incl >= g.tau0, queue, g, lane);
-        }
+        stream_rows<L>(st, base, nfull, rows - nfull * R, queue, g, lane);
         const uint32_t m = wave_max(st.lane_max);
         if (lane == 0) unit_max[u] = m;
     }
     while (st.q_count) drain(st, queue, g, lane);
-
-    const uint32_t worst = wave_max(st.check);
-    if (lane == 0 && worst > max_latency)
-        atomicOr(status, worst >= 0x80000000u ? DC_FLAG_NEGATIVE_LATENCY : DC_FLAG_RANGE);
+    report_range(st.check, max_latency, lane, status);
 
     __syncthreads();
     uint32_t* out = hist_part + (uint64_t)blockIdx.x * p2;
-    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = hist[i];
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = g.hist[i];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -538,6 +557,162 @@ void dc_finalize_kernel(unsigned long long* __restrict__ hist_total, unsigned lo
 }
 
 // ---------------------------------------------------------------------------------------------
+// Per-iteration speedup (Algorithm 2 as printed): one block per trial
+// ---------------------------------------------------------------------------------------------
+// S_t(tau) = (Tmax_t + c_t) / (min(tau, Tmax_t) + c_t) * done_t(tau) / (N*M) needs the completed count of
+// every trial separately, so here a block owns a whole trial: its histogram in LDS is the trial's,
+// and when the trial is read the block turns it into S_t for every threshold of the pass and adds
+// that to its running sums (float64, one owner thread per threshold, trials in a fixed order, so the
+// result does not depend on timing).  The per-block sums are added by dc_speedup_finalize_kernel.
+
+struct TrialShared {
+    double* acc;          // [p2] running sums of S_t per sorted threshold
+    uint32_t* wave_tot;   // [DC_SCAN_WAVES] scratch of the block-wide prefix sum
+    uint32_t* block_max;  // [1] the trial's largest worker total
+};
+
+// After every wave has binned its share of trial t: prefix sums over the histogram, S_t per threshold.
+__device__ __forceinline__ void finish_trial(const GridView& g, const TrialShared& sh, uint32_t kc, uint32_t t,
+                                             const long long* __restrict__ comm_per_trial, long long comm,
+                                             double elements_per_trial, uint32_t* status) {
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    __syncthreads();                                           // histogram and block_max complete
+    const uint32_t tmax = *sh.block_max;
+    const uint32_t per = (g.p2 + DC_SCAN_THREADS - 1) / DC_SCAN_THREADS;
+    const uint32_t b0 = threadIdx.x * per;
+    uint32_t mine = 0;
+    for (uint32_t i = 0; i < per; ++i) mine += (b0 + i < g.p2) ? g.hist[b0 + i] : 0u;
+    uint32_t incl = segmented_inclusive_scan<64>(mine, lane);  // prefix over the wave, then over waves
+    if (lane == 63) sh.wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < DC_SCAN_WAVES; ++w) {
+        const uint32_t v = sh.wave_tot[w];
+        before += w < wave ? v : 0u;
+        all += v;
+    }
+    const long long c = comm_per_trial ? comm_per_trial[t] : comm;
+    if (c < 0 && threadIdx.x == 0) atomicOr(status, DC_FLAG_NEGATIVE_TAU);
+    uint32_t run = before + incl - mine;                       // counted elements in bins below b0
+    for (uint32_t i = 0; i < per; ++i) {
+        const uint32_t b = b0 + i;
+        if (b >= kc) break;
+        run += g.hist[b];
+        const uint32_t not_done = all - run;                   // completion times at or above threshold b
+        const uint32_t tau = g.tau[b];
+        const long long capped = (long long)(tau < tmax ? tau : tmax);
+        const long long den = capped + c;
+        if (den <= 0) { atomicOr(status, DC_FLAG_ZERO_STEP); continue; }
+        const double done = elements_per_trial - (double)not_done;
+        sh.acc[b] += (double)((long long)tmax + c) / (double)den * (done / elements_per_trial);
+    }
+    __syncthreads();                                           // everyone has read the histogram
+    for (uint32_t i = threadIdx.x; i < g.p2; i += DC_SCAN_THREADS) g.hist[i] = 0u;
+    if (threadIdx.x == 0) *sh.block_max = 0u;
+    __syncthreads();
+}
+
+template <int L>
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_trial_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N,
+                               const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
+                               const long long* __restrict__ comm_per_trial, long long comm,
+                               double* __restrict__ partial, uint32_t* __restrict__ status, uint32_t max_latency) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
+    uint32_t* tables = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);
+    TrialShared sh;
+    sh.acc = reinterpret_cast<double*>(tables + 3 * p2);                                // 8-byte aligned: p2 is even
+    sh.wave_tot = reinterpret_cast<uint32_t*>(sh.acc + p2);
+    sh.block_max = sh.wave_tot + DC_SCAN_WAVES;
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) sh.acc[i] = 0.0;
+    if (threadIdx.x == 0) *sh.block_max = 0u;
+    const GridView g = stage_grid(tables, tau_chunk, kc, p2);
+
+    constexpr uint32_t R = 64 / L;
+    constexpr uint32_t M = 4 * L;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint4* queue = queue_all + wave * QUEUE_ITEMS;
+    const uint32_t nfull = N / R, tail_rows = N - nfull * R;
+    const uint32_t lo = (uint32_t)((uint64_t)nfull * wave / DC_SCAN_WAVES);             // this wave's contiguous share
+    const uint32_t hi = (uint32_t)((uint64_t)nfull * (wave + 1) / DC_SCAN_WAVES);
+    const double elements_per_trial = (double)N * (double)M;
+
+    WaveState st{0u, 0u, 0u, 0u};
+    for (uint32_t t = blockIdx.x; t < T; t += gridDim.x) {
+        const u32x4* base = reinterpret_cast<const u32x4*>(lat + ((uint64_t)t * N + (uint64_t)lo * R) * M) + lane;
+        st.lane_max = 0u;
+        stream_rows<L>(st, base, hi - lo, wave == DC_SCAN_WAVES - 1 ? tail_rows : 0u, queue, g, lane);
+        while (st.q_count) drain(st, queue, g, lane);
+        const uint32_t m = wave_max(st.lane_max);
+        if (lane == 0) atomicMax(sh.block_max, m);
+        finish_trial(g, sh, kc, t, comm_per_trial, comm, elements_per_trial, status);
+    }
+    report_range(st.check, max_latency, lane, status);
+    double* out = partial + (uint64_t)blockIdx.x * p2;
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = sh.acc[i];
+}
+
+// Any M >= 1, any 4-byte alignment: the waves of the block take the trial's rows in turn.
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_trial_scan_generic_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N, uint32_t M,
+                                  const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
+                                  const long long* __restrict__ comm_per_trial, long long comm,
+                                  double* __restrict__ partial, uint32_t* __restrict__ status, uint32_t max_latency) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint32_t* tables = reinterpret_cast<uint32_t*>(smem);
+    TrialShared sh;
+    sh.acc = reinterpret_cast<double*>(tables + 3 * p2);
+    sh.wave_tot = reinterpret_cast<uint32_t*>(sh.acc + p2);
+    sh.block_max = sh.wave_tot + DC_SCAN_WAVES;
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) sh.acc[i] = 0.0;
+    if (threadIdx.x == 0) *sh.block_max = 0u;
+    const GridView g = stage_grid(tables, tau_chunk, kc, p2);
+
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const double elements_per_trial = (double)N * (double)M;
+    uint32_t check = 0u;
+    for (uint32_t t = blockIdx.x; t < T; t += gridDim.x) {
+        uint32_t best = 0u;
+        for (uint32_t r = wave; r < N; r += DC_SCAN_WAVES) {
+            const int32_t* row = lat + ((uint64_t)t * N + r) * M;
+            uint32_t carry = 0u;
+            for (uint32_t m0 = 0; m0 < M; m0 += 64) {
+                const bool valid = m0 + lane < M;
+                const uint32_t x = valid ? (uint32_t)row[m0 + lane] : 0u;
+                check = umax(check, x);
+                const uint32_t p = carry + segmented_inclusive_scan<64>(x, lane);
+                if (valid && p >= g.tau0) atomicAdd(&g.hist[bin_of(g.tau, p2, p)], 1u);
+                carry = (uint32_t)__builtin_amdgcn_readlane((int)p, 63);
+            }
+            best = umax(best, carry);
+        }
+        if (lane == 0) atomicMax(sh.block_max, best);
+        finish_trial(g, sh, kc, t, comm_per_trial, comm, elements_per_trial, status);
+    }
+    report_range(check, max_latency, lane, status);
+    double* out = partial + (uint64_t)blockIdx.x * p2;
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = sh.acc[i];
+}
+
+// out_seff[j] = (sum over blocks, in block order, of the block's sum for j's sorted position) / T
+__global__ __launch_bounds__(256)
+void dc_speedup_finalize_kernel(const double* __restrict__ partial, uint32_t blocks, uint32_t p2, uint32_t kc,
+                                uint32_t chunk0, const uint32_t* __restrict__ pos, uint32_t K, double trials,
+                                double* __restrict__ out_seff) {
+    const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= K) return;
+    const uint32_t p = pos[j];
+    if (p < chunk0 || p >= chunk0 + kc) return;
+    double sum = 0.0;
+    for (uint32_t b = 0; b < blocks; ++b) sum += partial[(uint64_t)b * p2 + (p - chunk0)];
+    out_seff[j] = sum / trials;
+}
+
+// ---------------------------------------------------------------------------------------------
 // launchers (called from dc_api.hip)
 // ---------------------------------------------------------------------------------------------
 namespace dc {
@@ -630,6 +805,46 @@ void launch_finalize(const Plan& p, unsigned long long* hist_total, unsigned lon
                        trial_sum, kc, p.p2, chunk0, tau_sorted, pos, p.K, (unsigned long long)p.T,
                        (unsigned long long)p.elements, (long long)comm, (long long*)out_step, (long long*)out_done,
                        (long long*)chunk_step, (long long*)chunk_done);
+}
+
+size_t trial_scan_lds_bytes(const Plan& p) {
+    const size_t tables = (size_t)p.p2 * 12 + (size_t)p.p2 * 8 + (DC_SCAN_WAVES + 1) * 4;   // grid + sums + scratch
+    return p.vec4 ? tables + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4) : tables;
+}
+
+template <int L>
+static void launch_trial_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
+                              const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
+                              hipStream_t stream) {
+    hipLaunchKernelGGL(dc_trial_scan_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS), trial_scan_lds_bytes(p),
+                       stream, lat, p.T, p.N, tau_chunk, kc, p.p2, (const long long*)comm_per_trial, (long long)comm,
+                       partial, status, p.max_latency);
+}
+
+void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
+                       const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
+                       hipStream_t stream) {
+    if (!p.vec4) {
+        hipLaunchKernelGGL(dc_trial_scan_generic_kernel, dim3(p.grid), dim3(DC_SCAN_THREADS), trial_scan_lds_bytes(p),
+                           stream, lat, p.T, p.N, p.M, tau_chunk, kc, p.p2, (const long long*)comm_per_trial,
+                           (long long)comm, partial, status, p.max_latency);
+        return;
+    }
+    switch (p.M / 4) {
+        case 1:  launch_trial_vec4<1>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
+        case 2:  launch_trial_vec4<2>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
+        case 4:  launch_trial_vec4<4>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
+        case 8:  launch_trial_vec4<8>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
+        case 16: launch_trial_vec4<16>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
+        case 32: launch_trial_vec4<32>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
+        default: launch_trial_vec4<64>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
+    }
+}
+
+void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, uint32_t chunk0, const uint32_t* pos,
+                             double* out_seff, hipStream_t stream) {
+    hipLaunchKernelGGL(dc_speedup_finalize_kernel, dim3((p.K + 255) / 256), dim3(256), 0, stream, partial, p.grid,
+                       p.p2, kc, chunk0, pos, p.K, (double)p.T, out_seff);
 }
 
 }  // namespace dc

@@ -265,6 +265,82 @@ def test_kernel_timing_reports_positive_times(dev):
         dc.dc_set_kernel_timing(False)
 
 
+# ---- Algorithm 2 as printed: mean over iterations of the per-iteration speedup -------------------------
+
+SPEEDUP_RTOL = 1e-6        # stated bar for float ratios; the two sides differ only in rounding order (~1e-15)
+
+
+@pytest.mark.parametrize("name,shape", [
+    ("tiny", {"T": 200}),
+    ("lognormal64", {"T": 60}),
+    ("lognormal64", {"T": 9, "N": 61}),
+    ("additive200", {"T": 12, "N": 203}),
+    ("extrapolation2048", {"T": 5}),
+    ("heterogeneous2048", {"T": 3, "N": 1000}),
+])
+def test_per_step_speedup_parity(name, shape, dev):
+    r = config(name).with_shape(**shape, K=24)
+    lat = host.generate(r)
+    rng = np.random.default_rng(2)
+    taus = extra_thresholds(host.tau_grid(r), rng)
+    taus = taus[taus > 0]                                       # tau = 0 with comm = 0 would divide by zero
+    got = dc.dc_speedup_per_step(to_dev(lat, dev), taus, r.comm)
+    ref = oracle.per_step_speedup(lat, taus, r.comm)
+    assert np.allclose(got, ref, rtol=SPEEDUP_RTOL, atol=0)
+    assert np.allclose(got, ref, rtol=1e-11, atol=0)            # what the arithmetic actually delivers
+    comm_t = rng.integers(0, 2 * r.comm + 1, size=r.T)
+    got = dc.dc_speedup_per_step(to_dev(lat, dev), taus, 0, comm_t)
+    ref = oracle.per_step_speedup(lat, taus, comm_t)
+    assert np.allclose(got, ref, rtol=SPEEDUP_RTOL, atol=0)
+    again = dc.dc_speedup_per_step(to_dev(lat, dev), taus, 0, comm_t)
+    assert np.array_equal(got, again)                           # fixed summation order
+
+
+@pytest.mark.parametrize("M", [1, 3, 12, 100, 300, 8, 64])
+def test_per_step_speedup_shapes(M, dev):
+    rng = np.random.default_rng(100 + M)
+    lat = rng.integers(1, 3000, size=(7, 9, M), dtype=np.int32)
+    totals = lat.sum(axis=2, dtype=np.int64)
+    taus = rng.integers(1, int(totals.max()) + 50, size=19)
+    got = dc.dc_speedup_per_step(to_dev(lat, dev), taus, 11)
+    assert np.allclose(got, oracle.per_step_speedup(lat, taus, 11), rtol=SPEEDUP_RTOL, atol=0)
+
+
+def test_per_step_speedup_many_trials_and_thresholds(dev):
+    """More trials than blocks, more thresholds than one pass holds."""
+    rng = np.random.default_rng(9)
+    lat = rng.integers(0, 4000, size=(1500, 24, 16), dtype=np.int32)
+    taus = rng.integers(1, 16 * 4000, size=2500)
+    got = dc.dc_speedup_per_step(to_dev(lat, dev), taus, 40)
+    ref = oracle.per_step_speedup(lat, taus, 40)
+    assert np.allclose(got, ref, rtol=SPEEDUP_RTOL, atol=0)
+    assert dc.dc_speedup_per_step(to_dev(lat, dev), [BIG], 40)[0] == pytest.approx(1.0, abs=1e-12)
+
+
+def test_per_step_speedup_errors_and_async(dev):
+    lat = np.ones((3, 4, 16), dtype=np.int32)
+    with pytest.raises(dc.DcError) as e:                        # tau = 0 and comm = 0: step time 0
+        dc.dc_speedup_per_step(to_dev(lat, dev), [0, 5], 0)
+    assert e.value.status == dc.DC_ERR_INVALID_ARG
+    with pytest.raises(dc.DcError):
+        dc.dc_speedup_per_step(to_dev(lat, dev), [5], 0, [1, -1, 1])
+    bad = lat.copy(); bad[2, 1, 5] = -3
+    with pytest.raises(dc.DcError) as e:
+        dc.dc_speedup_per_step(to_dev(bad, dev), [5], 1)
+    assert e.value.status == dc.DC_ERR_NEGATIVE_LATENCY
+    r = config("extrapolation2048").with_shape(T=6, K=40)
+    lat = host.generate(r)
+    taus = host.tau_grid(r)
+    lat_d, taus_d = to_dev(lat, dev), torch.from_numpy(taus).to(dev)
+    out = torch.zeros(taus.size, dtype=torch.float64, device=dev)
+    ws = torch.empty(dc.dc_speedup_workspace_bytes(r.T, r.N, r.M, taus.size), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    dc.dc_speedup_per_step_async(lat_d, taus_d, r.comm, None, out, ws, stream)
+    assert dc.dc_workspace_status(ws, stream) == dc.DC_OK
+    assert np.allclose(out.cpu().numpy(), oracle.per_step_speedup(lat, taus, r.comm), rtol=SPEEDUP_RTOL, atol=0)
+
+
 # ---- full sizes of the two 2048-worker workloads, as the benchmark launches them -----------------------
 
 @pytest.mark.parametrize("name", ["extrapolation2048", "heterogeneous2048"])
