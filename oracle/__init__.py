@@ -142,3 +142,65 @@ def per_step_speedup(lat: np.ndarray, taus, comm):
     if rc != OK:
         raise OracleError(rc)
     return out
+
+
+# ---- analytical model (Sections 4.2-4.4, Appendix C.2) ---------------------------------------------------
+
+EULER_GAMMA = 0.5772156649015329
+
+
+def moments(lat: np.ndarray):
+    """Exact (count, sum, sum of squares) of all latencies as Python ints, and (mean, variance) as floats.
+
+    mu and sigma^2 are the single-micro-batch statistics that the closed forms of Section 4.2-4.3 take
+    (population variance, one distribution for all workers: Appendix C.2, first assumption).
+    """
+    flat = np.ascontiguousarray(lat, dtype=np.int64).reshape(-1)
+    if flat.size == 0 or (flat < 0).any():
+        raise OracleError(ERR_INVALID_ARG if flat.size == 0 else ERR_NEGATIVE_LATENCY)
+    n, s, q = int(flat.size), 0, 0
+    for start in range(0, n, 1 << 20):                      # chunks small enough that int64 squares cannot overflow a sum
+        part = flat[start:start + (1 << 20)]
+        s += int(part.sum())
+        hi, lo = part >> 16, part & 0xFFFF                  # x^2 = hi^2*2^32 + 2*hi*lo*2^16 + lo^2, each sum < 2^63
+        q += (int((hi * hi).sum()) << 32) + (int((hi * lo).sum()) << 17) + int((lo * lo).sum())
+    mean = s / n
+    variance = (q * n - s * s) / (n * n)
+    return n, s, q, mean, variance
+
+
+def analytic_curves(mu: float, sigma2: float, N: int, M: int, taus, comm: int, mean_tmax: float | None = None):
+    """Closed-form estimates from (mu, sigma^2) of one micro-batch latency.
+
+    e_done[k] = sum_{m=1..M} Phi((tau_k - m mu) / sqrt(m sigma^2))        expected completed micro-batches per
+                                                                          worker (Section 4.3, CLT estimate of M~)
+    e_t       = sqrt(M sigma^2) ((1-g) PhiInv(1 - 1/N) + g PhiInv(1 - 1/(e N))) + M mu
+                                                                          expected compute time of the slowest of N
+                                                                          workers (Section 4.2; compute only, N >= 2)
+    s_eff[k]  = e_done[k]/M * (ET + T^c) / (min(tau_k, ET) + T^c)         Section 4.4's S_eff with the estimates plugged
+                in; ET = mean_tmax when given ("analytical given E[T]", Appendix C.2), else e_t.  T^c is added
+                to ET in the numerator because T = max_n T_n excludes T^c in Sections 4.2-4.4.
+    best_k    = argmax_k e_done[k] / (tau_k + T^c)                        Appendix C.2, "Finding tau*"; ties: largest tau
+    """
+    from scipy.special import ndtr, ndtri
+    taus = np.asarray(taus, dtype=np.int64)
+    if N < 2 or M < 1 or sigma2 < 0 or comm < 0 or (taus < 0).any():
+        raise OracleError(ERR_INVALID_ARG)
+    m = np.arange(1, M + 1, dtype=np.float64)
+    e_done = np.empty(taus.size, dtype=np.float64)
+    for k, tau in enumerate(taus):
+        if sigma2 > 0:
+            e_done[k] = ndtr((float(tau) - m * mu) / np.sqrt(m * sigma2)).sum()
+        else:
+            e_done[k] = float(np.count_nonzero(m * mu < float(tau)))
+    z = (1 - EULER_GAMMA) * ndtri(1 - 1 / N) + EULER_GAMMA * ndtri(1 - 1 / (np.e * N))
+    e_t = float(np.sqrt(M * sigma2) * z + M * mu)
+    et = e_t if mean_tmax is None else float(mean_tmax)
+    tau_f = taus.astype(np.float64)
+    s_eff = e_done / M * (et + comm) / (np.minimum(tau_f, et) + comm)
+    score = e_done / (tau_f + comm)
+    best = 0
+    for k in range(1, taus.size):
+        if score[k] > score[best] or (score[k] == score[best] and taus[k] > taus[best]):
+            best = k
+    return e_done, e_t, s_eff, best

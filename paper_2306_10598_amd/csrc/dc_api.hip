@@ -209,7 +209,8 @@ int compute_units() {
 }
 
 int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, int64_t comm,
-                    const int64_t* comm_per_trial_dev, double* out_seff_dev, unsigned char* ws, hipStream_t stream) {
+                    const int64_t* comm_per_trial_dev, double* out_seff_dev, unsigned char* ws, hipStream_t stream,
+                    bool timed) {
     dc::Plan p = plan;
     const uint32_t want = (uint32_t)compute_units() * DC_SCAN_BLOCKS_PER_CU;   // always fits: <= 57 KiB LDS, 4 waves each
     if (p.grid > want) p.grid = want;
@@ -218,13 +219,26 @@ int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* tau
     uint32_t* tau_u32 = reinterpret_cast<uint32_t*>(ws + p.off_tau_u32);
     uint32_t* pos = reinterpret_cast<uint32_t*>(ws + p.off_pos);
     double* partial = reinterpret_cast<double*>(ws + p.off_partial);
-    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, nullptr, 0, stream);
     const uint32_t chunks = (p.K + p.chunk - 1) / p.chunk;
+    if (timed) {
+        int rc = ensure_events(chunks);
+        if (rc) return rc;
+        g_timing.used_pairs = chunks;
+        g_timing.valid = false;
+        DC_HIP(hipEventRecord(g_timing.begin, stream));
+    }
+    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, nullptr, 0, stream);
     for (uint32_t c = 0; c < chunks; ++c) {
         const uint32_t chunk0 = c * p.chunk;
         const uint32_t kc = p.K - chunk0 < p.chunk ? p.K - chunk0 : p.chunk;
+        if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c], stream));
         dc::launch_trial_scan(p, lat, tau_u32 + chunk0, kc, comm_per_trial_dev, comm, partial, status, stream);
+        if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c + 1], stream));
         dc::launch_speedup_finalize(p, partial, kc, chunk0, pos, out_seff_dev, stream);
+    }
+    if (timed) {
+        DC_HIP(hipEventRecord(g_timing.end, stream));
+        g_timing.valid = true;
     }
     DC_HIP(hipGetLastError());
     return DC_OK;
@@ -347,8 +361,10 @@ int dc_speedup_per_step_async(const int32_t* lat, int64_t T, int64_t N, int64_t 
     dc::Plan p{};
     if (!make_trial_plan(T, N, M, K, ((uintptr_t)lat & 15u) == 0, &p)) return DC_ERR_INVALID_ARG;
     if (workspace_bytes < p.bytes) return DC_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
     return enqueue_speedup(p, lat, taus_dev, comm, comm_per_trial_dev, out_seff_dev,
-                           static_cast<unsigned char*>(workspace_dev), static_cast<hipStream_t>(stream));
+                           static_cast<unsigned char*>(workspace_dev), static_cast<hipStream_t>(stream),
+                           g_timing.enabled);
 }
 
 int dc_speedup_per_step(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus, int64_t K,
@@ -375,7 +391,7 @@ int dc_speedup_per_step(const int32_t* lat, int64_t T, int64_t N, int64_t M, con
     hipStream_t stream = nullptr;
     DC_HIP(hipMemcpy(taus_dev, taus, (size_t)K * 8, hipMemcpyHostToDevice));
     if (comm_dev) DC_HIP(hipMemcpy(comm_dev, comm_per_trial, (size_t)T * 8, hipMemcpyHostToDevice));
-    rc = enqueue_speedup(p, lat, taus_dev, comm, comm_dev, seff_dev, ws, stream);
+    rc = enqueue_speedup(p, lat, taus_dev, comm, comm_dev, seff_dev, ws, stream, g_timing.enabled);
     if (rc) return rc;
     DC_HIP(hipStreamSynchronize(stream));
     uint32_t flags = 0;

@@ -698,17 +698,29 @@ void dc_trial_scan_generic_kernel(const int32_t* __restrict__ lat, uint32_t T, u
     for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = sh.acc[i];
 }
 
-// out_seff[j] = (sum over blocks, in block order, of the block's sum for j's sorted position) / T
+// out_seff[j] = (sum of the per-block sums for j's sorted position) / T.  A block of 256 threads serves 32
+// thresholds; the range of blocks is cut into 8 fixed slices that are summed in order and then
+// combined in slice order, so the grouping of the float additions never changes between calls.
 __global__ __launch_bounds__(256)
 void dc_speedup_finalize_kernel(const double* __restrict__ partial, uint32_t blocks, uint32_t p2, uint32_t kc,
                                 uint32_t chunk0, const uint32_t* __restrict__ pos, uint32_t K, double trials,
                                 double* __restrict__ out_seff) {
-    const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= K) return;
-    const uint32_t p = pos[j];
-    if (p < chunk0 || p >= chunk0 + kc) return;
+    __shared__ double slice_sum[8][32];
+    const uint32_t jj = threadIdx.x & 31u, slice = threadIdx.x >> 5;
+    const uint32_t j = blockIdx.x * 32 + jj;
+    const uint32_t p = j < K ? pos[j] : 0xFFFFFFFFu;
+    const bool mine = p >= chunk0 && p < chunk0 + kc;
+    const uint32_t per = (blocks + 7) / 8;
+    const uint32_t b0 = slice * per, b1 = b0 + per < blocks ? b0 + per : blocks;
     double sum = 0.0;
-    for (uint32_t b = 0; b < blocks; ++b) sum += partial[(uint64_t)b * p2 + (p - chunk0)];
+    if (mine)
+        for (uint32_t b = b0; b < b1; ++b) sum += partial[(uint64_t)b * p2 + (p - chunk0)];
+    slice_sum[slice][jj] = sum;
+    __syncthreads();
+    if (slice != 0 || !mine) return;
+    sum = 0.0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) sum += slice_sum[q][jj];
     out_seff[j] = sum / trials;
 }
 
@@ -843,7 +855,7 @@ void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_ch
 
 void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, uint32_t chunk0, const uint32_t* pos,
                              double* out_seff, hipStream_t stream) {
-    hipLaunchKernelGGL(dc_speedup_finalize_kernel, dim3((p.K + 255) / 256), dim3(256), 0, stream, partial, p.grid,
+    hipLaunchKernelGGL(dc_speedup_finalize_kernel, dim3((p.K + 31) / 32), dim3(256), 0, stream, partial, p.grid,
                        p.p2, kc, chunk0, pos, p.K, (double)p.T, out_seff);
 }
 
