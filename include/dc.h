@@ -130,6 +130,34 @@ int dc_speedup_per_step_async(const int32_t* lat, int64_t T, int64_t N, int64_t 
                               const int64_t* comm_per_trial_dev, double* out_seff_dev,
                               void* workspace_dev, size_t workspace_bytes, void* stream);
 
+/* Exact first and second moments of all T*N*M latencies (one streaming pass): the mu and sigma^2 of a single
+ * micro-batch that the closed forms of Sections 4.2-4.3 take (one distribution for all workers, Appendix C.2,
+ * first assumption; population variance).
+ *   *out_sum = sum lat;  out_sumsq[0], out_sumsq[1] = low and high 64 bits of sum lat^2 (exact integers);
+ *   *out_mean = sum / n;  *out_variance = (sumsq*n - sum^2) / n^2,  n = T*N*M.
+ * lat: DEVICE.  All outputs HOST, each may be NULL.  DC_ERR_NEGATIVE_LATENCY if some lat < 0.
+ * Null stream, synchronous, cached workspace as dc_simulate. */
+int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M,
+               int64_t* out_sum, uint64_t* out_sumsq, double* out_mean, double* out_variance);
+
+/* Closed-form estimates from (mu, sigma2) of one micro-batch latency (Sections 4.2-4.4, Appendix C.2):
+ *   out_edone[k] = sum_{m=1..M} Phi((taus[k] - m*mu) / sqrt(m*sigma2))     expected completed micro-batches per
+ *                  worker, the CLT estimate of M~ (Section 4.3); for sigma2 = 0 the count #{m : m*mu < tau}
+ *   *out_et      = sqrt(M*sigma2) * ((1-g)*PhiInv(1 - 1/N) + g*PhiInv(1 - 1/(e*N))) + M*mu, g = Euler's constant:
+ *                  expected compute time of the slowest of N workers (Section 4.2; without T^c; needs N >= 2)
+ *   out_seff[k]  = out_edone[k]/M * (ET + comm) / (min(taus[k], ET) + comm)  Section 4.4's S_eff with the
+ *                  estimates plugged in, where ET = mean_tmax if mean_tmax >= 0 (the measured mean iteration
+ *                  time: "analytical given E[T]" of Appendix C.2), else *out_et.  comm is added to ET in the
+ *                  numerator because T = max_n T_n excludes T^c in Sections 4.2-4.4.
+ *   *out_best_k  = argmax_k out_edone[k] / (taus[k] + comm)                  Appendix C.2, "Finding tau*";
+ *                  exact float ties go to the largest tau, then the lowest index
+ * The sum over m runs on the GPU (fixed order); everything else is O(K) host arithmetic.  taus: HOST, K int64 >= 0.
+ * out_edone: HOST K doubles (required if K > 0); out_seff, out_et, out_best_k may be NULL.
+ * mu >= 0, sigma2 >= 0 finite; N >= 2; else DC_ERR_INVALID_ARG. */
+int dc_analytic_curves(double mu, double sigma2, int64_t N, int64_t M, const int64_t* taus, int64_t K,
+                       int64_t comm, double mean_tmax,
+                       double* out_edone, double* out_seff, double* out_et, int64_t* out_best_k);
+
 /* Optional kernel timing for benchmarks.  When enabled, every dc_simulate / dc_simulate_async
  * brackets its streaming kernel (the single pass over lat) and the whole enqueued sequence with
  * HIP events on the stream it runs on.  dc_last_kernel_ms waits for those events and returns the

@@ -22,6 +22,7 @@ DC_MAX_THRESHOLDS = 65536
 EXPORTS = (
     "dc_simulate", "dc_workspace_bytes", "dc_simulate_async", "dc_workspace_status", "dc_select_tau",
     "dc_speedup_per_step", "dc_speedup_workspace_bytes", "dc_speedup_per_step_async",
+    "dc_moments", "dc_analytic_curves",
     "dc_set_kernel_timing", "dc_last_kernel_ms", "dc_status_string", "dc_last_device_error", "dc_shutdown",
 )
 
@@ -63,6 +64,10 @@ def _load():
     lib.dc_speedup_workspace_bytes.restype = sz
     lib.dc_speedup_per_step_async.argtypes = [p, i64, i64, i64, p, i64, i64, p, p, p, sz, p]
     lib.dc_speedup_per_step_async.restype = ctypes.c_int
+    lib.dc_moments.argtypes = [p, i64, i64, i64, p, p, p, p]
+    lib.dc_moments.restype = ctypes.c_int
+    lib.dc_analytic_curves.argtypes = [ctypes.c_double, ctypes.c_double, i64, i64, p, i64, i64, ctypes.c_double, p, p, p, p]
+    lib.dc_analytic_curves.restype = ctypes.c_int
     lib.dc_set_kernel_timing.argtypes = [ctypes.c_int]
     lib.dc_set_kernel_timing.restype = ctypes.c_int
     lib.dc_last_kernel_ms.argtypes = [p, p]
@@ -203,6 +208,35 @@ def dc_speedup_per_step_async(lat, taus_dev, comm: int, comm_per_trial_dev, out_
                                            per_ptr, out_seff_dev.data_ptr(), workspace.data_ptr(), workspace.numel(),
                                            handle)
     _check(rc, "dc_speedup_per_step_async")
+
+
+def dc_moments(lat):
+    """(sum, sum of squares) as exact Python ints and (mean, variance) as floats of a GPU int32 tensor."""
+    lat = _device_tensor(lat, "int32", "lat")
+    if lat.dim() != 3:
+        raise TypeError("lat must have shape [T][N][M]")
+    T, N, M = lat.shape
+    total = ctypes.c_int64(0)
+    sq = (ctypes.c_uint64 * 2)(0, 0)
+    mean, var = ctypes.c_double(0), ctypes.c_double(0)
+    rc = _load().dc_moments(lat.data_ptr(), T, N, M, ctypes.byref(total), sq, ctypes.byref(mean), ctypes.byref(var))
+    _check(rc, "dc_moments")
+    return int(total.value), (int(sq[1]) << 64) | int(sq[0]), float(mean.value), float(var.value)
+
+
+def dc_analytic_curves(mu: float, sigma2: float, N: int, M: int, taus, comm: int, mean_tmax=None):
+    """(e_done[K], e_t, s_eff[K], best_k): the closed-form estimates; mean_tmax=None uses the modelled E[T]."""
+    taus = np.ascontiguousarray(taus, dtype=np.int64)
+    K = taus.size
+    e_done = np.empty(K, dtype=np.float64)
+    s_eff = np.empty(K, dtype=np.float64)
+    e_t = ctypes.c_double(0)
+    best = ctypes.c_int64(-1)
+    rc = _load().dc_analytic_curves(float(mu), float(sigma2), N, M, taus.ctypes.data, K, int(comm),
+                                    -1.0 if mean_tmax is None else float(mean_tmax),
+                                    e_done.ctypes.data, s_eff.ctypes.data, ctypes.byref(e_t), ctypes.byref(best))
+    _check(rc, "dc_analytic_curves")
+    return e_done, float(e_t.value), s_eff, int(best.value)
 
 
 def dc_set_kernel_timing(enable: bool) -> None:

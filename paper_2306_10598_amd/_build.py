@@ -7,7 +7,7 @@ from pathlib import Path
 HERE = Path(__file__).resolve().parent
 ROOT = HERE.parent
 LIB_PATH = HERE / "libdc.so"
-SOURCES = [HERE / "csrc" / "dc_api.hip", HERE / "csrc" / "dc_kernels.hip"]
+SOURCES = [HERE / "csrc" / "dc_api.hip", HERE / "csrc" / "dc_kernels.hip", HERE / "csrc" / "dc_analytic.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

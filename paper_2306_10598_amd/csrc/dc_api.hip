@@ -402,6 +402,105 @@ int dc_speedup_per_step(const int32_t* lat, int64_t T, int64_t N, int64_t M, con
     return DC_OK;
 }
 
+int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t* out_sum, uint64_t* out_sumsq,
+               double* out_mean, double* out_variance) {
+    if (!lat || T < 1 || N < 1 || M < 1 || ((uintptr_t)lat & 3u)) return DC_ERR_INVALID_ARG;
+    if ((long double)T * (long double)N * (long double)M >= 4.6e18L) return DC_ERR_INVALID_ARG;
+    const uint64_t n = (uint64_t)T * (uint64_t)N * (uint64_t)M;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const uint32_t grid = (uint32_t)compute_units() * DC_SCAN_BLOCKS_PER_CU;
+    const size_t partial_bytes = align256((size_t)grid * 4 * 8);
+    int rc = ensure_cache(256 + 256 + partial_bytes);
+    if (rc) return rc;
+    uint32_t* status = reinterpret_cast<uint32_t*>(g_cache);
+    unsigned long long* result = reinterpret_cast<unsigned long long*>(g_cache + 256);
+    unsigned long long* partial = reinterpret_cast<unsigned long long*>(g_cache + 512);
+    hipStream_t stream = nullptr;
+    dc::launch_moments(lat, n, grid, partial, result, status, stream);
+    DC_HIP(hipGetLastError());
+    unsigned long long host[4] = {0, 0, 0, 0};
+    DC_HIP(hipMemcpy(host, result, sizeof(host), hipMemcpyDeviceToHost));
+    if (host[3] & 0x80000000ull) return DC_ERR_NEGATIVE_LATENCY;
+    if (out_sum) *out_sum = (int64_t)host[0];
+    if (out_sumsq) { out_sumsq[0] = host[1]; out_sumsq[1] = host[2]; }
+    const unsigned __int128 sq = ((unsigned __int128)host[2] << 64) | host[1];
+    if (out_mean) *out_mean = (double)host[0] / (double)n;
+    if (out_variance) {
+        // (sumsq*n - sum^2) / n^2 with the numerator exact in 128 bits when it fits, else in long double
+        const long double nl = (long double)n;
+        if (sq <= ((unsigned __int128)1 << 126) / n) {
+            const unsigned __int128 num = sq * n - (unsigned __int128)host[0] * host[0];
+            *out_variance = (double)((long double)num / (nl * nl));
+        } else {
+            const long double m = (long double)host[0] / nl;
+            *out_variance = (double)((long double)sq / nl - m * m);
+        }
+    }
+    return DC_OK;
+}
+
+namespace {
+
+// Standard normal quantile: a textbook starting value (rational approximation in t = sqrt(-2 ln q)),
+// then Newton steps on the upper tail 0.5*erfc(x/sqrt 2) = q, which converge to double precision.
+double normal_quantile(double p) {
+    if (!(p > 0.0 && p < 1.0)) return p <= 0.0 ? -INFINITY : INFINITY;
+    const bool upper = p > 0.5;
+    const double q = upper ? 1.0 - p : p;                    // tail mass, <= 0.5
+    if (q == 0.5) return 0.0;
+    const double t = std::sqrt(-2.0 * std::log(q));
+    double x = t - (2.30753 + 0.27061 * t) / (1.0 + 0.99229 * t + 0.04481 * t * t);
+    for (int it = 0; it < 8; ++it) {
+        const double tail = 0.5 * std::erfc(x * 0.70710678118654752440);
+        const double pdf = 0.39894228040143267794 * std::exp(-0.5 * x * x);
+        const double step = (tail - q) / pdf;               // d(tail)/dx = -pdf
+        x += step;
+        if (std::fabs(step) <= 1e-16 * std::fabs(x)) break;
+    }
+    return upper ? x : -x;
+}
+
+}  // namespace
+
+int dc_analytic_curves(double mu, double sigma2, int64_t N, int64_t M, const int64_t* taus, int64_t K, int64_t comm,
+                       double mean_tmax, double* out_edone, double* out_seff, double* out_et, int64_t* out_best_k) {
+    if (!(mu >= 0.0) || !(sigma2 >= 0.0) || !std::isfinite(mu) || !std::isfinite(sigma2)) return DC_ERR_INVALID_ARG;
+    if (N < 2 || M < 1 || M >= ((int64_t)1 << 31) || K < 0 || K > DC_MAX_THRESHOLDS || comm < 0) return DC_ERR_INVALID_ARG;
+    const double gamma = 0.57721566490153286061;
+    const double z = (1.0 - gamma) * normal_quantile(1.0 - 1.0 / (double)N) +
+                     gamma * normal_quantile(1.0 - 1.0 / (std::exp(1.0) * (double)N));
+    const double et_model = std::sqrt((double)M * sigma2) * z + (double)M * mu;
+    if (out_et) *out_et = et_model;
+    if (K == 0) return DC_OK;
+    if (!taus || !out_edone) return DC_ERR_INVALID_ARG;
+    for (int64_t k = 0; k < K; ++k)
+        if (taus[k] < 0) return DC_ERR_INVALID_ARG;
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const size_t io = align256((size_t)K * 8);
+    int rc = ensure_cache(2 * io);
+    if (rc) return rc;
+    int64_t* taus_dev = reinterpret_cast<int64_t*>(g_cache);
+    double* edone_dev = reinterpret_cast<double*>(g_cache + io);
+    hipStream_t stream = nullptr;
+    DC_HIP(hipMemcpy(taus_dev, taus, (size_t)K * 8, hipMemcpyHostToDevice));
+    dc::launch_expected_done(taus_dev, (uint32_t)K, (uint32_t)M, mu, sigma2, edone_dev, stream);
+    DC_HIP(hipGetLastError());
+    DC_HIP(hipMemcpy(out_edone, edone_dev, (size_t)K * 8, hipMemcpyDeviceToHost));
+
+    const double et = mean_tmax >= 0.0 ? mean_tmax : et_model;
+    int64_t best = 0;
+    double best_score = -1.0;
+    for (int64_t k = 0; k < K; ++k) {
+        const double tau = (double)taus[k];
+        if (out_seff) out_seff[k] = out_edone[k] / (double)M * (et + (double)comm) / ((tau < et ? tau : et) + (double)comm);
+        const double score = out_edone[k] / (tau + (double)comm);     // Appendix C.2, "Finding tau*"
+        if (k == 0 || score > best_score || (score == best_score && taus[k] > taus[best])) { best = k; best_score = score; }
+    }
+    if (out_best_k) *out_best_k = best;
+    return DC_OK;
+}
+
 int dc_select_tau(const int64_t* step_sum, const int64_t* done_sum, const int64_t* taus, int64_t K, int64_t T,
                   int64_t N, int64_t M, int64_t base_step_sum, double* out_thr, double* out_seff,
                   int64_t* out_best_k) {

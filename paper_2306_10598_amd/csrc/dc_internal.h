@@ -76,6 +76,10 @@ void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_ch
 void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, uint32_t chunk0, const uint32_t* pos,
                              double* out_seff, hipStream_t stream);
 size_t trial_scan_lds_bytes(const Plan& p);
+void launch_moments(const int32_t* lat, uint64_t n, uint32_t grid, unsigned long long* partial,
+                    unsigned long long* result, uint32_t* status, hipStream_t stream);
+void launch_expected_done(const int64_t* taus, uint32_t K, uint32_t M, double mu, double sigma2, double* out,
+                          hipStream_t stream);
 size_t scan_lds_bytes(const Plan& p);
 int scan_blocks_per_cu(const Plan& p);
 

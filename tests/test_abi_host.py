@@ -67,3 +67,16 @@ def test_select_tau_rejects_bad_input():
     assert e.value.status == dc.DC_ERR_INVALID_ARG
     with pytest.raises(dc.DcError):
         dc.dc_select_tau([], [], [], 1, 1, 1)
+
+
+def test_modelled_iteration_time_needs_no_gpu_and_matches_oracle():
+    """With K = 0 dc_analytic_curves only evaluates the normal-maximum formula (host arithmetic)."""
+    for N in (2, 3, 64, 200, 2048, 10**6):
+        for M, mu, s2 in ((1, 0.0, 1.0), (32, 100000.0, 1.0e8), (256, 108000.0, 1.2e9)):
+            _, e_t, _, _ = dc.dc_analytic_curves(mu, s2, N, M, [], 0)
+            _, ref, _, _ = oracle.analytic_curves(mu, s2, N, M, [1], 0)
+            assert e_t == pytest.approx(ref, rel=1e-13, abs=1e-12), (N, M)
+    with pytest.raises(dc.DcError):
+        dc.dc_analytic_curves(1.0, 1.0, 1, 4, [], 0)
+    with pytest.raises(dc.DcError):
+        dc.dc_analytic_curves(1.0, -1.0, 8, 4, [], 0)

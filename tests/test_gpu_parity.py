@@ -341,6 +341,52 @@ def test_per_step_speedup_errors_and_async(dev):
     assert np.allclose(out.cpu().numpy(), oracle.per_step_speedup(lat, taus, r.comm), rtol=SPEEDUP_RTOL, atol=0)
 
 
+# ---- analytical side: exact moments, closed-form curves ----------------------------------------------------
+
+@pytest.mark.parametrize("shape", [(3, 5, 7), (40, 64, 128), (9, 200, 64), (2, 2048, 256), (1, 1, 1), (5, 33, 1000)])
+def test_moments_are_exact(shape, dev):
+    rng = np.random.default_rng(sum(shape))
+    top = (2**31 - 1) // shape[2]
+    lat = rng.integers(0, top + 1, size=shape, dtype=np.int32)
+    n, s, q, mean, var = oracle.moments(lat)
+    gs, gq, gmean, gvar = dc.dc_moments(to_dev(lat, dev))
+    assert (gs, gq) == (s, q)
+    assert gmean == pytest.approx(mean, rel=1e-14) and gvar == pytest.approx(var, rel=1e-12)
+
+
+def test_moments_of_a_workload_and_errors(dev):
+    from dc_workloads import device
+    r = config("heterogeneous2048").with_shape(T=24)
+    gs, gq, gmean, gvar = dc.dc_moments(device.generate(r))
+    n, s, q, mean, var = oracle.moments(host.generate(r))
+    assert (gs, gq) == (s, q) and gvar == pytest.approx(var, rel=1e-12)
+    big = np.full((2, 3, 4), 2**31 - 1, dtype=np.int32)                    # squares overflow 64 bits
+    assert dc.dc_moments(to_dev(big, dev))[:2] == (24 * (2**31 - 1), 24 * (2**31 - 1) ** 2)
+    bad = np.ones((2, 3, 4), dtype=np.int32); bad[1, 1, 1] = -7
+    with pytest.raises(dc.DcError) as e:
+        dc.dc_moments(to_dev(bad, dev))
+    assert e.value.status == dc.DC_ERR_NEGATIVE_LATENCY
+    flat = torch.ones(4 * 5 * 64 + 1, dtype=torch.int32, device=dev)       # unaligned tensor
+    assert dc.dc_moments(flat[1:].view(4, 5, 64))[:2] == (1280, 1280)
+
+
+@pytest.mark.parametrize("name", ["lognormal64", "extrapolation2048", "heterogeneous2048"])
+def test_analytic_curves_parity(name, dev):
+    r = config(name).with_shape(T=6)
+    lat = host.generate(r)
+    n, s, q, mean, var = oracle.moments(lat)
+    taus = np.concatenate([host.tau_grid(r), [0, BIG, int(r.M * mean / 2)]]).astype(np.int64)
+    for mean_tmax in (None, 1.01 * r.M * mean):
+        e_done, e_t, s_eff, best = dc.dc_analytic_curves(mean, var, r.N, r.M, taus, r.comm, mean_tmax)
+        o_done, o_t, o_seff, o_best = oracle.analytic_curves(mean, var, r.N, r.M, taus, r.comm, mean_tmax)
+        assert np.allclose(e_done, o_done, rtol=1e-6, atol=0) and np.allclose(e_done, o_done, rtol=1e-11, atol=1e-13)
+        assert e_t == pytest.approx(o_t, rel=1e-12)
+        assert np.allclose(s_eff, o_seff, rtol=1e-6, atol=0)
+        assert best == o_best
+    e_done, _, _, _ = dc.dc_analytic_curves(10.0, 0.0, 4, 5, [10, 11, 30, 31, 1000], 1)
+    assert e_done.tolist() == [0.0, 1.0, 2.0, 3.0, 5.0]
+
+
 # ---- full sizes of the two 2048-worker workloads, as the benchmark launches them -----------------------
 
 @pytest.mark.parametrize("name", ["extrapolation2048", "heterogeneous2048"])
