@@ -158,15 +158,57 @@ def bench_per_step(args, r, lat, taus, taus_dev, stream) -> int:
     return 0
 
 
+def bench_analytic(args, r, lat, taus) -> int:
+    """Moments pass + closed-form curves; the roofline is the moments kernel's (one read of lat)."""
+    import numpy as np
+    import torch
+
+    import paper_2306_10598_amd as dc
+    K = taus.size
+
+    def step():
+        _, _, mean, var = dc.dc_moments(lat)
+        return dc.dc_analytic_curves(mean, var, r.N, r.M, taus, r.comm)
+
+    dc.dc_set_kernel_timing(True)
+    for _ in range(args.warmup):
+        step()
+    kernel_ms = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dc.dc_moments(lat)
+        kernel_ms.append(dc.dc_last_kernel_ms()[0])
+        _, _, mean, var = dc.dc_moments(lat)
+        e_done, e_t, s_eff, best = dc.dc_analytic_curves(mean, var, r.N, r.M, taus, r.comm)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / 2.0                     # two moments passes per loop turn
+    dc.dc_set_kernel_timing(False)
+    ms = float(np.mean(kernel_ms))
+    achieved = 4.0 * r.elements / (ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": METRIC, "value": float(r.elements) * K / (wall / args.steps), "unit": "evals/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * wall / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"{r.name}: T={r.T} N={r.N} M={r.M} K={K}", "path": "moments + closed-form curves",
+                   "mu_us": mean, "sigma_us": var ** 0.5, "modelled_iteration_time_us": e_t,
+                   "best_tau_us": int(taus[best])},
+        "roofline": {"bound": "hbm", "kernel": "dc_moments_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "kernel_ms": ms,
+                     "algorithmic_bytes": 4.0 * r.elements}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="heterogeneous2048")
-    ap.add_argument("--path", choices=("sums", "per-step"), default="sums",
+    ap.add_argument("--path", choices=("sums", "per-step", "analytic"), default="sums",
                     help="sums: dc_simulate_async + dc_select_tau (the headline path); "
-                         "per-step: dc_speedup_per_step_async, Algorithm 2's mean of per-iteration speedups")
+                         "per-step: dc_speedup_per_step_async, Algorithm 2's mean of per-iteration speedups; "
+                         "analytic: dc_moments + dc_analytic_curves, the closed-form curves")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 4 GiB device-to-device copy instead (scale factor for HBM byte counters)")
@@ -210,6 +252,8 @@ def main() -> int:
 
     if args.path == "per-step":
         return bench_per_step(args, r, lat, taus, taus_dev, stream)
+    if args.path == "analytic":
+        return bench_analytic(args, r, lat, taus)
 
     def step():
         dc.dc_simulate_async(lat, taus_dev, r.comm, out_step, out_done, ws, stream)

@@ -416,7 +416,21 @@ int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t* out
     unsigned long long* result = reinterpret_cast<unsigned long long*>(g_cache + 256);
     unsigned long long* partial = reinterpret_cast<unsigned long long*>(g_cache + 512);
     hipStream_t stream = nullptr;
+    const bool timed = g_timing.enabled;
+    if (timed) {
+        rc = ensure_events(1);
+        if (rc) return rc;
+        g_timing.used_pairs = 1;
+        g_timing.valid = false;
+        DC_HIP(hipEventRecord(g_timing.begin, stream));
+        DC_HIP(hipEventRecord(g_timing.scan[0], stream));
+    }
     dc::launch_moments(lat, n, grid, partial, result, status, stream);
+    if (timed) {
+        DC_HIP(hipEventRecord(g_timing.scan[1], stream));
+        DC_HIP(hipEventRecord(g_timing.end, stream));
+        g_timing.valid = true;
+    }
     DC_HIP(hipGetLastError());
     unsigned long long host[4] = {0, 0, 0, 0};
     DC_HIP(hipMemcpy(host, result, sizeof(host), hipMemcpyDeviceToHost));
