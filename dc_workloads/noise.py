@@ -1,0 +1,71 @@
+"""Workloads with the paper's own additive-noise models (synthetic; same integer generator as spec.py).
+
+  simulated_delay(...)   Appendix B.1: every accumulation takes t + mu*eps, eps = min(Z/alpha, beta),
+                         Z ~ LogNormal(4, 1), alpha = 2 e^4.5, beta = 5.5 (mean x1.5, at most x6.5).
+                         The undisturbed compute time t is taken constant (= mu); the appendix does not give
+                         its distribution.
+  additive_noise(...)    Appendix C.3: 12 accumulations of 0.45 s + eps, eps of mean 0.225 s and a chosen
+                         variance from one of five families (lognormal, normal, bernoulli, exponential, gamma),
+                         parameters derived from (mean, variance) as in the appendix's tables.
+Input preparation only; nothing of the simulated method is computed here.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+from scipy.special import gammaincinv, ndtri
+
+from .spec import Recipe, prob_to_thresh, quantile_tables
+
+FAMILIES = ("lognormal", "normal", "bernoulli", "exponential", "gamma")
+
+
+def simulated_delay(T: int, N: int, M: int = 12, base_us: int = 450_000, K: int = 128, comm_us: int = 100_000,
+                    seed: int = 0) -> Recipe:
+    alpha, beta = 2.0 * math.exp(4.5), 5.5
+
+    def q(u):
+        eps = np.minimum(np.exp(4.0 + ndtri(u)) / alpha, beta)
+        return base_us * (1.0 + eps)
+
+    return Recipe("simulated_delay", T=T, N=N, M=M, K=K, comm=comm_us, grid="pct", value=quantile_tables(q), seed=seed,
+                  description=f"round({base_us} * (1 + min(LogNormal(4,1)/(2e^4.5), 5.5))) us")
+
+
+def noise_parameters(family: str, mean: float, variance: float) -> dict:
+    """Distribution parameters (seconds) that give the requested mean and variance."""
+    if family == "lognormal":
+        s2 = math.log(1.0 + variance / mean ** 2)
+        return {"mu_log": math.log(mean) - s2 / 2.0, "sigma_log": math.sqrt(s2)}
+    if family == "normal":
+        return {"mu": mean, "sigma": math.sqrt(variance)}
+    if family == "bernoulli":                       # a * Br(p): mean a p, variance a^2 p (1-p)
+        p = mean ** 2 / (variance + mean ** 2)
+        return {"amplitude": mean / p, "p": p}
+    if family == "exponential":                     # one parameter: the appendix matches the variance (rate 1/sqrt(var))
+        return {"rate": 1.0 / math.sqrt(variance)}
+    if family == "gamma":
+        return {"shape": mean ** 2 / variance, "rate": mean / variance}
+    raise ValueError(family)
+
+
+def additive_noise(family: str, T: int, N: int, variance: float = 0.05, mean: float = 0.225, M: int = 12,
+                   base_s: float = 0.45, K: int = 128, comm_us: int = 100_000, seed: int = 0) -> Recipe:
+    """Accumulations of base_s + eps seconds, in integer microseconds; eps >= -base_s (latencies stay >= 0)."""
+    prm = noise_parameters(family, mean, variance)
+    base_us = base_s * 1e6
+    kw = {}
+    if family == "lognormal":
+        q = lambda u: base_us + 1e6 * np.exp(prm["mu_log"] + prm["sigma_log"] * ndtri(u))
+    elif family == "normal":
+        q = lambda u: base_us + 1e6 * (prm["mu"] + prm["sigma"] * ndtri(u))
+    elif family == "bernoulli":                     # exact two-point law through the spike mechanism
+        q = lambda u: np.full_like(u, base_us)
+        kw = {"spike_thresh": prob_to_thresh(prm["p"]), "spike_add": int(round(prm["amplitude"] * 1e6))}
+    elif family == "exponential":
+        q = lambda u: base_us - 1e6 * np.log1p(-u) / prm["rate"]
+    else:
+        q = lambda u: base_us + 1e6 * gammaincinv(prm["shape"], u) / prm["rate"]
+    return Recipe(f"additive_{family}", T=T, N=N, M=M, K=K, comm=comm_us, grid="pct", value=quantile_tables(q),
+                  seed=seed, description=f"{base_s} s + {family} noise (mean {mean} s, variance {variance} s^2), us", **kw)

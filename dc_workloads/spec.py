@@ -108,9 +108,11 @@ def quantile_tables(qfun: Callable[[np.ndarray], np.ndarray]) -> QuantileTables:
     hi[0] = main[MAIN_CELLS - TAIL_CELLS]
     lo = np.maximum.accumulate(np.minimum(lo, lo[-1]))
     hi = np.maximum.accumulate(np.maximum(hi, hi[0]))
-    for tab in (main, lo, hi):
+    # difference * fraction stays below 2^63 (the main table is only used in cells 16 .. 65519)
+    used = main[TAIL_CELLS:MAIN_CELLS - TAIL_CELLS + 1]
+    for tab, frac_bits in ((used, 32), (lo, 24), (hi, 24)):
         assert tab.min() >= 0 and tab.max() < (1 << 38)
-        assert np.diff(tab).max(initial=0) < (1 << 31)
+        assert np.diff(tab).max(initial=0) < (1 << (63 - frac_bits))
     return QuantileTables(main=main, lo=lo, hi=hi)
 
 

@@ -1,0 +1,66 @@
+#!/usr/bin/env python3
+"""Scale sweep with the paper's additive-noise models (Appendix B.1 and C.3) on one GPU.
+
+For each noise family and worker count N it generates synthetic latencies in HBM, runs the library
+(dc_simulate, dc_moments, dc_select_tau, dc_analytic_curves) and prints
+  E[T]/E[T_i]   mean iteration time of N workers over the mean time of one worker (the ratio the appendix tabulates;
+                the appendix does not state its N, so the sweep shows where each tabulated value would fall),
+  tau*, S_eff(tau*), the completed fraction at tau*, and the closed-form S_eff at the same tau.
+
+  python noise_study.py [--families lognormal normal ...] [--workers 8 64 512 2048] [--variance 0.05] [--delay]
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+PAPER_RATIO = {"lognormal": 1.496, "normal": 1.302, "bernoulli": 1.283, "exponential": 1.386, "gamma": 1.39}
+BIG = 1 << 40
+
+
+def study(recipe):
+    import numpy as np
+
+    import paper_2306_10598_amd as dc
+    from dc_workloads import device
+    lat = device.generate(recipe)
+    taus = np.append(device.tau_grid(recipe, lat), BIG)
+    step, done = dc.dc_simulate(lat, taus, recipe.comm)
+    _, _, mean, var = dc.dc_moments(lat)
+    T, N, M = recipe.T, recipe.N, recipe.M
+    base = int(step[-1])
+    thr, seff, best = dc.dc_select_tau(step, done, taus, T, N, M, base)
+    mean_tmax = (base - T * recipe.comm) / T
+    _, _, ana, _ = dc.dc_analytic_curves(mean, var, N, M, taus, recipe.comm, mean_tmax)
+    return {"ratio": mean_tmax / (M * mean), "tau": int(taus[best]), "seff": float(seff[best]),
+            "completed": float(done[best]) / (T * N * M), "analytic_seff": float(ana[best])}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--families", nargs="*", default=["lognormal", "normal", "bernoulli", "exponential", "gamma"])
+    ap.add_argument("--workers", nargs="*", type=int, default=[8, 32, 128, 512, 2048])
+    ap.add_argument("--variance", type=float, default=0.05)
+    ap.add_argument("--elements", type=int, default=1 << 26, help="approximate T*N*M per point")
+    ap.add_argument("--delay", action="store_true", help="also sweep the simulated-delay model of Appendix B.1")
+    args = ap.parse_args()
+    from dc_workloads import noise
+    print(f"{'noise':<16}{'N':>6}{'T':>8}{'E[T]/E[T_i]':>13}{'paper':>8}{'tau* us':>12}{'S_eff':>8}{'done':>8}{'closed form':>13}")
+    for family in args.families + (["delay"] if args.delay else []):
+        for N in args.workers:
+            T = max(16, args.elements // (N * 12))
+            r = noise.simulated_delay(T, N) if family == "delay" else noise.additive_noise(family, T, N, args.variance)
+            s = study(r)
+            ref = PAPER_RATIO.get(family) if abs(args.variance - 0.05) < 1e-12 else None
+            print(f"{family:<16}{N:>6}{T:>8}{s['ratio']:>13.3f}{(f'{ref:.3f}' if ref else '-'):>8}{s['tau']:>12}"
+                  f"{s['seff']:>8.3f}{s['completed']:>8.3f}{s['analytic_seff']:>13.3f}")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

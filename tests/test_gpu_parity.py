@@ -387,6 +387,22 @@ def test_analytic_curves_parity(name, dev):
     assert e_done.tolist() == [0.0, 1.0, 2.0, 3.0, 5.0]
 
 
+# ---- the paper's own noise models as workloads ----------------------------------------------------------------
+
+@pytest.mark.parametrize("family", ["delay", "lognormal", "normal", "bernoulli", "exponential", "gamma"])
+def test_noise_model_workloads_parity(family, dev):
+    from dc_workloads import device, noise
+    r = noise.simulated_delay(300, 64) if family == "delay" else noise.additive_noise(family, 300, 64)
+    lat = host.generate(r)
+    assert np.array_equal(device.generate(r).cpu().numpy(), lat)
+    taus = np.append(host.tau_grid(r), BIG)
+    assert np.array_equal(device.tau_grid(r, device.generate(r)), taus[:-1])
+    step, done = check(lat, taus, r.comm, dev)                  # M = 12: the general kernel
+    assert np.allclose(dc.dc_speedup_per_step(to_dev(lat, dev), taus, r.comm),
+                       oracle.per_step_speedup(lat, taus, r.comm), rtol=SPEEDUP_RTOL, atol=0)
+    assert dc.dc_moments(to_dev(lat, dev))[:2] == oracle.moments(lat)[1:3]
+
+
 # ---- full sizes of the two 2048-worker workloads, as the benchmark launches them -----------------------
 
 @pytest.mark.parametrize("name", ["extrapolation2048", "heterogeneous2048"])

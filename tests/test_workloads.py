@@ -100,3 +100,34 @@ def test_largest_latency_leaves_room_for_int32_worker_totals():
         smax = 65536 if scale is None else int(scale.max())
         top = ((int(r.value.hi[-1]) * smax * r.spike_mul + (1 << 23)) >> 24) + r.add + r.spike_add
         assert max(top, r.clip_min) <= (2 ** 31 - 1) // r.M, name
+
+
+# ---- the paper's own noise models (Appendix B.1, C.3) ---------------------------------------------------
+
+def test_simulated_delay_scales_mean_and_bounds_the_tail():
+    from dc_workloads import noise
+    r = noise.simulated_delay(T=40, N=64, M=12, base_us=450_000)
+    x = host.generate(r).astype(np.float64).reshape(-1) / 450_000
+    assert x.min() >= 1.0 and x.max() <= 6.5 + 1e-6
+    # eps = min(Z/alpha, 5.5): E[Z/alpha] = 0.5, the bound removes a little of it
+    assert 1.45 < x.mean() < 1.5
+    assert np.mean(x > 6.49) < 0.01
+
+
+@pytest.mark.parametrize("family", ["lognormal", "normal", "bernoulli", "exponential", "gamma"])
+def test_additive_noise_families_have_the_requested_moments(family):
+    from dc_workloads import noise
+    r = noise.additive_noise(family, T=60, N=64, variance=0.05)
+    eps = host.generate(r).astype(np.float64).reshape(-1) / 1e6 - 0.45
+    n = eps.size
+    want_mean = math.sqrt(0.05) if family == "exponential" else 0.225     # one-parameter family: rate 1/sqrt(var)
+    assert abs(eps.mean() - want_mean) < 5 * math.sqrt(0.05 / n) + 2e-3
+    assert abs(eps.var() - 0.05) < 0.004
+    prm = noise.noise_parameters(family, 0.225, 0.05)
+    if family == "lognormal":                      # the appendix quotes LN(-1.84, 0.83)
+        assert abs(prm["mu_log"] + 1.84) < 0.01 and abs(prm["sigma_log"] - 0.83) < 0.005
+    if family == "gamma":                          # gamma(alpha = 1, beta = 4.5)
+        assert abs(prm["shape"] - 1.0) < 0.02 and abs(prm["rate"] - 4.5) < 0.01
+    if family == "bernoulli":                      # 0.45 Br(0.5)
+        assert abs(prm["amplitude"] - 0.45) < 0.003 and abs(prm["p"] - 0.5) < 0.01
+        assert set(np.unique(np.round(eps, 3))) <= {0.0, round(prm["amplitude"], 3)}
