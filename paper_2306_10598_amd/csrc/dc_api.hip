@@ -35,8 +35,8 @@ uint32_t next_pow2_above(uint32_t n) {   // smallest power of two > n, at least 
     return p;
 }
 
-bool vec4_shape(int64_t M) {
-    return M >= 4 && M <= 256 && (M & (M - 1)) == 0;
+bool vec4_shape(int64_t M) {                 // rows of 1..64 lanes with 16-byte loads
+    return M >= 4 && M <= 256 && (M & 3) == 0;
 }
 
 // Returns false when the sizes are outside what the library handles.

@@ -63,6 +63,39 @@ __device__ __forceinline__ uint32_t segmented_inclusive_scan(uint32_t v, uint32_
 
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 
+// How the rows of lat sit in a wave's 16-byte loads.  The kernels are instantiated for L = 1,2,4,...,64
+// lanes per row (M = 4L a power of two: every lane used, rows aligned to the DPP rows) and once more,
+// as L = 0, for any other L <= 64 known only at run time: then a load holds floor(64/L) whole rows in
+// its first `active` lanes and the remaining lanes stay idle.
+struct RowShape {
+    uint32_t lanes;      // L: lanes per row
+    uint32_t rows;       // whole rows per load
+    uint32_t active;     // rows * lanes: lanes that take part (= 16-byte vectors per load)
+    uint32_t pos;        // this lane's position inside its row
+    bool ok;             // this lane takes part
+};
+
+template <int L>
+__device__ __forceinline__ RowShape row_shape(uint32_t lane, uint32_t lanes_per_row) {
+    RowShape r;
+    r.lanes = L ? (uint32_t)L : lanes_per_row;
+    r.rows = 64u / r.lanes;
+    r.active = r.rows * r.lanes;
+    r.pos = lane % r.lanes;
+    r.ok = lane < r.active;
+    return r;
+}
+
+// Inclusive prefix sum over groups of `lanes` consecutive lanes, any group length: Kogge-Stone steps
+// through the LDS crossbar (rows of 3, 5, 6, ... lanes do not line up with the 16-lane DPP rows).
+__device__ __forceinline__ uint32_t segmented_inclusive_scan_any(uint32_t v, const RowShape& r) {
+    for (uint32_t d = 1; d < r.lanes; d <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)v, d, 64);
+        v += r.pos >= d ? up : 0u;
+    }
+    return v;
+}
+
 // Maximum over the 64 lanes, returned in every lane: a running maximum with the scan's DPP
 // steps (0 is the identity of an unsigned maximum), then lane 63 holds the result.
 __device__ __forceinline__ uint32_t wave_max(uint32_t v) {
@@ -154,8 +187,9 @@ __device__ __forceinline__ void drain(WaveState& st, uint4* queue, const GridVie
 // worker are L consecutive lanes, so a wave holds 64/L whole rows.  Completion time of the lane's
 // last element:
 template <int L>
-__device__ __forceinline__ uint32_t lane_completion_time(u32x4 x, uint32_t lane) {
-    return segmented_inclusive_scan<L>(x.x + x.y + x.z + x.w, lane);
+__device__ __forceinline__ uint32_t lane_completion_time(u32x4 x, uint32_t lane, const RowShape& shape) {
+    if constexpr (L == 0) return segmented_inclusive_scan_any(x.x + x.y + x.z + x.w, shape);
+    else return segmented_inclusive_scan<L>(x.x + x.y + x.z + x.w, lane);
 }
 
 // Lanes whose last completion time reaches the smallest threshold put their four completion
@@ -178,17 +212,18 @@ __device__ __forceinline__ void enqueue_active(WaveState& st, u32x4 x, uint32_t 
 
 template <int L, int U>
 __device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U], uint4* queue, const GridView& g,
-                                              uint32_t lane) {
+                                              uint32_t lane, const RowShape& shape) {
     uint32_t incl[U];
 #pragma unroll
-    for (int k = 0; k < U; ++k) incl[k] = lane_completion_time<L>(x[k], lane);   // independent scans interleave
+    for (int k = 0; k < U; ++k) incl[k] = lane_completion_time<L>(x[k], lane, shape);   // independent scans interleave
 #pragma unroll
     for (int k = 0; k < U; ++k) {
         st.check = umax(st.check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
         st.lane_max = umax(st.lane_max, incl[k]);
     }
 #pragma unroll
-    for (int k = 0; k < U; ++k) enqueue_active(st, x[k], incl[k], incl[k] >= g.tau0, queue, g, lane);
+    for (int k = 0; k < U; ++k)
+        enqueue_active(st, x[k], incl[k], (L != 0 || shape.ok) && incl[k] >= g.tau0, queue, g, lane);
 }
 
 }  // namespace
@@ -270,47 +305,57 @@ __device__ __forceinline__ GridView stage_grid(uint32_t* tables, const uint32_t*
     return GridView{tau_s, lut, hist, p2, shift, tau_first};
 }
 
-// One wave streams `nfull` consecutive full loads (1 KiB each, 64/L whole rows) starting at `base`
-// (already offset by the lane), then, if tail_rows > 0, one partial load holding tail_rows rows.
+// One wave streams `nfull` consecutive full loads (shape.rows whole rows each, 1 KiB when every lane takes
+// part) starting at `base` (already offset by the lane), then, if tail_rows > 0, one partial load holding
+// tail_rows rows.
+template <int L>
+__device__ __forceinline__ u32x4 load_rows(const u32x4* p, const RowShape& shape) {
+    if constexpr (L != 0) return __builtin_nontemporal_load(p);
+    u32x4 x = {0u, 0u, 0u, 0u};
+    if (shape.ok) x = __builtin_nontemporal_load(p);
+    return x;
+}
+
 template <int L>
 __device__ __forceinline__ void stream_rows(WaveState& st, const u32x4* base, uint32_t nfull, uint32_t tail_rows,
-                                            uint4* queue, const GridView& g, uint32_t lane) {
+                                            uint4* queue, const GridView& g, uint32_t lane, const RowShape& shape) {
     constexpr int U = DC_SCAN_UNROLL;              // loads in flight per lane
+    const uint64_t stride = L ? 64u : shape.active;   // 16-byte vectors per load
     uint32_t i = 0;
 #if DC_SCAN_PREFETCH
     // software pipeline: the next group's loads are issued before the current group is processed
     if (nfull >= (uint32_t)U) {
         u32x4 cur[U];
 #pragma unroll
-        for (int k = 0; k < U; ++k) cur[k] = __builtin_nontemporal_load(base + (uint64_t)k * 64);
+        for (int k = 0; k < U; ++k) cur[k] = load_rows<L>(base + (uint64_t)k * stride, shape);
         for (; i + 2 * U <= nfull; i += U) {
             u32x4 nxt[U];
 #pragma unroll
-            for (int k = 0; k < U; ++k) nxt[k] = __builtin_nontemporal_load(base + (uint64_t)(i + U + k) * 64);
-            process_loads<L, U>(st, cur, queue, g, lane);
+            for (int k = 0; k < U; ++k) nxt[k] = load_rows<L>(base + (uint64_t)(i + U + k) * stride, shape);
+            process_loads<L, U>(st, cur, queue, g, lane, shape);
 #pragma unroll
             for (int k = 0; k < U; ++k) cur[k] = nxt[k];
         }
-        process_loads<L, U>(st, cur, queue, g, lane);
+        process_loads<L, U>(st, cur, queue, g, lane, shape);
         i += U;
     }
 #else
     for (; i + U <= nfull; i += U) {
         u32x4 x[U];
 #pragma unroll
-        for (int k = 0; k < U; ++k) x[k] = __builtin_nontemporal_load(base + (uint64_t)(i + k) * 64);
-        process_loads<L, U>(st, x, queue, g, lane);
+        for (int k = 0; k < U; ++k) x[k] = load_rows<L>(base + (uint64_t)(i + k) * stride, shape);
+        process_loads<L, U>(st, x, queue, g, lane, shape);
     }
 #endif
     for (; i < nfull; ++i) {
-        const u32x4 x[1] = {__builtin_nontemporal_load(base + (uint64_t)i * 64)};
-        process_loads<L, 1>(st, x, queue, g, lane);
+        const u32x4 x[1] = {load_rows<L>(base + (uint64_t)i * stride, shape)};
+        process_loads<L, 1>(st, x, queue, g, lane, shape);
     }
     if (tail_rows) {                                // rows beyond the trial's last worker belong to the next trial
-        const bool valid = lane < tail_rows * L;
+        const bool valid = lane < tail_rows * shape.lanes;
         u32x4 x = {0u, 0u, 0u, 0u};
-        if (valid) x = __builtin_nontemporal_load(base + (uint64_t)nfull * 64);
-        const uint32_t incl = lane_completion_time<L>(x, lane);
+        if (valid) x = __builtin_nontemporal_load(base + (uint64_t)nfull * stride);
+        const uint32_t incl = lane_completion_time<L>(x, lane, shape);
         st.check = umax(st.check, umax(umax(x.x, x.y), umax(x.z, x.w)));
         st.lane_max = umax(st.lane_max, incl);
         enqueue_active(st, x, incl, valid && incl >= g.tau0, queue, g, lane);
@@ -335,14 +380,15 @@ __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t units, uint32_t units_per_trial,
                          uint32_t loads_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
                          uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
-                         uint32_t* __restrict__ status, uint32_t max_latency) {
+                         uint32_t* __restrict__ status, uint32_t max_latency, uint32_t lanes_per_row) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
     const GridView g = stage_grid(reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS), tau_chunk, kc, p2);
 
-    constexpr uint32_t R = 64 / L;                 // rows per load
-    constexpr uint32_t M = 4 * L;
     const uint32_t lane = threadIdx.x & 63u;
+    const RowShape shape = row_shape<L>(lane, lanes_per_row);
+    const uint32_t R = shape.rows;                 // rows per load
+    const uint32_t M = 4 * shape.lanes;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction
     uint4* queue = queue_all + wave * QUEUE_ITEMS;
     const uint32_t total_waves = gridDim.x * DC_SCAN_WAVES;
@@ -357,7 +403,7 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
         const uint32_t nfull = rows / R;
         const u32x4* base = reinterpret_cast<const u32x4*>(lat + ((uint64_t)t * N + row0) * M) + lane;
         st.lane_max = 0u;
-        stream_rows<L>(st, base, nfull, rows - nfull * R, queue, g, lane);
+        stream_rows<L>(st, base, nfull, rows - nfull * R, queue, g, lane, shape);
         const uint32_t m = wave_max(st.lane_max);
         if (lane == 0) unit_max[u] = m;
     }
@@ -618,7 +664,8 @@ __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_trial_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N,
                                const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
                                const long long* __restrict__ comm_per_trial, long long comm,
-                               double* __restrict__ partial, uint32_t* __restrict__ status, uint32_t max_latency) {
+                               double* __restrict__ partial, uint32_t* __restrict__ status, uint32_t max_latency,
+                               uint32_t lanes_per_row) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
     uint32_t* tables = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);
@@ -630,9 +677,10 @@ void dc_trial_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
     if (threadIdx.x == 0) *sh.block_max = 0u;
     const GridView g = stage_grid(tables, tau_chunk, kc, p2);
 
-    constexpr uint32_t R = 64 / L;
-    constexpr uint32_t M = 4 * L;
     const uint32_t lane = threadIdx.x & 63u;
+    const RowShape shape = row_shape<L>(lane, lanes_per_row);
+    const uint32_t R = shape.rows;
+    const uint32_t M = 4 * shape.lanes;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint4* queue = queue_all + wave * QUEUE_ITEMS;
     const uint32_t nfull = N / R, tail_rows = N - nfull * R;
@@ -644,7 +692,7 @@ void dc_trial_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
     for (uint32_t t = blockIdx.x; t < T; t += gridDim.x) {
         const u32x4* base = reinterpret_cast<const u32x4*>(lat + ((uint64_t)t * N + (uint64_t)lo * R) * M) + lane;
         st.lane_max = 0u;
-        stream_rows<L>(st, base, hi - lo, wave == DC_SCAN_WAVES - 1 ? tail_rows : 0u, queue, g, lane);
+        stream_rows<L>(st, base, hi - lo, wave == DC_SCAN_WAVES - 1 ? tail_rows : 0u, queue, g, lane, shape);
         while (st.q_count) drain(st, queue, g, lane);
         const uint32_t m = wave_max(st.lane_max);
         if (lane == 0) atomicMax(sh.block_max, m);
@@ -766,7 +814,8 @@ int scan_blocks_per_cu(const Plan& p) {
         case 8:  return resident_vec4<8>(lds);
         case 16: return resident_vec4<16>(lds);
         case 32: return resident_vec4<32>(lds);
-        default: return resident_vec4<64>(lds);
+        case 64: return resident_vec4<64>(lds);
+        default: return resident_vec4<0>(lds);
     }
 }
 
@@ -775,7 +824,7 @@ static void launch_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_c
                         uint32_t* unit_max, uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
     hipLaunchKernelGGL(dc_scan_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
                        p.N, p.units, p.units_per_trial, p.per_unit, tau_chunk, kc, p.p2, unit_max, hist_part, status,
-                       p.max_latency);
+                       p.max_latency, p.M / 4);
 }
 
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
@@ -793,7 +842,8 @@ void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, u
         case 8:  launch_vec4<8>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
         case 16: launch_vec4<16>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
         case 32: launch_vec4<32>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
-        default: launch_vec4<64>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+        case 64: launch_vec4<64>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+        default: launch_vec4<0>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
     }
 }
 
@@ -830,7 +880,7 @@ static void launch_trial_vec4(const Plan& p, const int32_t* lat, const uint32_t*
                               hipStream_t stream) {
     hipLaunchKernelGGL(dc_trial_scan_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS), trial_scan_lds_bytes(p),
                        stream, lat, p.T, p.N, tau_chunk, kc, p.p2, (const long long*)comm_per_trial, (long long)comm,
-                       partial, status, p.max_latency);
+                       partial, status, p.max_latency, p.M / 4);
 }
 
 void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
@@ -849,7 +899,8 @@ void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_ch
         case 8:  launch_trial_vec4<8>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
         case 16: launch_trial_vec4<16>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
         case 32: launch_trial_vec4<32>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
-        default: launch_trial_vec4<64>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
+        case 64: launch_trial_vec4<64>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
+        default: launch_trial_vec4<0>(p, lat, tau_chunk, kc, comm_per_trial, comm, partial, status, stream); break;
     }
 }
 

@@ -132,7 +132,7 @@ def test_workload_parity_full_grid(name, T, dev):
 
 # ---- every vectorised row length, and the general kernel ------------------------------------------
 
-@pytest.mark.parametrize("M", [4, 8, 16, 32, 64, 128, 256])
+@pytest.mark.parametrize("M", [4, 8, 16, 32, 64, 128, 256, 12, 20, 24, 44, 100, 132, 252])
 @pytest.mark.parametrize("N", [1, 7, 64, 130])
 def test_vector_kernel_shapes(M, N, dev):
     rng = np.random.default_rng(M * 1000 + N)
@@ -296,7 +296,7 @@ def test_per_step_speedup_parity(name, shape, dev):
     assert np.array_equal(got, again)                           # fixed summation order
 
 
-@pytest.mark.parametrize("M", [1, 3, 12, 100, 300, 8, 64])
+@pytest.mark.parametrize("M", [1, 3, 12, 100, 300, 8, 64, 20, 252])
 def test_per_step_speedup_shapes(M, dev):
     rng = np.random.default_rng(100 + M)
     lat = rng.integers(1, 3000, size=(7, 9, M), dtype=np.int32)
