@@ -138,21 +138,36 @@ int ensure_events(size_t pairs) {
 // The kernel splits the work statically over its waves, so every block must be resident at once (a
 // block that waits for a free slot would run alone at the end), and the same number of blocks must
 // sit on every compute unit.  Queried once per (device, kernel variant, LDS size).
-struct ResidentKey { int device; bool vec4; uint32_t M; uint32_t p2; int blocks; };
+struct ResidentKey { int device; bool vec4; bool trial; uint32_t M; uint32_t p2; int blocks; };
 std::vector<ResidentKey> g_resident;
 
-uint32_t resident_blocks(const dc::Plan& p) {
+// Blocks per compute unit that stream best (measured on MI355X with 8 loads in flight per lane): long
+// rows have few completion times inside the threshold grid and want few, fat waves; short rows put a
+// large share of their lanes through the queue and the binning, whose LDS latencies need more waves
+// to hide.  `DC_SCAN_BLOCKS_PER_CU` overrides the choice at build time.
+uint32_t wanted_blocks_per_cu(const dc::Plan& p) {
+#ifdef DC_SCAN_BLOCKS_PER_CU
+    return DC_SCAN_BLOCKS_PER_CU;
+#else
+    if (p.vec4 && p.M >= 128) return 2;
+    return 8;
+#endif
+}
+
+uint32_t resident_blocks(const dc::Plan& p, bool trial = false) {
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return DC_MAX_SCAN_BLOCKS;
     for (const ResidentKey& k : g_resident)
-        if (k.device == device && k.vec4 == p.vec4 && k.M == (p.vec4 ? p.M : 0) && k.p2 == p.p2) return (uint32_t)k.blocks;
+        if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == (p.vec4 ? p.M : 0) && k.p2 == p.p2)
+            return (uint32_t)k.blocks;
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1) cus = 256;
-    int per_cu = dc::scan_blocks_per_cu(p);                    // what fits
+    int per_cu = trial ? dc::trial_scan_blocks_per_cu(p) : dc::scan_blocks_per_cu(p);   // what fits
     if (per_cu < 1) per_cu = 1;
-    if (per_cu > (int)DC_SCAN_BLOCKS_PER_CU) per_cu = DC_SCAN_BLOCKS_PER_CU;   // what streams best
+    const int wanted = (int)wanted_blocks_per_cu(p);                                    // what streams best
+    if (per_cu > wanted) per_cu = wanted;
     const int blocks = cus * per_cu;
-    g_resident.push_back({device, p.vec4, p.vec4 ? p.M : 0, p.p2, blocks});
+    g_resident.push_back({device, p.vec4, trial, p.vec4 ? p.M : 0, p.p2, blocks});
     return (uint32_t)blocks;
 }
 
@@ -212,8 +227,8 @@ int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* tau
                     const int64_t* comm_per_trial_dev, double* out_seff_dev, unsigned char* ws, hipStream_t stream,
                     bool timed) {
     dc::Plan p = plan;
-    const uint32_t want = (uint32_t)compute_units() * DC_SCAN_BLOCKS_PER_CU;   // always fits: <= 57 KiB LDS, 4 waves each
-    if (p.grid > want) p.grid = want;
+    const uint32_t resident = resident_blocks(p, true);
+    if (p.grid > resident) p.grid = resident;
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + p.off_status);
     int64_t* tau_sorted = reinterpret_cast<int64_t*>(ws + p.off_tau_sorted);
     uint32_t* tau_u32 = reinterpret_cast<uint32_t*>(ws + p.off_tau_u32);
@@ -408,7 +423,7 @@ int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t* out
     if ((long double)T * (long double)N * (long double)M >= 4.6e18L) return DC_ERR_INVALID_ARG;
     const uint64_t n = (uint64_t)T * (uint64_t)N * (uint64_t)M;
     std::lock_guard<std::mutex> lock(g_mutex);
-    const uint32_t grid = (uint32_t)compute_units() * DC_SCAN_BLOCKS_PER_CU;
+    const uint32_t grid = (uint32_t)compute_units() * 2u;        // 8 waves per compute unit saturate a plain read
     const size_t partial_bytes = align256((size_t)grid * 4 * 8);
     int rc = ensure_cache(256 + 256 + partial_bytes);
     if (rc) return rc;

@@ -16,9 +16,6 @@
 #ifndef DC_SCAN_PREFETCH
 #define DC_SCAN_PREFETCH 0               // 1: issue the next group of loads before processing the current one
 #endif
-#ifndef DC_SCAN_BLOCKS_PER_CU
-#define DC_SCAN_BLOCKS_PER_CU 2u        // measured best on MI355X: 8 waves per compute unit, 8 loads in flight each
-#endif
 #ifndef DC_MAX_SCAN_BLOCKS
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
 #endif
@@ -30,7 +27,7 @@
 #define DC_FINAL_THREADS 1024
 #define DC_CHUNK_THRESHOLDS 4095u      // thresholds handled by one pass over lat (LDS-resident grid)
 #define DC_TRIAL_CHUNK_THRESHOLDS 2047u // same for the per-iteration speedup pass (it also keeps float64 sums in LDS)
-#define DC_MAX_TRIAL_BLOCKS 1024u      // upper bound of that pass's grid (sizes its per-block sums in the workspace)
+#define DC_MAX_TRIAL_BLOCKS 2048u      // upper bound of that pass's grid (sizes its per-block sums in the workspace)
 #define DC_TAU_CLAMP 0x80000000u       // thresholds at or above 2^31 exceed every completion time
 
 #define DC_FLAG_NEGATIVE_TAU 1u
@@ -82,6 +79,7 @@ void launch_expected_done(const int64_t* taus, uint32_t K, uint32_t M, double mu
                           hipStream_t stream);
 size_t scan_lds_bytes(const Plan& p);
 int scan_blocks_per_cu(const Plan& p);
+int trial_scan_blocks_per_cu(const Plan& p);
 
 }  // namespace dc
 #endif

@@ -214,8 +214,25 @@ template <int L, int U>
 __device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U], uint4* queue, const GridView& g,
                                               uint32_t lane, const RowShape& shape) {
     uint32_t incl[U];
+    if constexpr (L == 0) {
+        // rows of any length: the Kogge-Stone steps of all U scans go through the LDS crossbar together,
+        // so their latencies overlap instead of adding up
 #pragma unroll
-    for (int k = 0; k < U; ++k) incl[k] = lane_completion_time<L>(x[k], lane, shape);   // independent scans interleave
+        for (int k = 0; k < U; ++k) incl[k] = x[k].x + x[k].y + x[k].z + x[k].w;
+        for (uint32_t d = 1; d < shape.lanes; d <<= 1) {
+            const int src = (int)lane - (int)d;
+            const int addr = (src < 0 ? (int)lane : src) << 2;
+            const bool take = shape.pos >= d;
+            uint32_t up[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) up[k] = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)incl[k]);
+#pragma unroll
+            for (int k = 0; k < U; ++k) incl[k] += take ? up[k] : 0u;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < U; ++k) incl[k] = lane_completion_time<L>(x[k], lane, shape);   // independent scans interleave
+    }
 #pragma unroll
     for (int k = 0; k < U; ++k) {
         st.check = umax(st.check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
@@ -867,6 +884,35 @@ void launch_finalize(const Plan& p, unsigned long long* hist_total, unsigned lon
                        trial_sum, kc, p.p2, chunk0, tau_sorted, pos, p.K, (unsigned long long)p.T,
                        (unsigned long long)p.elements, (long long)comm, (long long*)out_step, (long long*)out_done,
                        (long long*)chunk_step, (long long*)chunk_done);
+}
+
+template <int L>
+static int resident_trial_vec4(size_t lds) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_vec4_kernel<L>, DC_SCAN_THREADS, lds) != hipSuccess) n = 0;
+    return n;
+}
+
+size_t trial_scan_lds_bytes(const Plan& p);
+
+// Blocks of the per-trial kernel that one compute unit holds at a time (0 if the query fails).
+int trial_scan_blocks_per_cu(const Plan& p) {
+    const size_t lds = trial_scan_lds_bytes(p);
+    int n = 0;
+    if (!p.vec4) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_generic_kernel, DC_SCAN_THREADS, lds) != hipSuccess) n = 0;
+        return n;
+    }
+    switch (p.M / 4) {
+        case 1:  return resident_trial_vec4<1>(lds);
+        case 2:  return resident_trial_vec4<2>(lds);
+        case 4:  return resident_trial_vec4<4>(lds);
+        case 8:  return resident_trial_vec4<8>(lds);
+        case 16: return resident_trial_vec4<16>(lds);
+        case 32: return resident_trial_vec4<32>(lds);
+        case 64: return resident_trial_vec4<64>(lds);
+        default: return resident_trial_vec4<0>(lds);
+    }
 }
 
 size_t trial_scan_lds_bytes(const Plan& p) {
