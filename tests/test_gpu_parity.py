@@ -251,6 +251,33 @@ def test_async_entry_point_on_a_side_stream(dev):
         dc.dc_simulate_async(lat_d, taus_d, r.comm, out_step, out_done, small, stream)
 
 
+def test_async_entry_point_replays_from_a_graph(dev):
+    """The enqueued sequence uses no memset and no allocation, so it can be captured; every replay must
+    reproduce the eager result, with other work and synchronisations in between."""
+    r = config("lognormal64").with_shape(T=500)
+    lat = host.generate(r)
+    taus = host.tau_grid(r)
+    ref = oracle.simulate(lat, taus, r.comm, "sorted")
+    lat_d, taus_d = to_dev(lat, dev), torch.from_numpy(taus).to(dev)
+    out = torch.zeros((2, taus.size), dtype=torch.int64, device=dev)
+    ws = torch.empty(dc.dc_workspace_bytes(r.T, r.N, r.M, taus.size), dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream()
+    dc.dc_simulate_async(lat_d, taus_d, r.comm, out[0], out[1], ws, side)        # eager once (warms caches of the plan)
+    assert dc.dc_workspace_status(ws, side) == dc.DC_OK
+    eager = out.cpu().numpy().copy()
+    assert np.array_equal(eager[0], ref[0]) and np.array_equal(eager[1], ref[1])
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        dc.dc_simulate_async(lat_d, taus_d, r.comm, out[0], out[1], ws, torch.cuda.current_stream())
+    for i in range(4):
+        out.zero_()
+        ws.fill_(i)                                          # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), eager), i
+
+
 def test_kernel_timing_reports_positive_times(dev):
     r = config("extrapolation2048").with_shape(T=16)
     from dc_workloads import device
