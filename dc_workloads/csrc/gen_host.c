@@ -36,14 +36,16 @@ void dcgen_fill_host(int32_t* out, uint64_t idx0, uint64_t count,
                      const int64_t* main_t, const int64_t* lo_t, const int64_t* hi_t,
                      const uint32_t* scale_q16,
                      int64_t add, int64_t clip_min,
-                     uint32_t spike_thresh, uint32_t spike_mul, int64_t spike_add) {
+                     uint32_t spike_thresh, uint32_t spike_mul, int64_t spike_add, int64_t spike_workers) {
     for (uint64_t e = 0; e < count; ++e) {
         uint64_t i = idx0 + e;
         uint64_t q = draw_q8(mix64(key_value + DCGEN_GOLDEN * (i + 1)), main_t, lo_t, hi_t);
         uint64_t s = 65536u;
-        if (scale_q16) s = scale_q16[(i / (uint64_t)M) % (uint64_t)N];
+        const uint64_t worker = (i / (uint64_t)M) % (uint64_t)N;
+        if (scale_q16) s = scale_q16[worker];
         int spike = 0;
-        if (spike_thresh) spike = (uint32_t)(mix64(key_spike + DCGEN_GOLDEN * (i + 1)) >> 32) < spike_thresh;
+        if (spike_thresh && (spike_workers <= 0 || worker < (uint64_t)spike_workers))
+            spike = (uint32_t)(mix64(key_spike + DCGEN_GOLDEN * (i + 1)) >> 32) < spike_thresh;
         uint64_t mul = spike ? spike_mul : 1u;
         int64_t v = (int64_t)((q * s * mul + (1ull << 23)) >> 24);
         if (v < clip_min) v = clip_min;

@@ -40,7 +40,7 @@ def _load():
             raise ImportError(f"{_LIB_PATH} is missing: build it first")
         lib = ctypes.CDLL(str(_LIB_PATH))
         p, u64, i64, u32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int64, ctypes.c_uint32
-        lib.dcgen_fill_device.argtypes = [p, u64, u64, u64, u64, i64, i64, p, p, p, p, i64, i64, u32, u32, i64, p]
+        lib.dcgen_fill_device.argtypes = [p, u64, u64, u64, u64, i64, i64, p, p, p, p, i64, i64, u32, u32, i64, i64, p]
         lib.dcgen_fill_device.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -63,7 +63,7 @@ def generate(r: Recipe, t0: int = 0, t1: int | None = None, device: str = "cuda:
             spec.stream_key(r.seed, spec.STREAM_VALUE), spec.stream_key(r.seed, spec.STREAM_SPIKE),
             r.N, r.M, tables[0].data_ptr(), tables[1].data_ptr(), tables[2].data_ptr(),
             None if scale is None else scale.data_ptr(),
-            r.add, r.clip_min, r.spike_thresh, r.spike_mul, r.spike_add, int(stream.cuda_stream))
+            r.add, r.clip_min, r.spike_thresh, r.spike_mul, r.spike_add, r.spike_workers, int(stream.cuda_stream))
         if rc != 0:
             raise RuntimeError(f"dcgen_fill_device: hipError {rc}")
         stream.synchronize()          # the tables may be released once the kernel has run

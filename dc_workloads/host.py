@@ -46,7 +46,7 @@ def _load():
         lib.dcgen_fill_host.argtypes = [p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
                                         ctypes.c_int64, ctypes.c_int64, p, p, p, p,
                                         ctypes.c_int64, ctypes.c_int64,
-                                        ctypes.c_uint32, ctypes.c_uint32, ctypes.c_int64]
+                                        ctypes.c_uint32, ctypes.c_uint32, ctypes.c_int64, ctypes.c_int64]
         lib.dcgen_fill_host.restype = None
         lib.dcgen_draw_host.argtypes = [p, p, ctypes.c_uint64, ctypes.c_uint64, p, p, p]
         lib.dcgen_draw_host.restype = None
@@ -118,6 +118,8 @@ def generate_numpy(r: Recipe, idx0: int = 0, count: int | None = None) -> np.nda
     s = np.uint64(65536) if scale is None else scale[((i // np.uint64(r.M)) % np.uint64(r.N)).astype(np.int64)].astype(np.uint64)
     if r.spike_thresh:
         spike = (hash_counters(r.seed, spec.STREAM_SPIKE, i) >> np.uint64(32)) < np.uint64(r.spike_thresh)
+        if r.spike_workers:
+            spike &= ((i // np.uint64(r.M)) % np.uint64(r.N)) < np.uint64(r.spike_workers)
     else:
         spike = np.zeros(count, dtype=bool)
     mul = np.where(spike, np.uint64(r.spike_mul), np.uint64(1))
@@ -147,7 +149,7 @@ def fill(r: Recipe, out: np.ndarray, idx0: int, args: _Args | None = None) -> No
     _load().dcgen_fill_host(out.ctypes.data, idx0, out.size, a.key_value, a.key_spike, r.N, r.M,
                             a.main.ctypes.data, a.lo.ctypes.data, a.hi.ctypes.data,
                             None if a.scale is None else a.scale.ctypes.data,
-                            r.add, r.clip_min, r.spike_thresh, r.spike_mul, r.spike_add)
+                            r.add, r.clip_min, r.spike_thresh, r.spike_mul, r.spike_add, r.spike_workers)
 
 
 def generate(r: Recipe, t0: int = 0, t1: int | None = None, threads: int | None = None) -> np.ndarray:

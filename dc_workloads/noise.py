@@ -4,6 +4,11 @@
                          Z ~ LogNormal(4, 1), alpha = 2 e^4.5, beta = 5.5 (mean x1.5, at most x6.5).
                          The undisturbed compute time t is taken constant (= mu); the appendix does not give
                          its distribution.
+  local_sgd(...)         Appendix B.3: Local-SGD with periodic synchronisation; the threshold is checked at each local
+                         step, so a "micro-batch" is one local step and M is the synchronisation period.  At each
+                         local step a worker is a straggler with a 4% chance and then waits 1 s; either every worker
+                         can straggle ("uniform") or only the workers of one server ("single_server").  The
+                         undisturbed local-step time is not given in the appendix; 0.25 s is assumed.
   additive_noise(...)    Appendix C.3: 12 accumulations of 0.45 s + eps, eps of mean 0.225 s and a chosen
                          variance from one of five families (lognormal, normal, bernoulli, exponential, gamma),
                          parameters derived from (mean, variance) as in the appendix's tables.
@@ -69,3 +74,16 @@ def additive_noise(family: str, T: int, N: int, variance: float = 0.05, mean: fl
         q = lambda u: base_us + 1e6 * gammaincinv(prm["shape"], u) / prm["rate"]
     return Recipe(f"additive_{family}", T=T, N=N, M=M, K=K, comm=comm_us, grid="pct", value=quantile_tables(q),
                   seed=seed, description=f"{base_s} s + {family} noise (mean {mean} s, variance {variance} s^2), us", **kw)
+
+
+def local_sgd(T: int, period: int, scenario: str = "uniform", N: int = 32, step_us: int = 250_000,
+              straggler_p: float = 0.04, wait_us: int = 1_000_000, server_workers: int = 8, K: int = 64,
+              comm_us: int = 50_000, seed: int = 0) -> Recipe:
+    if scenario not in ("uniform", "single_server"):
+        raise ValueError(scenario)
+    return Recipe(f"local_sgd_{scenario}", T=T, N=N, M=period, K=K, comm=comm_us, grid="minmax",
+                  value=quantile_tables(lambda u: np.full_like(u, float(step_us))), seed=seed,
+                  spike_thresh=prob_to_thresh(straggler_p), spike_add=wait_us,
+                  spike_workers=server_workers if scenario == "single_server" else 0,
+                  description=f"{step_us} us per local step, +{wait_us} us w.p. {straggler_p} "
+                              f"({'workers of one server' if scenario == 'single_server' else 'any worker'})")

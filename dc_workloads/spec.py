@@ -32,7 +32,7 @@ bit-identical):
 
   Element i = (t*N + n)*M + m of a workload:
     q      = draw(h(seed, 0, i))                                  (q8 microseconds)
-    spike  = (h(seed, 1, i) >> 32) < spike_thresh
+    spike  = (h(seed, 1, i) >> 32) < spike_thresh   and, when spike_workers > 0, only for workers n < spike_workers
     mul    = spike ? spike_mul : 1
     v      = (q * scale_q16[n] * mul + 2^23) >> 24                (round half up)
     lat[i] = max(clip_min, v) + add + (spike ? spike_add : 0)
@@ -156,6 +156,7 @@ class Recipe:
     spike_thresh: int = 0
     spike_mul: int = 1
     spike_add: int = 0
+    spike_workers: int = 0         # > 0: only the first spike_workers workers can spike (stragglers of one server)
     worker_scale: Optional[QuantileTables] = None   # q8 tables of 65536*(s_n - 1)
     description: str = ""
 

@@ -7,7 +7,11 @@ For each noise family and worker count N it generates synthetic latencies in HBM
                 the appendix does not state its N, so the sweep shows where each tabulated value would fall),
   tau*, S_eff(tau*), the completed fraction at tau*, and the closed-form S_eff at the same tau.
 
+With --local-sgd it sweeps the synchronisation period of Local-SGD with random stragglers (Appendix B.3): throughput of
+Local-SGD, and of Local-SGD with the best drop threshold, relative to synchronising at every step.
+
   python noise_study.py [--families lognormal normal ...] [--workers 8 64 512 2048] [--variance 0.05] [--delay]
+  python noise_study.py --local-sgd [--periods 1 2 4 8 16 32]
 """
 from __future__ import annotations
 
@@ -41,6 +45,28 @@ def study(recipe):
             "completed": float(done[best]) / (T * N * M), "analytic_seff": float(ana[best])}
 
 
+def local_sgd_study(periods, trials: int) -> None:
+    import numpy as np
+
+    import paper_2306_10598_amd as dc
+    from dc_workloads import device, noise
+    print(f"{'scenario':<15}{'period':>7}{'local-SGD':>11}{'+ threshold':>13}{'tau* us':>10}{'dropped':>9}")
+    for scenario in ("uniform", "single_server"):
+        sync = None
+        for H in periods:
+            r = noise.local_sgd(trials, H, scenario)
+            lat = device.generate(r)
+            taus = np.append(device.tau_grid(r, lat), BIG)
+            step, done = dc.dc_simulate(lat, taus, r.comm)
+            thr, _, best = dc.dc_select_tau(step, done, taus, r.T, r.N, r.M, int(step[-1]))
+            if sync is None:                                     # period 1, no threshold: synchronous training
+                one = noise.local_sgd(trials, 1, scenario)
+                s1, d1 = dc.dc_simulate(device.generate(one), [BIG], one.comm)
+                sync = float(d1[0]) / float(s1[0])
+            print(f"{scenario:<15}{H:>7}{thr[-1] / sync:>11.3f}{thr[best] / sync:>13.3f}{int(taus[best]):>10}"
+                  f"{1 - float(done[best]) / (r.T * r.N * r.M):>9.3f}")
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--families", nargs="*", default=["lognormal", "normal", "bernoulli", "exponential", "gamma"])
@@ -48,7 +74,12 @@ def main() -> int:
     ap.add_argument("--variance", type=float, default=0.05)
     ap.add_argument("--elements", type=int, default=1 << 26, help="approximate T*N*M per point")
     ap.add_argument("--delay", action="store_true", help="also sweep the simulated-delay model of Appendix B.1")
+    ap.add_argument("--local-sgd", action="store_true", help="sweep Local-SGD's synchronisation period instead")
+    ap.add_argument("--periods", nargs="*", type=int, default=[1, 2, 4, 8, 16, 32])
     args = ap.parse_args()
+    if args.local_sgd:
+        local_sgd_study(args.periods, trials=20000)
+        return 0
     from dc_workloads import noise
     print(f"{'noise':<16}{'N':>6}{'T':>8}{'E[T]/E[T_i]':>13}{'paper':>8}{'tau* us':>12}{'S_eff':>8}{'done':>8}{'closed form':>13}")
     for family in args.families + (["delay"] if args.delay else []):

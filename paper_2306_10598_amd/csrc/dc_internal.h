@@ -13,9 +13,6 @@
 #ifndef DC_SCAN_UNROLL
 #define DC_SCAN_UNROLL 8                // 16-byte loads in flight per lane
 #endif
-#ifndef DC_SCAN_PREFETCH
-#define DC_SCAN_PREFETCH 0               // 1: issue the next group of loads before processing the current one
-#endif
 #ifndef DC_MAX_SCAN_BLOCKS
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
 #endif

@@ -339,31 +339,12 @@ __device__ __forceinline__ void stream_rows(WaveState& st, const u32x4* base, ui
     constexpr int U = DC_SCAN_UNROLL;              // loads in flight per lane
     const uint64_t stride = L ? 64u : shape.active;   // 16-byte vectors per load
     uint32_t i = 0;
-#if DC_SCAN_PREFETCH
-    // software pipeline: the next group's loads are issued before the current group is processed
-    if (nfull >= (uint32_t)U) {
-        u32x4 cur[U];
-#pragma unroll
-        for (int k = 0; k < U; ++k) cur[k] = load_rows<L>(base + (uint64_t)k * stride, shape);
-        for (; i + 2 * U <= nfull; i += U) {
-            u32x4 nxt[U];
-#pragma unroll
-            for (int k = 0; k < U; ++k) nxt[k] = load_rows<L>(base + (uint64_t)(i + U + k) * stride, shape);
-            process_loads<L, U>(st, cur, queue, g, lane, shape);
-#pragma unroll
-            for (int k = 0; k < U; ++k) cur[k] = nxt[k];
-        }
-        process_loads<L, U>(st, cur, queue, g, lane, shape);
-        i += U;
-    }
-#else
     for (; i + U <= nfull; i += U) {
         u32x4 x[U];
 #pragma unroll
         for (int k = 0; k < U; ++k) x[k] = load_rows<L>(base + (uint64_t)(i + k) * stride, shape);
         process_loads<L, U>(st, x, queue, g, lane, shape);
     }
-#endif
     for (; i < nfull; ++i) {
         const u32x4 x[1] = {load_rows<L>(base + (uint64_t)i * stride, shape)};
         process_loads<L, 1>(st, x, queue, g, lane, shape);

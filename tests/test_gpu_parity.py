@@ -430,6 +430,16 @@ def test_noise_model_workloads_parity(family, dev):
     assert dc.dc_moments(to_dev(lat, dev))[:2] == oracle.moments(lat)[1:3]
 
 
+@pytest.mark.parametrize("scenario,period", [("uniform", 1), ("uniform", 8), ("single_server", 16), ("single_server", 5)])
+def test_local_sgd_workloads_parity(scenario, period, dev):
+    from dc_workloads import device, noise
+    r = noise.local_sgd(700, period, scenario)
+    lat = host.generate(r)
+    assert np.array_equal(device.generate(r).cpu().numpy(), lat)
+    taus = np.append(host.tau_grid(r), BIG)
+    check(lat, taus, r.comm, dev, "literal")
+
+
 # ---- full sizes of the two 2048-worker workloads, as the benchmark launches them -----------------------
 
 @pytest.mark.parametrize("name", ["extrapolation2048", "heterogeneous2048"])

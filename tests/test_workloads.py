@@ -131,3 +131,16 @@ def test_additive_noise_families_have_the_requested_moments(family):
     if family == "bernoulli":                      # 0.45 Br(0.5)
         assert abs(prm["amplitude"] - 0.45) < 0.003 and abs(prm["p"] - 0.5) < 0.01
         assert set(np.unique(np.round(eps, 3))) <= {0.0, round(prm["amplitude"], 3)}
+
+
+def test_local_sgd_stragglers_by_scenario():
+    from dc_workloads import noise
+    for scenario, eligible in (("uniform", 32), ("single_server", 8)):
+        r = noise.local_sgd(T=400, period=16, scenario=scenario)
+        x = host.generate(r)
+        assert np.array_equal(host.generate_numpy(r).reshape(x.shape), x)
+        slow = x > 250_000
+        assert set(np.unique(x)) == {250_000, 1_250_000}
+        per_worker = slow.mean(axis=(0, 2))
+        assert np.all(per_worker[eligible:] == 0)
+        assert abs(per_worker[:eligible].mean() - 0.04) < 5 * math.sqrt(0.04 * 0.96 / (400 * 16 * eligible))
