@@ -36,7 +36,8 @@ __global__ __launch_bounds__(256)
 void dcgen_fill_kernel(int32_t* __restrict__ out, uint64_t idx0, uint64_t count, uint64_t key_value,
                        uint64_t key_spike, uint64_t N, uint64_t M, const int64_t* __restrict__ main_t,
                        const int64_t* __restrict__ lo_t, const int64_t* __restrict__ hi_t,
-                       const uint32_t* __restrict__ scale_q16, int64_t add, int64_t clip_min,
+                       const uint32_t* __restrict__ scale_q16, const int64_t* __restrict__ worker_add, int64_t add,
+                       int64_t clip_min,
                        uint32_t spike_thresh, uint32_t spike_mul, int64_t spike_add, int64_t spike_workers) {
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t e = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += stride) {
@@ -50,6 +51,7 @@ void dcgen_fill_kernel(int32_t* __restrict__ out, uint64_t idx0, uint64_t count,
             spike = (uint32_t)(mix64(key_spike + GOLDEN * (i + 1)) >> 32) < spike_thresh;
         const uint64_t mul = spike ? spike_mul : 1u;
         int64_t v = (int64_t)((q * s * mul + (1ull << 23)) >> 24);
+        if (worker_add) v += worker_add[worker];
         if (v < clip_min) v = clip_min;
         v += add + (spike ? spike_add : 0);
         out[e] = (int32_t)v;
@@ -58,18 +60,19 @@ void dcgen_fill_kernel(int32_t* __restrict__ out, uint64_t idx0, uint64_t count,
 
 }  // namespace
 
-// out, tables and scale_q16 are DEVICE pointers; scale_q16 may be NULL.  Enqueues on `stream`
+// out, tables, scale_q16 and worker_add are DEVICE pointers; scale_q16 and worker_add may be NULL.  Enqueues on `stream`
 // (hipStream_t as void*) and returns the hipError_t of the launch.
 extern "C" int dcgen_fill_device(int32_t* out, uint64_t idx0, uint64_t count, uint64_t key_value, uint64_t key_spike,
                                  int64_t N, int64_t M, const int64_t* main_t, const int64_t* lo_t,
-                                 const int64_t* hi_t, const uint32_t* scale_q16, int64_t add, int64_t clip_min,
+                                 const int64_t* hi_t, const uint32_t* scale_q16, const int64_t* worker_add, int64_t add,
+                                 int64_t clip_min,
                                  uint32_t spike_thresh, uint32_t spike_mul, int64_t spike_add, int64_t spike_workers,
                                  void* stream) {
     if (count == 0) return 0;
     uint64_t blocks = (count + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(dcgen_fill_kernel, dim3((uint32_t)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), out,
-                       idx0, count, key_value, key_spike, (uint64_t)N, (uint64_t)M, main_t, lo_t, hi_t, scale_q16, add,
+                       idx0, count, key_value, key_spike, (uint64_t)N, (uint64_t)M, main_t, lo_t, hi_t, scale_q16, worker_add, add,
                        clip_min, spike_thresh, spike_mul, spike_add, spike_workers);
     return (int)hipGetLastError();
 }

@@ -34,7 +34,7 @@ void dcgen_fill_host(int32_t* out, uint64_t idx0, uint64_t count,
                      uint64_t key_value, uint64_t key_spike,
                      int64_t N, int64_t M,
                      const int64_t* main_t, const int64_t* lo_t, const int64_t* hi_t,
-                     const uint32_t* scale_q16,
+                     const uint32_t* scale_q16, const int64_t* worker_add,
                      int64_t add, int64_t clip_min,
                      uint32_t spike_thresh, uint32_t spike_mul, int64_t spike_add, int64_t spike_workers) {
     for (uint64_t e = 0; e < count; ++e) {
@@ -48,6 +48,7 @@ void dcgen_fill_host(int32_t* out, uint64_t idx0, uint64_t count,
             spike = (uint32_t)(mix64(key_spike + DCGEN_GOLDEN * (i + 1)) >> 32) < spike_thresh;
         uint64_t mul = spike ? spike_mul : 1u;
         int64_t v = (int64_t)((q * s * mul + (1ull << 23)) >> 24);
+        if (worker_add) v += worker_add[worker];
         if (v < clip_min) v = clip_min;
         v += add + (spike ? spike_add : 0);
         out[e] = (int32_t)v;

@@ -40,7 +40,7 @@ def _load():
             raise ImportError(f"{_LIB_PATH} is missing: build it first")
         lib = ctypes.CDLL(str(_LIB_PATH))
         p, u64, i64, u32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int64, ctypes.c_uint32
-        lib.dcgen_fill_device.argtypes = [p, u64, u64, u64, u64, i64, i64, p, p, p, p, i64, i64, u32, u32, i64, i64, p]
+        lib.dcgen_fill_device.argtypes = [p, u64, u64, u64, u64, i64, i64, p, p, p, p, p, i64, i64, u32, u32, i64, i64, p]
         lib.dcgen_fill_device.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -56,13 +56,14 @@ def generate(r: Recipe, t0: int = 0, t1: int | None = None, device: str = "cuda:
               for t in (r.value.main, r.value.lo, r.value.hi)]
     scale_np = host.worker_scale_q16(r)
     scale = None if scale_np is None else torch.from_numpy(scale_np.view(np.int32).copy()).to(dev)
+    wadd = None if r.worker_add is None else torch.from_numpy(np.ascontiguousarray(r.worker_add, dtype=np.int64)).to(dev)
     with torch.cuda.device(dev):
         stream = torch.cuda.current_stream()
         rc = _load().dcgen_fill_device(
             out.data_ptr(), t0 * r.N * r.M, out.numel(),
             spec.stream_key(r.seed, spec.STREAM_VALUE), spec.stream_key(r.seed, spec.STREAM_SPIKE),
             r.N, r.M, tables[0].data_ptr(), tables[1].data_ptr(), tables[2].data_ptr(),
-            None if scale is None else scale.data_ptr(),
+            None if scale is None else scale.data_ptr(), None if wadd is None else wadd.data_ptr(),
             r.add, r.clip_min, r.spike_thresh, r.spike_mul, r.spike_add, r.spike_workers, int(stream.cuda_stream))
         if rc != 0:
             raise RuntimeError(f"dcgen_fill_device: hipError {rc}")

@@ -44,7 +44,7 @@ def _load():
         lib = ctypes.CDLL(str(_LIB_PATH))
         p = ctypes.c_void_p
         lib.dcgen_fill_host.argtypes = [p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
-                                        ctypes.c_int64, ctypes.c_int64, p, p, p, p,
+                                        ctypes.c_int64, ctypes.c_int64, p, p, p, p, p,
                                         ctypes.c_int64, ctypes.c_int64,
                                         ctypes.c_uint32, ctypes.c_uint32, ctypes.c_int64, ctypes.c_int64]
         lib.dcgen_fill_host.restype = None
@@ -103,6 +103,8 @@ def draw_q8(h: np.ndarray, tab: QuantileTables) -> np.ndarray:
 
 def worker_scale_q16(r: Recipe) -> np.ndarray | None:
     """Per-worker slowdown s_n in q16 fixed point, or None when every s_n = 1."""
+    if r.worker_scale_values is not None:
+        return np.asarray(r.worker_scale_values, dtype=np.uint32)
     if r.worker_scale is None:
         return None
     q = draw_q8(hash_counters(r.seed, spec.STREAM_WORKER, np.arange(r.N, dtype=np.uint64)), r.worker_scale)
@@ -124,6 +126,8 @@ def generate_numpy(r: Recipe, idx0: int = 0, count: int | None = None) -> np.nda
         spike = np.zeros(count, dtype=bool)
     mul = np.where(spike, np.uint64(r.spike_mul), np.uint64(1))
     v = ((q * s * mul + np.uint64(1 << 23)) >> np.uint64(24)).astype(np.int64)
+    if r.worker_add is not None:
+        v = v + np.asarray(r.worker_add, dtype=np.int64)[((i // np.uint64(r.M)) % np.uint64(r.N)).astype(np.int64)]
     v = np.maximum(v, r.clip_min) + r.add + np.where(spike, r.spike_add, 0)
     assert v.max(initial=0) < (1 << 31)
     return v.astype(np.int32)
@@ -138,6 +142,7 @@ class _Args:
         self.lo = np.ascontiguousarray(r.value.lo, dtype=np.int64)
         self.hi = np.ascontiguousarray(r.value.hi, dtype=np.int64)
         self.scale = worker_scale_q16(r)
+        self.worker_add = None if r.worker_add is None else np.ascontiguousarray(r.worker_add, dtype=np.int64)
         self.key_value = spec.stream_key(r.seed, spec.STREAM_VALUE)
         self.key_spike = spec.stream_key(r.seed, spec.STREAM_SPIKE)
 
@@ -149,6 +154,7 @@ def fill(r: Recipe, out: np.ndarray, idx0: int, args: _Args | None = None) -> No
     _load().dcgen_fill_host(out.ctypes.data, idx0, out.size, a.key_value, a.key_spike, r.N, r.M,
                             a.main.ctypes.data, a.lo.ctypes.data, a.hi.ctypes.data,
                             None if a.scale is None else a.scale.ctypes.data,
+                            None if a.worker_add is None else a.worker_add.ctypes.data,
                             r.add, r.clip_min, r.spike_thresh, r.spike_mul, r.spike_add, r.spike_workers)
 
 

@@ -9,6 +9,9 @@
                          local step a worker is a straggler with a 4% chance and then waits 1 s; either every worker
                          can straggle ("uniform") or only the workers of one server ("single_server").  The
                          undisturbed local-step time is not given in the appendix; 0.25 s is assumed.
+  per_worker_normal(...) Section 4.3 (iteration-time figure, "simulation" curve): every worker's iteration time T_n is
+                         drawn from a normal distribution with that worker's own mean and standard deviation; one
+                         "micro-batch" per worker (M = 1).
   additive_noise(...)    Appendix C.3: 12 accumulations of 0.45 s + eps, eps of mean 0.225 s and a chosen
                          variance from one of five families (lognormal, normal, bernoulli, exponential, gamma),
                          parameters derived from (mean, variance) as in the appendix's tables.
@@ -87,3 +90,18 @@ def local_sgd(T: int, period: int, scenario: str = "uniform", N: int = 32, step_
                   spike_workers=server_workers if scenario == "single_server" else 0,
                   description=f"{step_us} us per local step, +{wait_us} us w.p. {straggler_p} "
                               f"({'workers of one server' if scenario == 'single_server' else 'any worker'})")
+
+
+def per_worker_normal(T: int, mean_us, sd_us, K: int = 128, comm_us: int = 0, seed: int = 0) -> Recipe:
+    """T_n ~ Normal(mean_us[n], sd_us[n]^2), clipped at 0, M = 1.  The shared table holds (z + 8) * 1024 and each
+    worker scales it by sd/1024 and shifts it by mean - 8 sd, all in integers."""
+    mean_us = np.asarray(mean_us, dtype=np.float64)
+    sd_us = np.asarray(sd_us, dtype=np.float64)
+    if mean_us.shape != sd_us.shape or mean_us.ndim != 1 or (sd_us < 0).any() or (sd_us * 64 >= 2**32).any():
+        raise ValueError("mean_us and sd_us must be vectors of equal length, 0 <= sd < 2^26 us")
+    scale = np.rint(sd_us * 64.0).astype(np.uint32)                       # q16 of sd/1024
+    shift = np.rint(mean_us - 8.0 * scale.astype(np.float64) / 64.0).astype(np.int64)
+    return Recipe("per_worker_normal", T=T, N=mean_us.size, M=1, K=K, comm=comm_us, grid="pct",
+                  value=quantile_tables(lambda u: (ndtri(u) + 8.0) * 1024.0), seed=seed,
+                  worker_scale_values=tuple(int(v) for v in scale), worker_add=tuple(int(v) for v in shift),
+                  description="T_n ~ Normal(mean_n, sd_n^2) per worker, us")

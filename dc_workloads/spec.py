@@ -34,10 +34,10 @@ bit-identical):
     q      = draw(h(seed, 0, i))                                  (q8 microseconds)
     spike  = (h(seed, 1, i) >> 32) < spike_thresh   and, when spike_workers > 0, only for workers n < spike_workers
     mul    = spike ? spike_mul : 1
-    v      = (q * scale_q16[n] * mul + 2^23) >> 24                (round half up)
+    v      = ((q * scale_q16[n] * mul + 2^23) >> 24) + worker_add[n]   (round half up; worker_add defaults to 0)
     lat[i] = max(clip_min, v) + add + (spike ? spike_add : 0)
   scale_q16[n] = 65536 (no per-worker slowdown) or
-                 65536 + ((draw_scale(h(seed, 2, n)) + 128) >> 8).
+                 65536 + ((draw_scale(h(seed, 2, n)) + 128) >> 8), or explicit per-worker values.
 """
 from __future__ import annotations
 
@@ -158,6 +158,8 @@ class Recipe:
     spike_add: int = 0
     spike_workers: int = 0         # > 0: only the first spike_workers workers can spike (stragglers of one server)
     worker_scale: Optional[QuantileTables] = None   # q8 tables of 65536*(s_n - 1)
+    worker_scale_values: Optional[tuple] = None     # explicit scale_q16[n] (uint32) instead of drawn ones
+    worker_add: Optional[tuple] = None              # explicit per-worker offsets in microseconds (may be negative)
     description: str = ""
 
     @property

@@ -140,6 +140,17 @@ int dc_speedup_per_step_async(const int32_t* lat, int64_t T, int64_t N, int64_t 
 int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M,
                int64_t* out_sum, uint64_t* out_sumsq, double* out_mean, double* out_variance);
 
+/* Per-worker statistics of the compute time T_n = sum_m lat[t][n][m] over the T iterations (one streaming pass):
+ * the empirical mean and variance of each worker's iteration time, from which the paper's iteration-time figure
+ * redraws every T_n from a normal distribution (Section 4.3, "simulation" curve).  For worker n:
+ *   out_sum[n] = sum_t T_n;  out_sumsq[2n], out_sumsq[2n+1] = low and high 64 bits of sum_t T_n^2 (exact);
+ *   out_mean[n] = sum / T;   out_variance[n] = (sumsq*T - sum^2) / T^2  (population variance).
+ * lat: DEVICE.  Outputs HOST arrays of N (out_sumsq: 2N), each may be NULL.  N <= 2560 (the accumulators of all
+ * workers live in LDS), else DC_ERR_INVALID_ARG; latency preconditions and errors as dc_simulate.
+ * Null stream, synchronous, cached workspace. */
+int dc_worker_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M,
+                      int64_t* out_sum, uint64_t* out_sumsq, double* out_mean, double* out_variance);
+
 /* Closed-form estimates from (mu, sigma2) of one micro-batch latency (Sections 4.2-4.4, Appendix C.2):
  *   out_edone[k] = sum_{m=1..M} Phi((taus[k] - m*mu) / sqrt(m*sigma2))     expected completed micro-batches per
  *                  worker, the CLT estimate of M~ (Section 4.3); for sigma2 = 0 the count #{m : m*mu < tau}

@@ -12,6 +12,12 @@ Local-SGD, and of Local-SGD with the best drop threshold, relative to synchronis
 
   python noise_study.py [--families lognormal normal ...] [--workers 8 64 512 2048] [--variance 0.05] [--delay]
   python noise_study.py --local-sgd [--periods 1 2 4 8 16 32]
+
+With --surrogate it repeats the check of the paper's iteration-time figure: measure every worker's mean and variance
+of its iteration time (dc_worker_moments), redraw each T_n from a normal distribution with those moments, and compare
+the mean iteration time and the speedup curve of the surrogate with those of the original latencies.
+
+  python noise_study.py --surrogate [--workers 200]
 """
 from __future__ import annotations
 
@@ -67,6 +73,27 @@ def local_sgd_study(periods, trials: int) -> None:
                   f"{1 - float(done[best]) / (r.T * r.N * r.M):>9.3f}")
 
 
+def surrogate_study(N: int, trials: int) -> None:
+    import numpy as np
+
+    import paper_2306_10598_amd as dc
+    from dc_workloads import config, device, noise
+    r = config("heterogeneous2048").with_shape(T=trials, N=N, M=64, K=16)
+    lat = device.generate(r)
+    taus = np.append(device.tau_grid(r, lat), BIG)
+    step, done = dc.dc_simulate(lat, taus, r.comm)
+    _, _, mean, var = dc.dc_worker_moments(lat)
+    s = noise.per_worker_normal(trials, mean, np.sqrt(var), comm_us=r.comm)
+    s_step, _ = dc.dc_simulate(device.generate(s), taus, r.comm)
+    print(f"workers {N}, {trials} iterations, worker means {mean.min() / 1e6:.2f}..{mean.max() / 1e6:.2f} s")
+    print(f"mean iteration time: measured {(step[-1] / trials - r.comm) / 1e6:.4f} s, "
+          f"per-worker normal surrogate {(s_step[-1] / trials - r.comm) / 1e6:.4f} s")
+    print(f"{'tau us':>10}{'step speedup':>14}{'surrogate':>11}{'completed':>11}")
+    for k in range(taus.size - 1):
+        print(f"{int(taus[k]):>10}{step[-1] / step[k]:>14.4f}{s_step[-1] / s_step[k]:>11.4f}"
+              f"{done[k] / (trials * N * r.M):>11.4f}")
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--families", nargs="*", default=["lognormal", "normal", "bernoulli", "exponential", "gamma"])
@@ -75,8 +102,12 @@ def main() -> int:
     ap.add_argument("--elements", type=int, default=1 << 26, help="approximate T*N*M per point")
     ap.add_argument("--delay", action="store_true", help="also sweep the simulated-delay model of Appendix B.1")
     ap.add_argument("--local-sgd", action="store_true", help="sweep Local-SGD's synchronisation period instead")
+    ap.add_argument("--surrogate", action="store_true", help="per-worker normal surrogate of the iteration time")
     ap.add_argument("--periods", nargs="*", type=int, default=[1, 2, 4, 8, 16, 32])
     args = ap.parse_args()
+    if args.surrogate:
+        surrogate_study(args.workers[0] if len(args.workers) == 1 else 200, trials=4000)
+        return 0
     if args.local_sgd:
         local_sgd_study(args.periods, trials=20000)
         return 0

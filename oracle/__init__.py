@@ -204,3 +204,23 @@ def analytic_curves(mu: float, sigma2: float, N: int, M: int, taus, comm: int, m
         if score[k] > score[best] or (score[k] == score[best] and taus[k] > taus[best]):
             best = k
     return e_done, e_t, s_eff, best
+
+
+def worker_moments(lat: np.ndarray):
+    """Per worker n: exact sum and sum of squares over iterations of its compute time T_n = sum_m t_n^(m)
+    (Python ints), and mean / population variance as float arrays.  These are the per-worker statistics behind
+    the "simulation" curve of the paper's iteration-time figure (each worker's T_n redrawn from a normal
+    distribution with that worker's empirical mean and variance; Section 4.3).
+    """
+    lat = np.ascontiguousarray(lat, dtype=np.int64)
+    if lat.ndim != 3 or lat.size == 0:
+        raise OracleError(ERR_INVALID_ARG)
+    if (lat < 0).any():
+        raise OracleError(ERR_NEGATIVE_LATENCY)
+    T, N, _ = lat.shape
+    totals = lat.sum(axis=2)                                   # [T][N], each < 2^63
+    sums = [int(x) for x in totals.sum(axis=0)]
+    squares = [sum(int(v) * int(v) for v in totals[:, n]) for n in range(N)]
+    mean = np.array([s / T for s in sums], dtype=np.float64)
+    var = np.array([(q * T - s * s) / (T * T) for s, q in zip(sums, squares)], dtype=np.float64)
+    return sums, squares, mean, var

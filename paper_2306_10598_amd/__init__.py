@@ -22,7 +22,7 @@ DC_MAX_THRESHOLDS = 65536
 EXPORTS = (
     "dc_simulate", "dc_workspace_bytes", "dc_simulate_async", "dc_workspace_status", "dc_select_tau",
     "dc_speedup_per_step", "dc_speedup_workspace_bytes", "dc_speedup_per_step_async",
-    "dc_moments", "dc_analytic_curves",
+    "dc_moments", "dc_worker_moments", "dc_analytic_curves",
     "dc_set_kernel_timing", "dc_last_kernel_ms", "dc_status_string", "dc_last_device_error", "dc_shutdown",
 )
 
@@ -66,6 +66,8 @@ def _load():
     lib.dc_speedup_per_step_async.restype = ctypes.c_int
     lib.dc_moments.argtypes = [p, i64, i64, i64, p, p, p, p]
     lib.dc_moments.restype = ctypes.c_int
+    lib.dc_worker_moments.argtypes = [p, i64, i64, i64, p, p, p, p]
+    lib.dc_worker_moments.restype = ctypes.c_int
     lib.dc_analytic_curves.argtypes = [ctypes.c_double, ctypes.c_double, i64, i64, p, i64, i64, ctypes.c_double, p, p, p, p]
     lib.dc_analytic_curves.restype = ctypes.c_int
     lib.dc_set_kernel_timing.argtypes = [ctypes.c_int]
@@ -222,6 +224,23 @@ def dc_moments(lat):
     rc = _load().dc_moments(lat.data_ptr(), T, N, M, ctypes.byref(total), sq, ctypes.byref(mean), ctypes.byref(var))
     _check(rc, "dc_moments")
     return int(total.value), (int(sq[1]) << 64) | int(sq[0]), float(mean.value), float(var.value)
+
+
+def dc_worker_moments(lat):
+    """Per worker: (sums, sums of squares) of its iteration time as lists of exact Python ints, and (mean[N],
+    variance[N]) as NumPy float64 arrays."""
+    lat = _device_tensor(lat, "int32", "lat")
+    if lat.dim() != 3:
+        raise TypeError("lat must have shape [T][N][M]")
+    T, N, M = lat.shape
+    sums = np.empty(N, dtype=np.int64)
+    sq = np.empty(2 * N, dtype=np.uint64)
+    mean = np.empty(N, dtype=np.float64)
+    var = np.empty(N, dtype=np.float64)
+    rc = _load().dc_worker_moments(lat.data_ptr(), T, N, M, sums.ctypes.data, sq.ctypes.data, mean.ctypes.data,
+                                   var.ctypes.data)
+    _check(rc, "dc_worker_moments")
+    return ([int(v) for v in sums], [(int(sq[2 * n + 1]) << 64) | int(sq[2 * n]) for n in range(N)], mean, var)
 
 
 def dc_analytic_curves(mu: float, sigma2: float, N: int, M: int, taus, comm: int, mean_tmax=None):

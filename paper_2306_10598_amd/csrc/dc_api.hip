@@ -468,6 +468,45 @@ int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t* out
     return DC_OK;
 }
 
+int dc_worker_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t* out_sum, uint64_t* out_sumsq,
+                      double* out_mean, double* out_variance) {
+    if (!lat || ((uintptr_t)lat & 3u) || N > (int64_t)DC_MAX_STAT_WORKERS) return DC_ERR_INVALID_ARG;
+    dc::Plan p{};
+    if (!make_trial_plan(T, N, M, 1, ((uintptr_t)lat & 15u) == 0, &p)) return DC_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const uint32_t want = (uint32_t)compute_units() * 2u;             // 2 x 60 KiB of LDS always fit
+    if (p.grid > want) p.grid = want;
+    const size_t row_bytes = (size_t)N * 3 * 8;
+    int rc = ensure_cache(256 + align256(row_bytes) + align256((size_t)p.grid * row_bytes));
+    if (rc) return rc;
+    uint32_t* status = reinterpret_cast<uint32_t*>(g_cache);
+    unsigned long long* result = reinterpret_cast<unsigned long long*>(g_cache + 256);
+    unsigned long long* partial = reinterpret_cast<unsigned long long*>(g_cache + 256 + align256(row_bytes));
+    hipStream_t stream = nullptr;
+    dc::launch_worker_totals(p, lat, partial, result, status, stream);
+    DC_HIP(hipGetLastError());
+    uint32_t flags = 0;
+    DC_HIP(hipMemcpy(&flags, status, sizeof(flags), hipMemcpyDeviceToHost));
+    rc = flags_to_status(flags);
+    if (rc) return rc;
+    std::vector<unsigned long long> host((size_t)N * 3);
+    DC_HIP(hipMemcpy(host.data(), result, row_bytes, hipMemcpyDeviceToHost));
+    const long double tl = (long double)T;
+    for (int64_t n = 0; n < N; ++n) {
+        const unsigned long long sum = host[n], lo = host[N + n], hi = host[2 * N + n];
+        if (out_sum) out_sum[n] = (int64_t)sum;
+        if (out_sumsq) { out_sumsq[2 * n] = lo; out_sumsq[2 * n + 1] = hi; }
+        if (out_mean) out_mean[n] = (double)((long double)sum / tl);
+        if (out_variance) {
+            // (sumsq*T - sum^2) / T^2: sumsq < 2^93 and T < 2^31, so the numerator is exact in 128 bits
+            const unsigned __int128 sq = ((unsigned __int128)hi << 64) | lo;
+            const unsigned __int128 num = sq * (unsigned __int128)T - (unsigned __int128)sum * sum;
+            out_variance[n] = (double)((long double)num / (tl * tl));
+        }
+    }
+    return DC_OK;
+}
+
 namespace {
 
 // Standard normal quantile: a textbook starting value (rational approximation in t = sqrt(-2 ln q)),

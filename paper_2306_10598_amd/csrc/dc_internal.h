@@ -25,6 +25,7 @@
 #define DC_CHUNK_THRESHOLDS 4095u      // thresholds handled by one pass over lat (LDS-resident grid)
 #define DC_TRIAL_CHUNK_THRESHOLDS 2047u // same for the per-iteration speedup pass (it also keeps float64 sums in LDS)
 #define DC_MAX_TRIAL_BLOCKS 2048u      // upper bound of that pass's grid (sizes its per-block sums in the workspace)
+#define DC_MAX_STAT_WORKERS 2560u        // per-worker statistics keep 24 bytes per worker in LDS
 #define DC_TAU_CLAMP 0x80000000u       // thresholds at or above 2^31 exceed every completion time
 
 #define DC_FLAG_NEGATIVE_TAU 1u
@@ -70,6 +71,8 @@ void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_ch
 void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, uint32_t chunk0, const uint32_t* pos,
                              double* out_seff, hipStream_t stream);
 size_t trial_scan_lds_bytes(const Plan& p);
+void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long* partial,
+                          unsigned long long* result, uint32_t* status, hipStream_t stream);
 void launch_moments(const int32_t* lat, uint64_t n, uint32_t grid, unsigned long long* partial,
                     unsigned long long* result, uint32_t* status, hipStream_t stream);
 void launch_expected_done(const int64_t* taus, uint32_t K, uint32_t M, double mu, double sigma2, double* out,

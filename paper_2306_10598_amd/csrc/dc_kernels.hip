@@ -72,6 +72,7 @@ struct RowShape {
     uint32_t rows;       // whole rows per load
     uint32_t active;     // rows * lanes: lanes that take part (= 16-byte vectors per load)
     uint32_t pos;        // this lane's position inside its row
+    uint32_t row;        // which of the load's rows this lane belongs to
     bool ok;             // this lane takes part
 };
 
@@ -82,6 +83,7 @@ __device__ __forceinline__ RowShape row_shape(uint32_t lane, uint32_t lanes_per_
     r.rows = 64u / r.lanes;
     r.active = r.rows * r.lanes;
     r.pos = lane % r.lanes;
+    r.row = lane / r.lanes;
     r.ok = lane < r.active;
     return r;
 }
@@ -210,10 +212,11 @@ __device__ __forceinline__ void enqueue_active(WaveState& st, u32x4 x, uint32_t 
     }
 }
 
+// Completion time of each lane's last element for U loads at once (the U scans are independent, so
+// their DPP or crossbar steps interleave and no latency adds up).
 template <int L, int U>
-__device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U], uint4* queue, const GridView& g,
-                                              uint32_t lane, const RowShape& shape) {
-    uint32_t incl[U];
+__device__ __forceinline__ void completion_times(const u32x4 (&x)[U], uint32_t (&incl)[U], uint32_t lane,
+                                                 const RowShape& shape) {
     if constexpr (L == 0) {
         // rows of any length: the Kogge-Stone steps of all U scans go through the LDS crossbar together,
         // so their latencies overlap instead of adding up
@@ -233,6 +236,13 @@ __device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U]
 #pragma unroll
         for (int k = 0; k < U; ++k) incl[k] = lane_completion_time<L>(x[k], lane, shape);   // independent scans interleave
     }
+}
+
+template <int L, int U>
+__device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U], uint4* queue, const GridView& g,
+                                              uint32_t lane, const RowShape& shape) {
+    uint32_t incl[U];
+    completion_times<L, U>(x, incl, lane, shape);
 #pragma unroll
     for (int k = 0; k < U; ++k) {
         st.check = umax(st.check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
@@ -771,6 +781,126 @@ void dc_speedup_finalize_kernel(const double* __restrict__ partial, uint32_t blo
 }
 
 // ---------------------------------------------------------------------------------------------
+// Per-worker statistics of the compute time T_n = sum_m t_n^(m): sum and sum of squares over iterations
+// ---------------------------------------------------------------------------------------------
+// A block owns whole trials and a wave always the same rows of each trial, so every worker's accumulators
+// in LDS ([3][N]: sum, squares low word, squares high word) have one owner lane and need no atomics.
+
+__device__ __forceinline__ void add_worker_total(unsigned long long* acc, uint32_t N, uint32_t n, uint32_t total) {
+    acc[n] += total;
+    const unsigned long long sq = (unsigned long long)total * total;
+    const unsigned long long before = acc[N + n];
+    acc[N + n] = before + sq;
+    if (before + sq < before) acc[2 * N + n] += 1ull;
+}
+
+template <int L>
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N,
+                                  unsigned long long* __restrict__ partial, uint32_t* __restrict__ status,
+                                  uint32_t max_latency, uint32_t lanes_per_row) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
+    for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) acc[i] = 0ull;
+    __syncthreads();
+
+    constexpr int U = DC_SCAN_UNROLL;
+    const uint32_t lane = threadIdx.x & 63u;
+    const RowShape shape = row_shape<L>(lane, lanes_per_row);
+    const uint32_t R = shape.rows, M = 4 * shape.lanes;
+    const uint64_t stride = L ? 64u : shape.active;
+    const bool row_end = shape.ok && shape.pos == shape.lanes - 1;      // this lane ends a row: it holds the total
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t nfull = N / R, tail_rows = N - nfull * R;
+    const uint32_t lo = (uint32_t)((uint64_t)nfull * wave / DC_SCAN_WAVES);
+    const uint32_t hi = (uint32_t)((uint64_t)nfull * (wave + 1) / DC_SCAN_WAVES);
+    uint32_t check = 0u;
+    for (uint32_t t = blockIdx.x; t < T; t += gridDim.x) {
+        const u32x4* base = reinterpret_cast<const u32x4*>(lat + ((uint64_t)t * N + (uint64_t)lo * R) * M) + lane;
+        uint32_t i = 0;
+        for (; i + U <= hi - lo; i += U) {
+            u32x4 x[U];
+            uint32_t incl[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) x[k] = load_rows<L>(base + (uint64_t)(i + k) * stride, shape);
+            completion_times<L, U>(x, incl, lane, shape);
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                check = umax(check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
+                if (row_end) add_worker_total(acc, N, (lo + i + k) * R + shape.row, incl[k]);
+            }
+        }
+        for (; i < hi - lo; ++i) {
+            const u32x4 x[1] = {load_rows<L>(base + (uint64_t)i * stride, shape)};
+            uint32_t incl[1];
+            completion_times<L, 1>(x, incl, lane, shape);
+            check = umax(check, umax(umax(x[0].x, x[0].y), umax(x[0].z, x[0].w)));
+            if (row_end) add_worker_total(acc, N, (lo + i) * R + shape.row, incl[0]);
+        }
+        if (wave == DC_SCAN_WAVES - 1 && tail_rows) {
+            const bool valid = lane < tail_rows * shape.lanes;
+            u32x4 x[1] = {{0u, 0u, 0u, 0u}};
+            if (valid) x[0] = __builtin_nontemporal_load(base + (uint64_t)(hi - lo) * stride);
+            uint32_t incl[1];
+            completion_times<L, 1>(x, incl, lane, shape);
+            check = umax(check, umax(umax(x[0].x, x[0].y), umax(x[0].z, x[0].w)));
+            if (valid && row_end) add_worker_total(acc, N, nfull * R + shape.row, incl[0]);
+        }
+    }
+    report_range(check, max_latency, lane, status);
+    __syncthreads();
+    unsigned long long* out = partial + (uint64_t)blockIdx.x * 3 * N;
+    for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) out[i] = acc[i];
+}
+
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_worker_totals_generic_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N, uint32_t M,
+                                     unsigned long long* __restrict__ partial, uint32_t* __restrict__ status,
+                                     uint32_t max_latency) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
+    for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) acc[i] = 0ull;
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint32_t check = 0u;
+    for (uint32_t t = blockIdx.x; t < T; t += gridDim.x)
+        for (uint32_t r = wave; r < N; r += DC_SCAN_WAVES) {          // a wave keeps the same rows in every trial
+            const int32_t* row = lat + ((uint64_t)t * N + r) * M;
+            uint32_t carry = 0u;
+            for (uint32_t m0 = 0; m0 < M; m0 += 64) {
+                const uint32_t x = m0 + lane < M ? (uint32_t)row[m0 + lane] : 0u;
+                check = umax(check, x);
+                const uint32_t p = carry + segmented_inclusive_scan<64>(x, lane);
+                carry = (uint32_t)__builtin_amdgcn_readlane((int)p, 63);
+            }
+            if (lane == 0) add_worker_total(acc, N, r, carry);
+        }
+    report_range(check, max_latency, lane, status);
+    __syncthreads();
+    unsigned long long* out = partial + (uint64_t)blockIdx.x * 3 * N;
+    for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) out[i] = acc[i];
+}
+
+// result[3][N] = sums over blocks (the 128-bit squares with carry)
+__global__ __launch_bounds__(256)
+void dc_worker_totals_final_kernel(const unsigned long long* __restrict__ partial, uint32_t blocks, uint32_t N,
+                                   unsigned long long* __restrict__ result) {
+    const uint32_t n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    unsigned long long sum = 0ull;
+    unsigned __int128 sq = 0;
+    for (uint32_t b = 0; b < blocks; ++b) {
+        const unsigned long long* in = partial + (uint64_t)b * 3 * N;
+        sum += in[n];
+        sq += ((unsigned __int128)in[2 * N + n] << 64) | in[N + n];
+    }
+    result[n] = sum;
+    result[N + n] = (unsigned long long)sq;
+    result[2 * N + n] = (unsigned long long)(sq >> 64);
+}
+
+// ---------------------------------------------------------------------------------------------
 // launchers (called from dc_api.hip)
 // ---------------------------------------------------------------------------------------------
 namespace dc {
@@ -935,6 +1065,38 @@ void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, 
                              double* out_seff, hipStream_t stream) {
     hipLaunchKernelGGL(dc_speedup_finalize_kernel, dim3((p.K + 31) / 32), dim3(256), 0, stream, partial, p.grid,
                        p.p2, kc, chunk0, pos, p.K, (double)p.T, out_seff);
+}
+
+__global__ void dc_clear_status_kernel(uint32_t* status) { *status = 0u; }
+
+template <int L>
+static void launch_worker_vec4(const Plan& p, const int32_t* lat, unsigned long long* partial, uint32_t* status,
+                               hipStream_t stream) {
+    hipLaunchKernelGGL(dc_worker_totals_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS), (size_t)p.N * 24, stream,
+                       lat, p.T, p.N, partial, status, p.max_latency, p.M / 4);
+}
+
+// partial: [grid][3][N] u64; result: [3][N] u64 (sum, squares low, squares high per worker)
+void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long* partial,
+                          unsigned long long* result, uint32_t* status, hipStream_t stream) {
+    hipLaunchKernelGGL(dc_clear_status_kernel, dim3(1), dim3(1), 0, stream, status);
+    if (!p.vec4) {
+        hipLaunchKernelGGL(dc_worker_totals_generic_kernel, dim3(p.grid), dim3(DC_SCAN_THREADS), (size_t)p.N * 24,
+                           stream, lat, p.T, p.N, p.M, partial, status, p.max_latency);
+    } else {
+        switch (p.M / 4) {
+            case 1:  launch_worker_vec4<1>(p, lat, partial, status, stream); break;
+            case 2:  launch_worker_vec4<2>(p, lat, partial, status, stream); break;
+            case 4:  launch_worker_vec4<4>(p, lat, partial, status, stream); break;
+            case 8:  launch_worker_vec4<8>(p, lat, partial, status, stream); break;
+            case 16: launch_worker_vec4<16>(p, lat, partial, status, stream); break;
+            case 32: launch_worker_vec4<32>(p, lat, partial, status, stream); break;
+            case 64: launch_worker_vec4<64>(p, lat, partial, status, stream); break;
+            default: launch_worker_vec4<0>(p, lat, partial, status, stream); break;
+        }
+    }
+    hipLaunchKernelGGL(dc_worker_totals_final_kernel, dim3((p.N + 255) / 256), dim3(256), 0, stream, partial, p.grid,
+                       p.N, result);
 }
 
 }  // namespace dc

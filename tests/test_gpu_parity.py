@@ -397,6 +397,32 @@ def test_moments_of_a_workload_and_errors(dev):
     assert dc.dc_moments(flat[1:].view(4, 5, 64))[:2] == (1280, 1280)
 
 
+@pytest.mark.parametrize("shape", [(30, 64, 32), (7, 200, 64), (3, 2048, 256), (5, 2047, 128), (40, 33, 12),
+                                   (9, 10, 100), (6, 9, 300), (11, 5, 1), (4, 2560, 16)])
+def test_worker_moments_are_exact(shape, dev):
+    rng = np.random.default_rng(sum(shape))
+    top = (2**31 - 1) // shape[2]
+    lat = rng.integers(0, top + 1, size=shape, dtype=np.int32)
+    sums, squares, mean, var = oracle.worker_moments(lat)
+    gs, gq, gmean, gvar = dc.dc_worker_moments(to_dev(lat, dev))
+    assert gs == sums and gq == squares
+    assert np.allclose(gmean, mean, rtol=1e-14) and np.allclose(gvar, var, rtol=1e-12, atol=0)
+
+
+def test_worker_moments_of_a_workload_and_errors(dev):
+    r = config("heterogeneous2048").with_shape(T=20)
+    lat = host.generate(r)
+    sums, squares, mean, var = oracle.worker_moments(lat)
+    gs, gq, gmean, gvar = dc.dc_worker_moments(to_dev(lat, dev))
+    assert gs == sums and gq == squares
+    bad = np.ones((2, 3, 8), dtype=np.int32); bad[1, 2, 7] = -1
+    with pytest.raises(dc.DcError) as e:
+        dc.dc_worker_moments(to_dev(bad, dev))
+    assert e.value.status == dc.DC_ERR_NEGATIVE_LATENCY
+    with pytest.raises(dc.DcError):
+        dc.dc_worker_moments(torch.zeros((1, 2561, 4), dtype=torch.int32, device=dev))
+
+
 @pytest.mark.parametrize("name", ["lognormal64", "extrapolation2048", "heterogeneous2048"])
 def test_analytic_curves_parity(name, dev):
     r = config(name).with_shape(T=6)
@@ -438,6 +464,17 @@ def test_local_sgd_workloads_parity(scenario, period, dev):
     assert np.array_equal(device.generate(r).cpu().numpy(), lat)
     taus = np.append(host.tau_grid(r), BIG)
     check(lat, taus, r.comm, dev, "literal")
+
+
+def test_per_worker_normal_surrogate_parity(dev):
+    from dc_workloads import device, noise
+    r0 = config("heterogeneous2048").with_shape(T=60, N=96, M=64)
+    _, _, mean, var = dc.dc_worker_moments(device.generate(r0))
+    r = noise.per_worker_normal(3000, mean, np.sqrt(var), comm_us=r0.comm)
+    lat = host.generate(r)
+    assert np.array_equal(device.generate(r).cpu().numpy(), lat)
+    taus = np.append(host.tau_grid(r), BIG)
+    check(lat, taus, r.comm, dev)                                # M = 1
 
 
 # ---- full sizes of the two 2048-worker workloads, as the benchmark launches them -----------------------

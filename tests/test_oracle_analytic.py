@@ -76,3 +76,21 @@ def test_estimates_track_the_simulation_for_normal_latencies():
     assert np.allclose(e_done, done / (T * N), atol=0.03)
     assert e_t == pytest.approx((step[-1] - T * comm) / T, rel=2e-3)
     assert np.allclose(ana, sim, rtol=0.01)
+
+
+def test_worker_moments(golden_dir):
+    from tests.test_oracle_pins import read_golden
+    g = read_golden(golden_dir / "hand_example.txt")
+    lat = np.array(g["lat"], dtype=np.int32).reshape(1, 2, 3)
+    sums, squares, mean, var = oracle.worker_moments(lat)
+    assert sums == [12, 13] and squares == [144, 169] and var.tolist() == [0.0, 0.0]      # worker totals 12 and 13
+    rng = np.random.default_rng(4)
+    lat = rng.integers(0, 2**31 // 16, size=(50, 7, 16), dtype=np.int32)
+    sums, squares, mean, var = oracle.worker_moments(lat)
+    totals = lat.astype(np.float64).sum(axis=2)
+    assert np.allclose(mean, totals.mean(axis=0), rtol=1e-13) and np.allclose(var, totals.var(axis=0), rtol=1e-9)
+    assert sum(sums) == int(lat.astype(np.int64).sum())
+    # permuting iterations changes nothing; permuting workers permutes the result
+    perm = rng.permutation(7)
+    s2, q2, _, _ = oracle.worker_moments(lat[::-1][:, perm])
+    assert s2 == [sums[p] for p in perm] and q2 == [squares[p] for p in perm]

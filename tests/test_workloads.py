@@ -144,3 +144,17 @@ def test_local_sgd_stragglers_by_scenario():
         per_worker = slow.mean(axis=(0, 2))
         assert np.all(per_worker[eligible:] == 0)
         assert abs(per_worker[:eligible].mean() - 0.04) < 5 * math.sqrt(0.04 * 0.96 / (400 * 16 * eligible))
+
+
+def test_per_worker_normal_reproduces_each_workers_moments():
+    from dc_workloads import noise
+    rng = np.random.default_rng(3)
+    mean = rng.uniform(2.0e6, 4.0e6, size=24)
+    sd = rng.uniform(1.0e4, 3.0e5, size=24)
+    sd[5] = 0.0
+    r = noise.per_worker_normal(20000, mean, sd)
+    x = host.generate(r)
+    assert np.array_equal(host.generate_numpy(r, 0, 5000), x.reshape(-1)[:5000])
+    got_mean, got_sd = x[:, :, 0].mean(axis=0), x[:, :, 0].std(axis=0)
+    assert np.all(np.abs(got_mean - mean) <= 5 * sd / math.sqrt(20000) + 1.0)
+    assert np.allclose(got_sd, sd, rtol=0.03, atol=1.0)
