@@ -53,7 +53,12 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     if (p.vec4) {
         const uint64_t rows_per_load = 64 / (M / 4);
         const uint64_t loads_per_trial = ((uint64_t)N + rows_per_load - 1) / rows_per_load;
-        p.per_unit = DC_UNIT_LOADS;                               // 64 KiB of contiguous rows
+#ifdef DC_UNIT_LOADS
+        p.per_unit = DC_UNIT_LOADS;
+#else
+        // about 32 rows per unit, at least 16 loads (measured best on both 2048-worker workloads)
+        p.per_unit = (uint32_t)(32 / rows_per_load < 16 ? 16 : 32 / rows_per_load);
+#endif
         upt = (loads_per_trial + p.per_unit - 1) / p.per_unit;
     } else {
         uint64_t rows = 16384 / (4 * (uint64_t)M);                // about 16 KiB per unit
@@ -96,6 +101,10 @@ bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4
     p.elements = (uint64_t)T * (uint64_t)N * (uint64_t)M;
     p.vec4 = allow_vec4 && vec4_shape(M);
     p.grid = (uint32_t)(T < (int64_t)DC_MAX_TRIAL_BLOCKS ? T : DC_MAX_TRIAL_BLOCKS);
+    if (p.vec4) {
+        const uint32_t rows_per_load = 64u / (uint32_t)(M / 4);
+        p.per_unit = 32u / rows_per_load < 16u ? 16u : 32u / rows_per_load;         // as in make_plan
+    }
     p.chunk = p.K < DC_TRIAL_CHUNK_THRESHOLDS ? p.K : DC_TRIAL_CHUNK_THRESHOLDS;
     p.p2 = next_pow2_above(p.chunk);
     p.max_latency = (uint32_t)(2147483647ll / M);

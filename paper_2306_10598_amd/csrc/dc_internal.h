@@ -16,9 +16,6 @@
 #ifndef DC_MAX_SCAN_BLOCKS
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
 #endif
-#ifndef DC_UNIT_LOADS
-#define DC_UNIT_LOADS 64u               // 1 KiB loads per work unit (64 KiB of contiguous rows)
-#endif
 #define DC_SCAN_WAVES (DC_SCAN_THREADS / 64)
 #define DC_REDUCE_SLOTS 64u             // per-block histograms added by one block of the reduce kernel
 #define DC_FINAL_THREADS 1024
