@@ -56,8 +56,8 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
 #ifdef DC_UNIT_LOADS
         p.per_unit = DC_UNIT_LOADS;
 #else
-        // about 32 rows per unit, at least 16 loads (measured best on both 2048-worker workloads)
-        p.per_unit = (uint32_t)(32 / rows_per_load < 16 ? 16 : 32 / rows_per_load);
+        // measured: about 32 rows per unit for long rows (32 loads at M = 256, 16 at M = 128), 64 loads otherwise
+        p.per_unit = M >= 128 ? (uint32_t)(32 / rows_per_load < 16 ? 16 : 32 / rows_per_load) : 64u;
 #endif
         upt = (loads_per_trial + p.per_unit - 1) / p.per_unit;
     } else {
@@ -103,7 +103,7 @@ bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4
     p.grid = (uint32_t)(T < (int64_t)DC_MAX_TRIAL_BLOCKS ? T : DC_MAX_TRIAL_BLOCKS);
     if (p.vec4) {
         const uint32_t rows_per_load = 64u / (uint32_t)(M / 4);
-        p.per_unit = 32u / rows_per_load < 16u ? 16u : 32u / rows_per_load;         // as in make_plan
+        p.per_unit = M >= 128 ? (32u / rows_per_load < 16u ? 16u : 32u / rows_per_load) : 64u;   // as in make_plan
     }
     p.chunk = p.K < DC_TRIAL_CHUNK_THRESHOLDS ? p.K : DC_TRIAL_CHUNK_THRESHOLDS;
     p.p2 = next_pow2_above(p.chunk);

@@ -121,9 +121,9 @@ __device__ __forceinline__ uint32_t bin_of(const uint32_t* a, uint32_t p2, uint3
 
 // The threshold grid of one pass as the streaming kernel sees it, all in LDS:
 //   tau[p2]     ascending thresholds, padded with 0xFFFFFFFF
-//   lut[p2]     lut[c] = #{k : tau_k < tau0 + c*2^shift}: p2-1 uniform cells from tau0 on, the last one
-//               open-ended and beyond tau_last, so that a completion time v in cell c has its bin in
-//               [lut[c], lut[c+1]] (a short search; one step or none for evenly spaced thresholds)
+//   lut[p2]     lut[c] = #{k : tau_k < tau0 + c*2^shift} (lut[p2-1] = number of thresholds): p2-1 uniform
+//               cells from tau0 on, the last one open-ended, so that a completion time v in cell c has its
+//               bin in [lut[c], lut[c+1]] (a short search; one step or none for evenly spaced thresholds)
 //   hist[p2]    bin counts of the block
 struct GridView {
     const uint32_t* tau;
@@ -315,8 +315,15 @@ __device__ __forceinline__ GridView stage_grid(uint32_t* tables, const uint32_t*
         hist[i] = 0u;
     }
     __syncthreads();
-    // uniform cells of width 2^shift from the smallest threshold; the largest lands in a cell < p2-2
-    const uint32_t tau_first = tau_s[0], tau_last = tau_s[kc - 1];
+    // Uniform cells of width 2^shift from the smallest threshold.  They cover the thresholds up to tau_s[e];
+    // the last cell (p2-2) is open-ended and takes everything above.  e is the last threshold unless the
+    // list has a few far outliers at the top (typically one "infinite" threshold that yields the no-drop
+    // step time): those would stretch the cells until all other thresholds share two or three of them,
+    // so the top is peeled while the upper half of the range is more than 8 times as wide as the lower.
+    const uint32_t tau_first = tau_s[0];
+    uint32_t e = kc - 1;
+    while (e > (kc - 1) / 2 && (uint64_t)(tau_s[e] - tau_first) > 8ull * ((uint64_t)(tau_s[e / 2] - tau_first) + 1ull)) --e;
+    const uint32_t tau_last = tau_s[e];
     uint32_t shift = 0;                                        // p2 >= 4, so this stops at shift <= 31
     while (shift < 31 && ((tau_last - tau_first) >> shift) >= p2 - 2) ++shift;
     for (uint32_t c = threadIdx.x; c < p2; c += blockDim.x) {
@@ -326,7 +333,7 @@ __device__ __forceinline__ GridView stage_grid(uint32_t* tables, const uint32_t*
             const uint32_t mid = (lo + hi) >> 1;
             if ((uint64_t)tau_s[mid] < edge) lo = mid + 1; else hi = mid;
         }
-        lut[c] = lo;
+        lut[c] = c == p2 - 1 ? kc : lo;                        // upper end of the open-ended last cell
     }
     __syncthreads();
     return GridView{tau_s, lut, hist, p2, shift, tau_first};
