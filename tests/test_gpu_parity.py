@@ -164,6 +164,35 @@ def test_unaligned_tensor_takes_general_kernel(dev):
     assert np.array_equal(step, ref[0]) and np.array_equal(done, ref[1])
 
 
+# ---- random shapes, distributions and threshold lists -----------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_cases_against_the_literal_oracle(seed, dev):
+    rng = np.random.default_rng(1000 + seed)
+    M = int(rng.choice([1, 2, 4, 7, 8, 12, 16, 20, 32, 48, 64, 96, 128, 200, 256, 260, 384]))
+    N = int(rng.integers(1, 300))
+    T = int(rng.integers(1, max(2, 60000 // (N * M) + 2)))
+    top = min((2**31 - 1) // M, int(rng.choice([1, 10, 1000, 10**6, 10**9])))
+    kind = rng.integers(0, 4)
+    if kind == 0:
+        lat = rng.integers(0, top + 1, size=(T, N, M))
+    elif kind == 1:                                              # mostly equal rows: many ties with the thresholds
+        lat = np.full((T, N, M), top // 2) + rng.integers(0, 2, size=(T, N, M))
+    elif kind == 2:                                              # sparse: long runs of zero latency
+        lat = rng.integers(0, top + 1, size=(T, N, M)) * (rng.random((T, N, M)) < 0.1)
+    else:                                                        # heavy tail
+        lat = np.minimum(top, (top / 50 * rng.pareto(1.5, size=(T, N, M))).astype(np.int64))
+    lat = lat.astype(np.int32)
+    P = np.cumsum(lat.astype(np.int64), axis=2)
+    K = int(rng.choice([1, 2, 3, 17, 64, 300]))
+    pool = np.concatenate([P.reshape(-1), P.reshape(-1) + 1, [0, 1, int(P.max()) + 5, BIG, 1 << 31]])
+    taus = rng.choice(pool, size=K).astype(np.int64)             # thresholds on and next to completion times
+    if K > 3 and rng.random() < 0.5:
+        taus[rng.integers(0, K)] = int(P.max()) * 1000 + 7      # a far outlier
+    comm = int(rng.integers(0, 1000))
+    check(lat, taus, comm, dev, "literal")
+
+
 # ---- degenerate and adversarial inputs --------------------------------------------------------------
 
 def test_thresholds_spanning_every_completion_time(dev):
