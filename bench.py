@@ -81,6 +81,11 @@ def cpu_baseline(r, taus, target_seconds: float = 12.0):
         reps += 1
         dt = time.perf_counter() - t0
     sorted_rate = reps * trials * per_trial * taus.size / dt
+    # one thread, on a slab sized for a couple of seconds
+    t_one = max(1, min(trials, int(trials * 2.0 * reps / (dt * threads)) if dt > 0 else 1))
+    t0 = time.perf_counter()
+    oracle.simulate(lat[:t_one], taus, r.comm, "sorted")
+    d1 = time.perf_counter() - t0
     # the literal four-loop form on a slab small enough to finish in a few seconds
     t_lit = max(1, min(trials, int(2.0e10 // (per_trial * taus.size))))
     t0 = time.perf_counter()
@@ -90,6 +95,7 @@ def cpu_baseline(r, taus, target_seconds: float = 12.0):
         "value": sorted_rate, "unit": "evals/s", "cores": threads, "kind": "oracle",
         "sample": f"first {trials} of {r.T} trials of {r.name} (N={r.N}, M={r.M}, K={taus.size}), "
                   f"sorted-threshold oracle, {reps} passes in {dt:.2f} s; input generation not timed",
+        "value_1_thread": t_one * per_trial * taus.size / d1,
         "literal_value": t_lit * per_trial * taus.size / dl,
         "literal_sample": f"first {t_lit} trials, four-loop oracle, {dl:.2f} s",
     }
@@ -268,11 +274,13 @@ def main() -> int:
     if dc.dc_workspace_status(ws, stream) != dc.DC_OK:
         print("device reported a value error", file=sys.stderr)
         return 1
-    scan_ms = []
+    scan_ms, step_ms = [], []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
+        ts = time.perf_counter()
         thr, _, best = step()
+        step_ms.append(1e3 * (time.perf_counter() - ts))
         scan_ms.append(dc.dc_last_kernel_ms()[0])              # HIP events on the stream the kernel ran on
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -286,6 +294,7 @@ def main() -> int:
     line = {
         "metric": METRIC, "value": evals / (wall / args.steps), "unit": "evals/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": float(np.median(step_ms)), "ms_per_step_min": float(np.min(step_ms)),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"{r.name}: T={r.T} N={r.N} M={r.M} K={K} comm={r.comm}us, {r.description}",
