@@ -22,8 +22,9 @@
  *     current device; "HOST" pointers are ordinary host memory.
  *   - lat must be 4-byte aligned; rows are contiguous with m fastest: element (t,n,m) is at
  *     lat[(t*N + n)*M + m].  The fast kernels need lat 16-byte aligned and M a multiple of 4
- *     up to 256 (fastest when M is a power of two); every other M >= 1 (and any alignment)
- *     takes a slower kernel with the same results.
+ *     up to 256 (fastest when M is a power of two); longer rows with M a multiple of 4 use
+ *     16-byte loads in a general kernel; every other M >= 1 (and any alignment) takes a
+ *     slower kernel with the same results.
  *   - Preconditions on values, checked while streaming: every latency is >= 0
  *     (else DC_ERR_NEGATIVE_LATENCY) and <= floor((2^31-1)/M) (else DC_ERR_RANGE), which
  *     guarantees that no worker's total overflows 31 bits.

@@ -49,6 +49,7 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     p.T = (uint32_t)T; p.N = (uint32_t)N; p.M = (uint32_t)M; p.K = (uint32_t)K;
     p.elements = (uint64_t)T * (uint64_t)N * (uint64_t)M;
     p.vec4 = allow_vec4 && vec4_shape(M);
+    p.wide = allow_vec4 && !p.vec4 && (M & 3) == 0;
     uint64_t upt;
     if (p.vec4) {
         const uint64_t rows_per_load = 64 / (M / 4);
@@ -100,6 +101,7 @@ bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4
     p.T = (uint32_t)T; p.N = (uint32_t)N; p.M = (uint32_t)M; p.K = (uint32_t)K;
     p.elements = (uint64_t)T * (uint64_t)N * (uint64_t)M;
     p.vec4 = allow_vec4 && vec4_shape(M);
+    p.wide = allow_vec4 && !p.vec4 && (M & 3) == 0;
     p.grid = (uint32_t)(T < (int64_t)DC_MAX_TRIAL_BLOCKS ? T : DC_MAX_TRIAL_BLOCKS);
     if (p.vec4) {
         const uint32_t rows_per_load = 64u / (uint32_t)(M / 4);
@@ -167,7 +169,7 @@ uint32_t resident_blocks(const dc::Plan& p, bool trial = false) {
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return DC_MAX_SCAN_BLOCKS;
     for (const ResidentKey& k : g_resident)
-        if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == (p.vec4 ? p.M : 0) && k.p2 == p.p2)
+        if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == (p.vec4 ? p.M : (p.wide ? 1u : 0u)) && k.p2 == p.p2)
             return (uint32_t)k.blocks;
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1) cus = 256;
@@ -176,7 +178,7 @@ uint32_t resident_blocks(const dc::Plan& p, bool trial = false) {
     const int wanted = (int)wanted_blocks_per_cu(p);                                    // what streams best
     if (per_cu > wanted) per_cu = wanted;
     const int blocks = cus * per_cu;
-    g_resident.push_back({device, p.vec4, trial, p.vec4 ? p.M : 0, p.p2, blocks});
+    g_resident.push_back({device, p.vec4, trial, p.vec4 ? p.M : (p.wide ? 1u : 0u), p.p2, blocks});
     return (uint32_t)blocks;
 }
 

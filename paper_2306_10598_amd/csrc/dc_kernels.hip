@@ -438,9 +438,67 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
 }
 
 // ---------------------------------------------------------------------------------------------
-// dc_scan_generic_kernel: any M >= 1, any 4-byte alignment.  One wave walks the rows of its unit,
-// 64 elements at a time, carrying the running completion time from strip to strip.
+// The general kernels (any M >= 1): one wave walks a row in strips, carrying the running completion
+// time from strip to strip.  WIDE: 16-byte loads, 256 elements per strip (M a multiple of 4, lat
+// 16-byte aligned; this is the path of rows longer than 256); otherwise 4-byte loads, 64 per strip.
+// Four strips are in flight; their scans are independent, only the carries are chained.
+// visit(x, incl) is called for every lane that holds elements: x = its latencies (x.x only when
+// not WIDE), incl = the completion time of its last element.  Returns the row total.
 // ---------------------------------------------------------------------------------------------
+template <bool WIDE, typename F>
+__device__ __forceinline__ uint32_t walk_row(const int32_t* __restrict__ row, uint32_t M, uint32_t lane,
+                                             uint32_t& check, F&& visit) {
+    constexpr uint32_t E = WIDE ? 4u : 1u;
+    constexpr int S = 4;
+    uint32_t carry = 0u;
+    for (uint32_t m0 = 0; m0 < M; m0 += 64u * E * S) {
+        u32x4 x[S];
+        uint32_t incl[S];
+        bool valid[S];
+#pragma unroll
+        for (int k = 0; k < S; ++k) {
+            const uint32_t idx = m0 + (uint32_t)k * 64u * E + lane * E;
+            valid[k] = idx < M;                                 // WIDE: M % 4 == 0, so idx + 3 < M as well
+            x[k] = u32x4{0u, 0u, 0u, 0u};
+            if (valid[k]) {
+                if constexpr (WIDE) x[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + idx));
+                else x[k].x = (uint32_t)row[idx];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < S; ++k) {
+            check = umax(check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
+            incl[k] = segmented_inclusive_scan<64>(x[k].x + x[k].y + x[k].z + x[k].w, lane);
+        }
+#pragma unroll
+        for (int k = 0; k < S; ++k) {
+            incl[k] += carry;
+            carry = (uint32_t)__builtin_amdgcn_readlane((int)incl[k], 63);
+            if (valid[k]) visit(x[k], incl[k]);
+        }
+    }
+    return carry;
+}
+
+// Histogram update of one lane's completion times in the general kernels (no queue: rows that need
+// these kernels are either short and rare or long with few elements inside the grid).
+template <bool WIDE>
+__device__ __forceinline__ void bin_lane(const uint32_t* tau_s, uint32_t* hist, uint32_t p2, uint32_t tau0,
+                                         u32x4 x, uint32_t incl) {
+    if (incl < tau0) return;
+    atomicAdd(&hist[bin_of(tau_s, p2, incl)], 1u);
+    if constexpr (WIDE) {
+        const uint32_t c2 = incl - x.w, c1 = c2 - x.z, c0 = c1 - x.y;
+        if (c2 >= tau0) atomicAdd(&hist[bin_of(tau_s, p2, c2)], 1u);
+        if (c1 >= tau0) atomicAdd(&hist[bin_of(tau_s, p2, c1)], 1u);
+        if (c0 >= tau0) atomicAdd(&hist[bin_of(tau_s, p2, c0)], 1u);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dc_scan_generic_kernel: any M >= 1, any 4-byte alignment.  One wave walks the rows of its unit.
+// ---------------------------------------------------------------------------------------------
+template <bool WIDE>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_scan_generic_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t M, uint32_t units,
                             uint32_t units_per_trial, uint32_t rows_per_unit,
@@ -470,18 +528,9 @@ void dc_scan_generic_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_
         uint32_t best = 0u;
         for (uint32_t r = 0; r < rows; ++r) {
             const int32_t* row = lat + ((uint64_t)t * N + row0 + r) * M;
-            uint32_t carry = 0u;                                   // completion time before this strip
-            for (uint32_t m0 = 0; m0 < M; m0 += 64) {
-                const bool valid = m0 + lane < M;
-                const uint32_t x = valid ? (uint32_t)row[m0 + lane] : 0u;
-                check = umax(check, x);
-                const uint32_t p = carry + segmented_inclusive_scan<64>(x, lane);
-                if (valid && p >= tau0) {
-                    const uint32_t b = bin_of(tau_s, p2, p);
-                    atomicAdd(&hist[b], 1u);
-                }
-                carry = (uint32_t)__builtin_amdgcn_readlane((int)p, 63);
-            }
+            const uint32_t carry = walk_row<WIDE>(row, M, lane, check, [&](u32x4 x, uint32_t incl) {
+                bin_lane<WIDE>(tau_s, hist, p2, tau0, x, incl);
+            });
             best = umax(best, carry);                              // the worker's total
         }
         if (lane == 0) unit_max[u] = best;
@@ -736,6 +785,7 @@ void dc_trial_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
 }
 
 // Any M >= 1, any 4-byte alignment: the waves of the block take the trial's rows in turn.
+template <bool WIDE>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_trial_scan_generic_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N, uint32_t M,
                                   const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
@@ -759,15 +809,9 @@ void dc_trial_scan_generic_kernel(const int32_t* __restrict__ lat, uint32_t T, u
         uint32_t best = 0u;
         for (uint32_t r = wave; r < N; r += DC_SCAN_WAVES) {
             const int32_t* row = lat + ((uint64_t)t * N + r) * M;
-            uint32_t carry = 0u;
-            for (uint32_t m0 = 0; m0 < M; m0 += 64) {
-                const bool valid = m0 + lane < M;
-                const uint32_t x = valid ? (uint32_t)row[m0 + lane] : 0u;
-                check = umax(check, x);
-                const uint32_t p = carry + segmented_inclusive_scan<64>(x, lane);
-                if (valid && p >= g.tau0) atomicAdd(&g.hist[bin_of(g.tau, p2, p)], 1u);
-                carry = (uint32_t)__builtin_amdgcn_readlane((int)p, 63);
-            }
+            const uint32_t carry = walk_row<WIDE>(row, M, lane, check, [&](u32x4 x, uint32_t incl) {
+                bin_lane<WIDE>(g.tau, g.hist, p2, g.tau0, x, incl);
+            });
             best = umax(best, carry);
         }
         if (lane == 0) atomicMax(sh.block_max, best);
@@ -877,6 +921,7 @@ void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, u
     for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) out[i] = acc[i];
 }
 
+template <bool WIDE>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_worker_totals_generic_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N, uint32_t M,
                                      unsigned long long* __restrict__ partial, uint32_t* __restrict__ status,
@@ -891,13 +936,7 @@ void dc_worker_totals_generic_kernel(const int32_t* __restrict__ lat, uint32_t T
     for (uint32_t t = blockIdx.x; t < T; t += gridDim.x)
         for (uint32_t r = wave; r < N; r += DC_SCAN_WAVES) {          // a wave keeps the same rows in every trial
             const int32_t* row = lat + ((uint64_t)t * N + r) * M;
-            uint32_t carry = 0u;
-            for (uint32_t m0 = 0; m0 < M; m0 += 64) {
-                const uint32_t x = m0 + lane < M ? (uint32_t)row[m0 + lane] : 0u;
-                check = umax(check, x);
-                const uint32_t p = carry + segmented_inclusive_scan<64>(x, lane);
-                carry = (uint32_t)__builtin_amdgcn_readlane((int)p, 63);
-            }
+            const uint32_t carry = walk_row<WIDE>(row, M, lane, check, [](u32x4, uint32_t) {});
             if (lane == 0) add_worker_total(acc, N, r, carry);
         }
     report_range(check, max_latency, lane, status);
@@ -956,7 +995,8 @@ int scan_blocks_per_cu(const Plan& p) {
     const size_t lds = scan_lds_bytes(p);
     int n = 0;
     if (!p.vec4) {
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_generic_kernel, DC_SCAN_THREADS, lds) != hipSuccess) n = 0;
+        if ((p.wide ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_generic_kernel<true>, DC_SCAN_THREADS, lds)
+                    : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_generic_kernel<false>, DC_SCAN_THREADS, lds)) != hipSuccess) n = 0;
         return n;
     }
     switch (p.M / 4) {
@@ -982,9 +1022,14 @@ static void launch_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_c
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
                  uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
     if (!p.vec4) {
-        hipLaunchKernelGGL(dc_scan_generic_kernel, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
-                           lat, p.N, p.M, p.units, p.units_per_trial, p.per_unit, tau_chunk, kc, p.p2, unit_max,
-                           hist_part, status, p.max_latency);
+        if (p.wide)
+            hipLaunchKernelGGL(dc_scan_generic_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p),
+                               stream, lat, p.N, p.M, p.units, p.units_per_trial, p.per_unit, tau_chunk, kc, p.p2,
+                               unit_max, hist_part, status, p.max_latency);
+        else
+            hipLaunchKernelGGL(dc_scan_generic_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p),
+                               stream, lat, p.N, p.M, p.units, p.units_per_trial, p.per_unit, tau_chunk, kc, p.p2,
+                               unit_max, hist_part, status, p.max_latency);
         return;
     }
     switch (p.M / 4) {
@@ -1035,7 +1080,8 @@ int trial_scan_blocks_per_cu(const Plan& p) {
     const size_t lds = trial_scan_lds_bytes(p);
     int n = 0;
     if (!p.vec4) {
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_generic_kernel, DC_SCAN_THREADS, lds) != hipSuccess) n = 0;
+        if ((p.wide ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_generic_kernel<true>, DC_SCAN_THREADS, lds)
+                    : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_generic_kernel<false>, DC_SCAN_THREADS, lds)) != hipSuccess) n = 0;
         return n;
     }
     switch (p.M / 4) {
@@ -1068,9 +1114,14 @@ void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_ch
                        const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
                        hipStream_t stream) {
     if (!p.vec4) {
-        hipLaunchKernelGGL(dc_trial_scan_generic_kernel, dim3(p.grid), dim3(DC_SCAN_THREADS), trial_scan_lds_bytes(p),
-                           stream, lat, p.T, p.N, p.M, tau_chunk, kc, p.p2, (const long long*)comm_per_trial,
-                           (long long)comm, partial, status, p.max_latency);
+        if (p.wide)
+            hipLaunchKernelGGL(dc_trial_scan_generic_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS),
+                               trial_scan_lds_bytes(p), stream, lat, p.T, p.N, p.M, tau_chunk, kc, p.p2,
+                               (const long long*)comm_per_trial, (long long)comm, partial, status, p.max_latency);
+        else
+            hipLaunchKernelGGL(dc_trial_scan_generic_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS),
+                               trial_scan_lds_bytes(p), stream, lat, p.T, p.N, p.M, tau_chunk, kc, p.p2,
+                               (const long long*)comm_per_trial, (long long)comm, partial, status, p.max_latency);
         return;
     }
     switch (p.M / 4) {
@@ -1105,8 +1156,12 @@ void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long*
                           unsigned long long* result, uint32_t* status, hipStream_t stream) {
     hipLaunchKernelGGL(dc_clear_status_kernel, dim3(1), dim3(1), 0, stream, status);
     if (!p.vec4) {
-        hipLaunchKernelGGL(dc_worker_totals_generic_kernel, dim3(p.grid), dim3(DC_SCAN_THREADS), (size_t)p.N * 24,
-                           stream, lat, p.T, p.N, p.M, partial, status, p.max_latency);
+        if (p.wide)
+            hipLaunchKernelGGL(dc_worker_totals_generic_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS),
+                               (size_t)p.N * 24, stream, lat, p.T, p.N, p.M, partial, status, p.max_latency);
+        else
+            hipLaunchKernelGGL(dc_worker_totals_generic_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS),
+                               (size_t)p.N * 24, stream, lat, p.T, p.N, p.M, partial, status, p.max_latency);
     } else {
         switch (p.M / 4) {
             case 1:  launch_worker_vec4<1>(p, lat, partial, status, stream); break;
