@@ -170,12 +170,12 @@ int dc_analytic_curves(double mu, double sigma2, int64_t N, int64_t M, const int
                        int64_t comm, double mean_tmax,
                        double* out_edone, double* out_seff, double* out_et, int64_t* out_best_k);
 
-/* Optional kernel timing for benchmarks.  When enabled, every dc_simulate / dc_simulate_async
- * brackets its streaming kernel (the single pass over lat) and the whole enqueued sequence with
- * HIP events on the stream it runs on.  dc_last_kernel_ms waits for those events and returns the
- * elapsed milliseconds of the last call (scan_ms: streaming kernel(s) only; total_ms: all
- * kernels of the call).  Either pointer may be NULL.  DC_ERR_INVALID_ARG if timing is off or no
- * call has been timed yet. */
+/* Optional kernel timing for benchmarks.  enable = 1: every entry point that streams lat brackets its
+ * streaming kernel (the single pass over lat) with HIP events on the stream it runs on; enable = 2:
+ * also the whole enqueued sequence (two more event records per call); 0: off.  dc_last_kernel_ms waits
+ * for those events and returns the elapsed milliseconds of the last call (scan_ms: streaming kernel(s)
+ * only; total_ms: all kernels of the call, needs enable = 2).  Either pointer may be NULL.
+ * DC_ERR_INVALID_ARG if the requested timing is off or no call has been timed yet. */
 int dc_set_kernel_timing(int enable);
 int dc_last_kernel_ms(float* scan_ms, float* total_ms);
 

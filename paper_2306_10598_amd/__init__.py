@@ -258,15 +258,16 @@ def dc_analytic_curves(mu: float, sigma2: float, N: int, M: int, taus, comm: int
     return e_done, float(e_t.value), s_eff, int(best.value)
 
 
-def dc_set_kernel_timing(enable: bool) -> None:
-    _check(_load().dc_set_kernel_timing(1 if enable else 0), "dc_set_kernel_timing")
+def dc_set_kernel_timing(enable) -> None:
+    """False/0: off; True/1: time the streaming kernel; 2: also the whole enqueued sequence."""
+    _check(_load().dc_set_kernel_timing(int(enable)), "dc_set_kernel_timing")
 
 
-def dc_last_kernel_ms():
-    """(scan_ms, total_ms) of the last timed call."""
+def dc_last_kernel_ms(whole: bool = False):
+    """(scan_ms, total_ms) of the last timed call; total_ms is None unless whole=True (timing level 2)."""
     a, b = ctypes.c_float(0), ctypes.c_float(0)
-    _check(_load().dc_last_kernel_ms(ctypes.byref(a), ctypes.byref(b)), "dc_last_kernel_ms")
-    return float(a.value), float(b.value)
+    _check(_load().dc_last_kernel_ms(ctypes.byref(a), ctypes.byref(b) if whole else None), "dc_last_kernel_ms")
+    return float(a.value), (float(b.value) if whole else None)
 
 
 def dc_shutdown() -> None:

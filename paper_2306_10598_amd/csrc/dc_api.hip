@@ -124,6 +124,7 @@ bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4
 // ---- optional timing ---------------------------------------------------------------------------
 struct Timing {
     bool enabled = false;
+    bool whole = false;                // also bracket the whole enqueued sequence (two more event records)
     bool valid = false;
     hipEvent_t begin = nullptr, end = nullptr;
     std::vector<hipEvent_t> scan;      // pairs (before, after) per chunk
@@ -206,7 +207,7 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
         if (rc) return rc;
         g_timing.used_pairs = chunks;
         g_timing.valid = false;
-        DC_HIP(hipEventRecord(g_timing.begin, stream));
+        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.begin, stream));
     }
     dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, hist_total, 3 * p.p2, stream);
     for (uint32_t c = 0; c < chunks; ++c) {
@@ -220,7 +221,7 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
                             out_done_dev, chunk_step, chunk_done, stream);
     }
     if (timed) {
-        DC_HIP(hipEventRecord(g_timing.end, stream));
+        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.end, stream));
         g_timing.valid = true;
     }
     DC_HIP(hipGetLastError());
@@ -251,7 +252,7 @@ int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* tau
         if (rc) return rc;
         g_timing.used_pairs = chunks;
         g_timing.valid = false;
-        DC_HIP(hipEventRecord(g_timing.begin, stream));
+        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.begin, stream));
     }
     dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, nullptr, 0, stream);
     for (uint32_t c = 0; c < chunks; ++c) {
@@ -263,7 +264,7 @@ int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* tau
         dc::launch_speedup_finalize(p, partial, kc, chunk0, pos, out_seff_dev, stream);
     }
     if (timed) {
-        DC_HIP(hipEventRecord(g_timing.end, stream));
+        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.end, stream));
         g_timing.valid = true;
     }
     DC_HIP(hipGetLastError());
@@ -448,13 +449,13 @@ int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t* out
         if (rc) return rc;
         g_timing.used_pairs = 1;
         g_timing.valid = false;
-        DC_HIP(hipEventRecord(g_timing.begin, stream));
+        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.begin, stream));
         DC_HIP(hipEventRecord(g_timing.scan[0], stream));
     }
     dc::launch_moments(lat, n, grid, partial, result, status, stream);
     if (timed) {
         DC_HIP(hipEventRecord(g_timing.scan[1], stream));
-        DC_HIP(hipEventRecord(g_timing.end, stream));
+        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.end, stream));
         g_timing.valid = true;
     }
     DC_HIP(hipGetLastError());
@@ -606,15 +607,19 @@ int dc_select_tau(const int64_t* step_sum, const int64_t* done_sum, const int64_
 int dc_set_kernel_timing(int enable) {
     std::lock_guard<std::mutex> lock(g_mutex);
     g_timing.enabled = enable != 0;
+    g_timing.whole = enable >= 2;
     g_timing.valid = false;
     return DC_OK;
 }
 
 int dc_last_kernel_ms(float* scan_ms, float* total_ms) {
     std::lock_guard<std::mutex> lock(g_mutex);
-    if (!g_timing.enabled || !g_timing.valid) return DC_ERR_INVALID_ARG;
-    DC_HIP(hipEventSynchronize(g_timing.end));
-    if (total_ms) DC_HIP(hipEventElapsedTime(total_ms, g_timing.begin, g_timing.end));
+    if (!g_timing.enabled || !g_timing.valid || (total_ms && !g_timing.whole)) return DC_ERR_INVALID_ARG;
+    DC_HIP(hipEventSynchronize(g_timing.scan[2 * g_timing.used_pairs - 1]));
+    if (total_ms) {
+        DC_HIP(hipEventSynchronize(g_timing.end));
+        DC_HIP(hipEventElapsedTime(total_ms, g_timing.begin, g_timing.end));
+    }
     if (scan_ms) {
         float acc = 0.f;
         for (size_t c = 0; c < g_timing.used_pairs; ++c) {

@@ -574,34 +574,44 @@ void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t slots, ui
         }
         return;
     }
-    // (b) one thread per trial
+    // (b) one thread per trial.  The trial maxima of a block are binned in LDS first (maxima of one
+    // workload crowd into a few bins, and same-address atomics in device memory serialise), then the
+    // bins that were hit go to device memory: at most one addition per bin and block.
+    extern __shared__ unsigned long long bin_sum[];                       // [p2], then the counts
+    uint32_t* bin_cnt = reinterpret_cast<uint32_t*>(bin_sum + p2);        // [p2]
+    for (uint32_t i = threadIdx.x; i < p2; i += 256) {
+        bin_sum[i] = 0ull;
+        bin_cnt[i] = 0u;
+    }
+    __syncthreads();
     const uint32_t t = (blockIdx.x - hist_blocks) * 256 + threadIdx.x;
-    const bool live = t < T;
-    uint32_t tmax = 0u;
-    if (live) {
+    if (t < T) {
+        uint32_t tmax = 0u;
         const uint32_t* um = unit_max + (uint64_t)t * units_per_trial;
-        for (uint32_t j = 0; j < units_per_trial; ++j) tmax = umax(tmax, um[j]);
-    }
-    // b = #{i < kc : tau_i <= tmax}; the trial's step time is tmax for thresholds i >= b, tau_i below
-    uint32_t lo = 0, hi = kc;
-    while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (tau_chunk[mid] <= tmax) lo = mid + 1; else hi = mid;
-    }
-    // Trial maxima of one workload crowd into a few bins: when a whole wave agrees on the bin,
-    // it adds once instead of 64 times to the same address.
-    const uint32_t first = __builtin_amdgcn_readfirstlane(lo);
-    if (__all(live && lo == first)) {
-        unsigned long long sum = tmax;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
-        if (lane == 0) {
-            atomicAdd(&trial_cnt[first], 64ull);
-            atomicAdd(&trial_sum[first], sum);
+        if ((units_per_trial & 3u) == 0u) {                               // unit_max is 256-byte aligned
+            for (uint32_t j = 0; j < units_per_trial; j += 4) {
+                const uint4 v = *reinterpret_cast<const uint4*>(um + j);
+                tmax = umax(umax(tmax, v.x), umax(umax(v.y, v.z), v.w));
+            }
+        } else {
+            for (uint32_t j = 0; j < units_per_trial; ++j) tmax = umax(tmax, um[j]);
         }
-    } else if (live) {
-        atomicAdd(&trial_cnt[lo], 1ull);
-        atomicAdd(&trial_sum[lo], (unsigned long long)tmax);
+        // b = #{i < kc : tau_i <= tmax}; the trial's step time is tmax for thresholds i >= b, tau_i below
+        uint32_t lo = 0, hi = kc;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (tau_chunk[mid] <= tmax) lo = mid + 1; else hi = mid;
+        }
+        atomicAdd(&bin_cnt[lo], 1u);
+        atomicAdd(&bin_sum[lo], (unsigned long long)tmax);
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i <= kc; i += 256) {
+        const uint32_t c = bin_cnt[i];
+        if (c) {
+            atomicAdd(&trial_cnt[i], (unsigned long long)c);
+            atomicAdd(&trial_sum[i], bin_sum[i]);
+        }
     }
 }
 
@@ -1051,7 +1061,7 @@ void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long*
     const uint32_t slot_groups = (p.grid + DC_REDUCE_SLOTS - 1) / DC_REDUCE_SLOTS;
     const uint32_t hist_blocks = col_blocks * slot_groups;
     const uint32_t trial_blocks = (p.T + 255) / 256;
-    hipLaunchKernelGGL(dc_reduce_kernel, dim3(hist_blocks + trial_blocks), dim3(256), 0, stream, hist_part, p.grid,
+    hipLaunchKernelGGL(dc_reduce_kernel, dim3(hist_blocks + trial_blocks), dim3(256), (size_t)p.p2 * 12, stream, hist_part, p.grid,
                        p.p2, col_blocks, hist_blocks, hist_total, unit_max, p.T, p.units_per_trial, tau_chunk, kc,
                        trial_cnt, trial_sum);
 }

@@ -312,11 +312,16 @@ def test_kernel_timing_reports_positive_times(dev):
     from dc_workloads import device
     lat_d = device.generate(r)
     taus = host.tau_grid(r)
-    dc.dc_set_kernel_timing(True)
     try:
+        dc.dc_set_kernel_timing(2)
         dc.dc_simulate(lat_d, taus, r.comm)
-        scan_ms, total_ms = dc.dc_last_kernel_ms()
+        scan_ms, total_ms = dc.dc_last_kernel_ms(whole=True)
         assert 0 < scan_ms <= total_ms
+        dc.dc_set_kernel_timing(1)
+        dc.dc_simulate(lat_d, taus, r.comm)
+        assert dc.dc_last_kernel_ms()[0] > 0
+        with pytest.raises(dc.DcError):
+            dc.dc_last_kernel_ms(whole=True)
     finally:
         dc.dc_set_kernel_timing(False)
 
