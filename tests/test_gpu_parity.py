@@ -225,6 +225,26 @@ def test_more_thresholds_than_one_pass_holds(dev):
     check(lat, taus, 3, dev)
 
 
+def test_many_trials_with_scattered_maxima(dev):
+    """Tens of thousands of trials whose maxima fall in every bin of the grid, and a trial count that is no multiple of 256."""
+    rng = np.random.default_rng(9)
+    T, N, M = 70001, 3, 8
+    lat = (rng.integers(0, 500, size=(T, 1, 1)) + rng.integers(0, 20, size=(T, N, M))).astype(np.int32)
+    taus = rng.integers(0, 8 * 520 + 2, size=700)
+    check(lat, taus, 11, dev)
+    check(np.ascontiguousarray(lat[:, :2, :7]), taus[:5], 0, dev)                      # odd row length, few thresholds
+
+
+def test_largest_threshold_count(dev):
+    rng = np.random.default_rng(10)
+    lat = rng.integers(0, 3000, size=(5, 30, 32), dtype=np.int32)
+    taus = rng.integers(0, 32 * 3000, size=dc.DC_MAX_THRESHOLDS)
+    check(lat, taus, 3, dev)
+    with pytest.raises(dc.DcError) as e:
+        dc.dc_simulate(to_dev(lat, dev), np.zeros(dc.DC_MAX_THRESHOLDS + 1, dtype=np.int64), 0)
+    assert e.value.status == dc.DC_ERR_INVALID_ARG
+
+
 def test_largest_legal_latency(dev):
     M = 16
     top = (2**31 - 1) // M
