@@ -62,9 +62,9 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
 #endif
         upt = (loads_per_trial + p.per_unit - 1) / p.per_unit;
     } else {
-        uint64_t rows = 16384 / (4 * (uint64_t)M);                // about 16 KiB per unit
+        uint64_t rows = DC_FLAT_UNIT_ELEMENTS / (uint64_t)M;      // whole rows, about 32 KiB per unit
         if (rows < 1) rows = 1;
-        if (rows > 64) rows = 64;
+        if (rows > (uint64_t)N) rows = (uint64_t)N;
         p.per_unit = (uint32_t)rows;
         upt = ((uint64_t)N + rows - 1) / rows;
     }
@@ -166,11 +166,19 @@ uint32_t wanted_blocks_per_cu(const dc::Plan& p) {
 #endif
 }
 
+// Which instantiation a plan runs, as the M field of the key: the row length for the 16-byte kernels,
+// else a small code (per-trial pass: 4- or 16-byte walker; sums pass: rows below 4 elements or not).
+uint32_t variant_of(const dc::Plan& p, bool trial) {
+    if (p.vec4) return p.M;
+    if (trial) return p.wide ? 1u : 0u;
+    return p.M < 4 ? 2u : 3u;
+}
+
 uint32_t resident_blocks(const dc::Plan& p, bool trial = false) {
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return DC_MAX_SCAN_BLOCKS;
     for (const ResidentKey& k : g_resident)
-        if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == (p.vec4 ? p.M : (p.wide ? 1u : 0u)) && k.p2 == p.p2)
+        if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == variant_of(p, trial) && k.p2 == p.p2)
             return (uint32_t)k.blocks;
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1) cus = 256;
@@ -179,7 +187,7 @@ uint32_t resident_blocks(const dc::Plan& p, bool trial = false) {
     const int wanted = (int)wanted_blocks_per_cu(p);                                    // what streams best
     if (per_cu > wanted) per_cu = wanted;
     const int blocks = cus * per_cu;
-    g_resident.push_back({device, p.vec4, trial, p.vec4 ? p.M : (p.wide ? 1u : 0u), p.p2, blocks});
+    g_resident.push_back({device, p.vec4, trial, variant_of(p, trial), p.p2, blocks});
     return (uint32_t)blocks;
 }
 

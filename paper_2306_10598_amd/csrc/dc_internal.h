@@ -13,6 +13,12 @@
 #ifndef DC_SCAN_UNROLL
 #define DC_SCAN_UNROLL 8                // 16-byte loads in flight per lane
 #endif
+#ifndef DC_FLAT_UNROLL
+#define DC_FLAT_UNROLL 4                // the same for the kernel of arbitrary row lengths
+#endif
+#ifndef DC_FLAT_UNIT_ELEMENTS
+#define DC_FLAT_UNIT_ELEMENTS 8192u     // elements per unit of that kernel (whole rows, at least one)
+#endif
 #ifndef DC_MAX_SCAN_BLOCKS
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
 #endif

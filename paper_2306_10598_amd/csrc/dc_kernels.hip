@@ -496,52 +496,263 @@ __device__ __forceinline__ void bin_lane(const uint32_t* tau_s, uint32_t* hist, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// dc_scan_generic_kernel: any M >= 1, any 4-byte alignment.  One wave walks the rows of its unit.
+// dc_scan_flat_kernel: any M >= 1, any 4-byte alignment of lat.
+// The tensor is read as one flat run of 16-byte vectors from the 16-byte boundary at or below lat
+// ("vector space": element e of lat is component (e + off) & 3 of vector (e + off) >> 2, off = the
+// number of 4-byte words between that boundary and lat).  A unit is a run of whole rows of one trial;
+// its first and last vector may also hold elements of the neighbouring rows, which are masked to zero.
+// Row heads fall anywhere in a load, at positions every lane can work out by itself: lane l of load i
+// holds unit-relative elements q0 = 256 i + 4 l - k, ..., q0 + 3 (k = components of the unit's first
+// vector that precede it), so its first element sits at position pos0 = q0 mod M of its row.
+//
+// Rows of at least 4 elements (SMALL = false).  A lane then holds at most one row end.  With
+//   s_c   the lane's running sums of its four values,   X   the sum of all lanes before it (one DPP scan),
+//   ce    = M - pos0: components 0..ce-1 continue the row of the lane's first element, ce.. start the next,
+//   E     = X + s_{ce-1}: the load-wide running sum at the lane's row end (meaningful when ce <= 4),
+// the completion times are s_c + X - E' for components c < ce, where E' is E of the lane that holds the
+// previous row end (one ds_bpermute; when that row end lies before this load, -E' is the wave-uniform
+// carry: the open row's sum over the loads before), and s_c - s_{ce-1} for the others.  Sums wrap
+// modulo 2^32; the differences are exact because row totals stay below 2^31.
+//
+// Rows of 1..3 elements (SMALL = true): a completion time is the sum of at most three consecutive
+// values, the lane's own and the last two of the lane before.
 // ---------------------------------------------------------------------------------------------
-template <bool WIDE>
-__global__ __launch_bounds__(DC_SCAN_THREADS)
-void dc_scan_generic_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t M, uint32_t units,
-                            uint32_t units_per_trial, uint32_t rows_per_unit,
-                            const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
-                            uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
-                            uint32_t* __restrict__ status, uint32_t max_latency) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    uint32_t* tau_s = reinterpret_cast<uint32_t*>(smem);
-    uint32_t* hist = tau_s + p2;
-    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) {
-        tau_s[i] = i < kc ? tau_chunk[i] : 0xFFFFFFFFu;
-        hist[i] = 0u;
-    }
-    __syncthreads();
+struct FlatTensor {
+    const int32_t* lat;
+    const u32x4* vec;      // 16-byte boundary at or below lat
+    uint64_t total;        // elements of lat
+    uint32_t off;          // 4-byte words between vec and lat (0..3)
+};
 
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wave = threadIdx.x >> 6;
-    const uint32_t tau0 = tau_s[0];
-    const uint32_t total_waves = gridDim.x * DC_SCAN_WAVES;
-    uint32_t check = 0u;
-
-    for (uint32_t u = blockIdx.x * DC_SCAN_WAVES + wave; u < units; u += total_waves) {
-        const uint32_t t = u / units_per_trial;
-        const uint32_t j = u - t * units_per_trial;
-        const uint32_t row0 = j * rows_per_unit;
-        const uint32_t rows = (N - row0) < rows_per_unit ? (N - row0) : rows_per_unit;
-        uint32_t best = 0u;
-        for (uint32_t r = 0; r < rows; ++r) {
-            const int32_t* row = lat + ((uint64_t)t * N + row0 + r) * M;
-            const uint32_t carry = walk_row<WIDE>(row, M, lane, check, [&](u32x4 x, uint32_t incl) {
-                bin_lane<WIDE>(tau_s, hist, p2, tau0, x, incl);
-            });
-            best = umax(best, carry);                              // the worker's total
+// One lane's vector `v` of vector space.  guard: the load may touch a vector that sticks out of the tensor
+// (only the first vector when off != 0 and the last one when the tensor ends inside it): such a vector is
+// read one element at a time, so nothing outside [lat, lat + total) is ever addressed.
+__device__ __forceinline__ u32x4 flat_load(const FlatTensor& f, uint64_t v, bool in_range, bool guard) {
+    u32x4 x = {0u, 0u, 0u, 0u};
+    if (!in_range) return x;
+    if (guard) {
+        const int64_t e = (int64_t)(4u * v) - (int64_t)f.off;                // lat index of component 0
+        if (e < 0 || (uint64_t)e + 4u > f.total) {
+            if (e + 0 >= 0 && (uint64_t)(e + 0) < f.total) x.x = (uint32_t)f.lat[e + 0];
+            if (e + 1 >= 0 && (uint64_t)(e + 1) < f.total) x.y = (uint32_t)f.lat[e + 1];
+            if (e + 2 >= 0 && (uint64_t)(e + 2) < f.total) x.z = (uint32_t)f.lat[e + 2];
+            if (e + 3 >= 0 && (uint64_t)(e + 3) < f.total) x.w = (uint32_t)f.lat[e + 3];
+            return x;
         }
-        if (lane == 0) unit_max[u] = best;
     }
-    const uint32_t worst = wave_max(check);
-    if (lane == 0 && worst > max_latency)
-        atomicOr(status, worst >= 0x80000000u ? DC_FLAG_NEGATIVE_LATENCY : DC_FLAG_RANGE);
+    return __builtin_nontemporal_load(f.vec + v);
+}
+
+// Components of a lane's vector that belong to the unit, as a 4-bit mask: component c is unit element
+// 4*lane + c - first of this load, valid for first <= 4*lane + c < limit.
+__device__ __forceinline__ uint32_t flat_valid_mask(uint32_t lane, uint32_t first, uint32_t limit) {
+    uint32_t m = 0u;
+#pragma unroll
+    for (uint32_t c = 0; c < 4; ++c) {
+        const uint32_t e = 4u * lane + c;
+        m |= (e >= first && e < limit) ? (1u << c) : 0u;
+    }
+    return m;
+}
+
+__device__ __forceinline__ u32x4 flat_masked(u32x4 x, uint32_t vm) {
+    x.x = (vm & 1u) ? x.x : 0u;
+    x.y = (vm & 2u) ? x.y : 0u;
+    x.z = (vm & 4u) ? x.z : 0u;
+    x.w = (vm & 8u) ? x.w : 0u;
+    return x;
+}
+
+// Queue the four completion times of every lane that is wholly inside the unit and reaches the smallest
+// threshold; a lane that is only partly inside (first and last vector of a unit) bins its valid ones itself.
+template <bool EDGE>
+__device__ __forceinline__ void flat_count(WaveState& st, uint4 p, uint32_t vm, uint4* queue, const GridView& g,
+                                           uint32_t lane) {
+    const uint32_t top = umax(umax(p.x, p.y), umax(p.z, p.w));
+    st.lane_max = umax(st.lane_max, top);                    // masked components have completion time 0
+    const bool whole = !EDGE || vm == 0xFu;
+    const bool active = whole && top >= g.tau0;
+    const uint64_t mask = __ballot(active);
+    if (mask) {
+        if (active) {
+            const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            queue[(st.q_head + st.q_count + rank) & (QUEUE_ITEMS - 1)] = p;
+        }
+        st.q_count += (uint32_t)__popcll(mask);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (st.q_count >= 64u) drain(st, queue, g, lane);
+    }
+    if constexpr (EDGE) {
+        if (!whole && vm) {
+            const uint32_t val[4] = {p.x, p.y, p.z, p.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (((vm >> c) & 1u) && val[c] >= g.tau0) atomicAdd(&g.hist[bin_of(g.tau, g.p2, val[c])], 1u);
+        }
+    }
+}
+
+// Per-lane, per-unit state of the flat pass.
+struct FlatState {
+    uint32_t pos0;       // position of the lane's first element inside its row, for the next load
+    uint32_t carry;      // wave-uniform: sum of the open row over the loads before (rows >= 4)
+    uint32_t prev2, prev3;   // wave-uniform: last two values of the load before (rows < 4)
+};
+
+// U loads of rows with at least 4 elements.  x is already masked; vm is read only when EDGE.
+template <int U, bool EDGE>
+__device__ __forceinline__ void flat_process(WaveState& st, FlatState& fs, const u32x4 (&x)[U], const uint32_t (&vm)[U],
+                                             uint32_t M, uint32_t step, uint4* queue, const GridView& g, uint32_t lane) {
+    uint32_t s0[U], s1[U], s2[U], s3[U], before[U], ce[U], se[U], prev_end[U];
+    int src[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+        s0[k] = x[k].x; s1[k] = s0[k] + x[k].y; s2[k] = s1[k] + x[k].z; s3[k] = s2[k] + x[k].w;
+        st.check = umax(st.check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) before[k] = segmented_inclusive_scan<64>(s3[k], lane) - s3[k];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+        ce[k] = M - fs.pos0;
+        se[k] = ce[k] == 1u ? s0[k] : ce[k] == 2u ? s1[k] : ce[k] == 3u ? s2[k] : s3[k];
+        src[k] = ((int)(4u * lane) - (int)fs.pos0 - 1) >> 2;               // lane of the previous row end, < 0: earlier load
+        prev_end[k] = (uint32_t)__builtin_amdgcn_ds_bpermute((src[k] < 0 ? (int)lane : src[k]) << 2, (int)(before[k] + se[k]));
+        fs.pos0 += step;
+        fs.pos0 -= fs.pos0 >= M ? M : 0u;
+    }
+    uint4 p[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+        const uint32_t a = src[k] >= 0 ? before[k] - prev_end[k] : before[k] + fs.carry;
+        const uint32_t b = ce[k] <= 4u ? 0u - se[k] : a;
+        p[k].x = s0[k] + a;
+        p[k].y = s1[k] + (ce[k] > 1u ? a : b);
+        p[k].z = s2[k] + (ce[k] > 2u ? a : b);
+        p[k].w = s3[k] + (ce[k] > 3u ? a : b);
+        fs.carry = (uint32_t)__builtin_amdgcn_readlane((int)(ce[k] == 4u ? 0u : p[k].w), 63);
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) flat_count<EDGE>(st, p[k], vm[k], queue, g, lane);
+}
+
+// One load of rows with 1..3 elements.
+template <bool EDGE>
+__device__ __forceinline__ void flat_process_small(WaveState& st, FlatState& fs, u32x4 x, uint32_t vm, uint32_t M,
+                                                   uint32_t step, uint4* queue, const GridView& g, uint32_t lane) {
+    st.check = umax(st.check, umax(umax(x.x, x.y), umax(x.z, x.w)));
+    uint32_t y0 = (uint32_t)__shfl_up((int)x.z, 1, 64), y1 = (uint32_t)__shfl_up((int)x.w, 1, 64);
+    if (lane == 0) { y0 = fs.prev2; y1 = fs.prev3; }
+    const uint32_t y[6] = {y0, y1, x.x, x.y, x.z, x.w};
+    uint32_t out[4];
+#pragma unroll
+    for (uint32_t c = 0; c < 4; ++c) {
+        const uint32_t pc = (fs.pos0 + c) % M;
+        out[c] = y[c + 2] + (pc >= 1u ? y[c + 1] : 0u) + (pc >= 2u ? y[c] : 0u);
+    }
+    fs.prev2 = (uint32_t)__builtin_amdgcn_readlane((int)x.z, 63);
+    fs.prev3 = (uint32_t)__builtin_amdgcn_readlane((int)x.w, 63);
+    fs.pos0 += step;
+    fs.pos0 -= fs.pos0 >= M ? M : 0u;
+    flat_count<EDGE>(st, make_uint4(out[0], out[1], out[2], out[3]), vm, queue, g, lane);
+}
+
+template <bool SMALL>
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint32_t N, uint32_t M, uint32_t units,
+                         uint32_t units_per_trial, uint32_t rows_per_unit, const uint32_t* __restrict__ tau_chunk,
+                         uint32_t kc, uint32_t p2, uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
+                         uint32_t* __restrict__ status, uint32_t max_latency) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
+    const GridView g = stage_grid(reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS), tau_chunk, kc, p2);
+
+    constexpr int U = DC_FLAT_UNROLL;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint4* queue = queue_all + wave * QUEUE_ITEMS;
+    const uint32_t total_waves = gridDim.x * DC_SCAN_WAVES;
+
+    FlatTensor f;
+    f.lat = lat;
+    f.off = (uint32_t)(((uintptr_t)lat & 15u) >> 2);
+    f.vec = reinterpret_cast<const u32x4*>(reinterpret_cast<uintptr_t>(lat) & ~(uintptr_t)15u);
+    f.total = total;
+    const uint64_t total_vectors = (total + f.off + 3u) >> 2;
+    const bool ragged_end = ((total + f.off) & 3u) != 0u;
+    const uint32_t step = 256u % M;
+
+    WaveState st{0u, 0u, 0u, 0u};
+    for (uint32_t u0 = blockIdx.x * DC_SCAN_WAVES; u0 < units; u0 += total_waves) {       // block-uniform bound
+        const uint32_t u = u0 + wave;
+        if (u < units) {
+            const uint32_t t = u / units_per_trial;
+            const uint32_t j = u - t * units_per_trial;
+            const uint32_t row0 = j * rows_per_unit;
+            const uint32_t rows = (N - row0) < rows_per_unit ? (N - row0) : rows_per_unit;
+            const uint64_t start = ((uint64_t)t * N + row0) * M + f.off;      // vector-space element of the unit's head
+            const uint32_t len = rows * M;
+            const uint64_t v0 = start >> 2;
+            const uint32_t k = (uint32_t)start & 3u;
+            const uint32_t nv = (k + len + 3u) >> 2;
+            const uint32_t nloads = (nv + 63u) >> 6;
+            const bool guard = (f.off != 0u && v0 == 0u) || (ragged_end && v0 + nv == total_vectors);
+
+            FlatState fs{0u, 0u, 0u, 0u};
+            {
+                const int q0 = (int)(4u * lane) - (int)k;
+                fs.pos0 = q0 >= 0 ? (uint32_t)q0 % M : (M - ((uint32_t)(-q0) % M)) % M;
+            }
+            st.lane_max = 0u;
+            const uint32_t vl = lane;                                         // this lane's vector within a load
+            // first load: components before the unit's head, and maybe its end, are masked
+            {
+                const uint32_t limit = len + k < 256u ? len + k : 256u;
+                const uint32_t vm[1] = {flat_valid_mask(lane, k, limit)};
+                const u32x4 x[1] = {flat_masked(flat_load(f, v0 + vl, vl < nv, guard), vm[0])};
+                if constexpr (SMALL) flat_process_small<true>(st, fs, x[0], vm[0], M, step, queue, g, lane);
+                else flat_process<1, true>(st, fs, x, vm, M, step, queue, g, lane);
+            }
+            // middle loads: every component belongs to the unit
+            uint32_t i = 1;
+            if (nloads > 2u) {
+                const uint32_t none1[1] = {0u};
+                if constexpr (!SMALL) {
+                    const uint32_t none[U] = {};
+                    for (; i + U <= nloads - 1u; i += U) {
+                        u32x4 x[U];
+#pragma unroll
+                        for (int q = 0; q < U; ++q) x[q] = __builtin_nontemporal_load(f.vec + v0 + (uint64_t)(i + q) * 64u + vl);
+                        flat_process<U, false>(st, fs, x, none, M, step, queue, g, lane);
+                    }
+                }
+                for (; i < nloads - 1u; ++i) {
+                    const u32x4 x[1] = {__builtin_nontemporal_load(f.vec + v0 + (uint64_t)i * 64u + vl)};
+                    if constexpr (SMALL) flat_process_small<false>(st, fs, x[0], 0xFu, M, step, queue, g, lane);
+                    else flat_process<1, false>(st, fs, x, none1, M, step, queue, g, lane);
+                }
+            }
+            // last load (when it is not also the first)
+            if (nloads > 1u) {
+                i = nloads - 1u;
+                const uint32_t limit = len + k - 256u * i;                    // 1..256 by the choice of nloads
+                const uint32_t vm[1] = {flat_valid_mask(lane, 0u, limit)};
+                const u32x4 x[1] = {flat_masked(flat_load(f, v0 + (uint64_t)i * 64u + vl, i * 64u + vl < nv, guard), vm[0])};
+                if constexpr (SMALL) flat_process_small<true>(st, fs, x[0], vm[0], M, step, queue, g, lane);
+                else flat_process<1, true>(st, fs, x, vm, M, step, queue, g, lane);
+            }
+            const uint32_t m = wave_max(st.lane_max);
+            if (lane == 0) unit_max[u] = m;
+        }
+        __syncthreads();
+    }
+    while (st.q_count) drain(st, queue, g, lane);
+    report_range(st.check, max_latency, lane, status);
 
     __syncthreads();
     uint32_t* out = hist_part + (uint64_t)blockIdx.x * p2;
-    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = hist[i];
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = g.hist[i];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -989,7 +1200,6 @@ void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t*
 
 size_t scan_lds_bytes(const Plan& p) {
     const size_t tables = (size_t)p.p2 * 8;                       // thresholds + histogram
-    if (!p.vec4) return tables;
     return tables + (size_t)p.p2 * 4 + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);   // + cells + queues
 }
 
@@ -1005,8 +1215,8 @@ int scan_blocks_per_cu(const Plan& p) {
     const size_t lds = scan_lds_bytes(p);
     int n = 0;
     if (!p.vec4) {
-        if ((p.wide ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_generic_kernel<true>, DC_SCAN_THREADS, lds)
-                    : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_generic_kernel<false>, DC_SCAN_THREADS, lds)) != hipSuccess) n = 0;
+        if ((p.M < 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_flat_kernel<true>, DC_SCAN_THREADS, lds)
+                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_flat_kernel<false>, DC_SCAN_THREADS, lds)) != hipSuccess) n = 0;
         return n;
     }
     switch (p.M / 4) {
@@ -1032,14 +1242,14 @@ static void launch_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_c
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
                  uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
     if (!p.vec4) {
-        if (p.wide)
-            hipLaunchKernelGGL(dc_scan_generic_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p),
-                               stream, lat, p.N, p.M, p.units, p.units_per_trial, p.per_unit, tau_chunk, kc, p.p2,
-                               unit_max, hist_part, status, p.max_latency);
+        if (p.M < 4)
+            hipLaunchKernelGGL(dc_scan_flat_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
+                               lat, (uint64_t)p.elements, p.N, p.M, p.units, p.units_per_trial, p.per_unit, tau_chunk, kc,
+                               p.p2, unit_max, hist_part, status, p.max_latency);
         else
-            hipLaunchKernelGGL(dc_scan_generic_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p),
-                               stream, lat, p.N, p.M, p.units, p.units_per_trial, p.per_unit, tau_chunk, kc, p.p2,
-                               unit_max, hist_part, status, p.max_latency);
+            hipLaunchKernelGGL(dc_scan_flat_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
+                               lat, (uint64_t)p.elements, p.N, p.M, p.units, p.units_per_trial, p.per_unit, tau_chunk, kc,
+                               p.p2, unit_max, hist_part, status, p.max_latency);
         return;
     }
     switch (p.M / 4) {
