@@ -49,7 +49,6 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     p.T = (uint32_t)T; p.N = (uint32_t)N; p.M = (uint32_t)M; p.K = (uint32_t)K;
     p.elements = (uint64_t)T * (uint64_t)N * (uint64_t)M;
     p.vec4 = allow_vec4 && vec4_shape(M);
-    p.wide = allow_vec4 && !p.vec4 && (M & 3) == 0;
     uint64_t upt;
     if (p.vec4) {
         const uint64_t rows_per_load = 64 / (M / 4);
@@ -101,11 +100,15 @@ bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4
     p.T = (uint32_t)T; p.N = (uint32_t)N; p.M = (uint32_t)M; p.K = (uint32_t)K;
     p.elements = (uint64_t)T * (uint64_t)N * (uint64_t)M;
     p.vec4 = allow_vec4 && vec4_shape(M);
-    p.wide = allow_vec4 && !p.vec4 && (M & 3) == 0;
     p.grid = (uint32_t)(T < (int64_t)DC_MAX_TRIAL_BLOCKS ? T : DC_MAX_TRIAL_BLOCKS);
     if (p.vec4) {
         const uint32_t rows_per_load = 64u / (uint32_t)(M / 4);
         p.per_unit = M >= 128 ? (32u / rows_per_load < 16u ? 16u : 32u / rows_per_load) : 64u;   // as in make_plan
+    } else {
+        uint64_t rows = DC_FLAT_UNIT_ELEMENTS / (uint64_t)M;                                     // as in make_plan
+        if (rows < 1) rows = 1;
+        if (rows > (uint64_t)N) rows = (uint64_t)N;
+        p.per_unit = (uint32_t)rows;
     }
     p.chunk = p.K < DC_TRIAL_CHUNK_THRESHOLDS ? p.K : DC_TRIAL_CHUNK_THRESHOLDS;
     p.p2 = next_pow2_above(p.chunk);
@@ -166,11 +169,10 @@ uint32_t wanted_blocks_per_cu(const dc::Plan& p) {
 #endif
 }
 
-// Which instantiation a plan runs, as the M field of the key: the row length for the 16-byte kernels,
-// else a small code (per-trial pass: 4- or 16-byte walker; sums pass: rows below 4 elements or not).
-uint32_t variant_of(const dc::Plan& p, bool trial) {
+// Which instantiation a plan runs, as the M field of the key: the row length for the kernels of whole rows
+// per load, else which of the two kernels for arbitrary rows (rows below 4 elements or not).
+uint32_t variant_of(const dc::Plan& p) {
     if (p.vec4) return p.M;
-    if (trial) return p.wide ? 1u : 0u;
     return p.M < 4 ? 2u : 3u;
 }
 
@@ -178,7 +180,7 @@ uint32_t resident_blocks(const dc::Plan& p, bool trial = false) {
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return DC_MAX_SCAN_BLOCKS;
     for (const ResidentKey& k : g_resident)
-        if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == variant_of(p, trial) && k.p2 == p.p2)
+        if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == variant_of(p) && k.p2 == p.p2)
             return (uint32_t)k.blocks;
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1) cus = 256;
@@ -187,7 +189,7 @@ uint32_t resident_blocks(const dc::Plan& p, bool trial = false) {
     const int wanted = (int)wanted_blocks_per_cu(p);                                    // what streams best
     if (per_cu > wanted) per_cu = wanted;
     const int blocks = cus * per_cu;
-    g_resident.push_back({device, p.vec4, trial, variant_of(p, trial), p.p2, blocks});
+    g_resident.push_back({device, p.vec4, trial, variant_of(p), p.p2, blocks});
     return (uint32_t)blocks;
 }
 

@@ -44,7 +44,6 @@ struct Plan {
     uint32_t T, N, M, K;
     uint64_t elements;          // T*N*M
     bool vec4;                  // 16-byte loads, whole rows per load (M a multiple of 4 up to 256, lat 16-byte aligned)
-    bool wide;                  // general kernel with 16-byte loads (M a multiple of 4 above 256, lat 16-byte aligned)
     uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; generic: rows per unit
     uint32_t units_per_trial;
     uint32_t units;             // T * units_per_trial

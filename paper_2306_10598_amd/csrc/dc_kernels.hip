@@ -438,64 +438,6 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
 }
 
 // ---------------------------------------------------------------------------------------------
-// The general kernels (any M >= 1): one wave walks a row in strips, carrying the running completion
-// time from strip to strip.  WIDE: 16-byte loads, 256 elements per strip (M a multiple of 4, lat
-// 16-byte aligned; this is the path of rows longer than 256); otherwise 4-byte loads, 64 per strip.
-// Four strips are in flight; their scans are independent, only the carries are chained.
-// visit(x, incl) is called for every lane that holds elements: x = its latencies (x.x only when
-// not WIDE), incl = the completion time of its last element.  Returns the row total.
-// ---------------------------------------------------------------------------------------------
-template <bool WIDE, typename F>
-__device__ __forceinline__ uint32_t walk_row(const int32_t* __restrict__ row, uint32_t M, uint32_t lane,
-                                             uint32_t& check, F&& visit) {
-    constexpr uint32_t E = WIDE ? 4u : 1u;
-    constexpr int S = 4;
-    uint32_t carry = 0u;
-    for (uint32_t m0 = 0; m0 < M; m0 += 64u * E * S) {
-        u32x4 x[S];
-        uint32_t incl[S];
-        bool valid[S];
-#pragma unroll
-        for (int k = 0; k < S; ++k) {
-            const uint32_t idx = m0 + (uint32_t)k * 64u * E + lane * E;
-            valid[k] = idx < M;                                 // WIDE: M % 4 == 0, so idx + 3 < M as well
-            x[k] = u32x4{0u, 0u, 0u, 0u};
-            if (valid[k]) {
-                if constexpr (WIDE) x[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + idx));
-                else x[k].x = (uint32_t)row[idx];
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < S; ++k) {
-            check = umax(check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
-            incl[k] = segmented_inclusive_scan<64>(x[k].x + x[k].y + x[k].z + x[k].w, lane);
-        }
-#pragma unroll
-        for (int k = 0; k < S; ++k) {
-            incl[k] += carry;
-            carry = (uint32_t)__builtin_amdgcn_readlane((int)incl[k], 63);
-            if (valid[k]) visit(x[k], incl[k]);
-        }
-    }
-    return carry;
-}
-
-// Histogram update of one lane's completion times in the general kernels (no queue: rows that need
-// these kernels are either short and rare or long with few elements inside the grid).
-template <bool WIDE>
-__device__ __forceinline__ void bin_lane(const uint32_t* tau_s, uint32_t* hist, uint32_t p2, uint32_t tau0,
-                                         u32x4 x, uint32_t incl) {
-    if (incl < tau0) return;
-    atomicAdd(&hist[bin_of(tau_s, p2, incl)], 1u);
-    if constexpr (WIDE) {
-        const uint32_t c2 = incl - x.w, c1 = c2 - x.z, c0 = c1 - x.y;
-        if (c2 >= tau0) atomicAdd(&hist[bin_of(tau_s, p2, c2)], 1u);
-        if (c1 >= tau0) atomicAdd(&hist[bin_of(tau_s, p2, c1)], 1u);
-        if (c0 >= tau0) atomicAdd(&hist[bin_of(tau_s, p2, c0)], 1u);
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
 // dc_scan_flat_kernel: any M >= 1, any 4-byte alignment of lat.
 // The tensor is read as one flat run of 16-byte vectors from the 16-byte boundary at or below lat
 // ("vector space": element e of lat is component (e + off) & 3 of vector (e + off) >> 2, off = the
@@ -519,10 +461,29 @@ __device__ __forceinline__ void bin_lane(const uint32_t* tau_s, uint32_t* hist, 
 // ---------------------------------------------------------------------------------------------
 struct FlatTensor {
     const int32_t* lat;
-    const u32x4* vec;      // 16-byte boundary at or below lat
-    uint64_t total;        // elements of lat
-    uint32_t off;          // 4-byte words between vec and lat (0..3)
+    const u32x4* vec;          // 16-byte boundary at or below lat
+    uint64_t total;            // elements of lat
+    uint64_t total_vectors;    // vectors that hold them
+    uint32_t off;              // 4-byte words between vec and lat (0..3)
+    bool ragged_end;           // the tensor ends inside its last vector
+    uint32_t M;
+    uint32_t step;             // 256 mod M: how far a lane's position in its row moves from load to load
+    uint32_t row_step;         // 256 div M: how many rows it moves
 };
+
+__device__ __forceinline__ FlatTensor flat_tensor(const int32_t* lat, uint64_t total, uint32_t M) {
+    FlatTensor f;
+    f.lat = lat;
+    f.off = (uint32_t)(((uintptr_t)lat & 15u) >> 2);
+    f.vec = reinterpret_cast<const u32x4*>(reinterpret_cast<uintptr_t>(lat) & ~(uintptr_t)15u);
+    f.total = total;
+    f.total_vectors = (total + f.off + 3u) >> 2;
+    f.ragged_end = ((total + f.off) & 3u) != 0u;
+    f.M = M;
+    f.step = 256u % M;
+    f.row_step = 256u / M;
+    return f;
+}
 
 // One lane's vector `v` of vector space.  guard: the load may touch a vector that sticks out of the tensor
 // (only the first vector when off != 0 and the last one when the tensor ends inside it): such a vector is
@@ -543,8 +504,8 @@ __device__ __forceinline__ u32x4 flat_load(const FlatTensor& f, uint64_t v, bool
     return __builtin_nontemporal_load(f.vec + v);
 }
 
-// Components of a lane's vector that belong to the unit, as a 4-bit mask: component c is unit element
-// 4*lane + c - first of this load, valid for first <= 4*lane + c < limit.
+// Components of a lane's vector that belong to the unit, as a 4-bit mask: component c is element
+// 4*lane + c of the load, valid for first <= 4*lane + c < limit.
 __device__ __forceinline__ uint32_t flat_valid_mask(uint32_t lane, uint32_t first, uint32_t limit) {
     uint32_t m = 0u;
 #pragma unroll
@@ -563,64 +524,45 @@ __device__ __forceinline__ u32x4 flat_masked(u32x4 x, uint32_t vm) {
     return x;
 }
 
-// Queue the four completion times of every lane that is wholly inside the unit and reaches the smallest
-// threshold; a lane that is only partly inside (first and last vector of a unit) bins its valid ones itself.
-template <bool EDGE>
-__device__ __forceinline__ void flat_count(WaveState& st, uint4 p, uint32_t vm, uint4* queue, const GridView& g,
-                                           uint32_t lane) {
-    const uint32_t top = umax(umax(p.x, p.y), umax(p.z, p.w));
-    st.lane_max = umax(st.lane_max, top);                    // masked components have completion time 0
-    const bool whole = !EDGE || vm == 0xFu;
-    const bool active = whole && top >= g.tau0;
-    const uint64_t mask = __ballot(active);
-    if (mask) {
-        if (active) {
-            const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-            queue[(st.q_head + st.q_count + rank) & (QUEUE_ITEMS - 1)] = p;
-        }
-        st.q_count += (uint32_t)__popcll(mask);
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        if (st.q_count >= 64u) drain(st, queue, g, lane);
-    }
-    if constexpr (EDGE) {
-        if (!whole && vm) {
-            const uint32_t val[4] = {p.x, p.y, p.z, p.w};
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (((vm >> c) & 1u) && val[c] >= g.tau0) atomicAdd(&g.hist[bin_of(g.tau, g.p2, val[c])], 1u);
-        }
-    }
-}
-
 // Per-lane, per-unit state of the flat pass.
 struct FlatState {
-    uint32_t pos0;       // position of the lane's first element inside its row, for the next load
-    uint32_t carry;      // wave-uniform: sum of the open row over the loads before (rows >= 4)
+    uint32_t pos0;           // position of the lane's first element inside its row, for the next load
+    uint32_t row;            // that row's number within the unit ("negative", wrapped, in the masked run before the unit's head)
+    uint32_t carry;          // wave-uniform: sum of the open row over the loads before (rows >= 4)
     uint32_t prev2, prev3;   // wave-uniform: last two values of the load before (rows < 4)
 };
 
-// U loads of rows with at least 4 elements.  x is already masked; vm is read only when EDGE.
-template <int U, bool EDGE>
-__device__ __forceinline__ void flat_process(WaveState& st, FlatState& fs, const u32x4 (&x)[U], const uint32_t (&vm)[U],
-                                             uint32_t M, uint32_t step, uint4* queue, const GridView& g, uint32_t lane) {
-    uint32_t s0[U], s1[U], s2[U], s3[U], before[U], ce[U], se[U], prev_end[U];
+__device__ __forceinline__ void flat_advance(FlatState& fs, const FlatTensor& f) {
+    fs.pos0 += f.step;
+    const bool wrapped = fs.pos0 >= f.M;
+    fs.pos0 -= wrapped ? f.M : 0u;
+    fs.row += f.row_step + (wrapped ? 1u : 0u);
+}
+
+// U loads of rows with at least 4 elements.  x is already masked.  emit(p, vm, pos0, row) receives, per load,
+// the lane's four completion times (0 for masked components), the validity mask, and where the lane's first
+// element sits (position in its row, row number in the unit).
+template <int U, typename F>
+__device__ __forceinline__ void flat_process(uint32_t& check, FlatState& fs, const FlatTensor& f, const u32x4 (&x)[U],
+                                             const uint32_t (&vm)[U], uint32_t lane, F&& emit) {
+    uint32_t s0[U], s1[U], s2[U], s3[U], before[U], ce[U], se[U], prev_end[U], pos[U], row[U];
     int src[U];
 #pragma unroll
     for (int k = 0; k < U; ++k) {
         s0[k] = x[k].x; s1[k] = s0[k] + x[k].y; s2[k] = s1[k] + x[k].z; s3[k] = s2[k] + x[k].w;
-        st.check = umax(st.check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
+        check = umax(check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) before[k] = segmented_inclusive_scan<64>(s3[k], lane) - s3[k];
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-        ce[k] = M - fs.pos0;
+        pos[k] = fs.pos0;
+        row[k] = fs.row;
+        ce[k] = f.M - fs.pos0;
         se[k] = ce[k] == 1u ? s0[k] : ce[k] == 2u ? s1[k] : ce[k] == 3u ? s2[k] : s3[k];
         src[k] = ((int)(4u * lane) - (int)fs.pos0 - 1) >> 2;               // lane of the previous row end, < 0: earlier load
         prev_end[k] = (uint32_t)__builtin_amdgcn_ds_bpermute((src[k] < 0 ? (int)lane : src[k]) << 2, (int)(before[k] + se[k]));
-        fs.pos0 += step;
-        fs.pos0 -= fs.pos0 >= M ? M : 0u;
+        flat_advance(fs, f);
     }
     uint4 p[U];
 #pragma unroll
@@ -634,28 +576,115 @@ __device__ __forceinline__ void flat_process(WaveState& st, FlatState& fs, const
         fs.carry = (uint32_t)__builtin_amdgcn_readlane((int)(ce[k] == 4u ? 0u : p[k].w), 63);
     }
 #pragma unroll
-    for (int k = 0; k < U; ++k) flat_count<EDGE>(st, p[k], vm[k], queue, g, lane);
+    for (int k = 0; k < U; ++k) emit(p[k], vm[k], pos[k], row[k]);
 }
 
 // One load of rows with 1..3 elements.
-template <bool EDGE>
-__device__ __forceinline__ void flat_process_small(WaveState& st, FlatState& fs, u32x4 x, uint32_t vm, uint32_t M,
-                                                   uint32_t step, uint4* queue, const GridView& g, uint32_t lane) {
-    st.check = umax(st.check, umax(umax(x.x, x.y), umax(x.z, x.w)));
+template <typename F>
+__device__ __forceinline__ void flat_process_small(uint32_t& check, FlatState& fs, const FlatTensor& f, u32x4 x,
+                                                   uint32_t vm, uint32_t lane, F&& emit) {
+    check = umax(check, umax(umax(x.x, x.y), umax(x.z, x.w)));
     uint32_t y0 = (uint32_t)__shfl_up((int)x.z, 1, 64), y1 = (uint32_t)__shfl_up((int)x.w, 1, 64);
     if (lane == 0) { y0 = fs.prev2; y1 = fs.prev3; }
     const uint32_t y[6] = {y0, y1, x.x, x.y, x.z, x.w};
     uint32_t out[4];
 #pragma unroll
     for (uint32_t c = 0; c < 4; ++c) {
-        const uint32_t pc = (fs.pos0 + c) % M;
+        const uint32_t pc = (fs.pos0 + c) % f.M;
         out[c] = y[c + 2] + (pc >= 1u ? y[c + 1] : 0u) + (pc >= 2u ? y[c] : 0u);
     }
     fs.prev2 = (uint32_t)__builtin_amdgcn_readlane((int)x.z, 63);
     fs.prev3 = (uint32_t)__builtin_amdgcn_readlane((int)x.w, 63);
-    fs.pos0 += step;
-    fs.pos0 -= fs.pos0 >= M ? M : 0u;
-    flat_count<EDGE>(st, make_uint4(out[0], out[1], out[2], out[3]), vm, queue, g, lane);
+    const uint32_t pos = fs.pos0, row = fs.row;
+    flat_advance(fs, f);
+    emit(make_uint4(out[0], out[1], out[2], out[3]), vm, pos, row);
+}
+
+// One wave streams a unit: `len` elements (whole rows) from element `first` of lat.
+template <bool SMALL, typename F>
+__device__ __forceinline__ void flat_stream_unit(uint32_t& check, const FlatTensor& f, uint64_t first, uint32_t len,
+                                                 uint32_t lane, F&& emit) {
+    constexpr int U = DC_FLAT_UNROLL;
+    const uint64_t start = first + f.off;                  // vector-space element of the unit's head
+    const uint64_t v0 = start >> 2;
+    const uint32_t k = (uint32_t)start & 3u;               // components of vector v0 that precede the unit
+    const uint32_t nv = (k + len + 3u) >> 2;
+    const uint32_t nloads = (nv + 63u) >> 6;
+    const bool guard = (f.off != 0u && v0 == 0u) || (f.ragged_end && v0 + nv == f.total_vectors);
+
+    FlatState fs{0u, 0u, 0u, 0u, 0u};
+    {
+        const int q0 = (int)(4u * lane) - (int)k;          // unit-relative element of the lane's first component
+        fs.pos0 = q0 >= 0 ? (uint32_t)q0 % f.M : (f.M - ((uint32_t)(-q0) % f.M)) % f.M;
+        fs.row = q0 >= 0 ? (uint32_t)q0 / f.M : 0u - (((uint32_t)(-q0) + f.M - 1u) / f.M);   // floor(q0 / M)
+    }
+    // first load: components before the unit's head, and maybe beyond its end, are masked
+    {
+        const uint32_t limit = len + k < 256u ? len + k : 256u;
+        const uint32_t vm[1] = {flat_valid_mask(lane, k, limit)};
+        const u32x4 x[1] = {flat_masked(flat_load(f, v0 + lane, lane < nv, guard), vm[0])};
+        if constexpr (SMALL) flat_process_small(check, fs, f, x[0], vm[0], lane, emit);
+        else flat_process<1>(check, fs, f, x, vm, lane, emit);
+    }
+    // middle loads: every component belongs to the unit
+    uint32_t i = 1;
+    if (nloads > 2u) {
+        const u32x4* base = f.vec + v0 + lane;
+        if constexpr (!SMALL) {
+            uint32_t all[U];
+#pragma unroll
+            for (int q = 0; q < U; ++q) all[q] = 0xFu;
+            for (; i + U <= nloads - 1u; i += U) {
+                u32x4 x[U];
+#pragma unroll
+                for (int q = 0; q < U; ++q) x[q] = __builtin_nontemporal_load(base + (uint64_t)(i + q) * 64u);
+                flat_process<U>(check, fs, f, x, all, lane, emit);
+            }
+        }
+        const uint32_t all1[1] = {0xFu};
+        for (; i < nloads - 1u; ++i) {
+            const u32x4 x[1] = {__builtin_nontemporal_load(base + (uint64_t)i * 64u)};
+            if constexpr (SMALL) flat_process_small(check, fs, f, x[0], 0xFu, lane, emit);
+            else flat_process<1>(check, fs, f, x, all1, lane, emit);
+        }
+    }
+    // last load (when it is not also the first)
+    if (nloads > 1u) {
+        i = nloads - 1u;
+        const uint32_t limit = len + k - 256u * i;         // 1..256 by the choice of nloads
+        const uint32_t vm[1] = {flat_valid_mask(lane, 0u, limit)};
+        const u32x4 x[1] = {flat_masked(flat_load(f, v0 + (uint64_t)i * 64u + lane, i * 64u + lane < nv, guard), vm[0])};
+        if constexpr (SMALL) flat_process_small(check, fs, f, x[0], vm[0], lane, emit);
+        else flat_process<1>(check, fs, f, x, vm, lane, emit);
+    }
+}
+
+// Counting consumer: queue the four completion times of every lane that is wholly inside the unit and
+// reaches the smallest threshold; a lane that is only partly inside (first and last vector of a unit) bins
+// its valid ones itself.
+__device__ __forceinline__ void flat_count(WaveState& st, uint4 p, uint32_t vm, uint4* queue, const GridView& g,
+                                           uint32_t lane) {
+    const uint32_t top = umax(umax(p.x, p.y), umax(p.z, p.w));
+    st.lane_max = umax(st.lane_max, top);                    // masked components have completion time 0
+    const bool whole = vm == 0xFu;
+    const bool active = whole && top >= g.tau0;
+    const uint64_t mask = __ballot(active);
+    if (mask) {
+        if (active) {
+            const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                      __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            queue[(st.q_head + st.q_count + rank) & (QUEUE_ITEMS - 1)] = p;
+        }
+        st.q_count += (uint32_t)__popcll(mask);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (st.q_count >= 64u) drain(st, queue, g, lane);
+    }
+    if (!whole && vm) {
+        const uint32_t val[4] = {p.x, p.y, p.z, p.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (((vm >> c) & 1u) && val[c] >= g.tau0) atomicAdd(&g.hist[bin_of(g.tau, g.p2, val[c])], 1u);
+    }
 }
 
 template <bool SMALL>
@@ -668,20 +697,11 @@ void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint32
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
     const GridView g = stage_grid(reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS), tau_chunk, kc, p2);
 
-    constexpr int U = DC_FLAT_UNROLL;
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint4* queue = queue_all + wave * QUEUE_ITEMS;
     const uint32_t total_waves = gridDim.x * DC_SCAN_WAVES;
-
-    FlatTensor f;
-    f.lat = lat;
-    f.off = (uint32_t)(((uintptr_t)lat & 15u) >> 2);
-    f.vec = reinterpret_cast<const u32x4*>(reinterpret_cast<uintptr_t>(lat) & ~(uintptr_t)15u);
-    f.total = total;
-    const uint64_t total_vectors = (total + f.off + 3u) >> 2;
-    const bool ragged_end = ((total + f.off) & 3u) != 0u;
-    const uint32_t step = 256u % M;
+    const FlatTensor f = flat_tensor(lat, total, M);
 
     WaveState st{0u, 0u, 0u, 0u};
     for (uint32_t u0 = blockIdx.x * DC_SCAN_WAVES; u0 < units; u0 += total_waves) {       // block-uniform bound
@@ -691,57 +711,9 @@ void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint32
             const uint32_t j = u - t * units_per_trial;
             const uint32_t row0 = j * rows_per_unit;
             const uint32_t rows = (N - row0) < rows_per_unit ? (N - row0) : rows_per_unit;
-            const uint64_t start = ((uint64_t)t * N + row0) * M + f.off;      // vector-space element of the unit's head
-            const uint32_t len = rows * M;
-            const uint64_t v0 = start >> 2;
-            const uint32_t k = (uint32_t)start & 3u;
-            const uint32_t nv = (k + len + 3u) >> 2;
-            const uint32_t nloads = (nv + 63u) >> 6;
-            const bool guard = (f.off != 0u && v0 == 0u) || (ragged_end && v0 + nv == total_vectors);
-
-            FlatState fs{0u, 0u, 0u, 0u};
-            {
-                const int q0 = (int)(4u * lane) - (int)k;
-                fs.pos0 = q0 >= 0 ? (uint32_t)q0 % M : (M - ((uint32_t)(-q0) % M)) % M;
-            }
             st.lane_max = 0u;
-            const uint32_t vl = lane;                                         // this lane's vector within a load
-            // first load: components before the unit's head, and maybe its end, are masked
-            {
-                const uint32_t limit = len + k < 256u ? len + k : 256u;
-                const uint32_t vm[1] = {flat_valid_mask(lane, k, limit)};
-                const u32x4 x[1] = {flat_masked(flat_load(f, v0 + vl, vl < nv, guard), vm[0])};
-                if constexpr (SMALL) flat_process_small<true>(st, fs, x[0], vm[0], M, step, queue, g, lane);
-                else flat_process<1, true>(st, fs, x, vm, M, step, queue, g, lane);
-            }
-            // middle loads: every component belongs to the unit
-            uint32_t i = 1;
-            if (nloads > 2u) {
-                const uint32_t none1[1] = {0u};
-                if constexpr (!SMALL) {
-                    const uint32_t none[U] = {};
-                    for (; i + U <= nloads - 1u; i += U) {
-                        u32x4 x[U];
-#pragma unroll
-                        for (int q = 0; q < U; ++q) x[q] = __builtin_nontemporal_load(f.vec + v0 + (uint64_t)(i + q) * 64u + vl);
-                        flat_process<U, false>(st, fs, x, none, M, step, queue, g, lane);
-                    }
-                }
-                for (; i < nloads - 1u; ++i) {
-                    const u32x4 x[1] = {__builtin_nontemporal_load(f.vec + v0 + (uint64_t)i * 64u + vl)};
-                    if constexpr (SMALL) flat_process_small<false>(st, fs, x[0], 0xFu, M, step, queue, g, lane);
-                    else flat_process<1, false>(st, fs, x, none1, M, step, queue, g, lane);
-                }
-            }
-            // last load (when it is not also the first)
-            if (nloads > 1u) {
-                i = nloads - 1u;
-                const uint32_t limit = len + k - 256u * i;                    // 1..256 by the choice of nloads
-                const uint32_t vm[1] = {flat_valid_mask(lane, 0u, limit)};
-                const u32x4 x[1] = {flat_masked(flat_load(f, v0 + (uint64_t)i * 64u + vl, i * 64u + vl < nv, guard), vm[0])};
-                if constexpr (SMALL) flat_process_small<true>(st, fs, x[0], vm[0], M, step, queue, g, lane);
-                else flat_process<1, true>(st, fs, x, vm, M, step, queue, g, lane);
-            }
+            flat_stream_unit<SMALL>(st.check, f, ((uint64_t)t * N + row0) * M, rows * M, lane,
+                                    [&](uint4 p, uint32_t vm, uint32_t, uint32_t) { flat_count(st, p, vm, queue, g, lane); });
             const uint32_t m = wave_max(st.lane_max);
             if (lane == 0) unit_max[u] = m;
         }
@@ -1005,15 +977,17 @@ void dc_trial_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
     for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = sh.acc[i];
 }
 
-// Any M >= 1, any 4-byte alignment: the waves of the block take the trial's rows in turn.
-template <bool WIDE>
+// Any M >= 1, any 4-byte alignment: the waves of the block take the trial's units (runs of whole rows) in
+// turn, in step, with the flat pass of dc_scan_flat_kernel.
+template <bool SMALL>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
-void dc_trial_scan_generic_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N, uint32_t M,
-                                  const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
-                                  const long long* __restrict__ comm_per_trial, long long comm,
-                                  double* __restrict__ partial, uint32_t* __restrict__ status, uint32_t max_latency) {
+void dc_trial_scan_flat_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N, uint32_t M,
+                               uint32_t rows_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
+                               const long long* __restrict__ comm_per_trial, long long comm,
+                               double* __restrict__ partial, uint32_t* __restrict__ status, uint32_t max_latency) {
     extern __shared__ __align__(16) unsigned char smem[];
-    uint32_t* tables = reinterpret_cast<uint32_t*>(smem);
+    uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
+    uint32_t* tables = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);
     TrialShared sh;
     sh.acc = reinterpret_cast<double*>(tables + 3 * p2);
     sh.wave_tot = reinterpret_cast<uint32_t*>(sh.acc + p2);
@@ -1024,21 +998,30 @@ void dc_trial_scan_generic_kernel(const int32_t* __restrict__ lat, uint32_t T, u
 
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint4* queue = queue_all + wave * QUEUE_ITEMS;
+    const FlatTensor f = flat_tensor(lat, (uint64_t)T * N * M, M);
+    const uint32_t n_units = (N + rows_per_unit - 1) / rows_per_unit;
     const double elements_per_trial = (double)N * (double)M;
-    uint32_t check = 0u;
+
+    WaveState st{0u, 0u, 0u, 0u};
     for (uint32_t t = blockIdx.x; t < T; t += gridDim.x) {
-        uint32_t best = 0u;
-        for (uint32_t r = wave; r < N; r += DC_SCAN_WAVES) {
-            const int32_t* row = lat + ((uint64_t)t * N + r) * M;
-            const uint32_t carry = walk_row<WIDE>(row, M, lane, check, [&](u32x4 x, uint32_t incl) {
-                bin_lane<WIDE>(g.tau, g.hist, p2, g.tau0, x, incl);
-            });
-            best = umax(best, carry);
+        st.lane_max = 0u;
+        for (uint32_t j0 = 0; j0 < n_units; j0 += DC_SCAN_WAVES) {                        // block-uniform bound
+            const uint32_t j = j0 + wave;
+            if (j < n_units) {
+                const uint32_t row0 = j * rows_per_unit;
+                const uint32_t rows = (N - row0) < rows_per_unit ? (N - row0) : rows_per_unit;
+                flat_stream_unit<SMALL>(st.check, f, ((uint64_t)t * N + row0) * M, rows * M, lane,
+                                        [&](uint4 p, uint32_t vm, uint32_t, uint32_t) { flat_count(st, p, vm, queue, g, lane); });
+            }
+            __syncthreads();
         }
-        if (lane == 0) atomicMax(sh.block_max, best);
+        while (st.q_count) drain(st, queue, g, lane);
+        const uint32_t m = wave_max(st.lane_max);
+        if (lane == 0) atomicMax(sh.block_max, m);
         finish_trial(g, sh, kc, t, comm_per_trial, comm, elements_per_trial, status);
     }
-    report_range(check, max_latency, lane, status);
+    report_range(st.check, max_latency, lane, status);
     double* out = partial + (uint64_t)blockIdx.x * p2;
     for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = sh.acc[i];
 }
@@ -1142,23 +1125,41 @@ void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, u
     for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) out[i] = acc[i];
 }
 
-template <bool WIDE>
+// Any M >= 1, any 4-byte alignment: the flat pass; the lane that holds a row's last element holds its total.
+// Wave w takes units w, w + 4, ... of every trial, so a worker's accumulators always belong to the same wave.
+template <bool SMALL>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
-void dc_worker_totals_generic_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N, uint32_t M,
-                                     unsigned long long* __restrict__ partial, uint32_t* __restrict__ status,
-                                     uint32_t max_latency) {
+void dc_worker_totals_flat_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N, uint32_t M,
+                                  uint32_t rows_per_unit, unsigned long long* __restrict__ partial,
+                                  uint32_t* __restrict__ status, uint32_t max_latency) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
     for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) acc[i] = 0ull;
     __syncthreads();
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const FlatTensor f = flat_tensor(lat, (uint64_t)T * N * M, M);
+    const uint32_t n_units = (N + rows_per_unit - 1) / rows_per_unit;
     uint32_t check = 0u;
     for (uint32_t t = blockIdx.x; t < T; t += gridDim.x)
-        for (uint32_t r = wave; r < N; r += DC_SCAN_WAVES) {          // a wave keeps the same rows in every trial
-            const int32_t* row = lat + ((uint64_t)t * N + r) * M;
-            const uint32_t carry = walk_row<WIDE>(row, M, lane, check, [](u32x4, uint32_t) {});
-            if (lane == 0) add_worker_total(acc, N, r, carry);
+        for (uint32_t j = wave; j < n_units; j += DC_SCAN_WAVES) {
+            const uint32_t row0 = j * rows_per_unit;
+            const uint32_t rows = (N - row0) < rows_per_unit ? (N - row0) : rows_per_unit;
+            flat_stream_unit<SMALL>(check, f, ((uint64_t)t * N + row0) * M, rows * M, lane,
+                                    [&](uint4 p, uint32_t vm, uint32_t pos0, uint32_t row) {
+                const uint32_t val[4] = {p.x, p.y, p.z, p.w};
+                if constexpr (SMALL) {
+#pragma unroll
+                    for (uint32_t c = 0; c < 4; ++c) {
+                        const uint32_t e = pos0 + c;                      // < 6: position counted from the first element's row head
+                        if (((vm >> c) & 1u) && e % M == M - 1u) add_worker_total(acc, N, row0 + row + e / M, val[c]);
+                    }
+                } else {
+                    const uint32_t ce = M - pos0;                         // the row of the first element ends at component ce - 1
+                    if (ce <= 4u && ((vm >> (ce - 1u)) & 1u))
+                        add_worker_total(acc, N, row0 + row, ce == 1u ? val[0] : ce == 2u ? val[1] : ce == 3u ? val[2] : val[3]);
+                }
+            });
         }
     report_range(check, max_latency, lane, status);
     __syncthreads();
@@ -1300,8 +1301,8 @@ int trial_scan_blocks_per_cu(const Plan& p) {
     const size_t lds = trial_scan_lds_bytes(p);
     int n = 0;
     if (!p.vec4) {
-        if ((p.wide ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_generic_kernel<true>, DC_SCAN_THREADS, lds)
-                    : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_generic_kernel<false>, DC_SCAN_THREADS, lds)) != hipSuccess) n = 0;
+        if ((p.M < 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_flat_kernel<true>, DC_SCAN_THREADS, lds)
+                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_flat_kernel<false>, DC_SCAN_THREADS, lds)) != hipSuccess) n = 0;
         return n;
     }
     switch (p.M / 4) {
@@ -1318,7 +1319,7 @@ int trial_scan_blocks_per_cu(const Plan& p) {
 
 size_t trial_scan_lds_bytes(const Plan& p) {
     const size_t tables = (size_t)p.p2 * 12 + (size_t)p.p2 * 8 + (DC_SCAN_WAVES + 1) * 4;   // grid + sums + scratch
-    return p.vec4 ? tables + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4) : tables;
+    return tables + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);                    // + queues
 }
 
 template <int L>
@@ -1334,13 +1335,13 @@ void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_ch
                        const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
                        hipStream_t stream) {
     if (!p.vec4) {
-        if (p.wide)
-            hipLaunchKernelGGL(dc_trial_scan_generic_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS),
-                               trial_scan_lds_bytes(p), stream, lat, p.T, p.N, p.M, tau_chunk, kc, p.p2,
+        if (p.M < 4)
+            hipLaunchKernelGGL(dc_trial_scan_flat_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS),
+                               trial_scan_lds_bytes(p), stream, lat, p.T, p.N, p.M, p.per_unit, tau_chunk, kc, p.p2,
                                (const long long*)comm_per_trial, (long long)comm, partial, status, p.max_latency);
         else
-            hipLaunchKernelGGL(dc_trial_scan_generic_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS),
-                               trial_scan_lds_bytes(p), stream, lat, p.T, p.N, p.M, tau_chunk, kc, p.p2,
+            hipLaunchKernelGGL(dc_trial_scan_flat_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS),
+                               trial_scan_lds_bytes(p), stream, lat, p.T, p.N, p.M, p.per_unit, tau_chunk, kc, p.p2,
                                (const long long*)comm_per_trial, (long long)comm, partial, status, p.max_latency);
         return;
     }
@@ -1376,12 +1377,12 @@ void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long*
                           unsigned long long* result, uint32_t* status, hipStream_t stream) {
     hipLaunchKernelGGL(dc_clear_status_kernel, dim3(1), dim3(1), 0, stream, status);
     if (!p.vec4) {
-        if (p.wide)
-            hipLaunchKernelGGL(dc_worker_totals_generic_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS),
-                               (size_t)p.N * 24, stream, lat, p.T, p.N, p.M, partial, status, p.max_latency);
+        if (p.M < 4)
+            hipLaunchKernelGGL(dc_worker_totals_flat_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS),
+                               (size_t)p.N * 24, stream, lat, p.T, p.N, p.M, p.per_unit, partial, status, p.max_latency);
         else
-            hipLaunchKernelGGL(dc_worker_totals_generic_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS),
-                               (size_t)p.N * 24, stream, lat, p.T, p.N, p.M, partial, status, p.max_latency);
+            hipLaunchKernelGGL(dc_worker_totals_flat_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS),
+                               (size_t)p.N * 24, stream, lat, p.T, p.N, p.M, p.per_unit, partial, status, p.max_latency);
     } else {
         switch (p.M / 4) {
             case 1:  launch_worker_vec4<1>(p, lat, partial, status, stream); break;
