@@ -44,7 +44,7 @@ struct Plan {
     uint32_t T, N, M, K;
     uint64_t elements;          // T*N*M
     bool vec4;                  // 16-byte loads, whole rows per load (M a multiple of 4 up to 256, lat 16-byte aligned)
-    uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; generic: rows per unit
+    uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; otherwise rows per unit
     uint32_t units_per_trial;
     uint32_t units;             // T * units_per_trial
     uint32_t grid;              // blocks of the streaming kernel (= histogram slots)

@@ -504,7 +504,7 @@ def test_noise_model_workloads_parity(family, dev):
     assert np.array_equal(device.generate(r).cpu().numpy(), lat)
     taus = np.append(host.tau_grid(r), BIG)
     assert np.array_equal(device.tau_grid(r, device.generate(r)), taus[:-1])
-    step, done = check(lat, taus, r.comm, dev)                  # M = 12: the general kernel
+    step, done = check(lat, taus, r.comm, dev)                  # M = 12: three lanes per row
     assert np.allclose(dc.dc_speedup_per_step(to_dev(lat, dev), taus, r.comm),
                        oracle.per_step_speedup(lat, taus, r.comm), rtol=SPEEDUP_RTOL, atol=0)
     assert dc.dc_moments(to_dev(lat, dev))[:2] == oracle.moments(lat)[1:3]
