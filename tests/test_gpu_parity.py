@@ -151,7 +151,47 @@ def test_general_kernel_shapes(M, dev):
     check(lat, taus, 5, dev, "literal")
 
 
-def test_unaligned_tensor_takes_general_kernel(dev):
+@pytest.mark.parametrize("words", [1, 2, 3])
+@pytest.mark.parametrize("M", [1, 2, 3, 5, 8, 13, 64, 257, 700])
+def test_any_alignment_any_row_length(words, M, dev):
+    """Tensors that start 4, 8 or 12 bytes past a 16-byte boundary and end inside a vector, through all three
+    entry points that stream them; the last latency is the largest legal one, so a read of the wrong element shows."""
+    rng = np.random.default_rng(1000 * words + M)
+    T, N = 5, int(rng.integers(3, 40))
+    top = (2**31 - 1) // M
+    lat = rng.integers(0, min(top, 4000) + 1, size=(T, N, M), dtype=np.int32)
+    lat[0, 0, 0] = lat[-1, -1, -1] = min(top, 50000)
+    flat = torch.full((lat.size + words + 4,), -7, dtype=torch.int32, device=dev)     # negative guard values around it
+    view = flat[words:words + lat.size].view(T, N, M)
+    view.copy_(torch.from_numpy(lat))
+    assert view.data_ptr() % 16 == 4 * words
+    totals = lat.sum(axis=2, dtype=np.int64)
+    taus = rng.integers(0, int(totals.max()) + 50, size=33)
+    step, done = dc.dc_simulate(view, taus, 3)
+    ref = oracle.simulate(lat, taus, 3, "literal")
+    assert np.array_equal(step, ref[0]) and np.array_equal(done, ref[1])
+    taus1 = np.maximum(taus, 1)
+    assert np.allclose(dc.dc_speedup_per_step(view, taus1, 3), oracle.per_step_speedup(lat, taus1, 3), rtol=SPEEDUP_RTOL, atol=0)
+    gs, gq, _, _ = dc.dc_worker_moments(view)
+    sums, squares, _, _ = oracle.worker_moments(lat)
+    assert gs == sums and gq == squares
+
+
+def test_long_rows_and_many_rows_per_unit(dev):
+    """Rows longer than a unit (one row per unit, carries across dozens of loads) and units of thousands of short rows."""
+    rng = np.random.default_rng(12)
+    for shape, top in (((3, 5, 20011), 100000), ((2, 3, 65536), 30000), ((3, 9001, 1), 10**9), ((2, 5000, 3), 10**8)):
+        lat = rng.integers(0, min(top, (2**31 - 1) // shape[2]) + 1, size=shape, dtype=np.int32)
+        totals = lat.sum(axis=2, dtype=np.int64)
+        taus = np.concatenate([rng.integers(0, int(totals.max()) + 2, size=40), [int(totals.max()), int(totals.min())]])
+        check(lat, taus, 2, dev)
+        gs, gq, _, _ = dc.dc_worker_moments(to_dev(lat, dev)) if shape[1] <= 2560 else (None, None, None, None)
+        if gs is not None:
+            sums, squares, _, _ = oracle.worker_moments(lat)
+            assert gs == sums and gq == squares
+
+
+def test_unaligned_tensor(dev):
     rng = np.random.default_rng(77)
     lat = rng.integers(0, 3000, size=(5, 6, 64), dtype=np.int32)
     flat = torch.empty(lat.size + 1, dtype=torch.int32, device=dev)
@@ -452,7 +492,8 @@ def test_moments_of_a_workload_and_errors(dev):
 
 
 @pytest.mark.parametrize("shape", [(30, 64, 32), (7, 200, 64), (3, 2048, 256), (5, 2047, 128), (40, 33, 12),
-                                   (9, 10, 100), (6, 9, 300), (11, 5, 1), (4, 2560, 16)])
+                                   (9, 10, 100), (6, 9, 300), (11, 5, 1), (4, 2560, 16), (11, 50, 7), (20, 100, 3),
+                                   (6, 170, 2), (4, 9, 257), (3, 2, 5000)])
 def test_worker_moments_are_exact(shape, dev):
     rng = np.random.default_rng(sum(shape))
     top = (2**31 - 1) // shape[2]
