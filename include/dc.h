@@ -22,7 +22,7 @@
  *     current device; "HOST" pointers are ordinary host memory.
  *   - lat must be 4-byte aligned; rows are contiguous with m fastest: element (t,n,m) is at
  *     lat[(t*N + n)*M + m].  The fastest kernels need lat 16-byte aligned and M a multiple of 4
- *     up to 256 (best when M is a power of two); every other M >= 1 and any 4-byte alignment
+ *     up to 128, or 256 (best when M is a power of two); every other M >= 1 and any 4-byte alignment
  *     takes a kernel that reads the tensor as one flat run of 16-byte vectors, with the same
  *     results at 75-95 % of that speed for M >= 30 and about a third of it for M <= 5.
  *   - Preconditions on values, checked while streaming: every latency is >= 0

@@ -17,7 +17,7 @@
 #define DC_FLAT_UNROLL 4                // the same for the kernel of arbitrary row lengths
 #endif
 #ifndef DC_FLAT_UNIT_ELEMENTS
-#define DC_FLAT_UNIT_ELEMENTS 8192u     // elements per unit of that kernel (whole rows, at least one)
+#define DC_FLAT_UNIT_ELEMENTS 16384u    // target elements per unit of that kernel (whole rows, at least one)
 #endif
 #ifndef DC_MAX_SCAN_BLOCKS
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
@@ -43,7 +43,7 @@ namespace dc {
 struct Plan {
     uint32_t T, N, M, K;
     uint64_t elements;          // T*N*M
-    bool vec4;                  // 16-byte loads, whole rows per load (M a multiple of 4 up to 256, lat 16-byte aligned)
+    bool vec4;                  // 16-byte loads, whole rows per load (M a multiple of 4 up to 128, or 256; lat 16-byte aligned)
     uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; otherwise rows per unit
     uint32_t units_per_trial;
     uint32_t units;             // T * units_per_trial
