@@ -44,9 +44,11 @@ bool vec4_shape(int64_t M) {
 
 // Rows per unit of the kernels for arbitrary row lengths: a trial is cut into equal runs of whole rows of
 // about DC_FLAT_UNIT_ELEMENTS elements (at least one row), so that no short unit is left over at its end.
-uint64_t flat_rows_per_unit(int64_t N, int64_t M) {
+// share > 1: the units of a trial are dealt to that many waves, so their number is made a multiple of it.
+uint64_t flat_rows_per_unit(int64_t N, int64_t M, uint64_t share = 1) {
     const uint64_t per_trial = (uint64_t)N * (uint64_t)M;                   // < 2^62
     uint64_t pieces = (per_trial + DC_FLAT_UNIT_ELEMENTS - 1) / DC_FLAT_UNIT_ELEMENTS;
+    pieces = (pieces + share - 1) / share * share;
     if (pieces > (uint64_t)N) pieces = (uint64_t)N;
     return ((uint64_t)N + pieces - 1) / pieces;
 }
@@ -115,7 +117,7 @@ bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4
         const uint32_t rows_per_load = 64u / (uint32_t)(M / 4);
         p.per_unit = M >= 128 ? (32u / rows_per_load < 16u ? 16u : 32u / rows_per_load) : 64u;   // as in make_plan
     } else {
-        p.per_unit = (uint32_t)flat_rows_per_unit(N, M);
+        p.per_unit = (uint32_t)flat_rows_per_unit(N, M, DC_SCAN_WAVES);
     }
     p.chunk = p.K < DC_TRIAL_CHUNK_THRESHOLDS ? p.K : DC_TRIAL_CHUNK_THRESHOLDS;
     p.p2 = next_pow2_above(p.chunk);
@@ -512,7 +514,20 @@ int dc_worker_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64
     unsigned long long* result = reinterpret_cast<unsigned long long*>(g_cache + 256);
     unsigned long long* partial = reinterpret_cast<unsigned long long*>(g_cache + 256 + align256(row_bytes));
     hipStream_t stream = nullptr;
-    dc::launch_worker_totals(p, lat, partial, result, status, stream);
+    const bool timed = g_timing.enabled;
+    if (timed) {
+        rc = ensure_events(1);
+        if (rc) return rc;
+        g_timing.used_pairs = 1;
+        g_timing.valid = false;
+        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.begin, stream));
+    }
+    dc::launch_worker_totals(p, lat, partial, result, status, stream, timed ? g_timing.scan[0] : nullptr,
+                             timed ? g_timing.scan[1] : nullptr);
+    if (timed) {
+        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.end, stream));
+        g_timing.valid = true;
+    }
     DC_HIP(hipGetLastError());
     uint32_t flags = 0;
     DC_HIP(hipMemcpy(&flags, status, sizeof(flags), hipMemcpyDeviceToHost));

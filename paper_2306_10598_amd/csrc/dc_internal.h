@@ -75,7 +75,8 @@ void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, 
                              double* out_seff, hipStream_t stream);
 size_t trial_scan_lds_bytes(const Plan& p);
 void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long* partial,
-                          unsigned long long* result, uint32_t* status, hipStream_t stream);
+                          unsigned long long* result, uint32_t* status, hipStream_t stream, hipEvent_t before,
+                          hipEvent_t after);
 void launch_moments(const int32_t* lat, uint64_t n, uint32_t grid, unsigned long long* partial,
                     unsigned long long* result, uint32_t* status, hipStream_t stream);
 void launch_expected_done(const int64_t* taus, uint32_t K, uint32_t M, double mu, double sigma2, double* out,

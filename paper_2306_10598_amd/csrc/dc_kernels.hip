@@ -528,6 +528,7 @@ __device__ __forceinline__ u32x4 flat_masked(u32x4 x, uint32_t vm) {
 struct FlatState {
     uint32_t pos0;           // position of the lane's first element inside its row, for the next load
     uint32_t row;            // that row's number within the unit ("negative", wrapped, in the masked run before the unit's head)
+    uint32_t pos_last;       // wave-uniform: pos0 of lane 63
     uint32_t carry;          // wave-uniform: sum of the open row over the loads before (rows >= 4)
     uint32_t prev2, prev3;   // wave-uniform: last two values of the load before (rows < 4)
 };
@@ -537,6 +538,8 @@ __device__ __forceinline__ void flat_advance(FlatState& fs, const FlatTensor& f)
     const bool wrapped = fs.pos0 >= f.M;
     fs.pos0 -= wrapped ? f.M : 0u;
     fs.row += f.row_step + (wrapped ? 1u : 0u);
+    fs.pos_last += f.step;
+    fs.pos_last -= fs.pos_last >= f.M ? f.M : 0u;
 }
 
 // U loads of rows with at least 4 elements.  x is already masked.  emit(p, vm, pos0, row) receives, per load,
@@ -545,35 +548,43 @@ __device__ __forceinline__ void flat_advance(FlatState& fs, const FlatTensor& f)
 template <int U, typename F>
 __device__ __forceinline__ void flat_process(uint32_t& check, FlatState& fs, const FlatTensor& f, const u32x4 (&x)[U],
                                              const uint32_t (&vm)[U], uint32_t lane, F&& emit) {
-    uint32_t s0[U], s1[U], s2[U], s3[U], before[U], ce[U], se[U], prev_end[U], pos[U], row[U];
-    int src[U];
+    uint32_t s0[U], s1[U], s2[U], s3[U], before[U], se[U], prev_end[U], pos[U], row[U];
+    bool c1[U], c2[U], c3[U];                               // component 1, 2, 3 continues the row of component 0
+    int back[U];                                            // 4 * (lane of the previous row end) + its component; < 0: earlier load
+    const int lane4m1 = (int)(4u * lane) - 1;
 #pragma unroll
     for (int k = 0; k < U; ++k) {
         s0[k] = x[k].x; s1[k] = s0[k] + x[k].y; s2[k] = s1[k] + x[k].z; s3[k] = s2[k] + x[k].w;
-        check = umax(check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
+        check = umax(umax(check, x[k].x), x[k].y);
+        check = umax(umax(check, x[k].z), x[k].w);
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) before[k] = segmented_inclusive_scan<64>(s3[k], lane) - s3[k];
+    bool open_end[U];                                       // wave-uniform: the load's last element does not end a row
 #pragma unroll
     for (int k = 0; k < U; ++k) {
         pos[k] = fs.pos0;
         row[k] = fs.row;
-        ce[k] = f.M - fs.pos0;
-        se[k] = ce[k] == 1u ? s0[k] : ce[k] == 2u ? s1[k] : ce[k] == 3u ? s2[k] : s3[k];
-        src[k] = ((int)(4u * lane) - (int)fs.pos0 - 1) >> 2;               // lane of the previous row end, < 0: earlier load
-        prev_end[k] = (uint32_t)__builtin_amdgcn_ds_bpermute((src[k] < 0 ? (int)lane : src[k]) << 2, (int)(before[k] + se[k]));
+        const uint32_t ce = f.M - fs.pos0;
+        c1[k] = ce > 1u; c2[k] = ce > 2u; c3[k] = ce > 3u;
+        se[k] = c3[k] ? s3[k] : c2[k] ? s2[k] : c1[k] ? s1[k] : s0[k];      // s_{ce-1}; unused when ce > 4
+        back[k] = lane4m1 - (int)fs.pos0;
+        const int from = back[k] < 0 ? 0 : back[k];
+        prev_end[k] = (uint32_t)__builtin_amdgcn_ds_bpermute(from & ~3, (int)(before[k] + se[k]));
+        open_end[k] = f.M - fs.pos_last != 4u;
         flat_advance(fs, f);
     }
     uint4 p[U];
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-        const uint32_t a = src[k] >= 0 ? before[k] - prev_end[k] : before[k] + fs.carry;
-        const uint32_t b = ce[k] <= 4u ? 0u - se[k] : a;
+        const uint32_t a = before[k] - (back[k] >= 0 ? prev_end[k] : 0u - fs.carry);
+        const uint32_t b = 0u - se[k];
         p[k].x = s0[k] + a;
-        p[k].y = s1[k] + (ce[k] > 1u ? a : b);
-        p[k].z = s2[k] + (ce[k] > 2u ? a : b);
-        p[k].w = s3[k] + (ce[k] > 3u ? a : b);
-        fs.carry = (uint32_t)__builtin_amdgcn_readlane((int)(ce[k] == 4u ? 0u : p[k].w), 63);
+        p[k].y = s1[k] + (c1[k] ? a : b);
+        p[k].z = s2[k] + (c2[k] ? a : b);
+        p[k].w = s3[k] + (c3[k] ? a : b);
+        const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)p[k].w, 63);
+        fs.carry = open_end[k] ? last : 0u;
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) emit(p[k], vm[k], pos[k], row[k]);
@@ -601,10 +612,9 @@ __device__ __forceinline__ void flat_process_small(uint32_t& check, FlatState& f
 }
 
 // One wave streams a unit: `len` elements (whole rows) from element `first` of lat.
-template <bool SMALL, typename F>
+template <bool SMALL, int U = DC_FLAT_UNROLL, typename F>
 __device__ __forceinline__ void flat_stream_unit(uint32_t& check, const FlatTensor& f, uint64_t first, uint32_t len,
                                                  uint32_t lane, F&& emit) {
-    constexpr int U = DC_FLAT_UNROLL;
     const uint64_t start = first + f.off;                  // vector-space element of the unit's head
     const uint64_t v0 = start >> 2;
     const uint32_t k = (uint32_t)start & 3u;               // components of vector v0 that precede the unit
@@ -612,11 +622,12 @@ __device__ __forceinline__ void flat_stream_unit(uint32_t& check, const FlatTens
     const uint32_t nloads = (nv + 63u) >> 6;
     const bool guard = (f.off != 0u && v0 == 0u) || (f.ragged_end && v0 + nv == f.total_vectors);
 
-    FlatState fs{0u, 0u, 0u, 0u, 0u};
+    FlatState fs{0u, 0u, 0u, 0u, 0u, 0u};
     {
         const int q0 = (int)(4u * lane) - (int)k;          // unit-relative element of the lane's first component
         fs.pos0 = q0 >= 0 ? (uint32_t)q0 % f.M : (f.M - ((uint32_t)(-q0) % f.M)) % f.M;
         fs.row = q0 >= 0 ? (uint32_t)q0 / f.M : 0u - (((uint32_t)(-q0) + f.M - 1u) / f.M);   // floor(q0 / M)
+        fs.pos_last = (252u - k) % f.M;
     }
     // first load: components before the unit's head, and maybe beyond its end, are masked
     {
@@ -1145,8 +1156,9 @@ void dc_worker_totals_flat_kernel(const int32_t* __restrict__ lat, uint32_t T, u
         for (uint32_t j = wave; j < n_units; j += DC_SCAN_WAVES) {
             const uint32_t row0 = j * rows_per_unit;
             const uint32_t rows = (N - row0) < rows_per_unit ? (N - row0) : rows_per_unit;
-            flat_stream_unit<SMALL>(check, f, ((uint64_t)t * N + row0) * M, rows * M, lane,
-                                    [&](uint4 p, uint32_t vm, uint32_t pos0, uint32_t row) {
+            // few waves per compute unit here (the accumulators fill the LDS), so more loads in flight per lane
+            flat_stream_unit<SMALL, DC_SCAN_UNROLL>(check, f, ((uint64_t)t * N + row0) * M, rows * M, lane,
+                                                    [&](uint4 p, uint32_t vm, uint32_t pos0, uint32_t row) {
                 const uint32_t val[4] = {p.x, p.y, p.z, p.w};
                 if constexpr (SMALL) {
 #pragma unroll
@@ -1373,9 +1385,12 @@ static void launch_worker_vec4(const Plan& p, const int32_t* lat, unsigned long 
 }
 
 // partial: [grid][3][N] u64; result: [3][N] u64 (sum, squares low, squares high per worker)
+// before/after: optional events recorded around the streaming kernel
 void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long* partial,
-                          unsigned long long* result, uint32_t* status, hipStream_t stream) {
+                          unsigned long long* result, uint32_t* status, hipStream_t stream, hipEvent_t before,
+                          hipEvent_t after) {
     hipLaunchKernelGGL(dc_clear_status_kernel, dim3(1), dim3(1), 0, stream, status);
+    if (before) (void)hipEventRecord(before, stream);
     if (!p.vec4) {
         if (p.M < 4)
             hipLaunchKernelGGL(dc_worker_totals_flat_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS),
@@ -1395,6 +1410,7 @@ void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long*
             default: launch_worker_vec4<0>(p, lat, partial, status, stream); break;
         }
     }
+    if (after) (void)hipEventRecord(after, stream);
     hipLaunchKernelGGL(dc_worker_totals_final_kernel, dim3((p.N + 255) / 256), dim3(256), 0, stream, partial, p.grid,
                        p.N, result);
 }
