@@ -574,10 +574,14 @@ def test_per_worker_normal_surrogate_parity(dev):
 
 # ---- full sizes of the two 2048-worker workloads, as the benchmark launches them -----------------------
 
-@pytest.mark.parametrize("name", ["extrapolation2048", "heterogeneous2048"])
-def test_full_size_parity(name, dev):
+@pytest.mark.parametrize("name,rows", [("extrapolation2048", 0), ("heterogeneous2048", 0), ("heterogeneous2048", 63)])
+def test_full_size_parity(name, rows, dev):
+    """The two 2048-worker workloads at full size, and the larger one once more with 63 accumulations per worker
+    (same bytes, more than 2^32 elements through the kernel for arbitrary row lengths)."""
     from dc_workloads import device
     r = config(name)
+    if rows:
+        r = r.with_shape(T=r.T * r.M // rows, M=rows)
     threads = host.cpu_threads()
     progress(f"{name}: generating {r.nbytes / 1e9:.1f} GB on the GPU")
     lat_d = device.generate(r)
