@@ -223,7 +223,7 @@ def main() -> int:
                     help="run a plain 4 GiB device-to-device copy instead (scale factor for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        print("bench.py measures one GPU; the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         return 2
 
     ensure_built()
