@@ -3,7 +3,6 @@
 Integer outputs must be bit-exact; the float ratios of dc_select_tau within 1e-6 relative.
 Inputs are seeded and synthetic; the oracle always gets CPU-generated tensors and grids.
 """
-import os
 import sys
 import time
 
@@ -13,7 +12,6 @@ import pytest
 import oracle
 import paper_2306_10598_amd as dc
 from dc_workloads import config, host, spec
-from tests.conftest import ROOT
 
 pytestmark = pytest.mark.gpu
 
