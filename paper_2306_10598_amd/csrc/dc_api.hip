@@ -85,6 +85,7 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     p.units = (uint32_t)units;
     uint64_t grid = (units + DC_SCAN_WAVES - 1) / DC_SCAN_WAVES;
     p.grid = (uint32_t)(grid < DC_MAX_SCAN_BLOCKS ? grid : DC_MAX_SCAN_BLOCKS);
+    p.run = DC_SCAN_WAVES;                                     // settled in enqueue(), once the grid is known
     p.chunk = p.K < DC_CHUNK_THRESHOLDS ? p.K : DC_CHUNK_THRESHOLDS;
     p.p2 = next_pow2_above(p.chunk);
     p.max_latency = (uint32_t)(2147483647ll / M);
@@ -208,6 +209,14 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
     dc::Plan p = plan;
     const uint32_t resident = resident_blocks(p);
     if (p.grid > resident) p.grid = resident;                   // the workspace was sized for the larger grid
+    // Long runs of consecutive units per block stream best in the kernels with whole rows per load (+2-3.5 %), as
+    // long as every block still gets several runs; the flat kernel, with its larger units, is 6-11 % faster when
+    // every block jumps ahead by the whole grid after each round of four units.
+    p.run = DC_SCAN_WAVES;
+    if (p.vec4) {
+        p.run = DC_UNIT_RUN;
+        while (p.run > DC_SCAN_WAVES && (uint64_t)p.units < 4ull * p.run * p.grid) p.run >>= 1;
+    }
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + p.off_status);
     int64_t* tau_sorted = reinterpret_cast<int64_t*>(ws + p.off_tau_sorted);
     uint32_t* tau_u32 = reinterpret_cast<uint32_t*>(ws + p.off_tau_u32);

@@ -19,6 +19,9 @@
 #ifndef DC_FLAT_UNIT_ELEMENTS
 #define DC_FLAT_UNIT_ELEMENTS 16384u    // target elements per unit of that kernel (whole rows, at least one)
 #endif
+#ifndef DC_UNIT_RUN
+#define DC_UNIT_RUN 64u                 // units per run (power of two); halved while the tensor has too few runs for the grid
+#endif
 #ifndef DC_MAX_SCAN_BLOCKS
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
 #endif
@@ -47,6 +50,7 @@ struct Plan {
     uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; otherwise rows per unit
     uint32_t units_per_trial;
     uint32_t units;             // T * units_per_trial
+    uint32_t run;               // consecutive units that one block takes at a time (a multiple of DC_SCAN_WAVES)
     uint32_t grid;              // blocks of the streaming kernel (= histogram slots)
     uint32_t chunk;             // thresholds per pass, <= DC_CHUNK_THRESHOLDS
     uint32_t p2;                // power of two > chunk: padded length of the LDS threshold array
