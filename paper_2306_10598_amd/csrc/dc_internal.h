@@ -23,7 +23,7 @@
 #define DC_UNIT_RUN 64u                 // units per run (power of two); halved while the tensor has too few runs for the grid
 #endif
 #ifndef DC_DENSE_LANES
-#define DC_DENSE_LANES 16u              // lanes per load inside the threshold grid from which long rows are binned without the queue
+#define DC_DENSE_LANES 48u              // lanes per load inside the threshold grid from which long rows are binned without the queue
 #endif
 #ifndef DC_MAX_SCAN_BLOCKS
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
