@@ -236,6 +236,21 @@ def test_thresholds_spanning_every_completion_time(dev):
     check(lat, taus, 9, dev)
 
 
+@pytest.mark.parametrize("M", [128, 256, 64, 100, 63])
+def test_dense_grids_with_and_without_repeated_thresholds(M, dev):
+    """Grids that cover most completion times, through both ways of finding a bin: evenly spaced thresholds (at
+    most one per lookup cell), the same with repeats, with two far outliers, and an irregular list."""
+    rng = np.random.default_rng(300 + M)
+    lat = rng.integers(500, 1500, size=(24, 70, M), dtype=np.int32)
+    top = int(lat.sum(axis=2, dtype=np.int64).max())
+    even = np.linspace(0, top, 257).astype(np.int64)
+    check(lat, even, 7, dev)
+    check(lat, np.concatenate([even, even[::3]]), 7, dev)
+    check(lat, np.concatenate([even, [BIG, top * 50]]), 7, dev)
+    check(lat, np.concatenate([even[:100], rng.integers(0, top, size=300)]), 7, dev)
+    check(lat, np.linspace(top // 2, top, 100).astype(np.int64), 7, dev)
+
+
 def test_zero_latencies_and_constant_rows(dev):
     lat = np.zeros((4, 10, 32), dtype=np.int32)
     check(lat, [0, 1, 2], 4, dev, "literal")
