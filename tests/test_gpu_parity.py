@@ -632,3 +632,45 @@ def test_full_size_parity(name, rows, dev):
     assert np.array_equal(s, rs) and np.array_equal(d, rd)
     del lat_d
     torch.cuda.empty_cache()
+
+
+def test_full_size_widened_entry_points(dev):
+    """The 34 GB workload through the per-iteration speedup, the moments and the per-worker statistics: the result
+    for the whole tensor equals the combination of the results for its slabs (means weighted by trials, integer
+    sums added), and sampled slabs agree with the oracle."""
+    from dc_workloads import device
+    r = config("heterogeneous2048")
+    lat_d = device.generate(r)
+    taus = device.tau_grid(r, lat_d)
+    slab = 2048
+    starts = list(range(0, r.T, slab))
+
+    whole = dc.dc_speedup_per_step(lat_d, taus, r.comm)
+    parts = np.zeros(taus.size)
+    for t0 in starts:
+        parts += dc.dc_speedup_per_step(lat_d[t0:t0 + slab], taus, r.comm) * (min(slab, r.T - t0) / r.T)
+    assert np.allclose(whole, parts, rtol=1e-10, atol=0)
+    progress("per-iteration speedup: whole tensor equals its slabs")
+
+    total, squares = dc.dc_moments(lat_d)[:2]
+    slabs = [dc.dc_moments(lat_d[t0:t0 + slab])[:2] for t0 in starts]
+    assert total == sum(s[0] for s in slabs) and squares == sum(s[1] for s in slabs)
+
+    sums, sq, _, _ = dc.dc_worker_moments(lat_d)
+    acc_s, acc_q = [0] * r.N, [0] * r.N
+    for t0 in starts:
+        s, q, _, _ = dc.dc_worker_moments(lat_d[t0:t0 + slab])
+        acc_s = [a + b for a, b in zip(acc_s, s)]
+        acc_q = [a + b for a, b in zip(acc_q, q)]
+    assert sums == acc_s and sq == acc_q
+    progress("moments and per-worker statistics: whole tensor equals its slabs")
+
+    for t0 in (0, r.T // 2 + 5, r.T - 6):                       # sampled slabs against the oracle
+        lat = host.generate(r, t0, t0 + 6)
+        view = lat_d[t0:t0 + 6]
+        assert np.allclose(dc.dc_speedup_per_step(view, taus, r.comm), oracle.per_step_speedup(lat, taus, r.comm),
+                           rtol=SPEEDUP_RTOL, atol=0)
+        assert dc.dc_moments(view)[:2] == oracle.moments(lat)[1:3]
+        assert dc.dc_worker_moments(view)[:2] == oracle.worker_moments(lat)[:2]
+    del lat_d
+    torch.cuda.empty_cache()
