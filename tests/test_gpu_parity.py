@@ -674,3 +674,36 @@ def test_full_size_widened_entry_points(dev):
         assert dc.dc_worker_moments(view)[:2] == oracle.worker_moments(lat)[:2]
     del lat_d
     torch.cuda.empty_cache()
+
+
+def test_plain_c_caller_of_the_abi(dev, golden_dir):
+    """examples/dc_from_c (C, no Python, no torch) on the hand-worked example and on a random problem."""
+    import subprocess
+    from tests.conftest import ROOT
+    from tests.test_oracle_pins import read_golden
+    exe = ROOT / "examples" / "dc_from_c"
+    if not exe.exists():
+        import __graft_entry__
+        __graft_entry__.build_c_example()
+
+    def run(lat, taus, comm):
+        T, N, M = lat.shape
+        text = f"{T} {N} {M} {len(taus)} {comm}\n" + " ".join(map(str, lat.reshape(-1))) + "\n" + " ".join(map(str, taus)) + "\n"
+        res = subprocess.run([str(exe)], input=text, capture_output=True, text=True, timeout=100)
+        assert res.returncode == 0, res.stderr
+        lines = dict(line.split(" ", 1) for line in res.stdout.strip().splitlines())
+        return (np.array(lines["step"].split(), dtype=np.int64), np.array(lines["done"].split(), dtype=np.int64),
+                int(lines["best"]))
+
+    g = read_golden(golden_dir / "hand_example.txt")
+    lat = np.array(g["lat"], dtype=np.int32).reshape(g["T"][0], g["N"][0], g["M"][0])
+    step, done, _ = run(lat, g["taus"], g["comm"][0])
+    assert step.tolist() == g["step"] and done.tolist() == g["done"]
+
+    rng = np.random.default_rng(21)
+    lat = rng.integers(0, 5000, size=(7, 19, 12), dtype=np.int32)
+    taus = rng.integers(0, 12 * 5000, size=40).astype(np.int64)
+    step, done, best = run(lat, taus.tolist(), 9)
+    ref_step, ref_done = oracle.simulate(lat, taus, 9, "literal")
+    assert np.array_equal(step, ref_step) and np.array_equal(done, ref_done)
+    assert best == oracle.select_tau(ref_step, ref_done, taus, 7, 19, 12, 0)[2]
