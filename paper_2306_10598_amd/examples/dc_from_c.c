@@ -11,8 +11,8 @@
  * Exit status 0 on success, 1 on bad input, 2 when the library or the GPU reports an error.
  *
  * Build (see __graft_entry__.build):
- *     gcc -std=c11 -D__HIP_PLATFORM_AMD__ -I/opt/rocm/include -Iinclude examples/dc_from_c.c \
- *         -Lpaper_2306_10598_amd -ldc -L/opt/rocm/lib -lamdhip64 -Wl,-rpath,$PWD/paper_2306_10598_amd -o examples/dc_from_c
+ *     gcc -std=c11 -D__HIP_PLATFORM_AMD__ -I/opt/rocm/include -Iinclude paper_2306_10598_amd/examples/dc_from_c.c \
+ *         -Lpaper_2306_10598_amd -ldc -L/opt/rocm/lib -lamdhip64 -Wl,-rpath,$PWD/paper_2306_10598_amd -o paper_2306_10598_amd/examples/dc_from_c
  */
 #include <hip/hip_runtime_api.h>
 #include <inttypes.h>

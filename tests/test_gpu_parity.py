@@ -677,11 +677,11 @@ def test_full_size_widened_entry_points(dev):
 
 
 def test_plain_c_caller_of_the_abi(dev, golden_dir):
-    """examples/dc_from_c (C, no Python, no torch) on the hand-worked example and on a random problem."""
+    """paper_2306_10598_amd/examples/dc_from_c (C, no Python, no torch) on the hand-worked example and on a random problem."""
     import subprocess
     from tests.conftest import ROOT
     from tests.test_oracle_pins import read_golden
-    exe = ROOT / "examples" / "dc_from_c"
+    exe = ROOT / "paper_2306_10598_amd" / "examples" / "dc_from_c"
     if not exe.exists():
         import __graft_entry__
         __graft_entry__.build_c_example()
