@@ -314,6 +314,7 @@ bool sizes_ok(int64_t T, int64_t N, int64_t M, int64_t K, int64_t comm) {
 unsigned char* g_cache = nullptr;
 size_t g_cache_bytes = 0;
 int g_cache_device = -1;
+std::vector<unsigned char> g_staging;   // host side of the synchronous entry point's result copy
 
 // Grow (never shrink) the cached device allocation of the synchronous entry points.  Caller holds g_mutex.
 int ensure_cache(size_t need) {
@@ -377,6 +378,8 @@ int dc_simulate(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64
     if (!make_plan(T, N, M, K, aligned, &p)) return DC_ERR_INVALID_ARG;
 
     std::lock_guard<std::mutex> lock(g_mutex);
+    // cached allocation: thresholds | step | done | workspace (whose first word is the status): the two result
+    // arrays are adjacent, so one copy brings both back
     const size_t io_bytes = align256((size_t)K * 8);
     {
         int rc = ensure_cache(3 * io_bytes + p.bytes);
@@ -391,13 +394,15 @@ int dc_simulate(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64
     DC_HIP(hipMemcpy(taus_dev, taus, (size_t)K * 8, hipMemcpyHostToDevice));
     int rc = enqueue(p, lat, taus_dev, comm, step_dev, done_dev, ws, stream, g_timing.enabled);
     if (rc) return rc;
-    DC_HIP(hipStreamSynchronize(stream));
+    // results and status word in one device-to-host copy (it also waits for the kernels)
+    g_staging.resize(2 * io_bytes + 256);
+    DC_HIP(hipMemcpy(g_staging.data(), step_dev, 2 * io_bytes + 256, hipMemcpyDeviceToHost));
     uint32_t flags = 0;
-    DC_HIP(hipMemcpy(&flags, ws + p.off_status, sizeof(flags), hipMemcpyDeviceToHost));
+    memcpy(&flags, g_staging.data() + 2 * io_bytes + p.off_status, sizeof(flags));
     rc = flags_to_status(flags);
     if (rc) return rc;
-    DC_HIP(hipMemcpy(out_step, step_dev, (size_t)K * 8, hipMemcpyDeviceToHost));
-    DC_HIP(hipMemcpy(out_done, done_dev, (size_t)K * 8, hipMemcpyDeviceToHost));
+    memcpy(out_step, g_staging.data(), (size_t)K * 8);
+    memcpy(out_done, g_staging.data() + io_bytes, (size_t)K * 8);
     return DC_OK;
 }
 
