@@ -205,6 +205,78 @@ def bench_analytic(args, r, lat, taus) -> int:
     return 0
 
 
+def time_sums_path(r, lat, taus, taus_dev, stream, steps, warmup):
+    """`warmup` untimed and `steps` timed passes of the whole path (dc_simulate_async, one copy of the 2 K sums to
+    the host, dc_select_tau) on `stream`.  Returns (wall seconds, per-step ms, scan-kernel ms per step, thr, best),
+    or None if the device flagged a value error."""
+    import numpy as np
+    import torch
+
+    import paper_2306_10598_amd as dc
+    K = taus.size
+    out = torch.zeros((2, K), dtype=torch.int64, device=lat.device)     # out_step, out_done: one buffer, one copy back
+    host_out = torch.zeros((2, K), dtype=torch.int64).pin_memory()
+    host_step, host_done = host_out[0].numpy(), host_out[1].numpy()
+    ws = torch.empty(dc.dc_workspace_bytes(r.T, r.N, r.M, K), dtype=torch.uint8, device=lat.device)
+
+    def step():                                                  # `stream` is torch's current stream here
+        dc.dc_simulate_async(lat, taus_dev, r.comm, out[0], out[1], ws, stream)
+        host_out.copy_(out, non_blocking=True)
+        stream.synchronize()
+        return dc.dc_select_tau(host_step, host_done, taus, r.T, r.N, r.M, 0)
+
+    previous = torch.cuda.current_stream()
+    torch.cuda.set_stream(stream)
+    dc.dc_set_kernel_timing(True)
+    try:
+        for _ in range(warmup):
+            step()
+        if dc.dc_workspace_status(ws, stream) != dc.DC_OK:
+            return None
+        scan_ms, step_ms = [], []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            ts = time.perf_counter()
+            thr, _, best = step()
+            step_ms.append(1e3 * (time.perf_counter() - ts))
+            scan_ms.append(dc.dc_last_kernel_ms()[0])          # HIP events on the stream the kernel ran on
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    finally:
+        dc.dc_set_kernel_timing(False)
+        torch.cuda.set_stream(previous)
+    return wall, step_ms, scan_ms, thr, best
+
+
+def other_workloads(headline: str, stream, steps: int = 10, warmup: int = 3):
+    """Short runs of the same path on the remaining workloads (reported beside the headline, not part of `value`)."""
+    import numpy as np
+    import torch
+
+    from dc_workloads import config, device, spec
+    rows = []
+    for name in spec.CONFIG_NAMES:
+        if name == headline:
+            continue
+        r = config(name)
+        lat = device.generate(r)
+        taus = device.tau_grid(r, lat)
+        taus_dev = torch.from_numpy(taus).to(lat.device)
+        m = time_sums_path(r, lat, taus, taus_dev, stream, steps, warmup)
+        del lat
+        torch.cuda.empty_cache()
+        if m is None:
+            rows.append({"workload": name, "error": "device reported a value error"})
+            continue
+        wall, _, scan_ms, _, _ = m
+        rows.append({"workload": f"{name}: T={r.T} N={r.N} M={r.M} K={taus.size}", "tensor_bytes": r.nbytes,
+                     "value": float(r.elements) * taus.size / (wall / steps), "unit": "evals/s",
+                     "ms_per_step": 1e3 * wall / steps, "kernel_ms": float(np.mean(scan_ms)),
+                     "achieved_GBps": 4.0 * r.elements / (float(np.mean(scan_ms)) * 1e-3) / 1e9, "steps": steps})
+    return rows
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -219,6 +291,8 @@ def main() -> int:
                     help="run the workload with this many accumulations per worker instead of its own M, the number of "
                          "trials rescaled to keep the tensor's size (not a bench line: for timing other row lengths)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the short runs on the other workloads that are reported in `per_config`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 4 GiB device-to-device copy instead (scale factor for HBM byte counters)")
     args = ap.parse_args()
@@ -253,11 +327,6 @@ def main() -> int:
     taus = device.tau_grid(r, lat)
     K = taus.size
     taus_dev = torch.from_numpy(taus).to(dev)
-    out = torch.zeros((2, K), dtype=torch.int64, device=dev)     # out_step, out_done: one buffer, one copy back
-    out_step, out_done = out[0], out[1]
-    host_out = torch.zeros((2, K), dtype=torch.int64).pin_memory()
-    host_step, host_done = host_out[0].numpy(), host_out[1].numpy()
-    ws = torch.empty(dc.dc_workspace_bytes(r.T, r.N, r.M, K), dtype=torch.uint8, device=dev)
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
 
@@ -266,30 +335,11 @@ def main() -> int:
     if args.path == "analytic":
         return bench_analytic(args, r, lat, taus)
 
-    def step():                                                  # `stream` is torch's current stream here
-        dc.dc_simulate_async(lat, taus_dev, r.comm, out_step, out_done, ws, stream)
-        host_out.copy_(out, non_blocking=True)
-        stream.synchronize()
-        return dc.dc_select_tau(host_step, host_done, taus, r.T, r.N, r.M, 0)
-
-    torch.cuda.set_stream(stream)
-    dc.dc_set_kernel_timing(True)
-    for _ in range(args.warmup):
-        step()
-    if dc.dc_workspace_status(ws, stream) != dc.DC_OK:
+    m = time_sums_path(r, lat, taus, taus_dev, stream, args.steps, args.warmup)
+    if m is None:
         print("device reported a value error", file=sys.stderr)
         return 1
-    scan_ms, step_ms = [], []
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        ts = time.perf_counter()
-        thr, _, best = step()
-        step_ms.append(1e3 * (time.perf_counter() - ts))
-        scan_ms.append(dc.dc_last_kernel_ms()[0])              # HIP events on the stream the kernel ran on
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    dc.dc_set_kernel_timing(False)
+    wall, step_ms, scan_ms, thr, best = m
 
     ms_per_step = 1e3 * wall / args.steps
     whole_rows = r.M % 4 == 0 and (r.M <= 128 or r.M == 256)    # the library's choice between its two streaming kernels
@@ -311,9 +361,11 @@ def main() -> int:
                      "kernel_ms": scan_avg_ms, "kernel_ms_min": float(np.min(scan_ms)),
                      "algorithmic_bytes": algo_bytes},
     }
+    del lat
+    torch.cuda.empty_cache()
+    if not args.no_per_config and args.rows <= 0:
+        line["per_config"] = other_workloads(r.name, stream)
     if not args.no_cpu_baseline:
-        del lat
-        torch.cuda.empty_cache()
         line["cpu_baseline"] = cpu_baseline(r, taus)
     print(json.dumps(line))
     return 0
