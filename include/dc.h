@@ -175,7 +175,9 @@ int dc_analytic_curves(double mu, double sigma2, int64_t N, int64_t M, const int
  * also the whole enqueued sequence (two more event records per call); 0: off.  dc_last_kernel_ms waits
  * for those events and returns the elapsed milliseconds of the last call (scan_ms: streaming kernel(s)
  * only; total_ms: all kernels of the call, needs enable = 2).  Either pointer may be NULL.
- * DC_ERR_INVALID_ARG if the requested timing is off or no call has been timed yet. */
+ * DC_ERR_INVALID_ARG if the requested timing is off or no call has been timed yet.  The events belong to the
+ * device that was current when timing was first used; leave timing off while a stream is being captured
+ * into a graph (event records would become graph nodes whose times cannot be read back). */
 int dc_set_kernel_timing(int enable);
 int dc_last_kernel_ms(float* scan_ms, float* total_ms);
 
