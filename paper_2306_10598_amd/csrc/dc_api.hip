@@ -85,7 +85,8 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     p.units = (uint32_t)units;
     uint64_t grid = (units + DC_SCAN_WAVES - 1) / DC_SCAN_WAVES;
     p.grid = (uint32_t)(grid < DC_MAX_SCAN_BLOCKS ? grid : DC_MAX_SCAN_BLOCKS);
-    p.run = DC_SCAN_WAVES;                                     // settled in enqueue(), once the grid is known
+    p.grid_wide = p.grid;
+    p.run = DC_SCAN_WAVES;                                     // both settled in enqueue(), once the device's limits are known
     p.chunk = p.K < DC_CHUNK_THRESHOLDS ? p.K : DC_CHUNK_THRESHOLDS;
     p.p2 = next_pow2_above(p.chunk);
     p.max_latency = (uint32_t)(2147483647ll / M);
@@ -163,7 +164,7 @@ int ensure_events(size_t pairs) {
 // The kernel splits the work statically over its waves, so every block must be resident at once (a
 // block that waits for a free slot would run alone at the end), and the same number of blocks must
 // sit on every compute unit.  Queried once per (device, kernel variant, LDS size).
-struct ResidentKey { int device; bool vec4; bool trial; uint32_t M; uint32_t p2; int blocks; };
+struct ResidentKey { int device; bool vec4; bool trial; uint32_t M; uint32_t p2; int blocks; int wide_blocks; };
 std::vector<ResidentKey> g_resident;
 
 // Blocks per compute unit that stream best (measured on MI355X with 8 loads in flight per lane): long
@@ -186,29 +187,43 @@ uint32_t variant_of(const dc::Plan& p) {
     return p.M < 4 ? 2u : 3u;
 }
 
-uint32_t resident_blocks(const dc::Plan& p, bool trial = false) {
+struct Resident {
+    uint32_t blocks;        // the grid that streams the usual, narrow threshold grids best
+    uint32_t wide_blocks;   // long rows only: the larger grid for threshold grids that cover much of the data (else = blocks)
+};
+
+Resident resident_blocks(const dc::Plan& p, bool trial = false) {
     int device = 0;
-    if (hipGetDevice(&device) != hipSuccess) return DC_MAX_SCAN_BLOCKS;
+    if (hipGetDevice(&device) != hipSuccess) return {DC_MAX_SCAN_BLOCKS, DC_MAX_SCAN_BLOCKS};
     for (const ResidentKey& k : g_resident)
         if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == variant_of(p) && k.p2 == p.p2)
-            return (uint32_t)k.blocks;
+            return {(uint32_t)k.blocks, (uint32_t)k.wide_blocks};
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1) cus = 256;
-    int per_cu = trial ? dc::trial_scan_blocks_per_cu(p) : dc::scan_blocks_per_cu(p);   // what fits
-    if (per_cu < 1) per_cu = 1;
+    int fit = trial ? dc::trial_scan_blocks_per_cu(p) : dc::scan_blocks_per_cu(p);      // what fits
+    if (fit < 1) fit = 1;
     const int wanted = (int)wanted_blocks_per_cu(p);                                    // what streams best
-    if (per_cu > wanted) per_cu = wanted;
-    const int blocks = cus * per_cu;
-    g_resident.push_back({device, p.vec4, trial, variant_of(p), p.p2, blocks});
-    return (uint32_t)blocks;
+    const int per_cu = fit > wanted ? wanted : fit;
+    int wide_per_cu = per_cu;
+    if (!trial && p.vec4 && p.M >= 128 && per_cu < DC_DENSE_BLOCKS_PER_CU)
+        wide_per_cu = fit > DC_DENSE_BLOCKS_PER_CU ? DC_DENSE_BLOCKS_PER_CU : fit;
+    g_resident.push_back({device, p.vec4, trial, variant_of(p), p.p2, cus * per_cu, cus * wide_per_cu});
+    return {(uint32_t)(cus * per_cu), (uint32_t)(cus * wide_per_cu)};
 }
 
 // ---- the enqueued sequence ---------------------------------------------------------------------
 int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, int64_t comm, int64_t* out_step_dev,
             int64_t* out_done_dev, unsigned char* ws, hipStream_t stream, bool timed) {
     dc::Plan p = plan;
-    const uint32_t resident = resident_blocks(p);
-    if (p.grid > resident) p.grid = resident;                   // the workspace was sized for the larger grid
+    const Resident resident = resident_blocks(p);
+    // Long rows stream narrow threshold grids best with two blocks per compute unit and grids that cover much of
+    // the data with three (+25-30 % there, -4.5 % on narrow ones), so the kernel is launched once with either grid
+    // and a sample taken by the prep kernel decides on the device which launch works; the other returns at once.
+    const uint32_t planned = p.grid;                            // the workspace was sized for this many blocks
+    p.grid_wide = planned < resident.wide_blocks ? planned : resident.wide_blocks;
+    if (p.grid > resident.blocks) p.grid = resident.blocks;
+    if (p.grid_wide < p.grid) p.grid_wide = p.grid;
+    const uint32_t sample_rows = p.grid_wide > p.grid ? DC_SAMPLE_ROWS : 0u;
     // Long runs of consecutive units per block stream best in the kernels with whole rows per load (+2-3.5 %), as
     // long as every block still gets several runs; the flat kernel, with its larger units, is 6-11 % faster when
     // every block jumps ahead by the whole grid after each round of four units.
@@ -237,14 +252,15 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
         g_timing.valid = false;
         if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.begin, stream));
     }
-    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, hist_total, 3 * p.p2, stream);
+    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, hist_total, 3 * p.p2, lat,
+                    (uint64_t)p.T * p.N, p.M, sample_rows, stream);
     for (uint32_t c = 0; c < chunks; ++c) {
         const uint32_t chunk0 = c * p.chunk;
         const uint32_t kc = p.K - chunk0 < p.chunk ? p.K - chunk0 : p.chunk;
         if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c], stream));
         dc::launch_scan(p, lat, tau_u32 + chunk0, kc, unit_max, hist_part, status, stream);
         if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c + 1], stream));
-        dc::launch_reduce(p, hist_part, hist_total, unit_max, tau_u32 + chunk0, kc, trial_cnt, trial_sum, stream);
+        dc::launch_reduce(p, hist_part, hist_total, unit_max, tau_u32 + chunk0, kc, trial_cnt, trial_sum, status, stream);
         dc::launch_finalize(p, hist_total, trial_cnt, trial_sum, kc, chunk0, tau_sorted, pos, comm, out_step_dev,
                             out_done_dev, chunk_step, chunk_done, stream);
     }
@@ -267,7 +283,7 @@ int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* tau
                     const int64_t* comm_per_trial_dev, double* out_seff_dev, unsigned char* ws, hipStream_t stream,
                     bool timed) {
     dc::Plan p = plan;
-    const uint32_t resident = resident_blocks(p, true);
+    const uint32_t resident = resident_blocks(p, true).blocks;
     if (p.grid > resident) p.grid = resident;
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + p.off_status);
     int64_t* tau_sorted = reinterpret_cast<int64_t*>(ws + p.off_tau_sorted);
@@ -282,7 +298,7 @@ int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* tau
         g_timing.valid = false;
         if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.begin, stream));
     }
-    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, nullptr, 0, stream);
+    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, nullptr, 0, nullptr, 0, 0, 0, stream);
     for (uint32_t c = 0; c < chunks; ++c) {
         const uint32_t chunk0 = c * p.chunk;
         const uint32_t kc = p.K - chunk0 < p.chunk ? p.K - chunk0 : p.chunk;

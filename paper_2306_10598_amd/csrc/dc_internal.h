@@ -25,6 +25,13 @@
 #ifndef DC_DENSE_LANES
 #define DC_DENSE_LANES 48u              // lanes per load inside the threshold grid from which long rows are binned without the queue
 #endif
+#ifndef DC_DENSE_PERMILLE
+#define DC_DENSE_PERMILLE 180u          // share of completion times inside the grid (per mille, sampled) from which
+#endif                                  // long rows are streamed with DC_DENSE_BLOCKS_PER_CU blocks per compute unit
+#ifndef DC_DENSE_BLOCKS_PER_CU
+#define DC_DENSE_BLOCKS_PER_CU 3
+#endif
+#define DC_SAMPLE_ROWS 128u             // rows of lat that the sample reads
 #ifndef DC_MAX_SCAN_BLOCKS
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
 #endif
@@ -54,7 +61,8 @@ struct Plan {
     uint32_t units_per_trial;
     uint32_t units;             // T * units_per_trial
     uint32_t run;               // consecutive units that one block takes at a time (a multiple of DC_SCAN_WAVES)
-    uint32_t grid;              // blocks of the streaming kernel (= histogram slots)
+    uint32_t grid;              // blocks of the streaming kernel (= histogram slots) for narrow threshold grids ...
+    uint32_t grid_wide;         // ... and for dense ones (long rows only, else equal): both are launched, one works
     uint32_t chunk;             // thresholds per pass, <= DC_CHUNK_THRESHOLDS
     uint32_t p2;                // power of two > chunk: padded length of the LDS threshold array
     uint32_t max_latency;       // floor((2^31-1)/M)
@@ -65,12 +73,14 @@ struct Plan {
 };
 
 void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t* tau_u32, uint32_t* pos,
-                 uint32_t* status, unsigned long long* bins, uint32_t bins_words, hipStream_t stream);
+                 uint32_t* status, unsigned long long* bins, uint32_t bins_words, const int32_t* lat,
+                 uint64_t rows_total, uint32_t M, uint32_t sample_rows, hipStream_t stream);
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
                  uint32_t* hist_part, uint32_t* status, hipStream_t stream);
 void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long* hist_total,
                    const uint32_t* unit_max, const uint32_t* tau_chunk, uint32_t kc,
-                   unsigned long long* trial_cnt, unsigned long long* trial_sum, hipStream_t stream);
+                   unsigned long long* trial_cnt, unsigned long long* trial_sum, const uint32_t* status,
+                   hipStream_t stream);
 void launch_finalize(const Plan& p, unsigned long long* hist_total, unsigned long long* trial_cnt,
                      unsigned long long* trial_sum, uint32_t kc, uint32_t chunk0, const int64_t* tau_sorted,
                      const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done, int64_t* chunk_step,

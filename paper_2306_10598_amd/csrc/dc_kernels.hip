@@ -322,11 +322,53 @@ __device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U]
 // ---------------------------------------------------------------------------------------------
 // dc_prep_kernel: rank-sort the thresholds, clamp, validate, clear accumulators
 // ---------------------------------------------------------------------------------------------
+
+// Share of completion times at or above the smallest threshold, from `sample_rows` rows spread evenly over the
+// tensor (a wave per row, 64 elements at a time); 1 if it reaches DC_DENSE_PERMILLE.  Called by a whole block.
+__device__ __forceinline__ uint32_t sample_is_dense(const int64_t* __restrict__ taus, uint32_t K,
+                                                    const int32_t* __restrict__ lat, unsigned long long rows_total,
+                                                    uint32_t M, uint32_t sample_rows) {
+    __shared__ long long wave_min[4];
+    __shared__ uint32_t wave_hits[4];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    long long lowest = 0x7FFFFFFFFFFFFFFFll;
+    for (uint32_t i = threadIdx.x; i < K; i += blockDim.x) lowest = taus[i] < lowest ? taus[i] : lowest;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const long long other = __shfl_xor(lowest, d, 64);
+        lowest = other < lowest ? other : lowest;
+    }
+    if (lane == 0) wave_min[wave] = lowest;
+    __syncthreads();
+    lowest = wave_min[0];
+    for (int w = 1; w < 4; ++w) lowest = wave_min[w] < lowest ? wave_min[w] : lowest;
+    const uint32_t tau0 = lowest >= (long long)DC_TAU_CLAMP ? DC_TAU_CLAMP : (lowest < 0 ? 0u : (uint32_t)lowest);
+
+    uint32_t hits = 0u;                                           // wave-uniform
+    for (uint32_t sidx = wave; sidx < sample_rows; sidx += 4) {
+        const unsigned long long row = rows_total / sample_rows * sidx + rows_total % sample_rows * sidx / sample_rows;
+        const int32_t* src = lat + row * M;
+        uint32_t carry = 0u;
+        for (uint32_t m0 = 0; m0 < M; m0 += 64u) {
+            const uint32_t m = m0 + lane;
+            const uint32_t x = m < M ? (uint32_t)src[m] : 0u;
+            const uint32_t incl = segmented_inclusive_scan<64>(x, lane) + carry;
+            hits += (uint32_t)__popcll(__ballot(m < M && incl >= tau0));
+            carry = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        }
+    }
+    if (lane == 0) wave_hits[wave] = hits;
+    __syncthreads();
+    const unsigned long long all = (unsigned long long)wave_hits[0] + wave_hits[1] + wave_hits[2] + wave_hits[3];
+    return all * 1000ull >= (unsigned long long)DC_DENSE_PERMILLE * sample_rows * M ? 1u : 0u;
+}
+
 __global__ __launch_bounds__(256)
 void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
                     int64_t* __restrict__ tau_sorted, uint32_t* __restrict__ tau_u32,
                     uint32_t* __restrict__ pos, uint32_t* __restrict__ status,
-                    unsigned long long* __restrict__ bins, uint32_t bins_words) {
+                    unsigned long long* __restrict__ bins, uint32_t bins_words,
+                    const int32_t* __restrict__ lat, unsigned long long rows_total, uint32_t M, uint32_t sample_rows) {
     // A block ranks 32 thresholds; the comparisons of each are split over 8 threads.
     constexpr uint32_t TILE = 1024;
     __shared__ int64_t tile[TILE];
@@ -353,6 +395,12 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
     }
     partial[part][jj] = rank;
     __syncthreads();
+    // Block 0 also looks at a sample of rows (sample_rows > 0) and tells the streaming kernel which of its two
+    // launch shapes to use: status[1] = 1 when a large share of the completion times reaches the smallest threshold.
+    if (blockIdx.x == 0 && sample_rows != 0u) {
+        const uint32_t dense = sample_is_dense(taus, K, lat, rows_total, M, sample_rows);   // synchronises the block
+        if (threadIdx.x == 0) status[1] = dense;
+    }
     if (part != 0 || j >= K) return;
     rank = 0;
 #pragma unroll
@@ -445,6 +493,15 @@ __device__ __forceinline__ void stream_rows(WaveState& st, const u32x4* base, ui
     }
 }
 
+// The kernels for long rows are launched twice when the prep kernel sampled the data: once with the grid that
+// suits narrow threshold grids (shape 1) and once with the larger grid for dense ones (shape 2); the launch
+// that the sample (status[1]) did not choose returns at once.  shape 0: a single launch, always runs.
+__device__ __forceinline__ bool launch_is_chosen(uint32_t shape, const uint32_t* status) {
+    if (shape == 0u) return true;
+    const uint32_t dense = (uint32_t)__builtin_amdgcn_readfirstlane((int)status[1]);
+    return (dense != 0u) == (shape == 2u);
+}
+
 // How the units are dealt to the blocks: runs of `run` consecutive units (a multiple of the waves per block),
 // round-robin over the blocks.
 struct UnitRuns {
@@ -453,10 +510,10 @@ struct UnitRuns {
     uint32_t rounds;     // steps of DC_SCAN_WAVES units inside a run
 };
 
-__device__ __forceinline__ UnitRuns unit_runs(uint32_t units, uint32_t run) {
+__device__ __forceinline__ UnitRuns unit_runs(uint32_t units, uint32_t run, uint32_t blocks) {
     UnitRuns ur;
     ur.runs = (units + run - 1u) / run;
-    ur.padded = (ur.runs + gridDim.x - 1u) / gridDim.x * gridDim.x;
+    ur.padded = (ur.runs + blocks - 1u) / blocks * blocks;
     ur.rounds = run / DC_SCAN_WAVES;
     return ur;
 }
@@ -477,10 +534,11 @@ __device__ __forceinline__ void report_range(uint32_t check, uint32_t max_latenc
 template <int L>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t units, uint32_t units_per_trial,
-                         uint32_t run, uint32_t loads_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
+                         uint32_t run, uint32_t launch_shape, uint32_t loads_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
                          uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
                          uint32_t* __restrict__ status, uint32_t max_latency, uint32_t lanes_per_row) {
     extern __shared__ __align__(16) unsigned char smem[];
+    if (!launch_is_chosen(launch_shape, status)) return;
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
     const GridView g = stage_grid(reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS), tau_chunk, kc, p2);
 
@@ -497,7 +555,7 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
     // 64 units (2 MiB) 7.10-7.14 TB/s, runs of 4 (every block jumps ahead by the whole grid each time) 6.87-6.96.
     // Both loop bounds are the same for the whole block, so the barrier is reached by every wave the same
     // number of times; it only paces the waves (1-2 % faster than letting them drift apart).
-    const UnitRuns ur = unit_runs(units, run);
+    const UnitRuns ur = unit_runs(units, run, gridDim.x);
     for (uint32_t r = blockIdx.x; r < ur.padded; r += gridDim.x)
     for (uint32_t round = 0; round < ur.rounds; ++round) {
         const uint32_t u = r < ur.runs ? r * run + round * DC_SCAN_WAVES + wave : units;
@@ -801,7 +859,7 @@ void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint32
     const FlatTensor f = flat_tensor(lat, total, M);
 
     WaveState st{0u, 0u, 0u, 0u};
-    const UnitRuns ur = unit_runs(units, run);                                             // as in dc_scan_vec4_kernel
+    const UnitRuns ur = unit_runs(units, run, gridDim.x);                                  // as in dc_scan_vec4_kernel
     for (uint32_t r = blockIdx.x; r < ur.padded; r += gridDim.x)                          // block-uniform bounds
     for (uint32_t round = 0; round < ur.rounds; ++round) {
         const uint32_t u = r < ur.runs ? r * run + round * DC_SCAN_WAVES + wave : units;
@@ -833,7 +891,8 @@ void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint32
 // (cleared beforehand).  The remaining blocks do (b), one thread per trial.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256)
-void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t slots, uint32_t p2, uint32_t col_blocks,
+void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t narrow_slots, uint32_t wide_slots,
+                      const uint32_t* __restrict__ status, uint32_t p2, uint32_t col_blocks,
                       uint32_t hist_blocks, unsigned long long* __restrict__ hist_total,
                       const uint32_t* __restrict__ unit_max, uint32_t T, uint32_t units_per_trial,
                       const uint32_t* __restrict__ tau_chunk, uint32_t kc,
@@ -842,6 +901,8 @@ void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t slots, ui
     const uint32_t grp = threadIdx.x >> 6;
     if (blockIdx.x < hist_blocks) {
         __shared__ unsigned long long part[4][64];
+        // histograms were written by the launch of the streaming kernel that the sample chose
+        const uint32_t slots = wide_slots > narrow_slots && status[1] != 0u ? wide_slots : narrow_slots;
         const uint32_t col = (blockIdx.x % col_blocks) * 64 + lane;       // consecutive lanes, consecutive columns
         const uint32_t s0 = (blockIdx.x / col_blocks) * DC_REDUCE_SLOTS;
         const uint32_t s1 = s0 + DC_REDUCE_SLOTS < slots ? s0 + DC_REDUCE_SLOTS : slots;
@@ -1290,13 +1351,15 @@ void dc_worker_totals_final_kernel(const unsigned long long* __restrict__ partia
 // ---------------------------------------------------------------------------------------------
 namespace dc {
 
+// sample_rows > 0: also sample that many rows of lat ([rows_total][M]) for the choice of the launch shape
 void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t* tau_u32, uint32_t* pos,
-                 uint32_t* status, unsigned long long* bins, uint32_t bins_words, hipStream_t stream) {
+                 uint32_t* status, unsigned long long* bins, uint32_t bins_words, const int32_t* lat,
+                 uint64_t rows_total, uint32_t M, uint32_t sample_rows, hipStream_t stream) {
     const uint32_t threads = 256;                 // 32 thresholds per block
     uint32_t blocks = (K + 31) / 32;
     if (blocks == 0) blocks = 1;
     hipLaunchKernelGGL(dc_prep_kernel, dim3(blocks), dim3(threads), 0, stream, taus, K, tau_sorted, tau_u32, pos,
-                       status, bins, bins_words);
+                       status, bins, bins_words, lat, (unsigned long long)rows_total, M, sample_rows);
 }
 
 size_t scan_lds_bytes(const Plan& p) {
@@ -1335,9 +1398,14 @@ int scan_blocks_per_cu(const Plan& p) {
 template <int L>
 static void launch_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                         uint32_t* unit_max, uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
+    const bool two = p.grid_wide > p.grid;          // the sample decides on the device which of the two launches works
     hipLaunchKernelGGL(dc_scan_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
-                       p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max, hist_part, status,
-                       p.max_latency, p.M / 4);
+                       p.N, p.units, p.units_per_trial, p.run, two ? 1u : 0u, p.per_unit, tau_chunk, kc, p.p2, unit_max,
+                       hist_part, status, p.max_latency, p.M / 4);
+    if (two)
+        hipLaunchKernelGGL(dc_scan_vec4_kernel<L>, dim3(p.grid_wide), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
+                           p.N, p.units, p.units_per_trial, p.run, 2u, p.per_unit, tau_chunk, kc, p.p2, unit_max,
+                           hist_part, status, p.max_latency, p.M / 4);
 }
 
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
@@ -1367,14 +1435,15 @@ void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, u
 
 void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long* hist_total,
                    const uint32_t* unit_max, const uint32_t* tau_chunk, uint32_t kc,
-                   unsigned long long* trial_cnt, unsigned long long* trial_sum, hipStream_t stream) {
+                   unsigned long long* trial_cnt, unsigned long long* trial_sum, const uint32_t* status,
+                   hipStream_t stream) {
     const uint32_t col_blocks = (p.p2 + 63) / 64;
-    const uint32_t slot_groups = (p.grid + DC_REDUCE_SLOTS - 1) / DC_REDUCE_SLOTS;
+    const uint32_t slot_groups = (p.grid_wide + DC_REDUCE_SLOTS - 1) / DC_REDUCE_SLOTS;
     const uint32_t hist_blocks = col_blocks * slot_groups;
     const uint32_t trial_blocks = (p.T + 255) / 256;
     hipLaunchKernelGGL(dc_reduce_kernel, dim3(hist_blocks + trial_blocks), dim3(256), (size_t)p.p2 * 12, stream, hist_part, p.grid,
-                       p.p2, col_blocks, hist_blocks, hist_total, unit_max, p.T, p.units_per_trial, tau_chunk, kc,
-                       trial_cnt, trial_sum);
+                       p.grid_wide, status, p.p2, col_blocks, hist_blocks, hist_total, unit_max, p.T, p.units_per_trial,
+                       tau_chunk, kc, trial_cnt, trial_sum);
 }
 
 void launch_finalize(const Plan& p, unsigned long long* hist_total, unsigned long long* trial_cnt,

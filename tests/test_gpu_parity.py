@@ -707,3 +707,25 @@ def test_plain_c_caller_of_the_abi(dev, golden_dir):
     ref_step, ref_done = oracle.simulate(lat, taus, 9, "literal")
     assert np.array_equal(step, ref_step) and np.array_equal(done, ref_done)
     assert best == oracle.select_tau(ref_step, ref_done, taus, 7, 19, 12, 0)[2]
+
+
+def test_launch_shape_follows_the_threshold_grid(dev):
+    """Long rows on one workspace with threshold grids that cover almost nothing, everything, and almost nothing
+    again: the device-side choice between the two launch shapes must never leave stale partial histograms behind."""
+    r = config("heterogeneous2048").with_shape(T=700)                    # enough units for the larger grid
+    lat = host.generate(r)
+    lat_d = to_dev(lat, dev)
+    top = int(host.worker_totals(lat).max())
+    grids = [np.linspace(top - top // 50, top, 64).astype(np.int64), np.linspace(0, top, 200).astype(np.int64),
+             np.array([top + 5], dtype=np.int64), np.linspace(top // 3, top, 90).astype(np.int64),
+             np.linspace(top - top // 40, top + 9, 64).astype(np.int64)]
+    K = max(g.size for g in grids)
+    ws = torch.empty(dc.dc_workspace_bytes(r.T, r.N, r.M, K), dtype=torch.uint8, device=dev)
+    out = torch.zeros((2, K), dtype=torch.int64, device=dev)
+    for taus in grids + grids[::-1]:
+        k = taus.size
+        dc.dc_simulate_async(lat_d, torch.from_numpy(taus).to(dev), r.comm, out[0, :k], out[1, :k], ws, None)
+        torch.cuda.synchronize()
+        assert dc.dc_workspace_status(ws, None) == dc.DC_OK
+        ref_step, ref_done = oracle.simulate_threaded(lat, taus, r.comm, "sorted", host.cpu_threads())
+        assert np.array_equal(out[0, :k].cpu().numpy(), ref_step) and np.array_equal(out[1, :k].cpu().numpy(), ref_done)
