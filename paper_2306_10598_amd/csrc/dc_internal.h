@@ -31,7 +31,7 @@
 #ifndef DC_DENSE_BLOCKS_PER_CU
 #define DC_DENSE_BLOCKS_PER_CU 3
 #endif
-#define DC_SAMPLE_ROWS 128u             // rows of lat that the sample reads
+#define DC_SAMPLE_ROWS 32               // rows of lat that the sample reads (a multiple of 4: a quarter per wave)
 #ifndef DC_MAX_SCAN_BLOCKS
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
 #endif

@@ -323,16 +323,40 @@ __device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U]
 // dc_prep_kernel: rank-sort the thresholds, clamp, validate, clear accumulators
 // ---------------------------------------------------------------------------------------------
 
-// Share of completion times at or above the smallest threshold, from `sample_rows` rows spread evenly over the
-// tensor (a wave per row, 64 elements at a time); 1 if it reaches DC_DENSE_PERMILLE.  Called by a whole block.
-__device__ __forceinline__ uint32_t sample_is_dense(const int64_t* __restrict__ taus, uint32_t K,
-                                                    const int32_t* __restrict__ lat, unsigned long long rows_total,
-                                                    uint32_t M, uint32_t sample_rows) {
+// Share of completion times at or above the smallest threshold, from `sample_rows` <= DC_SAMPLE_ROWS rows spread
+// evenly over the tensor.  Rows here are 128 or 256 elements of a 16-byte aligned tensor: one 16-byte load per lane
+// covers a row.  sample_begin issues every load (a wave has DC_SAMPLE_ROWS / 4 rows in flight, and its share of the
+// thresholds) so that their latency passes behind other work; sample_is_dense, called later by the whole block of
+// 256 threads, returns 1 if the share reaches DC_DENSE_PERMILLE.
+struct Sample {
+    u32x4 x[DC_SAMPLE_ROWS / 4];
+    long long lowest;          // smallest threshold among those this thread read
+};
+
+__device__ __forceinline__ Sample sample_begin(const int64_t* __restrict__ taus, uint32_t K,
+                                               const int32_t* __restrict__ lat, unsigned long long rows_total,
+                                               uint32_t M, uint32_t sample_rows) {
+    constexpr int PER_WAVE = DC_SAMPLE_ROWS / 4;
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    Sample sm;
+    sm.lowest = 0x7FFFFFFFFFFFFFFFll;
+    for (uint32_t i = threadIdx.x; i < K; i += blockDim.x) sm.lowest = taus[i] < sm.lowest ? taus[i] : sm.lowest;
+#pragma unroll
+    for (int q = 0; q < PER_WAVE; ++q) {
+        const uint32_t sidx = wave * PER_WAVE + (uint32_t)q;
+        const unsigned long long row = rows_total / sample_rows * sidx + rows_total % sample_rows * sidx / sample_rows;
+        sm.x[q] = u32x4{0u, 0u, 0u, 0u};
+        if (sidx < sample_rows && lane < M / 4u) sm.x[q] = *(reinterpret_cast<const u32x4*>(lat + row * M) + lane);
+    }
+    return sm;
+}
+
+__device__ __forceinline__ uint32_t sample_is_dense(const Sample& sm, uint32_t M, uint32_t sample_rows) {
+    constexpr int PER_WAVE = DC_SAMPLE_ROWS / 4;
     __shared__ long long wave_min[4];
     __shared__ uint32_t wave_hits[4];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    long long lowest = 0x7FFFFFFFFFFFFFFFll;
-    for (uint32_t i = threadIdx.x; i < K; i += blockDim.x) lowest = taus[i] < lowest ? taus[i] : lowest;
+    long long lowest = sm.lowest;
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
         const long long other = __shfl_xor(lowest, d, 64);
@@ -344,19 +368,17 @@ __device__ __forceinline__ uint32_t sample_is_dense(const int64_t* __restrict__ 
     for (int w = 1; w < 4; ++w) lowest = wave_min[w] < lowest ? wave_min[w] : lowest;
     const uint32_t tau0 = lowest >= (long long)DC_TAU_CLAMP ? DC_TAU_CLAMP : (lowest < 0 ? 0u : (uint32_t)lowest);
 
-    uint32_t hits = 0u;                                           // wave-uniform
-    for (uint32_t sidx = wave; sidx < sample_rows; sidx += 4) {
-        const unsigned long long row = rows_total / sample_rows * sidx + rows_total % sample_rows * sidx / sample_rows;
-        const int32_t* src = lat + row * M;
-        uint32_t carry = 0u;
-        for (uint32_t m0 = 0; m0 < M; m0 += 64u) {
-            const uint32_t m = m0 + lane;
-            const uint32_t x = m < M ? (uint32_t)src[m] : 0u;
-            const uint32_t incl = segmented_inclusive_scan<64>(x, lane) + carry;
-            hits += (uint32_t)__popcll(__ballot(m < M && incl >= tau0));
-            carry = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-        }
+    uint32_t hits = 0u;                                           // per lane; added up below
+#pragma unroll
+    for (int q = 0; q < PER_WAVE; ++q) {
+        const u32x4 x = sm.x[q];
+        const uint32_t c3 = segmented_inclusive_scan<64>(x.x + x.y + x.z + x.w, lane);
+        const uint32_t c2 = c3 - x.w, c1 = c2 - x.z, c0 = c1 - x.y;
+        if (wave * PER_WAVE + (uint32_t)q < sample_rows && lane < M / 4u)
+            hits += (c0 >= tau0 ? 1u : 0u) + (c1 >= tau0 ? 1u : 0u) + (c2 >= tau0 ? 1u : 0u) + (c3 >= tau0 ? 1u : 0u);
     }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) hits += (uint32_t)__shfl_xor((int)hits, d, 64);
     if (lane == 0) wave_hits[wave] = hits;
     __syncthreads();
     const unsigned long long all = (unsigned long long)wave_hits[0] + wave_hits[1] + wave_hits[2] + wave_hits[3];
@@ -375,6 +397,11 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
     __shared__ uint32_t partial[8][32];
     const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
     const uint32_t stride = gridDim.x * blockDim.x;
+    // Block 0 also looks at a sample of rows (sample_rows > 0) and tells the streaming kernel which of its two launch
+    // shapes to use; its loads are issued here and used after the ranking.
+    const bool sampling = blockIdx.x == 0 && sample_rows != 0u;
+    Sample sm{};
+    if (sampling) sm = sample_begin(taus, K, lat, rows_total, M, sample_rows);
     if (gid == 0) *status = 0u;                   // kernels that set flags run later on the stream
     for (uint32_t i = gid; i < bins_words; i += stride) bins[i] = 0ull;
     const uint32_t jj = threadIdx.x & 31u, part = threadIdx.x >> 5;
@@ -395,10 +422,9 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
     }
     partial[part][jj] = rank;
     __syncthreads();
-    // Block 0 also looks at a sample of rows (sample_rows > 0) and tells the streaming kernel which of its two
-    // launch shapes to use: status[1] = 1 when a large share of the completion times reaches the smallest threshold.
-    if (blockIdx.x == 0 && sample_rows != 0u) {
-        const uint32_t dense = sample_is_dense(taus, K, lat, rows_total, M, sample_rows);   // synchronises the block
+    // status[1] = 1 when a large share of the sampled completion times reaches the smallest threshold
+    if (sampling) {
+        const uint32_t dense = sample_is_dense(sm, M, sample_rows);   // synchronises the block
         if (threadIdx.x == 0) status[1] = dense;
     }
     if (part != 0 || j >= K) return;
@@ -493,13 +519,15 @@ __device__ __forceinline__ void stream_rows(WaveState& st, const u32x4* base, ui
     }
 }
 
-// The kernels for long rows are launched twice when the prep kernel sampled the data: once with the grid that
-// suits narrow threshold grids (shape 1) and once with the larger grid for dense ones (shape 2); the launch
-// that the sample (status[1]) did not choose returns at once.  shape 0: a single launch, always runs.
-__device__ __forceinline__ bool launch_is_chosen(uint32_t shape, const uint32_t* status) {
-    if (shape == 0u) return true;
+// The kernel for long rows is launched twice when the prep kernel sampled the data: once with the grid that suits
+// narrow threshold grids (SHAPE 1) and once with the larger grid for dense ones (SHAPE 2); the launch that the
+// sample (status[1]) did not choose returns at once.  SHAPE 0: a single launch, always runs.  The shape is part
+// of the kernel's name, so a profile tells the working launch from the idle one.
+template <int SHAPE>
+__device__ __forceinline__ bool launch_is_chosen(const uint32_t* status) {
+    if constexpr (SHAPE == 0) return true;
     const uint32_t dense = (uint32_t)__builtin_amdgcn_readfirstlane((int)status[1]);
-    return (dense != 0u) == (shape == 2u);
+    return (dense != 0u) == (SHAPE == 2);
 }
 
 // How the units are dealt to the blocks: runs of `run` consecutive units (a multiple of the waves per block),
@@ -531,14 +559,14 @@ __device__ __forceinline__ void report_range(uint32_t check, uint32_t max_latenc
 // loads_per_unit consecutive loads inside one trial; waves take units round-robin.  Every wave owns
 // its queue and the histogram is updated with LDS atomics, so the only block-level synchronisation
 // in the loop is one barrier per unit that keeps the block's waves in step.
-template <int L>
+template <int L, int SHAPE>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t units, uint32_t units_per_trial,
-                         uint32_t run, uint32_t launch_shape, uint32_t loads_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
+                         uint32_t run, uint32_t loads_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
                          uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
                          uint32_t* __restrict__ status, uint32_t max_latency, uint32_t lanes_per_row) {
     extern __shared__ __align__(16) unsigned char smem[];
-    if (!launch_is_chosen(launch_shape, status)) return;
+    if (!launch_is_chosen<SHAPE>(status)) return;
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
     const GridView g = stage_grid(reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS), tau_chunk, kc, p2);
 
@@ -1370,7 +1398,7 @@ size_t scan_lds_bytes(const Plan& p) {
 template <int L>
 static int resident_vec4(size_t lds) {
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_vec4_kernel<L>, DC_SCAN_THREADS, lds) != hipSuccess) n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_vec4_kernel<L, 0>, DC_SCAN_THREADS, lds) != hipSuccess) n = 0;
     return n;
 }
 
@@ -1398,14 +1426,20 @@ int scan_blocks_per_cu(const Plan& p) {
 template <int L>
 static void launch_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                         uint32_t* unit_max, uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
-    const bool two = p.grid_wide > p.grid;          // the sample decides on the device which of the two launches works
-    hipLaunchKernelGGL(dc_scan_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
-                       p.N, p.units, p.units_per_trial, p.run, two ? 1u : 0u, p.per_unit, tau_chunk, kc, p.p2, unit_max,
-                       hist_part, status, p.max_latency, p.M / 4);
-    if (two)
-        hipLaunchKernelGGL(dc_scan_vec4_kernel<L>, dim3(p.grid_wide), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
-                           p.N, p.units, p.units_per_trial, p.run, 2u, p.per_unit, tau_chunk, kc, p.p2, unit_max,
-                           hist_part, status, p.max_latency, p.M / 4);
+    if (p.grid_wide > p.grid) {                     // the sample decides on the device which of the two launches works
+        if constexpr (L == 32 || L == 64) {
+            hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 1>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
+                               lat, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max,
+                               hist_part, status, p.max_latency, p.M / 4);
+            hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 2>), dim3(p.grid_wide), dim3(DC_SCAN_THREADS), scan_lds_bytes(p),
+                               stream, lat, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2,
+                               unit_max, hist_part, status, p.max_latency, p.M / 4);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 0>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
+                       p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max, hist_part,
+                       status, p.max_latency, p.M / 4);
 }
 
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,

@@ -729,3 +729,33 @@ def test_launch_shape_follows_the_threshold_grid(dev):
         assert dc.dc_workspace_status(ws, None) == dc.DC_OK
         ref_step, ref_done = oracle.simulate_threaded(lat, taus, r.comm, "sorted", host.cpu_threads())
         assert np.array_equal(out[0, :k].cpu().numpy(), ref_step) and np.array_equal(out[1, :k].cpu().numpy(), ref_done)
+
+
+def test_graph_replay_picks_the_launch_shape_from_the_data(dev):
+    """A captured sequence for long rows holds both launch shapes; each replay chooses on the device.  The graph is
+    replayed on a tensor whose contents change between replays (scaled so that the same thresholds cover almost
+    nothing, then everything), and must match the oracle each time."""
+    r = config("extrapolation2048").with_shape(T=300)
+    base = host.generate(r)
+    top = int(host.worker_totals(base).max())
+    taus = np.linspace(top - top // 40, top, 128).astype(np.int64)
+    taus_d = torch.from_numpy(taus).to(dev)
+    lat_d = to_dev(base, dev)
+    out = torch.zeros((2, taus.size), dtype=torch.int64, device=dev)
+    ws = torch.empty(dc.dc_workspace_bytes(r.T, r.N, r.M, taus.size), dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream()
+    dc.dc_simulate_async(lat_d, taus_d, r.comm, out[0], out[1], ws, side)
+    assert dc.dc_workspace_status(ws, side) == dc.DC_OK
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        dc.dc_simulate_async(lat_d, taus_d, r.comm, out[0], out[1], ws, torch.cuda.current_stream())
+    for factor in (1, 3, 1, 2, 3, 1):                            # x3: every completion time passes the smallest threshold early
+        lat = base * factor
+        lat_d.copy_(torch.from_numpy(lat))
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref_step, ref_done = oracle.simulate_threaded(lat, taus, r.comm, "sorted", host.cpu_threads())
+        got = out.cpu().numpy()
+        assert np.array_equal(got[0], ref_step) and np.array_equal(got[1], ref_done), factor
