@@ -205,6 +205,15 @@ def bench_analytic(args, r, lat, taus) -> int:
     return 0
 
 
+def scan_kernel_name(M: int) -> str:
+    """The streaming kernel the library runs for rows of M elements (16-byte aligned tensor), as a profile names it."""
+    if M % 4 == 0 and (M <= 128 or M == 256):
+        lanes = M // 4
+        known = lanes if lanes & (lanes - 1) == 0 else 0              # one instantiation serves every other lane count
+        return f"{SCAN_KERNEL}<{known}, {1 if M >= 128 else 0}>"      # long rows: <L, 1> works on narrow grids, <L, 2> on dense ones
+    return f"dc_scan_flat_kernel<{'true' if M < 4 else 'false'}>"
+
+
 def time_sums_path(r, lat, taus, taus_dev, stream, steps, warmup):
     """`warmup` untimed and `steps` timed passes of the whole path (dc_simulate_async, one copy of the 2 K sums to
     the host, dc_select_tau) on `stream`.  Returns (wall seconds, per-step ms, scan-kernel ms per step, thr, best),
@@ -342,7 +351,6 @@ def main() -> int:
     wall, step_ms, scan_ms, thr, best = m
 
     ms_per_step = 1e3 * wall / args.steps
-    whole_rows = r.M % 4 == 0 and (r.M <= 128 or r.M == 256)    # the library's choice between its two streaming kernels
     evals = float(r.elements) * K
     scan_avg_ms = float(np.mean(scan_ms))
     algo_bytes = 4.0 * r.elements                              # every latency read once, nothing written back
@@ -355,7 +363,7 @@ def main() -> int:
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"{r.name}: T={r.T} N={r.N} M={r.M} K={K} comm={r.comm}us, {r.description}",
                    "tensor_bytes": r.nbytes, "best_tau_us": int(taus[best]), "best_thr_per_us": float(thr[best])},
-        "roofline": {"bound": "hbm", "kernel": SCAN_KERNEL if whole_rows else "dc_scan_flat_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(r.M), "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": None if args.rows > 0 else recorded_traffic(r.name),
                      "kernel_ms": scan_avg_ms, "kernel_ms_min": float(np.min(scan_ms)),
