@@ -260,9 +260,8 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
         if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c], stream));
         dc::launch_scan(p, lat, tau_u32 + chunk0, kc, unit_max, hist_part, status, stream);
         if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c + 1], stream));
-        dc::launch_reduce(p, hist_part, hist_total, unit_max, tau_u32 + chunk0, kc, trial_cnt, trial_sum, status, stream);
-        dc::launch_finalize(p, hist_total, trial_cnt, trial_sum, kc, chunk0, tau_sorted, pos, comm, out_step_dev,
-                            out_done_dev, chunk_step, chunk_done, stream);
+        dc::launch_reduce(p, hist_part, hist_total, unit_max, tau_u32 + chunk0, kc, trial_cnt, trial_sum, status, chunk0,
+                          tau_sorted, pos, comm, out_step_dev, out_done_dev, chunk_step, chunk_done, stream);
     }
     if (timed) {
         if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.end, stream));

@@ -37,7 +37,6 @@
 #endif
 #define DC_SCAN_WAVES (DC_SCAN_THREADS / 64)
 #define DC_REDUCE_SLOTS 64u             // per-block histograms added by one block of the reduce kernel
-#define DC_FINAL_THREADS 1024
 #define DC_CHUNK_THRESHOLDS 4095u      // thresholds handled by one pass over lat (LDS-resident grid)
 #define DC_TRIAL_CHUNK_THRESHOLDS 2047u // same for the per-iteration speedup pass (it also keeps float64 sums in LDS)
 #define DC_MAX_TRIAL_BLOCKS 2048u      // upper bound of that pass's grid (sizes its per-block sums in the workspace)
@@ -79,12 +78,9 @@ void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, u
                  uint32_t* hist_part, uint32_t* status, hipStream_t stream);
 void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long* hist_total,
                    const uint32_t* unit_max, const uint32_t* tau_chunk, uint32_t kc,
-                   unsigned long long* trial_cnt, unsigned long long* trial_sum, const uint32_t* status,
-                   hipStream_t stream);
-void launch_finalize(const Plan& p, unsigned long long* hist_total, unsigned long long* trial_cnt,
-                     unsigned long long* trial_sum, uint32_t kc, uint32_t chunk0, const int64_t* tau_sorted,
-                     const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done, int64_t* chunk_step,
-                     int64_t* chunk_done, hipStream_t stream);
+                   unsigned long long* trial_cnt, unsigned long long* trial_sum, uint32_t* status, uint32_t chunk0,
+                   const int64_t* tau_sorted, const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done,
+                   int64_t* chunk_step, int64_t* chunk_done, hipStream_t stream);
 void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                        const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
                        hipStream_t stream);

@@ -1,11 +1,12 @@
 // Device kernels of the DropCompute step-time simulator, written for gfx950 (wave64, DPP, LDS).
 //
 // Pipeline of one call (all on one stream):
-//   dc_prep_kernel       sort the K thresholds by rank, clamp them to 32 bits, clear accumulators
+//   dc_prep_kernel       sort the K thresholds by rank, clamp them to 32 bits, clear accumulators; for long rows
+//                        also sample the tensor to choose the streaming kernel's launch shape
 //   dc_scan_vec4_kernel  the single pass over lat: completion times by a segmented wave scan,
-//     / dc_scan_generic  histogram of completion times over the threshold grid, per-unit maxima
-//   dc_reduce_kernel     add the per-block histograms; per-trial maximum -> binned count and sum
-//   dc_finalize_kernel   prefix sums over the bins -> out_step, out_done in the caller's order
+//     / dc_scan_flat     histogram of completion times over the threshold grid, per-unit maxima
+//   dc_reduce_kernel     add the per-block histograms; per-trial maximum -> binned count and sum; the last block
+//                        to finish takes prefix sums over the bins -> out_step, out_done in the caller's order
 //
 // Counting rests on two facts.  Latencies are >= 0, so a worker's completion times
 // P[m] = sum_{j<=m} lat[j] (Section 4.3) are non-decreasing.  And "P < tau_k" (strict, Section 4.3)
@@ -402,7 +403,7 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
     const bool sampling = blockIdx.x == 0 && sample_rows != 0u;
     Sample sm{};
     if (sampling) sm = sample_begin(taus, K, lat, rows_total, M, sample_rows);
-    if (gid == 0) *status = 0u;                   // kernels that set flags run later on the stream
+    if (gid == 0) { status[0] = 0u; status[2] = 0u; }   // value flags (set by later kernels) and the reduce kernel's ticket
     for (uint32_t i = gid; i < bins_words; i += stride) bins[i] = 0ull;
     const uint32_t jj = threadIdx.x & 31u, part = threadIdx.x >> 5;
     const uint32_t j = blockIdx.x * 32 + jj;
@@ -913,22 +914,109 @@ void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint32
 }
 
 // ---------------------------------------------------------------------------------------------
-// dc_reduce_kernel: (a) column sums of the per-block histograms, (b) per-trial maximum binned
-// over the chunk's thresholds.  Blocks [0, hist_blocks) do (a): block (c, g) adds slots
-// [g*DC_REDUCE_SLOTS, ...) of columns [64c, 64c+64) and adds its partial sums to hist_total
-// (cleared beforehand).  The remaining blocks do (b), one thread per trial.
+// The last step of a pass, run by one block of THREADS threads once every sum is in.  Running sums over the bins
+// give, for sorted threshold i of the chunk: not_done[i] = sum_{b>i} hist[b];
+// below[i] = #{t : Tmax_t < tau_i} = sum_{b<=i} cnt[b];  below_sum[i] = sum_{b<=i} sum[b].  Then
+//   done[i] = T*N*M - not_done[i]
+//   step[i] = below_sum[i] + tau_i * (T - below[i]) + T*comm
+// and results go to the caller's positions.  The accumulators are cleared for the next chunk.  They were written
+// with device-scope atomics by other blocks, hence the device-scope loads.
+// ---------------------------------------------------------------------------------------------
+struct FinalArgs {
+    unsigned long long* hist_total;
+    unsigned long long* trial_cnt;
+    unsigned long long* trial_sum;
+    uint32_t kc, p2, chunk0, K;
+    const int64_t* tau_sorted;
+    const uint32_t* pos;
+    unsigned long long T, elements;
+    long long comm;
+    long long* out_step;
+    long long* out_done;
+    long long* chunk_step;
+    long long* chunk_done;
+};
+
+__device__ __forceinline__ unsigned long long load_device_scope(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <uint32_t THREADS>
+__device__ __forceinline__ void finalize_chunk(const FinalArgs& f) {
+    constexpr uint32_t MAX_PER = (DC_CHUNK_THRESHOLDS + 1u + THREADS - 1u) / THREADS;   // p2 <= 4096
+    __shared__ unsigned long long s_a[THREADS], s_b[THREADS], s_c[THREADS];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t per = (f.p2 + THREADS - 1) / THREADS;           // each thread owns a contiguous run of bins
+    const uint32_t b0 = tid * per;
+    unsigned long long h[MAX_PER], c[MAX_PER], s[MAX_PER];
+    unsigned long long th = 0, tc = 0, ts = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < MAX_PER; ++i) {
+        const uint32_t b = b0 + i;
+        h[i] = i < per && b < f.p2 ? load_device_scope(&f.hist_total[b]) : 0ull;
+        c[i] = i < per && b <= f.kc ? load_device_scope(&f.trial_cnt[b]) : 0ull;
+        s[i] = i < per && b <= f.kc ? load_device_scope(&f.trial_sum[b]) : 0ull;
+        th += h[i]; tc += c[i]; ts += s[i];
+    }
+    s_a[tid] = th; s_b[tid] = tc; s_c[tid] = ts;
+    __syncthreads();
+    for (uint32_t d = 1; d < THREADS; d <<= 1) {                    // inclusive scan over threads
+        unsigned long long xa = 0, xb = 0, xc = 0;
+        if (tid >= d) { xa = s_a[tid - d]; xb = s_b[tid - d]; xc = s_c[tid - d]; }
+        __syncthreads();
+        s_a[tid] += xa; s_b[tid] += xb; s_c[tid] += xc;
+        __syncthreads();
+    }
+    const unsigned long long all_hist = s_a[THREADS - 1];
+    unsigned long long run_h = s_a[tid] - th, run_c = s_b[tid] - tc, run_s = s_c[tid] - ts;   // exclusive
+#pragma unroll
+    for (uint32_t i = 0; i < MAX_PER; ++i) {
+        const uint32_t b = b0 + i;
+        run_h += h[i]; run_c += c[i]; run_s += s[i];                 // inclusive up to bin b
+        if (i < per && b < f.kc) {
+            const unsigned long long not_done = all_hist - run_h;
+            const long long tau = f.tau_sorted[f.chunk0 + b];
+            const unsigned long long tau_c = tau >= (long long)DC_TAU_CLAMP ? (unsigned long long)DC_TAU_CLAMP
+                                                                           : (unsigned long long)(tau < 0 ? 0 : tau);
+            f.chunk_done[b] = (long long)(f.elements - not_done);
+            f.chunk_step[b] = (long long)(run_s + tau_c * (f.T - run_c) + f.T * (unsigned long long)f.comm);
+        }
+    }
+    __syncthreads();
+    for (uint32_t b = tid; b < f.p2; b += THREADS) {
+        f.hist_total[b] = 0ull;
+        if (b <= f.kc) { f.trial_cnt[b] = 0ull; f.trial_sum[b] = 0ull; }
+    }
+    __threadfence_block();
+    __syncthreads();
+    for (uint32_t j = tid; j < f.K; j += THREADS) {
+        const uint32_t p = f.pos[j];
+        if (p >= f.chunk0 && p < f.chunk0 + f.kc) {
+            f.out_step[j] = f.chunk_step[p - f.chunk0];
+            f.out_done[j] = f.chunk_done[p - f.chunk0];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dc_reduce_kernel: (a) column sums of the per-block histograms, (b) per-trial maximum binned over the chunk's
+// thresholds, (c) the final running sums.  Blocks [0, hist_blocks) do (a): block (c, g) adds slots
+// [g*DC_REDUCE_SLOTS, ...) of columns [64c, 64c+64) and adds its partial sums to hist_total (cleared beforehand).
+// The remaining blocks do (b), one thread per trial.  Every block then takes a ticket (status[2], cleared by the
+// prep kernel and again here); the block that draws the last one knows that all sums are in and does (c).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256)
 void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t narrow_slots, uint32_t wide_slots,
-                      const uint32_t* __restrict__ status, uint32_t p2, uint32_t col_blocks,
-                      uint32_t hist_blocks, unsigned long long* __restrict__ hist_total,
-                      const uint32_t* __restrict__ unit_max, uint32_t T, uint32_t units_per_trial,
-                      const uint32_t* __restrict__ tau_chunk, uint32_t kc,
-                      unsigned long long* __restrict__ trial_cnt, unsigned long long* __restrict__ trial_sum) {
+                      uint32_t* __restrict__ status, uint32_t col_blocks, uint32_t hist_blocks,
+                      const uint32_t* __restrict__ unit_max, uint32_t units_per_trial,
+                      const uint32_t* __restrict__ tau_chunk, FinalArgs f) {
+    extern __shared__ unsigned long long bin_sum[];                       // (b): [p2], then the counts
+    __shared__ unsigned long long part[4][64];
+    __shared__ uint32_t is_last;
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t grp = threadIdx.x >> 6;
+    const uint32_t p2 = f.p2, kc = f.kc;
     if (blockIdx.x < hist_blocks) {
-        __shared__ unsigned long long part[4][64];
         // histograms were written by the launch of the streaming kernel that the sample chose
         const uint32_t slots = wide_slots > narrow_slots && status[1] != 0u ? wide_slots : narrow_slots;
         const uint32_t col = (blockIdx.x % col_blocks) * 64 + lane;       // consecutive lanes, consecutive columns
@@ -941,117 +1029,60 @@ void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t narrow_sl
         __syncthreads();
         if (grp == 0 && col < p2) {
             const unsigned long long sum = part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane];
-            if (sum) atomicAdd(&hist_total[col], sum);
+            if (sum) atomicAdd(&f.hist_total[col], sum);
         }
-        return;
-    }
-    // (b) one thread per trial.  The trial maxima of a block are binned in LDS first (maxima of one
-    // workload crowd into a few bins, and same-address atomics in device memory serialise), then the
-    // bins that were hit go to device memory: at most one addition per bin and block.
-    extern __shared__ unsigned long long bin_sum[];                       // [p2], then the counts
-    uint32_t* bin_cnt = reinterpret_cast<uint32_t*>(bin_sum + p2);        // [p2]
-    for (uint32_t i = threadIdx.x; i < p2; i += 256) {
-        bin_sum[i] = 0ull;
-        bin_cnt[i] = 0u;
-    }
-    __syncthreads();
-    const uint32_t t = (blockIdx.x - hist_blocks) * 256 + threadIdx.x;
-    if (t < T) {
-        uint32_t tmax = 0u;
-        const uint32_t* um = unit_max + (uint64_t)t * units_per_trial;
-        if ((units_per_trial & 3u) == 0u) {                               // unit_max is 256-byte aligned
-            for (uint32_t j = 0; j < units_per_trial; j += 4) {
-                const uint4 v = *reinterpret_cast<const uint4*>(um + j);
-                tmax = umax(umax(tmax, v.x), umax(umax(v.y, v.z), v.w));
+    } else {
+        // (b) one thread per trial.  The trial maxima of a block are binned in LDS first (maxima of one
+        // workload crowd into a few bins, and same-address atomics in device memory serialise), then the
+        // bins that were hit go to device memory: at most one addition per bin and block.
+        uint32_t* bin_cnt = reinterpret_cast<uint32_t*>(bin_sum + p2);    // [p2]
+        for (uint32_t i = threadIdx.x; i < p2; i += 256) {
+            bin_sum[i] = 0ull;
+            bin_cnt[i] = 0u;
+        }
+        __syncthreads();
+        const uint32_t t = (blockIdx.x - hist_blocks) * 256 + threadIdx.x;
+        if (t < (uint32_t)f.T) {
+            uint32_t tmax = 0u;
+            const uint32_t* um = unit_max + (uint64_t)t * units_per_trial;
+            if ((units_per_trial & 3u) == 0u) {                           // unit_max is 256-byte aligned
+                for (uint32_t j = 0; j < units_per_trial; j += 4) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(um + j);
+                    tmax = umax(umax(tmax, v.x), umax(umax(v.y, v.z), v.w));
+                }
+            } else {
+                for (uint32_t j = 0; j < units_per_trial; ++j) tmax = umax(tmax, um[j]);
             }
-        } else {
-            for (uint32_t j = 0; j < units_per_trial; ++j) tmax = umax(tmax, um[j]);
+            // b = #{i < kc : tau_i <= tmax}; the trial's step time is tmax for thresholds i >= b, tau_i below
+            uint32_t lo = 0, hi = kc;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (tau_chunk[mid] <= tmax) lo = mid + 1; else hi = mid;
+            }
+            atomicAdd(&bin_cnt[lo], 1u);
+            atomicAdd(&bin_sum[lo], (unsigned long long)tmax);
         }
-        // b = #{i < kc : tau_i <= tmax}; the trial's step time is tmax for thresholds i >= b, tau_i below
-        uint32_t lo = 0, hi = kc;
-        while (lo < hi) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if (tau_chunk[mid] <= tmax) lo = mid + 1; else hi = mid;
-        }
-        atomicAdd(&bin_cnt[lo], 1u);
-        atomicAdd(&bin_sum[lo], (unsigned long long)tmax);
-    }
-    __syncthreads();
-    for (uint32_t i = threadIdx.x; i <= kc; i += 256) {
-        const uint32_t c = bin_cnt[i];
-        if (c) {
-            atomicAdd(&trial_cnt[i], (unsigned long long)c);
-            atomicAdd(&trial_sum[i], bin_sum[i]);
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// dc_finalize_kernel: one block.  Running sums over the bins give, for sorted threshold i of the
-// chunk: not_done[i] = sum_{b>i} hist[b];  below[i] = #{t : Tmax_t < tau_i} = sum_{b<=i} cnt[b];
-// below_sum[i] = sum_{b<=i} sum[b].  Then
-//   done[i] = T*N*M - not_done[i]
-//   step[i] = below_sum[i] + tau_i * (T - below[i]) + T*comm
-// and results go to the caller's positions.  The accumulators are cleared for the next chunk.
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(DC_FINAL_THREADS)
-void dc_finalize_kernel(unsigned long long* __restrict__ hist_total, unsigned long long* __restrict__ trial_cnt,
-                        unsigned long long* __restrict__ trial_sum, uint32_t kc, uint32_t p2, uint32_t chunk0,
-                        const int64_t* __restrict__ tau_sorted, const uint32_t* __restrict__ pos, uint32_t K,
-                        unsigned long long T, unsigned long long elements, long long comm,
-                        long long* __restrict__ out_step, long long* __restrict__ out_done,
-                        long long* __restrict__ chunk_step, long long* __restrict__ chunk_done) {
-    __shared__ unsigned long long s_a[DC_FINAL_THREADS], s_b[DC_FINAL_THREADS], s_c[DC_FINAL_THREADS];
-    const uint32_t tid = threadIdx.x;
-    // each thread owns a contiguous run of bins; p2 <= 4096, so at most 4 bins per thread
-    const uint32_t per = (p2 + DC_FINAL_THREADS - 1) / DC_FINAL_THREADS;
-    const uint32_t b0 = tid * per;
-    unsigned long long h[4], c[4], s[4];
-    unsigned long long th = 0, tc = 0, ts = 0;
-    for (uint32_t i = 0; i < per; ++i) {
-        const uint32_t b = b0 + i;
-        h[i] = b < p2 ? hist_total[b] : 0ull;
-        c[i] = b <= kc ? trial_cnt[b] : 0ull;
-        s[i] = b <= kc ? trial_sum[b] : 0ull;
-        th += h[i]; tc += c[i]; ts += s[i];
-    }
-    s_a[tid] = th; s_b[tid] = tc; s_c[tid] = ts;
-    __syncthreads();
-    for (uint32_t d = 1; d < DC_FINAL_THREADS; d <<= 1) {            // inclusive scan over threads
-        unsigned long long xa = 0, xb = 0, xc = 0;
-        if (tid >= d) { xa = s_a[tid - d]; xb = s_b[tid - d]; xc = s_c[tid - d]; }
         __syncthreads();
-        s_a[tid] += xa; s_b[tid] += xb; s_c[tid] += xc;
-        __syncthreads();
-    }
-    const unsigned long long all_hist = s_a[DC_FINAL_THREADS - 1];
-    unsigned long long run_h = s_a[tid] - th, run_c = s_b[tid] - tc, run_s = s_c[tid] - ts;   // exclusive
-    for (uint32_t i = 0; i < per; ++i) {
-        const uint32_t b = b0 + i;
-        run_h += h[i]; run_c += c[i]; run_s += s[i];                 // inclusive up to bin b
-        if (b < kc) {
-            const unsigned long long not_done = all_hist - run_h;
-            const long long tau = tau_sorted[chunk0 + b];
-            const unsigned long long tau_c = tau >= (long long)DC_TAU_CLAMP ? (unsigned long long)DC_TAU_CLAMP
-                                                                           : (unsigned long long)(tau < 0 ? 0 : tau);
-            chunk_done[b] = (long long)(elements - not_done);
-            chunk_step[b] = (long long)(run_s + tau_c * (T - run_c) + T * (unsigned long long)comm);
+        for (uint32_t i = threadIdx.x; i <= kc; i += 256) {
+            const uint32_t c = bin_cnt[i];
+            if (c) {
+                atomicAdd(&f.trial_cnt[i], (unsigned long long)c);
+                atomicAdd(&f.trial_sum[i], bin_sum[i]);
+            }
         }
     }
-    __syncthreads();
-    for (uint32_t b = tid; b < p2; b += DC_FINAL_THREADS) {
-        hist_total[b] = 0ull;
-        if (b <= kc) { trial_cnt[b] = 0ull; trial_sum[b] = 0ull; }
+    // (c) the block that draws the last ticket finishes the pass
+    __threadfence();                                   // this thread's additions are visible device-wide ...
+    __syncthreads();                                   // ... for every thread of the block, before its ticket is drawn
+    if (threadIdx.x == 0) {
+        const uint32_t ticket = atomicAdd(&status[2], 1u);
+        is_last = ticket == gridDim.x - 1u ? 1u : 0u;
     }
-    __threadfence_block();
     __syncthreads();
-    for (uint32_t j = tid; j < K; j += DC_FINAL_THREADS) {
-        const uint32_t p = pos[j];
-        if (p >= chunk0 && p < chunk0 + kc) {
-            out_step[j] = chunk_step[p - chunk0];
-            out_done[j] = chunk_done[p - chunk0];
-        }
-    }
+    if (!is_last) return;
+    __threadfence();
+    if (threadIdx.x == 0) status[2] = 0u;              // next pass (kernels on a stream run one after the other)
+    finalize_chunk<256>(f);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1467,27 +1498,25 @@ void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, u
     }
 }
 
+// One launch ends a pass: sums of the per-block histograms, binned trial maxima, then the chunk's results.
 void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long* hist_total,
                    const uint32_t* unit_max, const uint32_t* tau_chunk, uint32_t kc,
-                   unsigned long long* trial_cnt, unsigned long long* trial_sum, const uint32_t* status,
-                   hipStream_t stream) {
+                   unsigned long long* trial_cnt, unsigned long long* trial_sum, uint32_t* status, uint32_t chunk0,
+                   const int64_t* tau_sorted, const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done,
+                   int64_t* chunk_step, int64_t* chunk_done, hipStream_t stream) {
     const uint32_t col_blocks = (p.p2 + 63) / 64;
     const uint32_t slot_groups = (p.grid_wide + DC_REDUCE_SLOTS - 1) / DC_REDUCE_SLOTS;
     const uint32_t hist_blocks = col_blocks * slot_groups;
     const uint32_t trial_blocks = (p.T + 255) / 256;
-    hipLaunchKernelGGL(dc_reduce_kernel, dim3(hist_blocks + trial_blocks), dim3(256), (size_t)p.p2 * 12, stream, hist_part, p.grid,
-                       p.grid_wide, status, p.p2, col_blocks, hist_blocks, hist_total, unit_max, p.T, p.units_per_trial,
-                       tau_chunk, kc, trial_cnt, trial_sum);
-}
-
-void launch_finalize(const Plan& p, unsigned long long* hist_total, unsigned long long* trial_cnt,
-                     unsigned long long* trial_sum, uint32_t kc, uint32_t chunk0, const int64_t* tau_sorted,
-                     const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done, int64_t* chunk_step,
-                     int64_t* chunk_done, hipStream_t stream) {
-    hipLaunchKernelGGL(dc_finalize_kernel, dim3(1), dim3(DC_FINAL_THREADS), 0, stream, hist_total, trial_cnt,
-                       trial_sum, kc, p.p2, chunk0, tau_sorted, pos, p.K, (unsigned long long)p.T,
-                       (unsigned long long)p.elements, (long long)comm, (long long*)out_step, (long long*)out_done,
-                       (long long*)chunk_step, (long long*)chunk_done);
+    FinalArgs f;
+    f.hist_total = hist_total; f.trial_cnt = trial_cnt; f.trial_sum = trial_sum;
+    f.kc = kc; f.p2 = p.p2; f.chunk0 = chunk0; f.K = p.K;
+    f.tau_sorted = tau_sorted; f.pos = pos;
+    f.T = p.T; f.elements = p.elements; f.comm = (long long)comm;
+    f.out_step = (long long*)out_step; f.out_done = (long long*)out_done;
+    f.chunk_step = (long long*)chunk_step; f.chunk_done = (long long*)chunk_done;
+    hipLaunchKernelGGL(dc_reduce_kernel, dim3(hist_blocks + trial_blocks), dim3(256), (size_t)p.p2 * 12, stream, hist_part,
+                       p.grid, p.grid_wide, status, col_blocks, hist_blocks, unit_max, p.units_per_trial, tau_chunk, f);
 }
 
 template <int L>
