@@ -115,6 +115,7 @@ bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4
     p.elements = (uint64_t)T * (uint64_t)N * (uint64_t)M;
     p.vec4 = allow_vec4 && vec4_shape(M);
     p.grid = (uint32_t)(T < (int64_t)DC_MAX_TRIAL_BLOCKS ? T : DC_MAX_TRIAL_BLOCKS);
+    p.grid_wide = p.grid;
     if (p.vec4) {
         const uint32_t rows_per_load = 64u / (uint32_t)(M / 4);
         p.per_unit = M >= 128 ? (32u / rows_per_load < 16u ? 16u : 32u / rows_per_load) : 64u;   // as in make_plan
@@ -205,7 +206,7 @@ Resident resident_blocks(const dc::Plan& p, bool trial = false) {
     const int wanted = (int)wanted_blocks_per_cu(p);                                    // what streams best
     const int per_cu = fit > wanted ? wanted : fit;
     int wide_per_cu = per_cu;
-    if (!trial && p.vec4 && p.M >= 128 && per_cu < DC_DENSE_BLOCKS_PER_CU)
+    if (p.vec4 && p.M >= 128 && per_cu < DC_DENSE_BLOCKS_PER_CU)
         wide_per_cu = fit > DC_DENSE_BLOCKS_PER_CU ? DC_DENSE_BLOCKS_PER_CU : fit;
     g_resident.push_back({device, p.vec4, trial, variant_of(p), p.p2, cus * per_cu, cus * wide_per_cu});
     return {(uint32_t)(cus * per_cu), (uint32_t)(cus * wide_per_cu)};
@@ -282,8 +283,12 @@ int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* tau
                     const int64_t* comm_per_trial_dev, double* out_seff_dev, unsigned char* ws, hipStream_t stream,
                     bool timed) {
     dc::Plan p = plan;
-    const uint32_t resident = resident_blocks(p, true).blocks;
-    if (p.grid > resident) p.grid = resident;
+    const Resident resident = resident_blocks(p, true);
+    const uint32_t planned = p.grid;                            // the workspace was sized for this many blocks
+    p.grid_wide = planned < resident.wide_blocks ? planned : resident.wide_blocks;   // two launch shapes, as in enqueue()
+    if (p.grid > resident.blocks) p.grid = resident.blocks;
+    if (p.grid_wide < p.grid) p.grid_wide = p.grid;
+    const uint32_t sample_rows = p.grid_wide > p.grid ? DC_SAMPLE_ROWS : 0u;
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + p.off_status);
     int64_t* tau_sorted = reinterpret_cast<int64_t*>(ws + p.off_tau_sorted);
     uint32_t* tau_u32 = reinterpret_cast<uint32_t*>(ws + p.off_tau_u32);
@@ -297,14 +302,15 @@ int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* tau
         g_timing.valid = false;
         if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.begin, stream));
     }
-    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, nullptr, 0, nullptr, 0, 0, 0, stream);
+    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, nullptr, 0, lat, (uint64_t)p.T * p.N, p.M,
+                    sample_rows, stream);
     for (uint32_t c = 0; c < chunks; ++c) {
         const uint32_t chunk0 = c * p.chunk;
         const uint32_t kc = p.K - chunk0 < p.chunk ? p.K - chunk0 : p.chunk;
         if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c], stream));
         dc::launch_trial_scan(p, lat, tau_u32 + chunk0, kc, comm_per_trial_dev, comm, partial, status, stream);
         if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c + 1], stream));
-        dc::launch_speedup_finalize(p, partial, kc, chunk0, pos, out_seff_dev, stream);
+        dc::launch_speedup_finalize(p, partial, kc, chunk0, pos, status, out_seff_dev, stream);
     }
     if (timed) {
         if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.end, stream));

@@ -1142,13 +1142,14 @@ __device__ __forceinline__ void finish_trial(const GridView& g, const TrialShare
     __syncthreads();
 }
 
-template <int L>
+template <int L, int SHAPE>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_trial_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N,
                                const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
                                const long long* __restrict__ comm_per_trial, long long comm,
                                double* __restrict__ partial, uint32_t* __restrict__ status, uint32_t max_latency,
                                uint32_t lanes_per_row, uint32_t loads_per_unit) {
+    if (!launch_is_chosen<SHAPE>(status)) return;         // two launch shapes for long rows, as in dc_scan_vec4_kernel
     extern __shared__ __align__(16) unsigned char smem[];
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
     uint32_t* tables = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);
@@ -1249,10 +1250,13 @@ void dc_trial_scan_flat_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
 // thresholds; the range of blocks is cut into 8 fixed slices that are summed in order and then
 // combined in slice order, so the grouping of the float additions never changes between calls.
 __global__ __launch_bounds__(256)
-void dc_speedup_finalize_kernel(const double* __restrict__ partial, uint32_t blocks, uint32_t p2, uint32_t kc,
+void dc_speedup_finalize_kernel(const double* __restrict__ partial, uint32_t narrow_blocks, uint32_t wide_blocks,
+                                const uint32_t* __restrict__ status, uint32_t p2, uint32_t kc,
                                 uint32_t chunk0, const uint32_t* __restrict__ pos, uint32_t K, double trials,
                                 double* __restrict__ out_seff) {
     __shared__ double slice_sum[8][32];
+    // per-block sums were written by the launch of the per-trial kernel that the sample chose
+    const uint32_t blocks = wide_blocks > narrow_blocks && status[1] != 0u ? wide_blocks : narrow_blocks;
     const uint32_t jj = threadIdx.x & 31u, slice = threadIdx.x >> 5;
     const uint32_t j = blockIdx.x * 32 + jj;
     const uint32_t p = j < K ? pos[j] : 0xFFFFFFFFu;
@@ -1522,7 +1526,7 @@ void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long*
 template <int L>
 static int resident_trial_vec4(size_t lds) {
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_vec4_kernel<L>, DC_SCAN_THREADS, lds) != hipSuccess) n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_vec4_kernel<L, 0>, DC_SCAN_THREADS, lds) != hipSuccess) n = 0;
     return n;
 }
 
@@ -1558,7 +1562,19 @@ template <int L>
 static void launch_trial_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                               const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
                               hipStream_t stream) {
-    hipLaunchKernelGGL(dc_trial_scan_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS), trial_scan_lds_bytes(p),
+    if (p.grid_wide > p.grid) {                     // the sample decides on the device which of the two launches works
+        if constexpr (L == 32 || L == 64) {
+            hipLaunchKernelGGL((dc_trial_scan_vec4_kernel<L, 1>), dim3(p.grid), dim3(DC_SCAN_THREADS), trial_scan_lds_bytes(p),
+                               stream, lat, p.T, p.N, tau_chunk, kc, p.p2, (const long long*)comm_per_trial, (long long)comm,
+                               partial, status, p.max_latency, p.M / 4, p.per_unit);
+            hipLaunchKernelGGL((dc_trial_scan_vec4_kernel<L, 2>), dim3(p.grid_wide), dim3(DC_SCAN_THREADS),
+                               trial_scan_lds_bytes(p), stream, lat, p.T, p.N, tau_chunk, kc, p.p2,
+                               (const long long*)comm_per_trial, (long long)comm, partial, status, p.max_latency, p.M / 4,
+                               p.per_unit);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((dc_trial_scan_vec4_kernel<L, 0>), dim3(p.grid), dim3(DC_SCAN_THREADS), trial_scan_lds_bytes(p),
                        stream, lat, p.T, p.N, tau_chunk, kc, p.p2, (const long long*)comm_per_trial, (long long)comm,
                        partial, status, p.max_latency, p.M / 4, p.per_unit);
 }
@@ -1590,9 +1606,9 @@ void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_ch
 }
 
 void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, uint32_t chunk0, const uint32_t* pos,
-                             double* out_seff, hipStream_t stream) {
+                             const uint32_t* status, double* out_seff, hipStream_t stream) {
     hipLaunchKernelGGL(dc_speedup_finalize_kernel, dim3((p.K + 31) / 32), dim3(256), 0, stream, partial, p.grid,
-                       p.p2, kc, chunk0, pos, p.K, (double)p.T, out_seff);
+                       p.grid_wide, status, p.p2, kc, chunk0, pos, p.K, (double)p.T, out_seff);
 }
 
 __global__ void dc_clear_status_kernel(uint32_t* status) { *status = 0u; }

@@ -759,3 +759,26 @@ def test_graph_replay_picks_the_launch_shape_from_the_data(dev):
         ref_step, ref_done = oracle.simulate_threaded(lat, taus, r.comm, "sorted", host.cpu_threads())
         got = out.cpu().numpy()
         assert np.array_equal(got[0], ref_step) and np.array_equal(got[1], ref_done), factor
+
+
+def test_per_step_speedup_launch_shapes(dev):
+    """The per-iteration speedup of long rows over more trials than the narrow launch has blocks, with threshold
+    grids that cover almost nothing and almost everything (the two launch shapes): the result must equal the
+    trial-weighted combination of slabs small enough to take the single-shape path, and a slab must match the oracle."""
+    r = config("extrapolation2048").with_shape(T=900)
+    from dc_workloads import device
+    lat_d = device.generate(r)
+    top = int(lat_d.sum(dim=2, dtype=torch.int64).max().item())
+    grids = [np.linspace(top - top // 40, top, 48).astype(np.int64), np.linspace(1, top, 96).astype(np.int64),
+             np.linspace(top - top // 30, top + 3, 20).astype(np.int64)]
+    for taus in grids + grids[::-1]:
+        whole = dc.dc_speedup_per_step(lat_d, taus, r.comm)
+        parts = np.zeros(taus.size)
+        for t0 in range(0, r.T, 300):
+            parts += dc.dc_speedup_per_step(lat_d[t0:t0 + 300], taus, r.comm) * (300 / r.T)
+        assert np.allclose(whole, parts, rtol=1e-10, atol=0)
+        assert np.array_equal(whole, dc.dc_speedup_per_step(lat_d, taus, r.comm))     # same launch shape, same bits
+    lat = host.generate(r, 450, 454)
+    for taus in grids[:2]:
+        assert np.allclose(dc.dc_speedup_per_step(lat_d[450:454], taus[::4], r.comm),
+                           oracle.per_step_speedup(lat, taus[::4], r.comm), rtol=SPEEDUP_RTOL, atol=0)
