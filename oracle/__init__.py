@@ -9,8 +9,9 @@ package imports nothing of the GPU library.
       method="sorted" : same numbers via one walk over sorted thresholds (for large inputs)
   select_tau(step_sum, done_sum, taus, T, N, M, base_step_sum) -> (thr[K], s_eff[K], best_k)
       throughput N*M~/(min{tau,T}+T^c) and S_eff (Section 4.4), argmax (Algorithm 2, last line)
-  per_step_speedup(lat, taus, comm) -> S_eff[K] as the mean of per-iteration ratios S_i(tau)
-      (Algorithm 2 exactly as printed; float64)
+  per_step_speedup(lat, taus, comm) -> S_eff[K] as the mean over iterations of the per-iteration speedup
+      S_i(tau) (Section 4.4's ratio taken iteration by iteration, then averaged: Algorithm 2; float64)
+  per_step_best(s_eff, taus) -> index of the threshold with the largest S_eff (Algorithm 2, its final argmax)
 """
 from __future__ import annotations
 
@@ -58,9 +59,9 @@ def _load():
             fn = getattr(lib, name)
             fn.argtypes = sig
             fn.restype = ctypes.c_int
-        lib.dc_oracle_per_step_speedup.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
-                                                   ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
-        lib.dc_oracle_per_step_speedup.restype = ctypes.c_int
+        lib.dc_oracle_per_step_speedup_sums.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                                        ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        lib.dc_oracle_per_step_speedup_sums.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -125,10 +126,12 @@ def select_tau(step_sum, done_sum, taus, T: int, N: int, M: int, base_step_sum: 
     return thr, seff, best
 
 
-def per_step_speedup(lat: np.ndarray, taus, comm):
-    """Algorithm 2 as printed: S_i(tau) per iteration, then the mean over iterations (float64).
+def per_step_speedup(lat: np.ndarray, taus, comm, threads: int = 1):
+    """Mean over iterations of the per-iteration effective speedup S_i(tau) (Section 4.4 per iteration,
+    averaged as in Algorithm 2; float64).
 
-    comm may be a scalar or one value per iteration (T_i^c).
+    comm may be a scalar or one value per iteration (T_i^c).  threads > 1 splits the iterations into that many
+    contiguous runs whose sums are added in order (the float additions are then grouped by run).
     """
     lat = np.ascontiguousarray(lat, dtype=np.int32)
     if lat.ndim != 3:
@@ -136,12 +139,43 @@ def per_step_speedup(lat: np.ndarray, taus, comm):
     T, N, M = lat.shape
     taus = np.ascontiguousarray(taus, dtype=np.int64)
     comm = np.ascontiguousarray(np.broadcast_to(np.asarray(comm, dtype=np.int64), (T,)))
-    out = np.zeros(taus.size, dtype=np.float64)
-    fn = _load().dc_oracle_per_step_speedup
-    rc = fn(lat.ctypes.data, T, N, M, taus.ctypes.data, taus.size, comm.ctypes.data, out.ctypes.data)
-    if rc != OK:
-        raise OracleError(rc)
-    return out
+    fn = _load().dc_oracle_per_step_speedup_sums
+
+    def run(t0: int, t1: int) -> np.ndarray:
+        part, c, out = lat[t0:t1], comm[t0:t1], np.zeros(taus.size, dtype=np.float64)
+        rc = fn(part.ctypes.data, t1 - t0, N, M, taus.ctypes.data, taus.size, c.ctypes.data, out.ctypes.data)
+        if rc != OK:
+            raise OracleError(rc)
+        return out
+
+    threads = max(1, min(int(threads), T))
+    bounds = [T * i // threads for i in range(threads + 1)]
+    if threads == 1:
+        sums = [run(0, T)]
+    else:
+        with ThreadPoolExecutor(threads) as ex:
+            sums = list(ex.map(lambda i: run(bounds[i], bounds[i + 1]), range(threads)))
+    total = np.zeros(taus.size, dtype=np.float64)
+    for part in sums:
+        total += part
+    return total / float(T)
+
+
+def per_step_best(s_eff, taus) -> int:
+    """tau* = argmax_tau S_eff(tau), the last step of Algorithm 2, as an index into taus.
+
+    The paper does not say which of several equal maxima is meant; as in select_tau the largest tau wins
+    (fewest dropped micro-batches), then the lowest index.
+    """
+    s_eff = [float(x) for x in s_eff]
+    tau = [int(x) for x in taus]
+    if not tau or len(s_eff) != len(tau) or any(x != x for x in s_eff):
+        raise OracleError(ERR_INVALID_ARG)
+    best = 0
+    for k in range(1, len(tau)):
+        if s_eff[k] > s_eff[best] or (s_eff[k] == s_eff[best] and tau[k] > tau[best]):
+            best = k
+    return best
 
 
 # ---- analytical model (Sections 4.2-4.4, Appendix C.2) ---------------------------------------------------
@@ -220,7 +254,14 @@ def worker_moments(lat: np.ndarray):
     T, N, _ = lat.shape
     totals = lat.sum(axis=2)                                   # [T][N], each < 2^63
     sums = [int(x) for x in totals.sum(axis=0)]
-    squares = [sum(int(v) * int(v) for v in totals[:, n]) for n in range(N)]
+    if int(totals.max()) < (1 << 32) and T < (1 << 30):
+        # x^2 = hi^2 2^32 + 2 hi lo 2^16 + lo^2 with 16-bit halves: every column sum stays below 2^63, so the
+        # int64 sums are exact and the squares are assembled as Python ints
+        hi, lo = totals >> 16, totals & 0xFFFF
+        hh, hl, ll = (hi * hi).sum(axis=0), (hi * lo).sum(axis=0), (lo * lo).sum(axis=0)
+        squares = [(int(a) << 32) + (int(b) << 17) + int(c) for a, b, c in zip(hh, hl, ll)]
+    else:
+        squares = [sum(int(v) * int(v) for v in totals[:, n]) for n in range(N)]
     mean = np.array([s / T for s in sums], dtype=np.float64)
     var = np.array([(q * T - s * s) / (T * T) for s, q in zip(sums, squares)], dtype=np.float64)
     return sums, squares, mean, var

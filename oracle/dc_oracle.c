@@ -2,17 +2,19 @@
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the checker the GPU library is compared
  * against; the library never links, loads or calls it.  It shares no code with the HIP
- * path and is written directly from the paper:
+ * path and is written from the paper's definitions:
  *
  *   - completion time of micro-batch m on worker n: T_n^(m) = sum_{j<=m} t_n^(j)   (Section 4.3)
  *   - a micro-batch counts as completed iff T_n^(m) < tau (strict)                 (Section 4.3, M~ definition;
- *                                                                                    Algorithm 2 inner loop)
+ *                                                                                    Algorithm 2, Appendix C.1)
  *   - compute time of an iteration: T = max_n T_n^(M)                              (Section 4.2)
  *   - iteration time under a threshold: min{tau, T} + T^c                          (Section 4.3)
+ *   - effective speedup of one iteration, S = M~ (T + T^c) / (M (min{tau,T} + T^c)) (Section 4.4, eq:auto_eff)
  *   - reduction over iterations and choice of tau                                  (Appendix C.1, Algorithm 2)
  *
- * Everything is int64 integer arithmetic on integer-microsecond latencies, so results are
- * exact and independent of summation order.  Outputs are un-normalised sums over trials:
+ * Counts, completion times and step times are int64 integer arithmetic on integer-microsecond
+ * latencies, so they are exact and independent of summation order.  Integer outputs are
+ * un-normalised sums over trials:
  *   step_sum[k] = sum_i ( min(tau_k, T_i) + comm )
  *   done_sum[k] = sum_i sum_n #{ m : T_{i,n}^(m) < tau_k }       ( = N * sum_i M~_i(tau_k) )
  *
@@ -37,35 +39,46 @@ static int has_negative(const int32_t* lat, int64_t count) {
     return 0;
 }
 
-/* The definition, loop for loop: thresholds, iterations, workers, micro-batches
- * (Appendix C.1, Algorithm 2), with the per-iteration quantities kept as integers. */
+/* Completion times T_n^(m), m = 1..M, of one worker in one iteration (Section 4.3); returns T_n = T_n^(M). */
+static int64_t completion_times(const int32_t* t, int64_t M, int64_t* out) {
+    int64_t elapsed = 0;
+    for (int64_t m = 0; m < M; ++m) {
+        elapsed += t[m];
+        out[m] = elapsed;
+    }
+    return elapsed;
+}
+
+/* How many of a worker's completion times lie strictly below tau (Section 4.3, the indicator inside M~). */
+static int64_t completed_below(const int64_t* done_at, int64_t M, int64_t tau) {
+    int64_t count = 0;
+    for (int64_t m = 0; m < M; ++m) count += done_at[m] < tau;
+    return count;
+}
+
+/* The definition, every (iteration, worker, micro-batch, threshold) combination evaluated: O(K*T*N*M).
+ * Per iteration: every worker's completion times, the count of those below each threshold summed over the
+ * workers (N * M~(tau), Section 4.3), the slowest worker's total (Section 4.2), and the step time
+ * min{tau, T} + T^c (Section 4.3). */
 int dc_oracle_simulate_literal(const int32_t* lat, int64_t T, int64_t N, int64_t M,
                                const int64_t* taus, int64_t K, int64_t comm,
                                int64_t* step_sum, int64_t* done_sum) {
     int rc = check_args(lat, T, N, M, taus, K, comm, step_sum, done_sum);
     if (rc) return rc;
     if (has_negative(lat, T * N * M)) return DCO_ERR_NEGATIVE_LATENCY;
-    for (int64_t k = 0; k < K; ++k) {
-        const int64_t tau = taus[k];
-        int64_t steps = 0, done = 0;
-        for (int64_t i = 0; i < T; ++i) {
-            int64_t completed = 0;          /* N * M~_i(tau) */
-            int64_t slowest = 0;            /* T_i */
-            for (int64_t n = 0; n < N; ++n) {
-                const int32_t* t = lat + (i * N + n) * M;
-                int64_t elapsed = 0;        /* T_{i,n} */
-                for (int64_t m = 0; m < M; ++m) {
-                    elapsed += t[m];
-                    if (elapsed < tau) completed += 1;
-                }
-                if (elapsed > slowest) slowest = elapsed;
-            }
-            steps += (tau < slowest ? tau : slowest) + comm;
-            done += completed;
+    int64_t* done_at = (int64_t*)malloc((size_t)M * sizeof(int64_t));
+    if (!done_at) return DCO_ERR_INVALID_ARG;
+    for (int64_t k = 0; k < K; ++k) step_sum[k] = done_sum[k] = 0;
+    for (int64_t i = 0; i < T; ++i) {
+        int64_t slowest = 0;                                        /* T = max_n T_n */
+        for (int64_t n = 0; n < N; ++n) {
+            const int64_t total = completion_times(lat + (i * N + n) * M, M, done_at);
+            if (total > slowest) slowest = total;
+            for (int64_t k = 0; k < K; ++k) done_sum[k] += completed_below(done_at, M, taus[k]);
         }
-        step_sum[k] = steps;
-        done_sum[k] = done;
+        for (int64_t k = 0; k < K; ++k) step_sum[k] += (taus[k] < slowest ? taus[k] : slowest) + comm;
     }
+    free(done_at);
     return DCO_OK;
 }
 
@@ -120,37 +133,38 @@ int dc_oracle_simulate_sorted(const int32_t* lat, int64_t T, int64_t N, int64_t 
     return DCO_OK;
 }
 
-/* Algorithm 2 exactly as printed (Appendix C.1): for every threshold, the effective speedup of each
- * iteration, S_i(tau) = (T_i + T_i^c) / (min(tau, T_i) + T_i^c) * M~_i(tau) / M, with M~_i(tau) built up in
- * steps of 1/N, then the mean over the I iterations.  comm[i] is T_i^c (one value per iteration).
- * float64 throughout, as a direct reading of the listing's real-valued quantities.
+/* Effective speedup per iteration, summed over the iterations given (Section 4.4, eq:auto_eff, applied to each
+ * iteration as Algorithm 2 of Appendix C.1 does; the caller divides by the number of iterations for the mean):
+ *   S_i(tau) = M~_i(tau) (T_i + T_i^c) / (M (min{tau, T_i} + T_i^c)),
+ *   M~_i(tau) = (1/N) sum_n #{ m : T_{i,n}^(m) < tau }          (Section 4.3),   T_i = max_n T_{i,n}   (Section 4.2).
+ * The count is an exact integer, divided once; the ratio and the sum over iterations are float64, iterations
+ * added in order.  comm[i] is T_i^c (one value per iteration).
  * Returns DCO_ERR_INVALID_ARG if some iteration has min(tau, T_i) + T_i^c = 0 (the ratio is undefined). */
-int dc_oracle_per_step_speedup(const int32_t* lat, int64_t T, int64_t N, int64_t M,
-                               const int64_t* taus, int64_t K, const int64_t* comm, double* s_eff) {
-    if (T < 1 || N < 1 || M < 1 || K < 0 || !lat || !comm || (K > 0 && (!taus || !s_eff))) return DCO_ERR_INVALID_ARG;
+int dc_oracle_per_step_speedup_sums(const int32_t* lat, int64_t T, int64_t N, int64_t M,
+                                    const int64_t* taus, int64_t K, const int64_t* comm, double* s_sum) {
+    if (T < 1 || N < 1 || M < 1 || K < 0 || !lat || !comm || (K > 0 && (!taus || !s_sum))) return DCO_ERR_INVALID_ARG;
     for (int64_t k = 0; k < K; ++k) if (taus[k] < 0) return DCO_ERR_INVALID_ARG;
     for (int64_t i = 0; i < T; ++i) if (comm[i] < 0) return DCO_ERR_INVALID_ARG;
     if (has_negative(lat, T * N * M)) return DCO_ERR_NEGATIVE_LATENCY;
-    for (int64_t k = 0; k < K; ++k) {
-        const int64_t tau = taus[k];
-        double total = 0.0;
-        for (int64_t i = 0; i < T; ++i) {
-            double completed = 0.0;         /* M~_i(tau) */
-            int64_t slowest = 0;            /* T_i */
-            for (int64_t n = 0; n < N; ++n) {
-                const int32_t* t = lat + (i * N + n) * M;
-                int64_t elapsed = 0;        /* T_{i,n} */
-                for (int64_t m = 0; m < M; ++m) {
-                    elapsed += t[m];
-                    if (elapsed < tau) completed += 1.0 / (double)N;
-                }
-                if (elapsed > slowest) slowest = elapsed;
-            }
-            const int64_t capped = tau < slowest ? tau : slowest;
-            if (capped + comm[i] == 0) return DCO_ERR_INVALID_ARG;
-            total += (double)(slowest + comm[i]) / (double)(capped + comm[i]) * completed / (double)M;
+    int64_t* done_at = (int64_t*)malloc((size_t)(N * M) * sizeof(int64_t));      /* one iteration's completion times */
+    if (!done_at) return DCO_ERR_INVALID_ARG;
+    for (int64_t k = 0; k < K; ++k) s_sum[k] = 0.0;
+    int status = DCO_OK;
+    for (int64_t i = 0; i < T && status == DCO_OK; ++i) {
+        int64_t slowest = 0;
+        for (int64_t n = 0; n < N; ++n) {
+            const int64_t total = completion_times(lat + (i * N + n) * M, M, done_at + n * M);
+            if (total > slowest) slowest = total;
         }
-        s_eff[k] = total / (double)T;
+        for (int64_t k = 0; k < K; ++k) {
+            const int64_t tau = taus[k];
+            const int64_t step = (tau < slowest ? tau : slowest) + comm[i];
+            if (step == 0) { status = DCO_ERR_INVALID_ARG; break; }
+            const int64_t completed = completed_below(done_at, N * M, tau);      /* N * M~_i(tau) */
+            const double m_tilde = (double)completed / (double)N;
+            s_sum[k] += m_tilde * (double)(slowest + comm[i]) / ((double)M * (double)step);
+        }
     }
-    return DCO_OK;
+    free(done_at);
+    return status;
 }

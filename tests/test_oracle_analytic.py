@@ -63,6 +63,35 @@ def test_speedup_estimate_identities():
         oracle.analytic_curves(mu, s2, 1, M, taus, comm)                                # the estimate needs N >= 2
 
 
+def test_analytic_best_threshold_worked_by_hand():
+    """Appendix C.2, "Finding tau*": tau* = argmax (1/(tau + T^c)) sum_m Phi((tau - m mu)/sqrt(m sigma^2)).
+
+    One micro-batch per worker (M = 1), mu = 100, sigma = 10, so the sum is one normal CDF at a whole number of
+    standard deviations; Phi(0), Phi(2), Phi(3) from a table: 0.5, 0.97725, 0.99865.
+      T^c = 0:     tau 100: 0.5/100 = 0.00500   tau 120: 0.97725/120 = 0.008144   tau 130: 0.99865/130 = 0.007682
+      T^c = 1000:  tau 100: 0.5/1100 = 0.000455 tau 120: 0.97725/1120 = 0.000873  tau 130: 0.99865/1130 = 0.000884
+    A long serial part moves the best threshold up: with T^c = 0 it is 120, with T^c = 1000 it is 130."""
+    taus = [100, 120, 130]
+    e_done, _, _, best = oracle.analytic_curves(100.0, 100.0, 4, 1, taus, 0)
+    assert np.allclose(e_done, [0.5, 0.97725, 0.99865], atol=5e-6) and best == 1
+    assert oracle.analytic_curves(100.0, 100.0, 4, 1, taus, 1000)[3] == 2
+    assert oracle.analytic_curves(100.0, 100.0, 4, 1, [130, 100, 120], 0)[3] == 2        # any order of the list
+    assert oracle.analytic_curves(100.0, 100.0, 4, 1, taus, 0, mean_tmax=105.0)[3] == 1  # no estimate of T enters
+    assert oracle.analytic_curves(100.0, 100.0, 4, 1, [120, 100, 120], 0)[3] == 0        # equal thresholds: lowest index
+    # deterministic latencies of 10 with M = 3 (sigma = 0): completed = #{m : 10 m < tau}; T^c = 5
+    #   tau 10: 0/15   tau 11: 1/16 = 0.0625   tau 21: 2/26 = 0.0769   tau 31: 3/36 = 0.0833   tau 60: 3/65 = 0.046
+    assert oracle.analytic_curves(10.0, 0.0, 2, 3, [10, 11, 21, 31, 60], 5)[3] == 3
+
+
+def test_worker_moments_squares_against_python_integers():
+    rng = np.random.default_rng(8)
+    lat = rng.integers(0, (2**31 - 1) // 4, size=(300, 5, 4), dtype=np.int32)              # totals up to 2^31
+    sums, squares, _, _ = oracle.worker_moments(lat)
+    for n in range(5):
+        totals = [sum(int(v) for v in lat[t, n]) for t in range(300)]
+        assert sums[n] == sum(totals) and squares[n] == sum(v * v for v in totals)
+
+
 def test_estimates_track_the_simulation_for_normal_latencies():
     """Normal samples: the analytical S_eff follows the simulated one (the paper's Figure 3a claim)."""
     T, N, M, mu, sigma, comm = 3000, 64, 32, 100000.0, 10000.0, 30000

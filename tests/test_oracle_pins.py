@@ -277,6 +277,40 @@ def test_per_step_speedup_pins():
         oracle.per_step_speedup(np.zeros((1, 1, 2), dtype=np.int32), [5], 0)      # 0/0 step time
 
 
+def test_per_step_best_on_hand_worked_values(golden_dir):
+    """The final argmax of Algorithm 2 on speedups worked by hand from Section 4.4's ratio.
+
+    One iteration, two workers with completion times {4, 8} and {5, 10}, T = 10, T^c = 2, N*M = 4:
+      tau  completed  S = completed/4 * (10 + 2)/(min(tau, 10) + 2)
+        5      1      1/4 * 12/7  = 3/7   ~ 0.4286
+        6      2      2/4 * 12/8  = 3/4
+        9      3      3/4 * 12/11 = 9/11  ~ 0.8182      <- largest
+       10      3      3/4 * 12/12 = 3/4                  (10 is not < 10)
+       11      4      1
+       50      4      1
+    so S_eff peaks at 1 for tau = 11 and tau = 50: the tie goes to the larger threshold."""
+    lat = np.array([[[4, 4], [5, 5]]], dtype=np.int32)
+    taus = [5, 6, 9, 10, 11, 50]
+    s = oracle.per_step_speedup(lat, taus, 2)
+    assert np.allclose(s, [3 / 7, 3 / 4, 9 / 11, 3 / 4, 1.0, 1.0], rtol=1e-15)
+    assert oracle.per_step_best(s, taus) == 5
+    assert oracle.per_step_best(s[:4], taus[:4]) == 2                     # without the no-drop thresholds: tau = 9
+    assert oracle.per_step_best(s[[5, 4, 2]], [50, 11, 9]) == 0           # any order of the list
+    assert oracle.per_step_best([0.5, 0.7, 0.7, 0.2], [10, 30, 30, 40]) == 1    # equal tau too: the lowest index
+    # two iterations: the mean of the two ratios, not the ratio of the means.  Second iteration: completion
+    # times {1, 2} and {12, 20}, T = 20; at tau = 9: 2 completed, S = 2/4 * 22/11 = 1; mean (9/11 + 1)/2 = 10/11
+    two = np.array([[[4, 4], [5, 5]], [[1, 1], [12, 8]]], dtype=np.int32)
+    s2 = oracle.per_step_speedup(two, [9, 50], 2)
+    assert np.allclose(s2, [10 / 11, 1.0], rtol=1e-15)
+    assert oracle.per_step_best(s2, [9, 50]) == 1
+    step, done = oracle.simulate(two, [9, 50], 2, "literal")             # ratio of means: 5/8 * (30+4)/(18+4) = 85/88
+    _, ratio_of_means, _ = oracle.select_tau(step, done, [9, 50], 2, 2, 2, int(step[1]))
+    assert ratio_of_means[0] == pytest.approx(85 / 88, rel=1e-15) and s2[0] < 0.95 < ratio_of_means[0]
+    with pytest.raises(oracle.OracleError):
+        oracle.per_step_best([], [])
+    assert np.allclose(oracle.per_step_speedup(two, [9, 50], 2, threads=2), s2, rtol=1e-15)
+
+
 # --- error behaviour ------------------------------------------------------------------------
 
 @pytest.mark.parametrize("method", METHODS)
