@@ -82,6 +82,26 @@ int dc_simulate_async(const int32_t* lat, int64_t T, int64_t N, int64_t M,
                       int64_t* out_step_dev, int64_t* out_done_dev,
                       void* workspace_dev, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or carry a workspace around (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): dc_simulate_async with the workspace
+ * replaced by a fixed array of DC_STATIC_SCRATCH_BYTES that is part of the library's device code (one per
+ * GPU, held until the process ends).  The call allocates nothing, on the device or on the host, and never
+ * synchronises.  lat, taus_dev, out_step_dev, out_done_dev, stream: as for dc_simulate_async.
+ * out_status_dev: DEVICE, one int32, may be NULL; when the work has finished on the stream it holds the
+ * dc_status of the value checks made on the device (DC_OK, DC_ERR_INVALID_ARG for a negative threshold,
+ * DC_ERR_NEGATIVE_LATENCY, DC_ERR_RANGE).
+ * Sizes whose workspace (dc_workspace_bytes) exceeds DC_STATIC_SCRATCH_BYTES are refused with
+ * DC_ERR_INVALID_ARG before anything is enqueued (dc_last_device_error says how much was needed); the five
+ * workloads of the benchmark need up to 12.1 MB, and a pass with 4095 thresholds needs 33 MB and is refused.
+ * Every call on one GPU uses that GPU's array and starts by clearing what it needs cleared: calls on one GPU
+ * whose work overlaps in time (two streams, or two threads) race on it and give wrong results; calls that
+ * follow one another on a stream are fine.  The first call on a device looks up the array's address, which
+ * must not happen while a stream is being captured: call once eagerly before capturing. */
+#define DC_STATIC_SCRATCH_BYTES (16u << 20)
+int dc_simulate_static(const int32_t* lat, int64_t T, int64_t N, int64_t M,
+                       const int64_t* taus_dev, int64_t K, int64_t comm,
+                       int64_t* out_step_dev, int64_t* out_done_dev, int32_t* out_status_dev, void* stream);
+
 /* Waits for `stream` and returns the dc_status that the last dc_simulate_async using
  * workspace_dev recorded on the device (DC_OK, DC_ERR_INVALID_ARG for a negative threshold,
  * DC_ERR_NEGATIVE_LATENCY, DC_ERR_RANGE) or DC_ERR_DEVICE if the stream reports an error. */

@@ -20,7 +20,7 @@ DC_OK, DC_ERR_INVALID_ARG, DC_ERR_NEGATIVE_LATENCY, DC_ERR_RANGE, DC_ERR_DEVICE,
 DC_MAX_THRESHOLDS = 65536
 
 EXPORTS = (
-    "dc_simulate", "dc_workspace_bytes", "dc_simulate_async", "dc_workspace_status", "dc_select_tau",
+    "dc_simulate", "dc_workspace_bytes", "dc_simulate_async", "dc_simulate_static", "dc_workspace_status", "dc_select_tau",
     "dc_speedup_per_step", "dc_speedup_workspace_bytes", "dc_speedup_per_step_async",
     "dc_moments", "dc_worker_moments", "dc_analytic_curves",
     "dc_set_kernel_timing", "dc_last_kernel_ms", "dc_status_string", "dc_last_device_error", "dc_shutdown",
@@ -54,6 +54,8 @@ def _load():
     lib.dc_workspace_bytes.restype = sz
     lib.dc_simulate_async.argtypes = [p, i64, i64, i64, p, i64, i64, p, p, p, sz, p]
     lib.dc_simulate_async.restype = ctypes.c_int
+    lib.dc_simulate_static.argtypes = [p, i64, i64, i64, p, i64, i64, p, p, p, p]
+    lib.dc_simulate_static.restype = ctypes.c_int
     lib.dc_workspace_status.argtypes = [p, p]
     lib.dc_workspace_status.restype = ctypes.c_int
     lib.dc_select_tau.argtypes = [p, p, p, i64, i64, i64, i64, i64, p, p, p]
@@ -140,6 +142,28 @@ def dc_simulate_async(lat, taus_dev, comm: int, out_step_dev, out_done_dev, work
                                    out_step_dev.data_ptr(), out_done_dev.data_ptr(),
                                    workspace.data_ptr(), workspace.numel(), handle)
     _check(rc, "dc_simulate_async")
+
+
+DC_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def dc_simulate_static(lat, taus_dev, comm: int, out_step_dev, out_done_dev, status_dev=None, stream=None) -> None:
+    """dc_simulate_async without a workspace: the library's fixed device array serves instead (nothing is allocated)."""
+    lat = _device_tensor(lat, "int32", "lat")
+    if lat.dim() != 3:
+        raise TypeError("lat must have shape [T][N][M]")
+    T, N, M = lat.shape
+    taus_dev = _device_tensor(taus_dev, "int64", "taus_dev")
+    K = taus_dev.numel()
+    out_step_dev = _device_tensor(out_step_dev, "int64", "out_step_dev")
+    out_done_dev = _device_tensor(out_done_dev, "int64", "out_done_dev")
+    if out_step_dev.numel() < K or out_done_dev.numel() < K:
+        raise ValueError("output tensors are shorter than the threshold list")
+    status_ptr = None if status_dev is None else _device_tensor(status_dev, "int32", "status_dev").data_ptr()
+    handle = 0 if stream is None else int(stream.cuda_stream)
+    rc = _load().dc_simulate_static(lat.data_ptr(), T, N, M, taus_dev.data_ptr(), K, int(comm),
+                                    out_step_dev.data_ptr(), out_done_dev.data_ptr(), status_ptr, handle)
+    _check(rc, "dc_simulate_static")
 
 
 def dc_workspace_status(workspace, stream=None) -> int:

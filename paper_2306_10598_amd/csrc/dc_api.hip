@@ -166,7 +166,9 @@ int ensure_events(size_t pairs) {
 // block that waits for a free slot would run alone at the end), and the same number of blocks must
 // sit on every compute unit.  Queried once per (device, kernel variant, LDS size).
 struct ResidentKey { int device; bool vec4; bool trial; uint32_t M; uint32_t p2; int blocks; int wide_blocks; };
-std::vector<ResidentKey> g_resident;
+constexpr size_t RESIDENT_SLOTS = 64;         // a fixed table: the enqueue path never touches the host heap
+ResidentKey g_resident[RESIDENT_SLOTS];
+size_t g_resident_used = 0, g_resident_next = 0;
 
 // Blocks per compute unit that stream best (measured on MI355X with 8 loads in flight per lane): long
 // rows have few completion times inside the threshold grid and want few, fat waves; short rows put a
@@ -196,9 +198,11 @@ struct Resident {
 Resident resident_blocks(const dc::Plan& p, bool trial = false) {
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return {DC_MAX_SCAN_BLOCKS, DC_MAX_SCAN_BLOCKS};
-    for (const ResidentKey& k : g_resident)
+    for (size_t i = 0; i < g_resident_used; ++i) {
+        const ResidentKey& k = g_resident[i];
         if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == variant_of(p) && k.p2 == p.p2)
             return {(uint32_t)k.blocks, (uint32_t)k.wide_blocks};
+    }
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1) cus = 256;
     int fit = trial ? dc::trial_scan_blocks_per_cu(p) : dc::scan_blocks_per_cu(p);      // what fits
@@ -208,7 +212,9 @@ Resident resident_blocks(const dc::Plan& p, bool trial = false) {
     int wide_per_cu = per_cu;
     if (p.vec4 && p.M >= 128 && per_cu < DC_DENSE_BLOCKS_PER_CU)
         wide_per_cu = fit > DC_DENSE_BLOCKS_PER_CU ? DC_DENSE_BLOCKS_PER_CU : fit;
-    g_resident.push_back({device, p.vec4, trial, variant_of(p), p.p2, cus * per_cu, cus * wide_per_cu});
+    g_resident[g_resident_next] = {device, p.vec4, trial, variant_of(p), p.p2, cus * per_cu, cus * wide_per_cu};
+    g_resident_next = (g_resident_next + 1) % RESIDENT_SLOTS;          // when full, the oldest entry is replaced
+    if (g_resident_used < RESIDENT_SLOTS) ++g_resident_used;
     return {(uint32_t)(cus * per_cu), (uint32_t)(cus * wide_per_cu)};
 }
 
@@ -352,6 +358,32 @@ int ensure_cache(size_t need) {
     return DC_OK;
 }
 
+// ---- device memory for the entry point that allocates nothing ---------------------------------------
+// One array per GPU, part of the loaded code object and held until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the address it returns (looked up once per device,
+// with that device current) is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[DC_STATIC_SCRATCH_BYTES];
+constexpr int SCRATCH_DEVICES = 64;
+unsigned char* g_scratch_ptr[SCRATCH_DEVICES] = {};        // guarded by g_mutex
+
+int scratch_pointer(unsigned char** out) {
+    int device = 0;
+    DC_HIP(hipGetDevice(&device));
+    if (device < 0 || device >= SCRATCH_DEVICES) return DC_ERR_INVALID_ARG;
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return device_error(e, "hipGetSymbolAddress(scratch)");
+        if (!ptr || ((uintptr_t)ptr & 255u)) {
+            snprintf(g_error_text, sizeof(g_error_text), "hipGetSymbolAddress(scratch): unusable address %p", ptr);
+            return DC_ERR_DEVICE;
+        }
+        g_scratch_ptr[device] = static_cast<unsigned char*>(ptr);
+    }
+    *out = g_scratch_ptr[device];
+    return DC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -377,6 +409,33 @@ int dc_simulate_async(const int32_t* lat, int64_t T, int64_t N, int64_t M, const
     std::lock_guard<std::mutex> lock(g_mutex);
     return enqueue(p, lat, taus_dev, comm, out_step_dev, out_done_dev, static_cast<unsigned char*>(workspace_dev),
                    static_cast<hipStream_t>(stream), g_timing.enabled);
+}
+
+int dc_simulate_static(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus_dev, int64_t K,
+                       int64_t comm, int64_t* out_step_dev, int64_t* out_done_dev, int32_t* out_status_dev,
+                       void* stream) {
+    if (!sizes_ok(T, N, M, K, comm) || !lat) return DC_ERR_INVALID_ARG;
+    if (K == 0) return DC_OK;
+    if (!taus_dev || !out_step_dev || !out_done_dev || ((uintptr_t)lat & 3u)) return DC_ERR_INVALID_ARG;
+    dc::Plan p{};
+    if (!make_plan(T, N, M, K, ((uintptr_t)lat & 15u) == 0, &p)) return DC_ERR_INVALID_ARG;
+    if (p.bytes > (size_t)DC_STATIC_SCRATCH_BYTES) {
+        snprintf(g_error_text, sizeof(g_error_text), "dc_simulate_static: these sizes need %zu bytes of scratch, the limit is %u",
+                 p.bytes, (unsigned)DC_STATIC_SCRATCH_BYTES);
+        return DC_ERR_INVALID_ARG;
+    }
+    std::lock_guard<std::mutex> lock(g_mutex);
+    unsigned char* ws = nullptr;
+    int rc = scratch_pointer(&ws);
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = enqueue(p, lat, taus_dev, comm, out_step_dev, out_done_dev, ws, s, false);
+    if (rc) return rc;
+    if (out_status_dev) {
+        dc::launch_export_status(reinterpret_cast<const uint32_t*>(ws + p.off_status), out_status_dev, s);
+        DC_HIP(hipGetLastError());
+    }
+    return DC_OK;
 }
 
 int dc_workspace_status(const void* workspace_dev, void* stream) {

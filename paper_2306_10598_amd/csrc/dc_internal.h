@@ -94,6 +94,7 @@ void launch_moments(const int32_t* lat, uint64_t n, uint32_t grid, unsigned long
                     unsigned long long* result, uint32_t* status, hipStream_t stream);
 void launch_expected_done(const int64_t* taus, uint32_t K, uint32_t M, double mu, double sigma2, double* out,
                           hipStream_t stream);
+void launch_export_status(const uint32_t* status, int32_t* out, hipStream_t stream);
 size_t scan_lds_bytes(const Plan& p);
 int scan_blocks_per_cu(const Plan& p);
 int trial_scan_blocks_per_cu(const Plan& p);

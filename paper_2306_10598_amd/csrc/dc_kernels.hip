@@ -1613,6 +1613,20 @@ void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, 
 
 __global__ void dc_clear_status_kernel(uint32_t* status) { *status = 0u; }
 
+// The value flags of a finished call as a dc_status code, for callers that cannot read the workspace.
+__global__ void dc_export_status_kernel(const uint32_t* __restrict__ status, int32_t* __restrict__ out) {
+    const uint32_t flags = status[0];
+    int32_t code = 0;                                                            // DC_OK
+    if (flags & (DC_FLAG_NEGATIVE_TAU | DC_FLAG_ZERO_STEP)) code = 1;            // DC_ERR_INVALID_ARG
+    else if (flags & DC_FLAG_NEGATIVE_LATENCY) code = 2;                         // DC_ERR_NEGATIVE_LATENCY
+    else if (flags & DC_FLAG_RANGE) code = 3;                                    // DC_ERR_RANGE
+    *out = code;
+}
+
+void launch_export_status(const uint32_t* status, int32_t* out, hipStream_t stream) {
+    hipLaunchKernelGGL(dc_export_status_kernel, dim3(1), dim3(1), 0, stream, status, out);
+}
+
 template <int L>
 static void launch_worker_vec4(const Plan& p, const int32_t* lat, unsigned long long* partial, uint32_t* status,
                                hipStream_t stream) {
