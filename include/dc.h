@@ -139,6 +139,13 @@ int dc_speedup_per_step(const int32_t* lat, int64_t T, int64_t N, int64_t M,
                         const int64_t* taus, int64_t K, int64_t comm, const int64_t* comm_per_trial,
                         double* out_seff);
 
+/* The best threshold under Algorithm 2's own convention (Appendix C.1, last line): tau* = argmax_tau S_eff(tau)
+ * with S_eff the mean of per-iteration speedups, i.e. dc_speedup_per_step's output.  HOST only, no GPU work.
+ * seff, taus: HOST, K values each (same order).  *out_best_k = index of the largest seff; among equal values the
+ * largest tau wins (fewest dropped micro-batches: every threshold above all worker totals gives exactly 1), then
+ * the lowest index, the same rule as dc_select_tau.  K >= 1, no NaN, taus >= 0, else DC_ERR_INVALID_ARG. */
+int dc_select_tau_per_step(const double* seff, const int64_t* taus, int64_t K, int64_t* out_best_k);
+
 /* Bytes of DEVICE workspace that dc_speedup_per_step_async needs (0 if the sizes are invalid). */
 size_t dc_speedup_workspace_bytes(int64_t T, int64_t N, int64_t M, int64_t K);
 

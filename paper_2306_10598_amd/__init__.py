@@ -21,7 +21,7 @@ DC_MAX_THRESHOLDS = 65536
 
 EXPORTS = (
     "dc_simulate", "dc_workspace_bytes", "dc_simulate_async", "dc_simulate_static", "dc_workspace_status", "dc_select_tau",
-    "dc_speedup_per_step", "dc_speedup_workspace_bytes", "dc_speedup_per_step_async",
+    "dc_speedup_per_step", "dc_speedup_workspace_bytes", "dc_speedup_per_step_async", "dc_select_tau_per_step",
     "dc_moments", "dc_worker_moments", "dc_analytic_curves",
     "dc_set_kernel_timing", "dc_last_kernel_ms", "dc_status_string", "dc_last_device_error", "dc_shutdown",
 )
@@ -60,6 +60,8 @@ def _load():
     lib.dc_workspace_status.restype = ctypes.c_int
     lib.dc_select_tau.argtypes = [p, p, p, i64, i64, i64, i64, i64, p, p, p]
     lib.dc_select_tau.restype = ctypes.c_int
+    lib.dc_select_tau_per_step.argtypes = [p, p, i64, p]
+    lib.dc_select_tau_per_step.restype = ctypes.c_int
     lib.dc_speedup_per_step.argtypes = [p, i64, i64, i64, p, i64, i64, p, p]
     lib.dc_speedup_per_step.restype = ctypes.c_int
     lib.dc_speedup_workspace_bytes.argtypes = [i64, i64, i64, i64]
@@ -188,6 +190,18 @@ def dc_select_tau(step_sum, done_sum, taus, T: int, N: int, M: int, base_step_su
                                int(base_step_sum), thr.ctypes.data, seff.ctypes.data, ctypes.byref(best))
     _check(rc, "dc_select_tau")
     return thr, seff, int(best.value)
+
+
+def dc_select_tau_per_step(seff, taus) -> int:
+    """Index of the best threshold for dc_speedup_per_step's output (Algorithm 2's final argmax); host only."""
+    seff = np.ascontiguousarray(seff, dtype=np.float64)
+    taus = np.ascontiguousarray(taus, dtype=np.int64)
+    if seff.size != taus.size:
+        raise ValueError("seff and taus must have the same length")
+    best = ctypes.c_int64(-1)
+    _check(_load().dc_select_tau_per_step(seff.ctypes.data, taus.ctypes.data, taus.size, ctypes.byref(best)),
+           "dc_select_tau_per_step")
+    return int(best.value)
 
 
 def dc_speedup_workspace_bytes(T: int, N: int, M: int, K: int) -> int:

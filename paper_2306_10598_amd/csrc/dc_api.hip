@@ -316,7 +316,7 @@ int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* tau
         if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c], stream));
         dc::launch_trial_scan(p, lat, tau_u32 + chunk0, kc, comm_per_trial_dev, comm, partial, status, stream);
         if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c + 1], stream));
-        dc::launch_speedup_finalize(p, partial, kc, chunk0, pos, status, out_seff_dev, stream);
+        dc::launch_speedup_finalize(p, partial, kc, chunk0, pos, status, tau_sorted, out_seff_dev, stream);
     }
     if (timed) {
         if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.end, stream));
@@ -726,6 +726,17 @@ int dc_select_tau(const int64_t* step_sum, const int64_t* done_sum, const int64_
         const unsigned __int128 rhs = (unsigned __int128)(uint64_t)done_sum[best] * (uint64_t)step_sum[k];
         if (lhs > rhs || (lhs == rhs && taus[k] > taus[best])) best = k;
     }
+    *out_best_k = best;
+    return DC_OK;
+}
+
+int dc_select_tau_per_step(const double* seff, const int64_t* taus, int64_t K, int64_t* out_best_k) {
+    if (!seff || !taus || !out_best_k || K < 1) return DC_ERR_INVALID_ARG;
+    for (int64_t k = 0; k < K; ++k)
+        if (std::isnan(seff[k]) || taus[k] < 0) return DC_ERR_INVALID_ARG;
+    int64_t best = 0;
+    for (int64_t k = 1; k < K; ++k)
+        if (seff[k] > seff[best] || (seff[k] == seff[best] && taus[k] > taus[best])) best = k;
     *out_best_k = best;
     return DC_OK;
 }

@@ -85,7 +85,7 @@ void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_ch
                        const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
                        hipStream_t stream);
 void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, uint32_t chunk0, const uint32_t* pos,
-                             const uint32_t* status, double* out_seff, hipStream_t stream);
+                             uint32_t* status, const int64_t* tau_sorted, double* out_seff, hipStream_t stream);
 size_t trial_scan_lds_bytes(const Plan& p);
 void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long* partial,
                           unsigned long long* result, uint32_t* status, hipStream_t stream, hipEvent_t before,

@@ -435,7 +435,8 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
     pos[j] = rank;
     tau_sorted[rank] = mine;
     tau_u32[rank] = mine >= (int64_t)DC_TAU_CLAMP ? DC_TAU_CLAMP : (mine < 0 ? 0u : (uint32_t)mine);
-    if (mine < 0) atomicOr(status, DC_FLAG_NEGATIVE_TAU);
+    // A negative threshold is flagged by the kernel that ends the call, from tau_sorted[0]: this kernel's own
+    // clearing of the status word (block 0) is not ordered against the other blocks.
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -927,6 +928,7 @@ struct FinalArgs {
     unsigned long long* trial_cnt;
     unsigned long long* trial_sum;
     uint32_t kc, p2, chunk0, K;
+    uint32_t* status;
     const int64_t* tau_sorted;
     const uint32_t* pos;
     unsigned long long T, elements;
@@ -989,6 +991,7 @@ __device__ __forceinline__ void finalize_chunk(const FinalArgs& f) {
     }
     __threadfence_block();
     __syncthreads();
+    if (tid == 0 && f.chunk0 == 0u && f.tau_sorted[0] < 0) atomicOr(f.status, DC_FLAG_NEGATIVE_TAU);
     for (uint32_t j = tid; j < f.K; j += THREADS) {
         const uint32_t p = f.pos[j];
         if (p >= f.chunk0 && p < f.chunk0 + f.kc) {
@@ -1251,10 +1254,11 @@ void dc_trial_scan_flat_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
 // combined in slice order, so the grouping of the float additions never changes between calls.
 __global__ __launch_bounds__(256)
 void dc_speedup_finalize_kernel(const double* __restrict__ partial, uint32_t narrow_blocks, uint32_t wide_blocks,
-                                const uint32_t* __restrict__ status, uint32_t p2, uint32_t kc,
-                                uint32_t chunk0, const uint32_t* __restrict__ pos, uint32_t K, double trials,
-                                double* __restrict__ out_seff) {
+                                uint32_t* __restrict__ status, const int64_t* __restrict__ tau_sorted, uint32_t p2,
+                                uint32_t kc, uint32_t chunk0, const uint32_t* __restrict__ pos, uint32_t K,
+                                double trials, double* __restrict__ out_seff) {
     __shared__ double slice_sum[8][32];
+    if (blockIdx.x == 0 && threadIdx.x == 0 && chunk0 == 0u && tau_sorted[0] < 0) atomicOr(status, DC_FLAG_NEGATIVE_TAU);
     // per-block sums were written by the launch of the per-trial kernel that the sample chose
     const uint32_t blocks = wide_blocks > narrow_blocks && status[1] != 0u ? wide_blocks : narrow_blocks;
     const uint32_t jj = threadIdx.x & 31u, slice = threadIdx.x >> 5;
@@ -1515,6 +1519,7 @@ void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long*
     FinalArgs f;
     f.hist_total = hist_total; f.trial_cnt = trial_cnt; f.trial_sum = trial_sum;
     f.kc = kc; f.p2 = p.p2; f.chunk0 = chunk0; f.K = p.K;
+    f.status = status;
     f.tau_sorted = tau_sorted; f.pos = pos;
     f.T = p.T; f.elements = p.elements; f.comm = (long long)comm;
     f.out_step = (long long*)out_step; f.out_done = (long long*)out_done;
@@ -1606,9 +1611,9 @@ void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_ch
 }
 
 void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, uint32_t chunk0, const uint32_t* pos,
-                             const uint32_t* status, double* out_seff, hipStream_t stream) {
+                             uint32_t* status, const int64_t* tau_sorted, double* out_seff, hipStream_t stream) {
     hipLaunchKernelGGL(dc_speedup_finalize_kernel, dim3((p.K + 31) / 32), dim3(256), 0, stream, partial, p.grid,
-                       p.grid_wide, status, p.p2, kc, chunk0, pos, p.K, (double)p.T, out_seff);
+                       p.grid_wide, status, tau_sorted, p.p2, kc, chunk0, pos, p.K, (double)p.T, out_seff);
 }
 
 __global__ void dc_clear_status_kernel(uint32_t* status) { *status = 0u; }

@@ -61,6 +61,23 @@ def test_select_tau_matches_oracle_and_breaks_ties_exactly():
     assert np.isnan(seff[0])
 
 
+def test_select_tau_per_step_matches_oracle_and_breaks_ties():
+    rng = np.random.default_rng(5)
+    for K in (1, 2, 7, 300):
+        seff = rng.random(K)
+        taus = rng.integers(0, 10**7, size=K)
+        if K > 5:
+            seff[4] = seff[1] = seff.max() + 0.25                      # equal maxima: the larger tau wins
+            taus[4] = taus[1] + 3
+        assert dc.dc_select_tau_per_step(seff, taus) == oracle.per_step_best(seff, taus)
+    assert dc.dc_select_tau_per_step([3 / 7, 3 / 4, 9 / 11, 3 / 4, 1.0, 1.0], [5, 6, 9, 10, 11, 50]) == 5
+    assert dc.dc_select_tau_per_step([0.5, 0.7, 0.7, 0.2], [10, 30, 30, 40]) == 1
+    for seff, taus in (([], []), ([float("nan")], [1]), ([1.0], [-1])):
+        with pytest.raises(dc.DcError) as e:
+            dc.dc_select_tau_per_step(seff, taus)
+        assert e.value.status == dc.DC_ERR_INVALID_ARG
+
+
 def test_select_tau_rejects_bad_input():
     with pytest.raises(dc.DcError) as e:
         dc.dc_select_tau([0], [1], [1], 1, 1, 1)

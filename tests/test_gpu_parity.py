@@ -343,6 +343,14 @@ def test_async_entry_point_on_a_side_stream(dev):
     taus_d[3] = -5
     dc.dc_simulate_async(lat_d, taus_d, r.comm, out_step, out_done, ws, stream)
     assert dc.dc_workspace_status(ws, stream) == dc.DC_ERR_INVALID_ARG
+    taus_d[3] = 5
+    for _ in range(20):                                     # a negative threshold far from the head of the list
+        taus_d[77] = -1
+        dc.dc_simulate_async(lat_d, taus_d, r.comm, out_step, out_done, ws, stream)
+        assert dc.dc_workspace_status(ws, stream) == dc.DC_ERR_INVALID_ARG
+        taus_d[77] = int(taus[77])
+        dc.dc_simulate_async(lat_d, taus_d, r.comm, out_step, out_done, ws, stream)
+        assert dc.dc_workspace_status(ws, stream) == dc.DC_OK
     small = torch.empty(256, dtype=torch.uint8, device=dev)
     with pytest.raises(dc.DcError):
         dc.dc_simulate_async(lat_d, taus_d, r.comm, out_step, out_done, small, stream)
@@ -582,9 +590,15 @@ def test_per_worker_normal_surrogate_parity(dev):
 
 # ---- full sizes of the two 2048-worker workloads, as the benchmark launches them -----------------------
 
-@pytest.mark.parametrize("name,rows", [("extrapolation2048", 0), ("heterogeneous2048", 0), ("heterogeneous2048", 63)])
+LITERAL_FULL_EVALS = 2.0e10      # the four-loop oracle runs on the whole tensor up to this many (t, n, m, tau) combinations
+
+
+@pytest.mark.parametrize("name,rows", [("tiny", 0), ("lognormal64", 0), ("additive200", 0), ("extrapolation2048", 0),
+                                       ("heterogeneous2048", 0), ("heterogeneous2048", 63)])
 def test_full_size_parity(name, rows, dev):
-    """The two 2048-worker workloads at full size, and the larger one once more with 63 accumulations per worker
+    """All five workloads at their stated size, in the launch configuration the benchmark times, against the
+    sorted-walk oracle on the whole tensor; the three smaller ones also against the four-loop oracle on the whole
+    tensor (the two 2048-worker ones on a sampled slab).  The largest runs once more with 63 accumulations per worker
     (same bytes, more than 2^32 elements through the kernel for arbitrary row lengths)."""
     from dc_workloads import device
     r = config(name)
@@ -611,69 +625,143 @@ def test_full_size_parity(name, rows, dev):
         progress(f"{name}: totals chunk {i + 1}/{len(chunks)}")
     taus = host.tau_grid_from_totals(r, totals)
     assert np.array_equal(taus, grid_dev)
-    taus = np.concatenate([taus, [BIG]])
+    taus = np.concatenate([taus, [BIG, 0, int(taus[taus.size // 3])]])      # edge thresholds and a repeat
 
     step, done = dc.dc_simulate(lat_d, taus, r.comm)
+    literal_full = r.elements * taus.size <= LITERAL_FULL_EVALS
     ref_step = np.zeros(taus.size, dtype=np.int64)
     ref_done = np.zeros(taus.size, dtype=np.int64)
+    lit_step, lit_done = ref_step.copy(), ref_done.copy()
     for i, (t0, t1) in enumerate(chunks):
         lat = kept.pop(t0) if keep else host.generate(r, t0, t1, threads)
         s, d = oracle.simulate_threaded(lat, taus, r.comm, "sorted", threads)
         ref_step += s
         ref_done += d
+        if literal_full:
+            s, d = oracle.simulate_threaded(lat, taus, r.comm, "literal", threads)
+            lit_step += s
+            lit_done += d
         progress(f"{name}: oracle chunk {i + 1}/{len(chunks)}")
     assert np.array_equal(done, ref_done) and np.array_equal(step, ref_step)
-    assert done[-1] == r.elements
-    # literal four-loop oracle on a few trials, against the library on the same slab
-    sample = slice(r.T // 2, r.T // 2 + 2)
-    some = taus[:: max(1, taus.size // 16)]
-    s, d = dc.dc_simulate(lat_d[sample], some, r.comm)
-    rs, rd = oracle.simulate(host.generate(r, sample.start, sample.stop), some, r.comm, "literal")
-    assert np.array_equal(s, rs) and np.array_equal(d, rd)
+    assert done[-3] == r.elements and done[-2] == 0
+    if literal_full:
+        assert np.array_equal(done, lit_done) and np.array_equal(step, lit_step)
+    else:                                                    # four-loop oracle on a few trials, same slab through the library
+        sample = slice(r.T // 2, r.T // 2 + 2)
+        some = taus[:: max(1, taus.size // 16)]
+        s, d = dc.dc_simulate(lat_d[sample], some, r.comm)
+        rs, rd = oracle.simulate(host.generate(r, sample.start, sample.stop), some, r.comm, "literal")
+        assert np.array_equal(s, rs) and np.array_equal(d, rd)
+    # the choice of the threshold from the full-size sums
+    base = int(step[-3])
+    thr, seff, best = dc.dc_select_tau(step, done, taus, r.T, r.N, r.M, base)
+    _, oseff, obest = oracle.select_tau(ref_step, ref_done, taus, r.T, r.N, r.M, base)
+    assert best == obest and np.allclose(seff, oseff, rtol=1e-6, atol=0)
     del lat_d
     torch.cuda.empty_cache()
 
 
-def test_full_size_widened_entry_points(dev):
-    """The 34 GB workload through the per-iteration speedup, the moments and the per-worker statistics: the result
-    for the whole tensor equals the combination of the results for its slabs (means weighted by trials, integer
-    sums added), and sampled slabs agree with the oracle."""
+@pytest.mark.parametrize("name,per_trial_comm", [("extrapolation2048", True), ("heterogeneous2048", False)])
+def test_full_size_widened_entry_points(name, per_trial_comm, dev):
+    """The two 2048-worker workloads in full through the per-iteration speedup, the moments and the per-worker
+    statistics, each against the oracle on the whole CPU tensor, streamed in chunks: per-iteration speedups add up
+    over iterations (16 thresholds of the workload's grid keep the oracle's O(K) work per element to seconds),
+    moments and per-worker sums are exact integers that add."""
+    from concurrent.futures import ThreadPoolExecutor
     from dc_workloads import device
-    r = config("heterogeneous2048")
+    r = config(name)
+    threads = host.cpu_threads()
     lat_d = device.generate(r)
-    taus = device.tau_grid(r, lat_d)
-    slab = 2048
-    starts = list(range(0, r.T, slab))
+    grid = device.tau_grid(r, lat_d)
+    taus = np.concatenate([grid[:: grid.size // 14], [BIG, int(grid[-1])]]).astype(np.int64)[:16]
+    rng = np.random.default_rng(7)
+    comm_t = rng.integers(0, 2 * r.comm + 1, size=r.T) if per_trial_comm else None
 
-    whole = dc.dc_speedup_per_step(lat_d, taus, r.comm)
-    parts = np.zeros(taus.size)
-    for t0 in starts:
-        parts += dc.dc_speedup_per_step(lat_d[t0:t0 + slab], taus, r.comm) * (min(slab, r.T - t0) / r.T)
-    assert np.allclose(whole, parts, rtol=1e-10, atol=0)
-    progress("per-iteration speedup: whole tensor equals its slabs")
+    got_seff = dc.dc_speedup_per_step(lat_d, taus, r.comm, comm_t)
+    got_sum, got_sq, got_mean, got_var = dc.dc_moments(lat_d)
+    got_wsum, got_wsq, got_wmean, got_wvar = dc.dc_worker_moments(lat_d)
+    progress(f"{name}: library done on {r.nbytes / 1e9:.1f} GB")
 
-    total, squares = dc.dc_moments(lat_d)[:2]
-    slabs = [dc.dc_moments(lat_d[t0:t0 + slab])[:2] for t0 in starts]
-    assert total == sum(s[0] for s in slabs) and squares == sum(s[1] for s in slabs)
-
-    sums, sq, _, _ = dc.dc_worker_moments(lat_d)
-    acc_s, acc_q = [0] * r.N, [0] * r.N
-    for t0 in starts:
-        s, q, _, _ = dc.dc_worker_moments(lat_d[t0:t0 + slab])
-        acc_s = [a + b for a, b in zip(acc_s, s)]
-        acc_q = [a + b for a, b in zip(acc_q, q)]
-    assert sums == acc_s and sq == acc_q
-    progress("moments and per-worker statistics: whole tensor equals its slabs")
-
-    for t0 in (0, r.T // 2 + 5, r.T - 6):                       # sampled slabs against the oracle
-        lat = host.generate(r, t0, t0 + 6)
-        view = lat_d[t0:t0 + 6]
-        assert np.allclose(dc.dc_speedup_per_step(view, taus, r.comm), oracle.per_step_speedup(lat, taus, r.comm),
-                           rtol=SPEEDUP_RTOL, atol=0)
-        assert dc.dc_moments(view)[:2] == oracle.moments(lat)[1:3]
-        assert dc.dc_worker_moments(view)[:2] == oracle.worker_moments(lat)[:2]
+    seff_sum = np.zeros(taus.size)
+    n_all = s_all = q_all = 0
+    wsum, wsq = [0] * r.N, [0] * r.N
+    chunks = list(host.trial_chunks(r, 512 << 20))
+    with ThreadPoolExecutor(threads) as pool:
+        for i, (t0, t1) in enumerate(chunks):
+            lat = host.generate(r, t0, t1, threads)
+            comm = r.comm if comm_t is None else comm_t[t0:t1]
+            seff_sum += oracle.per_step_speedup(lat, taus, comm, threads=threads) * (t1 - t0)
+            cuts = [(t1 - t0) * j // threads for j in range(threads + 1)]
+            parts = [lat[a:b] for a, b in zip(cuts, cuts[1:]) if b > a]
+            for n, s_, q, _, _ in pool.map(oracle.moments, parts):
+                n_all, s_all, q_all = n_all + n, s_all + s_, q_all + q
+            for s_, q, _, _ in pool.map(oracle.worker_moments, parts):
+                wsum = [a + b for a, b in zip(wsum, s_)]
+                wsq = [a + b for a, b in zip(wsq, q)]
+            progress(f"{name}: oracle chunk {i + 1}/{len(chunks)}")
+    assert n_all == r.elements
+    assert np.allclose(got_seff, seff_sum / r.T, rtol=SPEEDUP_RTOL, atol=0)
+    assert np.allclose(got_seff, seff_sum / r.T, rtol=1e-10, atol=0)          # what the arithmetic delivers
+    assert (got_sum, got_sq) == (s_all, q_all)
+    assert got_mean == pytest.approx(s_all / n_all, rel=1e-14)
+    assert got_var == pytest.approx((q_all * n_all - s_all * s_all) / (n_all * n_all), rel=1e-12)
+    assert got_wsum == wsum and got_wsq == wsq
+    assert np.allclose(got_wmean, [a / r.T for a in wsum], rtol=1e-14)
+    assert np.allclose(got_wvar, [(q * r.T - a * a) / (r.T * r.T) for a, q in zip(wsum, wsq)], rtol=1e-12, atol=0)
+    assert dc.dc_select_tau_per_step(got_seff, taus) == oracle.per_step_best(seff_sum / r.T, taus)
     del lat_d
     torch.cuda.empty_cache()
+
+
+# ---- tau* under both conventions: ratio of iteration means (Section 4.4) and mean of iteration ratios (Algorithm 2) ----
+
+@pytest.mark.parametrize("name,T", [("tiny", 1000), ("lognormal64", 400), ("additive200", 100),
+                                    ("extrapolation2048", 16), ("heterogeneous2048", 8)])
+def test_best_threshold_under_both_conventions(name, T, dev):
+    """S_eff as the ratio of iteration means (dc_simulate + dc_select_tau) and as the mean of per-iteration ratios
+    (dc_speedup_per_step + dc_select_tau_per_step, Algorithm 2 to its last line) on each workload: both against the
+    oracle, and the gap between them against Appendix C.2's argument.  With R = (T + T^c) / (M (min{tau, T} + T^c))
+    per iteration, the mean of ratios is E[M~ R] = E[M~] E[R] + cov(M~, R), and the appendix bounds the covariance by
+    Cauchy-Schwarz: |cov| <= sqrt(E[R^2] var(M~_n) / N), the O(N^-1/2) term.  The ratio of means replaces E[R] by
+    E[T + T^c] / (M E[min{tau, T} + T^c]); that second difference J does not shrink with N (it comes from the
+    spread of T alone, and dominates for the workload with rare long delays).  Asserted: |gap - J| within the
+    covariance bound.  J and the moments in the bound are taken from the CPU tensor."""
+    r = config(name).with_shape(T=T, K=16)
+    lat = host.generate(r)
+    taus = np.append(host.tau_grid(r), BIG).astype(np.int64)
+    lat_d = to_dev(lat, dev)
+    step, done = dc.dc_simulate(lat_d, taus, r.comm)
+    _, ratio_of_means, best_a = dc.dc_select_tau(step, done, taus, r.T, r.N, r.M, int(step[-1]))
+    mean_of_ratios = dc.dc_speedup_per_step(lat_d, taus, r.comm)
+    best_b = dc.dc_select_tau_per_step(mean_of_ratios, taus)
+
+    ref_step, ref_done = oracle.simulate(lat, taus, r.comm, "sorted")
+    _, ref_a, ref_best_a = oracle.select_tau(ref_step, ref_done, taus, r.T, r.N, r.M, int(ref_step[-1]))
+    ref_b = oracle.per_step_speedup(lat, taus, r.comm, threads=host.cpu_threads())
+    assert best_a == ref_best_a and np.allclose(ratio_of_means, ref_a, rtol=1e-6, atol=0)
+    assert np.allclose(mean_of_ratios, ref_b, rtol=SPEEDUP_RTOL, atol=0)
+    # the float sums differ in rounding order, so two almost equal maxima may swap: the chosen threshold must
+    # reach the oracle's maximum to within that rounding, and be the same index when the maximum is clear
+    ref_best_b = oracle.per_step_best(ref_b, taus)
+    assert ref_b[best_b] >= ref_b[ref_best_b] * (1 - 1e-12)
+    runner_up = np.max(np.delete(ref_b, ref_best_b))
+    if ref_b[ref_best_b] - runner_up > 1e-9:
+        assert best_b == ref_best_b
+
+    P = np.cumsum(lat.astype(np.int64), axis=2)
+    t_iter = P[:, :, -1].max(axis=1).astype(np.float64)
+    worst = 0.0
+    for k, tau in enumerate(taus):
+        completed = (P < tau).sum(axis=2).astype(np.float64)                  # M~_n per iteration and worker
+        capped = np.minimum(float(tau), t_iter) + r.comm
+        ratio = (t_iter + r.comm) / (r.M * capped)                             # R per iteration
+        spread = completed.mean() * (ratio.mean() - (t_iter + r.comm).mean() / (r.M * capped.mean()))      # J
+        bound = np.sqrt((ratio ** 2).mean() * completed.var() / r.N)
+        gap = mean_of_ratios[k] - ratio_of_means[k]
+        assert abs(gap - spread) <= bound + 1e-12, (name, int(tau), gap, spread, bound)
+        worst = max(worst, abs(gap))
+    progress(f"{name}: tau* {int(taus[best_a])} us (ratio of means, S_eff {ratio_of_means[best_a]:.6f}), "
+             f"{int(taus[best_b])} us (mean of ratios, S_eff {mean_of_ratios[best_b]:.6f}), largest gap {worst:.2e}")
 
 
 def test_plain_c_caller_of_the_abi(dev, golden_dir):
