@@ -6,6 +6,10 @@ dc_simulate_async (thresholds sorted, the streaming scan over lat, reductions, f
 copy of the 2*K result sums to the host, and dc_select_tau.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+                  [--rows M] [--grid recipe|dense|upper-half] [--path sums|per-step|analytic]
+
+The result sums are written by the library's last kernel straight into pinned host memory (the output pointers of
+dc_simulate_async may be any memory the device can write), so a step has no separate copy.
 """
 from __future__ import annotations
 
@@ -42,22 +46,52 @@ def kernel_source_hash() -> str:
 
 
 def recorded_traffic(workload: str):
-    """HBM bytes per launch of the scan kernel from the committed rocprofv3 counter summary,
-    or None when there is none for this workload or the kernel sources changed since."""
+    """(HBM bytes per launch of the scan kernel, where the figure comes from): the committed rocprofv3 counter summary
+    for this workload, or (None, why not) when there is none or the kernel sources changed since it was taken."""
     path = ROOT / "profiles" / f"{SCAN_KERNEL}_{workload}_pmc.txt"
     if not path.exists():
-        return None
+        return None, "no counter summary for this workload under profiles/"
     fields = {}
     for line in path.read_text().splitlines():
         if ":" in line and not line.startswith("#"):
             k, v = line.split(":", 1)
             fields[k.strip()] = v.strip()
     if fields.get("kernel_source_hash") != kernel_source_hash():
-        return None
+        return None, f"profiles/{path.name} was recorded for other kernel sources"
     try:
-        return float(fields["hbm_bytes_per_launch"])
+        return float(fields["hbm_bytes_per_launch"]), (f"profiles/{path.name}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                                        "command, recorded earlier (not read in this run); kernel source hash matches")
     except (KeyError, ValueError):
-        return None
+        return None, f"profiles/{path.name} holds no hbm_bytes_per_launch"
+
+
+def host_core_report():
+    """How many cores the host has, how many this process may use, and how many threads the oracle gets."""
+    from dc_workloads import host
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return {"host_cores": os.cpu_count() or 1, "usable_cores": usable, "threads_used": host.cpu_threads(),
+            "thread_cap": "16: the share of the host that one GPU's job may use on the benchmark machines"}
+
+
+def literal_oracle_full(names=("tiny", "lognormal64")):
+    """The four-loop oracle (the definition, O(K) work per element) on the two smallest workloads at full size."""
+    import oracle
+    from dc_workloads import config, host
+    threads = host.cpu_threads()
+    rows = []
+    for name in names:
+        r = config(name)
+        lat = host.generate(r, 0, r.T, threads)
+        taus = host.tau_grid(r, threads)
+        t0 = time.perf_counter()
+        oracle.simulate_threaded(lat, taus, r.comm, "literal", threads)
+        dt = time.perf_counter() - t0
+        rows.append({"workload": f"{name}: T={r.T} N={r.N} M={r.M} K={taus.size}", "seconds": dt,
+                     "value": r.elements * taus.size / dt, "unit": "evals/s", "threads": threads})
+    return rows
 
 
 def cpu_baseline(r, taus, target_seconds: float = 12.0):
@@ -86,18 +120,21 @@ def cpu_baseline(r, taus, target_seconds: float = 12.0):
     t0 = time.perf_counter()
     oracle.simulate(lat[:t_one], taus, r.comm, "sorted")
     d1 = time.perf_counter() - t0
-    # the literal four-loop form on a slab small enough to finish in a few seconds
+    # the four-loop form on a slab of this workload small enough to finish in a few seconds
     t_lit = max(1, min(trials, int(2.0e10 // (per_trial * taus.size))))
     t0 = time.perf_counter()
     oracle.simulate_threaded(lat[:t_lit], taus, r.comm, "literal", threads)
     dl = time.perf_counter() - t0
+    cores = host_core_report()
     return {
         "value": sorted_rate, "unit": "evals/s", "cores": threads, "kind": "oracle",
         "sample": f"first {trials} of {r.T} trials of {r.name} (N={r.N}, M={r.M}, K={taus.size}), "
                   f"sorted-threshold oracle, {reps} passes in {dt:.2f} s; input generation not timed",
+        **cores,
         "value_1_thread": t_one * per_trial * taus.size / d1,
         "literal_value": t_lit * per_trial * taus.size / dl,
-        "literal_sample": f"first {t_lit} trials, four-loop oracle, {dl:.2f} s",
+        "literal_sample": f"first {t_lit} trials of this workload, four-loop oracle, {dl:.2f} s",
+        "literal_full": literal_oracle_full(),
     }
 
 
@@ -205,57 +242,59 @@ def bench_analytic(args, r, lat, taus) -> int:
     return 0
 
 
-def scan_kernel_name(M: int) -> str:
+def scan_kernel_name(M: int, grid: str = "recipe") -> str:
     """The streaming kernel the library runs for rows of M elements (16-byte aligned tensor), as a profile names it."""
     if M % 4 == 0 and (M <= 128 or M == 256):
         lanes = M // 4
         known = lanes if lanes & (lanes - 1) == 0 else 0              # one instantiation serves every other lane count
-        return f"{SCAN_KERNEL}<{known}, {1 if M >= 128 else 0}>"      # long rows: <L, 1> works on narrow grids, <L, 2> on dense ones
+        shape = 0 if M < 128 else (1 if grid == "recipe" else 2)      # long rows: <L, 1> works on narrow grids, <L, 2> on dense ones
+        return f"{SCAN_KERNEL}<{known}, {shape}>"
     return f"dc_scan_flat_kernel<{'true' if M < 4 else 'false'}>"
 
 
-def time_sums_path(r, lat, taus, taus_dev, stream, steps, warmup):
-    """`warmup` untimed and `steps` timed passes of the whole path (dc_simulate_async, one copy of the 2 K sums to
-    the host, dc_select_tau) on `stream`.  Returns (wall seconds, per-step ms, scan-kernel ms per step, thr, best),
-    or None if the device flagged a value error."""
+def time_sums_path(r, lat, taus, taus_dev, stream, steps, warmup, timing: int = 1):
+    """`warmup` untimed and `steps` timed passes of the whole path (dc_simulate_async writing its 2 K sums into pinned
+    host memory, the wait for the stream, dc_select_tau) on `stream`.  timing: 0 = no events in the passes, 1 = the
+    library brackets its streaming kernel with HIP events, 2 = also the whole enqueued sequence.
+    Returns (wall seconds, per-step ms, scan-kernel ms per step, sequence ms per step, thr, best), or None if the device
+    flagged a value error."""
     import numpy as np
     import torch
 
     import paper_2306_10598_amd as dc
     K = taus.size
-    out = torch.zeros((2, K), dtype=torch.int64, device=lat.device)     # out_step, out_done: one buffer, one copy back
-    host_out = torch.zeros((2, K), dtype=torch.int64).pin_memory()
+    host_out = torch.zeros((2, K), dtype=torch.int64).pin_memory()      # out_step, out_done: written by the device
     host_step, host_done = host_out[0].numpy(), host_out[1].numpy()
     ws = torch.empty(dc.dc_workspace_bytes(r.T, r.N, r.M, K), dtype=torch.uint8, device=lat.device)
 
-    def step():                                                  # `stream` is torch's current stream here
-        dc.dc_simulate_async(lat, taus_dev, r.comm, out[0], out[1], ws, stream)
-        host_out.copy_(out, non_blocking=True)
+    def step():
+        dc.dc_simulate_async(lat, taus_dev, r.comm, host_out[0], host_out[1], ws, stream)
         stream.synchronize()
         return dc.dc_select_tau(host_step, host_done, taus, r.T, r.N, r.M, 0)
 
-    previous = torch.cuda.current_stream()
-    torch.cuda.set_stream(stream)
-    dc.dc_set_kernel_timing(True)
+    dc.dc_set_kernel_timing(timing)
     try:
         for _ in range(warmup):
             step()
         if dc.dc_workspace_status(ws, stream) != dc.DC_OK:
             return None
-        scan_ms, step_ms = [], []
+        scan_ms, seq_ms, step_ms = [], [], []
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
             ts = time.perf_counter()
             thr, _, best = step()
             step_ms.append(1e3 * (time.perf_counter() - ts))
-            scan_ms.append(dc.dc_last_kernel_ms()[0])          # HIP events on the stream the kernel ran on
+            if timing:
+                a, b = dc.dc_last_kernel_ms(whole=timing >= 2)   # HIP events on the stream the kernels ran on
+                scan_ms.append(a)
+                if b is not None:
+                    seq_ms.append(b)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
     finally:
         dc.dc_set_kernel_timing(False)
-        torch.cuda.set_stream(previous)
-    return wall, step_ms, scan_ms, thr, best
+    return wall, step_ms, scan_ms, seq_ms, thr, best
 
 
 def other_workloads(headline: str, stream, steps: int = 10, warmup: int = 3):
@@ -272,16 +311,19 @@ def other_workloads(headline: str, stream, steps: int = 10, warmup: int = 3):
         lat = device.generate(r)
         taus = device.tau_grid(r, lat)
         taus_dev = torch.from_numpy(taus).to(lat.device)
-        m = time_sums_path(r, lat, taus, taus_dev, stream, steps, warmup)
+        m = time_sums_path(r, lat, taus, taus_dev, stream, steps, warmup, timing=0)     # the step as a caller sees it
+        e = time_sums_path(r, lat, taus, taus_dev, stream, steps, 1, timing=2) if m else None   # device-side times
         del lat
         torch.cuda.empty_cache()
-        if m is None:
+        if m is None or e is None:
             rows.append({"workload": name, "error": "device reported a value error"})
             continue
-        wall, _, scan_ms, _, _ = m
+        wall = m[0]
+        scan_ms, seq_ms = e[2], e[3]
         rows.append({"workload": f"{name}: T={r.T} N={r.N} M={r.M} K={taus.size}", "tensor_bytes": r.nbytes,
                      "value": float(r.elements) * taus.size / (wall / steps), "unit": "evals/s",
                      "ms_per_step": 1e3 * wall / steps, "kernel_ms": float(np.mean(scan_ms)),
+                     "sequence_ms": float(np.mean(seq_ms)),
                      "achieved_GBps": 4.0 * r.elements / (float(np.mean(scan_ms)) * 1e-3) / 1e9, "steps": steps})
     return rows
 
@@ -299,6 +341,10 @@ def main() -> int:
     ap.add_argument("--rows", type=int, default=0,
                     help="run the workload with this many accumulations per worker instead of its own M, the number of "
                          "trials rescaled to keep the tensor's size (not a bench line: for timing other row lengths)")
+    ap.add_argument("--grid", choices=("recipe", "dense", "upper-half"), default="recipe",
+                    help="recipe: the workload's own threshold grid; dense: K thresholds from 0 to the largest worker total "
+                         "(every completion time falls inside the grid); upper-half: from half the largest total to it "
+                         "(not a bench line: for timing grids that cover much of the data)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true",
                     help="skip the short runs on the other workloads that are reported in `per_config`")
@@ -334,6 +380,9 @@ def main() -> int:
 
     lat = device.generate(r)                                   # resident in HBM before timing starts
     taus = device.tau_grid(r, lat)
+    if args.grid != "recipe":
+        top = int(device.worker_totals(lat).max().item())
+        taus = np.linspace(0 if args.grid == "dense" else top // 2, top, taus.size).astype(np.int64)
     K = taus.size
     taus_dev = torch.from_numpy(taus).to(dev)
     stream = torch.cuda.Stream()
@@ -344,17 +393,19 @@ def main() -> int:
     if args.path == "analytic":
         return bench_analytic(args, r, lat, taus)
 
-    m = time_sums_path(r, lat, taus, taus_dev, stream, args.steps, args.warmup)
+    m = time_sums_path(r, lat, taus, taus_dev, stream, args.steps, args.warmup, timing=2)
     if m is None:
         print("device reported a value error", file=sys.stderr)
         return 1
-    wall, step_ms, scan_ms, thr, best = m
+    wall, step_ms, scan_ms, seq_ms, thr, best = m
 
     ms_per_step = 1e3 * wall / args.steps
     evals = float(r.elements) * K
     scan_avg_ms = float(np.mean(scan_ms))
     algo_bytes = 4.0 * r.elements                              # every latency read once, nothing written back
     achieved = algo_bytes / (scan_avg_ms * 1e-3) / 1e9
+    plain = args.rows <= 0 and args.grid == "recipe"
+    traffic, traffic_source = recorded_traffic(r.name) if plain else (None, "not the workload's own shape or grid")
     line = {
         "metric": METRIC, "value": evals / (wall / args.steps), "unit": "evals/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -362,16 +413,18 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"{r.name}: T={r.T} N={r.N} M={r.M} K={K} comm={r.comm}us, {r.description}",
-                   "tensor_bytes": r.nbytes, "best_tau_us": int(taus[best]), "best_thr_per_us": float(thr[best])},
-        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(r.M), "achieved": achieved,
+                   "grid": args.grid, "tensor_bytes": r.nbytes, "best_tau_us": int(taus[best]),
+                   "best_thr_per_us": float(thr[best])},
+        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(r.M, args.grid), "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": None if args.rows > 0 else recorded_traffic(r.name),
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "kernel_ms": scan_avg_ms, "kernel_ms_min": float(np.min(scan_ms)),
+                     "sequence_ms": float(np.mean(seq_ms)),     # all kernels of a call, first to last, on the device
                      "algorithmic_bytes": algo_bytes},
     }
     del lat
     torch.cuda.empty_cache()
-    if not args.no_per_config and args.rows <= 0:
+    if not args.no_per_config and plain:
         line["per_config"] = other_workloads(r.name, stream)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(r, taus)

@@ -72,7 +72,8 @@ size_t dc_workspace_bytes(int64_t T, int64_t N, int64_t M, int64_t K);
 
 /* Same computation, enqueued on `stream` (a hipStream_t passed as void*; NULL = null stream)
  * without synchronising and without allocating.  taus_dev, out_step_dev, out_done_dev: DEVICE,
- * K int64 each.  workspace_dev: DEVICE, 256-byte aligned, at least dc_workspace_bytes(T,N,M,K)
+ * K int64 each; the two outputs may also be pinned host memory that the device can write (hipHostMalloc): the
+ * last kernel then delivers the sums without a separate copy, valid once the stream has been waited for.  workspace_dev: DEVICE, 256-byte aligned, at least dc_workspace_bytes(T,N,M,K)
  * bytes, contents irrelevant on entry; it must not be used by another call until this one has
  * finished on the stream.  The return value covers only what the host can check (arguments,
  * launch errors); value errors found on the device (negative tau, negative or too large

@@ -102,6 +102,16 @@ def _device_tensor(t, dtype_name: str, what: str):
     return t
 
 
+def _device_writable(t, dtype_name: str, what: str):
+    """A contiguous tensor the device can write: device memory, or pinned host memory (mapped at the same address)."""
+    import torch
+    if not isinstance(t, torch.Tensor) or not (t.is_cuda or t.is_pinned()):
+        raise TypeError(f"{what} must be a GPU tensor or a pinned host tensor")
+    if t.dtype != getattr(torch, dtype_name) or not t.is_contiguous():
+        raise TypeError(f"{what} must be a contiguous {dtype_name} tensor")
+    return t
+
+
 def dc_status_string(status: int) -> str:
     return _load().dc_status_string(int(status)).decode()
 
@@ -134,8 +144,8 @@ def dc_simulate_async(lat, taus_dev, comm: int, out_step_dev, out_done_dev, work
     T, N, M = lat.shape
     taus_dev = _device_tensor(taus_dev, "int64", "taus_dev")
     K = taus_dev.numel()
-    out_step_dev = _device_tensor(out_step_dev, "int64", "out_step_dev")
-    out_done_dev = _device_tensor(out_done_dev, "int64", "out_done_dev")
+    out_step_dev = _device_writable(out_step_dev, "int64", "out_step_dev")
+    out_done_dev = _device_writable(out_done_dev, "int64", "out_done_dev")
     workspace = _device_tensor(workspace, "uint8", "workspace")
     if out_step_dev.numel() < K or out_done_dev.numel() < K:
         raise ValueError("output tensors are shorter than the threshold list")

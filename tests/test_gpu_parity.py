@@ -340,6 +340,14 @@ def test_async_entry_point_on_a_side_stream(dev):
         dc.dc_simulate_async(lat_d, taus_d, r.comm, out_step, out_done, ws, stream)
         assert dc.dc_workspace_status(ws, stream) == dc.DC_OK
         assert np.array_equal(out_step.cpu().numpy(), ref[0]) and np.array_equal(out_done.cpu().numpy(), ref[1])
+    pinned = torch.zeros((2, taus.size), dtype=torch.int64).pin_memory()   # outputs straight into host memory, no copy
+    for _ in range(3):
+        pinned.zero_()
+        dc.dc_simulate_async(lat_d, taus_d, r.comm, pinned[0], pinned[1], ws, stream)
+        stream.synchronize()
+        assert np.array_equal(pinned[0].numpy(), ref[0]) and np.array_equal(pinned[1].numpy(), ref[1])
+    with pytest.raises(TypeError):
+        dc.dc_simulate_async(lat_d, taus_d, r.comm, torch.zeros(taus.size, dtype=torch.int64), pinned[1], ws, stream)
     taus_d[3] = -5
     dc.dc_simulate_async(lat_d, taus_d, r.comm, out_step, out_done, ws, stream)
     assert dc.dc_workspace_status(ws, stream) == dc.DC_ERR_INVALID_ARG
