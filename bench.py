@@ -249,7 +249,7 @@ def scan_kernel_name(M: int, grid: str = "recipe") -> str:
         known = lanes if lanes & (lanes - 1) == 0 else 0              # one instantiation serves every other lane count
         shape = 0 if M < 128 else (1 if grid == "recipe" else 2)      # long rows: <L, 1> works on narrow grids, <L, 2> on dense ones
         return f"{SCAN_KERNEL}<{known}, {shape}>"
-    return f"dc_scan_flat_kernel<{'true' if M < 4 else 'false'}>"
+    return f"dc_scan_flat_kernel<{M if M < 4 else 0}>"
 
 
 def time_sums_path(r, lat, taus, taus_dev, stream, steps, warmup, timing: int = 1):

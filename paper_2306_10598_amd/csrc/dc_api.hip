@@ -184,10 +184,10 @@ uint32_t wanted_blocks_per_cu(const dc::Plan& p) {
 }
 
 // Which instantiation a plan runs, as the M field of the key: the row length for the kernels of whole rows
-// per load, else which of the two kernels for arbitrary rows (rows below 4 elements or not).
+// per load, else which of the kernels for arbitrary rows (built for rows of 1, 2, 3 elements, or for any longer row).
 uint32_t variant_of(const dc::Plan& p) {
     if (p.vec4) return p.M;
-    return p.M < 4 ? 2u : 3u;
+    return p.M < 4 ? p.M : 4u;
 }
 
 struct Resident {

@@ -122,38 +122,38 @@ __device__ __forceinline__ uint32_t bin_of(const uint32_t* a, uint32_t p2, uint3
 
 // The threshold grid of one pass as the streaming kernel sees it, all in LDS:
 //   tau[p2]     ascending thresholds, padded with 0xFFFFFFFF
-//   lut[p2]     lut[c] = #{k : tau_k < tau0 + c*2^shift} (lut[p2-1] = number of thresholds): p2-1 uniform
+//   cells[p2]   cells[c].x = #{k : tau_k < tau0 + c*2^shift} (cells[p2-1].x = number of thresholds): p2-1 uniform
 //               cells from tau0 on, the last one open-ended, so that a completion time v in cell c has its
-//               bin in [lut[c], lut[c+1]] (a short search; one step or none for evenly spaced thresholds)
+//               bin in [cells[c].x, cells[c+1].x] (a short search; one step or none for evenly spaced thresholds);
+//               cells[c].y = tau[cells[c].x], the first threshold at or above the cell's lower edge, so that one
+//               8-byte read gives both when no cell holds more than one threshold
 //   hist[p2]    bin counts of the block
 struct GridView {
     const uint32_t* tau;
-    const uint32_t* lut;
+    const uint2* cells;
     uint32_t* hist;
     uint32_t p2;
     uint32_t shift;
     uint32_t tau0;
-    bool exact;          // no cell holds more than one threshold: lut[c] and one comparison give the bin
+    bool exact;          // no cell holds more than one threshold: cells[c] and one comparison give the bin
 };
 
 // Bins b(v) = #{k : tau_k <= v} of N values at once (the searches interleave their LDS reads).
 template <int N>
 __device__ __forceinline__ void bins_of(const GridView& g, const uint32_t (&val)[N], uint32_t (&lo)[N]) {
     if (g.exact) {
-        // evenly spaced thresholds (the usual case) leave at most one per cell: bin = lut[c] + (tau[lut[c]] <= v);
+        // evenly spaced thresholds (the usual case) leave at most one per cell: bin = cells[c].x + (cells[c].y <= v);
         // tau is padded with 0xFFFFFFFF, so a cell without a threshold, or past the last one, adds nothing
-        uint32_t t[N];
+        uint2 cell[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             uint32_t c = (val[i] - g.tau0) >> g.shift;
             c = c < g.p2 - 2 ? c : g.p2 - 2;
-            lo[i] = g.lut[c];
+            cell[i] = g.cells[c];
         }
 #pragma unroll
-        for (int i = 0; i < N; ++i) t[i] = g.tau[lo[i]];                     // lo <= kc <= p2-1
-#pragma unroll
         for (int i = 0; i < N; ++i) {
-            lo[i] += t[i] <= val[i] ? 1u : 0u;
+            lo[i] = cell[i].x + (cell[i].y <= val[i] ? 1u : 0u);
             lo[i] = val[i] < g.tau0 ? 0u : lo[i];                             // below every threshold
         }
         return;
@@ -163,8 +163,8 @@ __device__ __forceinline__ void bins_of(const GridView& g, const uint32_t (&val)
     for (int i = 0; i < N; ++i) {
         uint32_t c = (val[i] - g.tau0) >> g.shift;
         c = c < g.p2 - 2 ? c : g.p2 - 2;
-        lo[i] = g.lut[c];
-        hi[i] = g.lut[c + 1];
+        lo[i] = g.cells[c].x;
+        hi[i] = g.cells[c + 1].x;
         if (val[i] < g.tau0) lo[i] = hi[i] = 0u;               // below every threshold
     }
     for (;;) {
@@ -443,13 +443,13 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
 // shared pieces of the streaming kernels
 // ---------------------------------------------------------------------------------------------
 
-// Stage one pass's thresholds in LDS (tau[p2] | hist[p2] | lut[p2] at `tables`), clear the histogram
+// Stage one pass's thresholds in LDS (tau[p2] | hist[p2] | cells[p2], 16 p2 bytes at `tables`), clear the histogram
 // and build the lookup cells.  Every thread of the block must call it (it synchronises the block).
 __device__ __forceinline__ GridView stage_grid(uint32_t* tables, const uint32_t* __restrict__ tau_chunk,
                                                uint32_t kc, uint32_t p2) {
     uint32_t* tau_s = tables;
     uint32_t* hist = tau_s + p2;
-    uint32_t* lut = hist + p2;
+    uint2* cells = reinterpret_cast<uint2*>(hist + p2);
     for (uint32_t i = threadIdx.x; i < p2; i += blockDim.x) {
         tau_s[i] = i < kc ? tau_chunk[i] : 0xFFFFFFFFu;
         hist[i] = 0u;
@@ -473,13 +473,14 @@ __device__ __forceinline__ GridView stage_grid(uint32_t* tables, const uint32_t*
             const uint32_t mid = (lo + hi) >> 1;
             if ((uint64_t)tau_s[mid] < edge) lo = mid + 1; else hi = mid;
         }
-        lut[c] = c == p2 - 1 ? kc : lo;                        // upper end of the open-ended last cell
+        const uint32_t first = c == p2 - 1 ? kc : lo;          // upper end of the open-ended last cell
+        cells[c] = make_uint2(first, tau_s[first]);            // first <= kc <= p2 - 1
     }
     __syncthreads();
     bool single = true;                                        // does every cell hold at most one threshold?
-    for (uint32_t c = threadIdx.x; c + 1 < p2; c += blockDim.x) single = single && lut[c + 1] - lut[c] <= 1u;
+    for (uint32_t c = threadIdx.x; c + 1 < p2; c += blockDim.x) single = single && cells[c + 1].x - cells[c].x <= 1u;
     const bool exact = __syncthreads_and(single) != 0;
-    return GridView{tau_s, lut, hist, p2, shift, tau_first, exact};
+    return GridView{tau_s, cells, hist, p2, shift, tau_first, exact};
 }
 
 // One wave streams `nfull` consecutive full loads (shape.rows whole rows each, 1 KiB when every lane takes
@@ -765,29 +766,37 @@ __device__ __forceinline__ void flat_process(uint32_t& check, FlatState& fs, con
     for (int k = 0; k < U; ++k) emit(p[k], vm[k], pos[k], row[k]);
 }
 
-// One load of rows with 1..3 elements.
-template <typename F>
+// One load of rows with 1..3 elements.  MS: the row length when the kernel was built for it (then positions wrap by
+// a mask or one subtraction, and rows of one element need nothing from the neighbouring lane), else 0.
+template <int MS, typename F>
 __device__ __forceinline__ void flat_process_small(uint32_t& check, FlatState& fs, const FlatTensor& f, u32x4 x,
                                                    uint32_t vm, uint32_t lane, F&& emit) {
     check = umax(check, umax(umax(x.x, x.y), umax(x.z, x.w)));
-    uint32_t y0 = (uint32_t)__shfl_up((int)x.z, 1, 64), y1 = (uint32_t)__shfl_up((int)x.w, 1, 64);
-    if (lane == 0) { y0 = fs.prev2; y1 = fs.prev3; }
-    const uint32_t y[6] = {y0, y1, x.x, x.y, x.z, x.w};
     uint32_t out[4];
+    if constexpr (MS == 1) {
+        out[0] = x.x; out[1] = x.y; out[2] = x.z; out[3] = x.w;          // a completion time is the latency itself
+    } else {
+        uint32_t y0 = (uint32_t)__shfl_up((int)x.z, 1, 64), y1 = (uint32_t)__shfl_up((int)x.w, 1, 64);
+        if (lane == 0) { y0 = fs.prev2; y1 = fs.prev3; }
+        const uint32_t y[6] = {y0, y1, x.x, x.y, x.z, x.w};
 #pragma unroll
-    for (uint32_t c = 0; c < 4; ++c) {
-        const uint32_t pc = (fs.pos0 + c) % f.M;
-        out[c] = y[c + 2] + (pc >= 1u ? y[c + 1] : 0u) + (pc >= 2u ? y[c] : 0u);
+        for (uint32_t c = 0; c < 4; ++c) {
+            uint32_t pc = fs.pos0 + c;                                    // <= 5
+            if constexpr (MS == 2) pc &= 1u;
+            else if constexpr (MS == 3) pc -= pc >= 3u ? 3u : 0u;
+            else pc %= f.M;
+            out[c] = y[c + 2] + (pc >= 1u ? y[c + 1] : 0u) + (pc >= 2u ? y[c] : 0u);
+        }
+        fs.prev2 = (uint32_t)__builtin_amdgcn_readlane((int)x.z, 63);
+        fs.prev3 = (uint32_t)__builtin_amdgcn_readlane((int)x.w, 63);
     }
-    fs.prev2 = (uint32_t)__builtin_amdgcn_readlane((int)x.z, 63);
-    fs.prev3 = (uint32_t)__builtin_amdgcn_readlane((int)x.w, 63);
     const uint32_t pos = fs.pos0, row = fs.row;
     flat_advance(fs, f);
     emit(make_uint4(out[0], out[1], out[2], out[3]), vm, pos, row);
 }
 
 // One wave streams a unit: `len` elements (whole rows) from element `first` of lat.
-template <bool SMALL, int U = DC_FLAT_UNROLL, typename F>
+template <bool SMALL, int U = DC_FLAT_UNROLL, int MS = 0, typename F>
 __device__ __forceinline__ void flat_stream_unit(uint32_t& check, const FlatTensor& f, uint64_t first, uint32_t len,
                                                  uint32_t lane, F&& emit) {
     const uint64_t start = first + f.off;                  // vector-space element of the unit's head
@@ -809,7 +818,7 @@ __device__ __forceinline__ void flat_stream_unit(uint32_t& check, const FlatTens
         const uint32_t limit = len + k < 256u ? len + k : 256u;
         const uint32_t vm[1] = {flat_valid_mask(lane, k, limit)};
         const u32x4 x[1] = {flat_masked(flat_load(f, v0 + lane, lane < nv, guard), vm[0])};
-        if constexpr (SMALL) flat_process_small(check, fs, f, x[0], vm[0], lane, emit);
+        if constexpr (SMALL) flat_process_small<MS>(check, fs, f, x[0], vm[0], lane, emit);
         else flat_process<1>(check, fs, f, x, vm, lane, emit);
     }
     // middle loads: every component belongs to the unit
@@ -826,11 +835,19 @@ __device__ __forceinline__ void flat_stream_unit(uint32_t& check, const FlatTens
                 for (int q = 0; q < U; ++q) x[q] = __builtin_nontemporal_load(base + (uint64_t)(i + q) * 64u);
                 flat_process<U>(check, fs, f, x, all, lane, emit);
             }
+        } else {
+            for (; i + U <= nloads - 1u; i += U) {              // U loads in flight, then taken in order
+                u32x4 x[U];
+#pragma unroll
+                for (int q = 0; q < U; ++q) x[q] = __builtin_nontemporal_load(base + (uint64_t)(i + q) * 64u);
+#pragma unroll
+                for (int q = 0; q < U; ++q) flat_process_small<MS>(check, fs, f, x[q], 0xFu, lane, emit);
+            }
         }
         const uint32_t all1[1] = {0xFu};
         for (; i < nloads - 1u; ++i) {
             const u32x4 x[1] = {__builtin_nontemporal_load(base + (uint64_t)i * 64u)};
-            if constexpr (SMALL) flat_process_small(check, fs, f, x[0], 0xFu, lane, emit);
+            if constexpr (SMALL) flat_process_small<MS>(check, fs, f, x[0], 0xFu, lane, emit);
             else flat_process<1>(check, fs, f, x, all1, lane, emit);
         }
     }
@@ -840,7 +857,7 @@ __device__ __forceinline__ void flat_stream_unit(uint32_t& check, const FlatTens
         const uint32_t limit = len + k - 256u * i;         // 1..256 by the choice of nloads
         const uint32_t vm[1] = {flat_valid_mask(lane, 0u, limit)};
         const u32x4 x[1] = {flat_masked(flat_load(f, v0 + (uint64_t)i * 64u + lane, i * 64u + lane < nv, guard), vm[0])};
-        if constexpr (SMALL) flat_process_small(check, fs, f, x[0], vm[0], lane, emit);
+        if constexpr (SMALL) flat_process_small<MS>(check, fs, f, x[0], vm[0], lane, emit);
         else flat_process<1>(check, fs, f, x, vm, lane, emit);
     }
 }
@@ -855,7 +872,17 @@ __device__ __forceinline__ void flat_count(WaveState& st, uint4 p, uint32_t vm, 
     const bool whole = vm == 0xFu;
     const bool active = whole && top >= g.tau0;
     const uint64_t mask = __ballot(active);
-    if (mask) {
+    if ((uint32_t)__popcll(mask) >= DC_DENSE_LANES) {
+        // Most lanes hold completion times inside the threshold grid (short rows, whose every element is a row end or
+        // close to one; grids that cover much of the data): the queue would only copy what is already in registers.
+        if (active) {
+            uint32_t b[4];
+            bins_of4(g, p, b);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (b[i]) atomicAdd(&g.hist[b[i]], 1u);
+        }
+    } else if (mask) {
         if (active) {
             const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
                                       __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
@@ -873,7 +900,7 @@ __device__ __forceinline__ void flat_count(WaveState& st, uint4 p, uint32_t vm, 
     }
 }
 
-template <bool SMALL>
+template <int MS>        // 0: rows of at least 4 elements; 1, 2, 3: rows of exactly that many
 __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint32_t N, uint32_t M, uint32_t units,
                          uint32_t units_per_trial, uint32_t run, uint32_t rows_per_unit, const uint32_t* __restrict__ tau_chunk,
@@ -899,7 +926,7 @@ void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint32
             const uint32_t row0 = j * rows_per_unit;
             const uint32_t rows = (N - row0) < rows_per_unit ? (N - row0) : rows_per_unit;
             st.lane_max = 0u;
-            flat_stream_unit<SMALL>(st.check, f, ((uint64_t)t * N + row0) * M, rows * M, lane,
+            flat_stream_unit<(MS != 0), DC_FLAT_UNROLL, MS>(st.check, f, ((uint64_t)t * N + row0) * M, rows * M, lane,
                                     [&](uint4 p, uint32_t vm, uint32_t, uint32_t) { flat_count(st, p, vm, queue, g, lane); });
             const uint32_t m = wave_max(st.lane_max);
             if (lane == 0) unit_max[u] = m;
@@ -1157,7 +1184,7 @@ void dc_trial_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
     uint32_t* tables = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);
     TrialShared sh;
-    sh.acc = reinterpret_cast<double*>(tables + 3 * p2);                                // 8-byte aligned: p2 is even
+    sh.acc = reinterpret_cast<double*>(tables + 4 * p2);                                // 8-byte aligned: p2 is even
     sh.wave_tot = reinterpret_cast<uint32_t*>(sh.acc + p2);
     sh.block_max = sh.wave_tot + DC_SCAN_WAVES;
     for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) sh.acc[i] = 0.0;
@@ -1212,7 +1239,7 @@ void dc_trial_scan_flat_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
     uint32_t* tables = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);
     TrialShared sh;
-    sh.acc = reinterpret_cast<double*>(tables + 3 * p2);
+    sh.acc = reinterpret_cast<double*>(tables + 4 * p2);
     sh.wave_tot = reinterpret_cast<uint32_t*>(sh.acc + p2);
     sh.block_max = sh.wave_tot + DC_SCAN_WAVES;
     for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) sh.acc[i] = 0.0;
@@ -1431,7 +1458,7 @@ void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t*
 
 size_t scan_lds_bytes(const Plan& p) {
     const size_t tables = (size_t)p.p2 * 8;                       // thresholds + histogram
-    return tables + (size_t)p.p2 * 4 + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);   // + cells + queues
+    return tables + (size_t)p.p2 * 8 + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);   // + cells + queues
 }
 
 template <int L>
@@ -1446,9 +1473,14 @@ int scan_blocks_per_cu(const Plan& p) {
     const size_t lds = scan_lds_bytes(p);
     int n = 0;
     if (!p.vec4) {
-        if ((p.M < 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_flat_kernel<true>, DC_SCAN_THREADS, lds)
-                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_flat_kernel<false>, DC_SCAN_THREADS, lds)) != hipSuccess) n = 0;
-        return n;
+        hipError_t e;
+        switch (p.M) {
+            case 1:  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_flat_kernel<1>, DC_SCAN_THREADS, lds); break;
+            case 2:  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_flat_kernel<2>, DC_SCAN_THREADS, lds); break;
+            case 3:  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_flat_kernel<3>, DC_SCAN_THREADS, lds); break;
+            default: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_flat_kernel<0>, DC_SCAN_THREADS, lds); break;
+        }
+        return e == hipSuccess ? n : 0;
     }
     switch (p.M / 4) {
         case 1:  return resident_vec4<1>(lds);
@@ -1481,17 +1513,23 @@ static void launch_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_c
                        status, p.max_latency, p.M / 4);
 }
 
+template <int MS>
+static void launch_flat(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
+                        uint32_t* unit_max, uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
+    hipLaunchKernelGGL(dc_scan_flat_kernel<MS>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
+                       (uint64_t)p.elements, p.N, p.M, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2,
+                       unit_max, hist_part, status, p.max_latency);
+}
+
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
                  uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
     if (!p.vec4) {
-        if (p.M < 4)
-            hipLaunchKernelGGL(dc_scan_flat_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
-                               lat, (uint64_t)p.elements, p.N, p.M, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc,
-                               p.p2, unit_max, hist_part, status, p.max_latency);
-        else
-            hipLaunchKernelGGL(dc_scan_flat_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
-                               lat, (uint64_t)p.elements, p.N, p.M, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc,
-                               p.p2, unit_max, hist_part, status, p.max_latency);
+        switch (p.M) {
+            case 1:  launch_flat<1>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+            case 2:  launch_flat<2>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+            case 3:  launch_flat<3>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+            default: launch_flat<0>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+        }
         return;
     }
     switch (p.M / 4) {
@@ -1559,7 +1597,7 @@ int trial_scan_blocks_per_cu(const Plan& p) {
 }
 
 size_t trial_scan_lds_bytes(const Plan& p) {
-    const size_t tables = (size_t)p.p2 * 12 + (size_t)p.p2 * 8 + (DC_SCAN_WAVES + 1) * 4;   // grid + sums + scratch
+    const size_t tables = (size_t)p.p2 * 16 + (size_t)p.p2 * 8 + (DC_SCAN_WAVES + 1) * 4;   // grid + sums + scratch
     return tables + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);                    // + queues
 }
 
