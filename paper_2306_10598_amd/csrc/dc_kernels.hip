@@ -132,6 +132,7 @@ struct GridView {
     const uint32_t* tau;
     const uint2* cells;
     uint32_t* hist;
+    uint32_t* sink;      // this lane's word for counts that nobody reads (values below every threshold)
     uint32_t p2;
     uint32_t shift;
     uint32_t tau0;
@@ -144,18 +145,16 @@ __device__ __forceinline__ void bins_of(const GridView& g, const uint32_t (&val)
     if (g.exact) {
         // evenly spaced thresholds (the usual case) leave at most one per cell: bin = cells[c].x + (cells[c].y <= v);
         // tau is padded with 0xFFFFFFFF, so a cell without a threshold, or past the last one, adds nothing
+        // a value below every threshold lands in cell 0, whose threshold tau0 it does not reach: bin 0
         uint2 cell[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            uint32_t c = (val[i] - g.tau0) >> g.shift;
+            uint32_t c = (umax(val[i], g.tau0) - g.tau0) >> g.shift;
             c = c < g.p2 - 2 ? c : g.p2 - 2;
             cell[i] = g.cells[c];
         }
 #pragma unroll
-        for (int i = 0; i < N; ++i) {
-            lo[i] = cell[i].x + (cell[i].y <= val[i] ? 1u : 0u);
-            lo[i] = val[i] < g.tau0 ? 0u : lo[i];                             // below every threshold
-        }
+        for (int i = 0; i < N; ++i) lo[i] = cell[i].x + (cell[i].y <= val[i] ? 1u : 0u);
         return;
     }
     uint32_t hi[N];
@@ -187,6 +186,12 @@ __device__ __forceinline__ void bins_of(const GridView& g, const uint32_t (&val)
 __device__ __forceinline__ void bins_of4(const GridView& g, uint4 v, uint32_t (&lo)[4]) {
     const uint32_t val[4] = {v.x, v.y, v.z, v.w};
     bins_of<4>(g, val, lo);
+}
+
+// One more completion time in bin b, for the paths that bin straight from registers: bin 0 (below every threshold) is
+// never read, and sending it to a word of the lane's own costs one select instead of a branch around the atomic.
+__device__ __forceinline__ void count_bin(const GridView& g, uint32_t b) {
+    atomicAdd(b ? &g.hist[b] : g.sink, 1u);
 }
 
 // Per-wave state of the streaming pass.
@@ -256,8 +261,7 @@ __device__ __forceinline__ void bin_direct(const u32x4* x, const uint32_t* incl,
     }
     bins_of<4 * G>(g, val, b);
 #pragma unroll
-    for (int i = 0; i < 4 * G; ++i)
-        if (b[i]) atomicAdd(&g.hist[b[i]], 1u);
+    for (int i = 0; i < 4 * G; ++i) count_bin(g, b[i]);
 }
 
 // Completion time of each lane's last element for U loads at once (the U scans are independent, so
@@ -447,6 +451,7 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
 // and build the lookup cells.  Every thread of the block must call it (it synchronises the block).
 __device__ __forceinline__ GridView stage_grid(uint32_t* tables, const uint32_t* __restrict__ tau_chunk,
                                                uint32_t kc, uint32_t p2) {
+    __shared__ uint32_t s_sink[64];
     uint32_t* tau_s = tables;
     uint32_t* hist = tau_s + p2;
     uint2* cells = reinterpret_cast<uint2*>(hist + p2);
@@ -480,7 +485,7 @@ __device__ __forceinline__ GridView stage_grid(uint32_t* tables, const uint32_t*
     bool single = true;                                        // does every cell hold at most one threshold?
     for (uint32_t c = threadIdx.x; c + 1 < p2; c += blockDim.x) single = single && cells[c + 1].x - cells[c].x <= 1u;
     const bool exact = __syncthreads_and(single) != 0;
-    return GridView{tau_s, cells, hist, p2, shift, tau_first, exact};
+    return GridView{tau_s, cells, hist, &s_sink[threadIdx.x & 63u], p2, shift, tau_first, exact};
 }
 
 // One wave streams `nfull` consecutive full loads (shape.rows whole rows each, 1 KiB when every lane takes
@@ -879,8 +884,7 @@ __device__ __forceinline__ void flat_count(WaveState& st, uint4 p, uint32_t vm, 
             uint32_t b[4];
             bins_of4(g, p, b);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (b[i]) atomicAdd(&g.hist[b[i]], 1u);
+            for (int i = 0; i < 4; ++i) count_bin(g, b[i]);
         }
     } else if (mask) {
         if (active) {
