@@ -62,7 +62,9 @@ typedef enum {
  * K int64 each, in the caller's threshold order.
  * Runs on the null stream of the current device and returns after the results are on the
  * host.  Uses a workspace that the library allocates on first use, keeps per process and
- * grows when needed (dc_shutdown frees it); calls from several threads are serialised. */
+ * grows when needed (dc_shutdown frees it); the synchronous entry points share it, so calls of theirs from
+ * several threads are serialised.  The *_async entry points and dc_simulate_static hold no lock while they
+ * enqueue and may be called from several threads at once, each call with a workspace of its own. */
 int dc_simulate(const int32_t* lat, int64_t T, int64_t N, int64_t M,
                 const int64_t* taus, int64_t K, int64_t comm,
                 int64_t* out_step, int64_t* out_done);
@@ -102,6 +104,20 @@ int dc_simulate_async(const int32_t* lat, int64_t T, int64_t N, int64_t M,
 int dc_simulate_static(const int32_t* lat, int64_t T, int64_t N, int64_t M,
                        const int64_t* taus_dev, int64_t K, int64_t comm,
                        int64_t* out_step_dev, int64_t* out_done_dev, int32_t* out_status_dev, void* stream);
+
+/* The same two calls for a tensor whose trials are not adjacent: element (t,n,m) is at
+ * lat[t*trial_stride + n*M + m], trial_stride >= N*M elements (else DC_ERR_INVALID_ARG).  This is how the first
+ * N' of N workers of a resident tensor [T][N][M] are simulated without a copy (lat, N', trial_stride = N*M), or
+ * the workers n0 .. n0+N'-1 (lat + n0*M): the slab of the latency samples that one worker group holds before the
+ * one-time synchronisation of Section 4.4, and the way a scale sweep over the number of workers reads one tensor.
+ * Everything else as dc_simulate / dc_simulate_async; dc_workspace_bytes(T, N, M, K) bytes of workspace suffice.
+ * Trials that do not start on 16-byte boundaries (trial_stride not a multiple of 4) take the kernel for any alignment. */
+int dc_simulate_strided(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t trial_stride,
+                        const int64_t* taus, int64_t K, int64_t comm, int64_t* out_step, int64_t* out_done);
+int dc_simulate_strided_async(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t trial_stride,
+                              const int64_t* taus_dev, int64_t K, int64_t comm,
+                              int64_t* out_step_dev, int64_t* out_done_dev,
+                              void* workspace_dev, size_t workspace_bytes, void* stream);
 
 /* Waits for `stream` and returns the dc_status that the last dc_simulate_async using
  * workspace_dev recorded on the device (DC_OK, DC_ERR_INVALID_ARG for a negative threshold,
@@ -164,7 +180,9 @@ int dc_speedup_per_step_async(const int32_t* lat, int64_t T, int64_t N, int64_t 
  * first assumption; population variance).
  *   *out_sum = sum lat;  out_sumsq[0], out_sumsq[1] = low and high 64 bits of sum lat^2 (exact integers);
  *   *out_mean = sum / n;  *out_variance = (sumsq*n - sum^2) / n^2,  n = T*N*M.
- * lat: DEVICE.  All outputs HOST, each may be NULL.  DC_ERR_NEGATIVE_LATENCY if some lat < 0.
+ * lat: DEVICE.  All outputs HOST, each may be NULL.  DC_ERR_NEGATIVE_LATENCY if some lat < 0.  The sum is kept in
+ * 64 bits: DC_ERR_RANGE when n times the bitwise OR of all latencies (an upper bound of the largest) reaches 2^63,
+ * i.e. when it cannot be shown that the sum stayed below 2^63 (never for n <= 2^32).
  * Null stream, synchronous, cached workspace as dc_simulate. */
 int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M,
                int64_t* out_sum, uint64_t* out_sumsq, double* out_mean, double* out_variance);
@@ -174,11 +192,14 @@ int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M,
  * redraws every T_n from a normal distribution (Section 4.3, "simulation" curve).  For worker n:
  *   out_sum[n] = sum_t T_n;  out_sumsq[2n], out_sumsq[2n+1] = low and high 64 bits of sum_t T_n^2 (exact);
  *   out_mean[n] = sum / T;   out_variance[n] = (sumsq*T - sum^2) / T^2  (population variance).
- * lat: DEVICE.  Outputs HOST arrays of N (out_sumsq: 2N), each may be NULL.  N <= 2560 (the accumulators of all
- * workers live in LDS), else DC_ERR_INVALID_ARG; latency preconditions and errors as dc_simulate.
- * Null stream, synchronous, cached workspace. */
+ * lat: DEVICE.  Outputs HOST arrays of N (out_sumsq: 2N), each may be NULL.  The accumulators live in LDS, 2560
+ * workers at a time: more workers take one pass over their rows of lat per 2560.  Latency preconditions and errors
+ * as dc_simulate.  Null stream, synchronous, cached workspace.
+ * dc_worker_moments_strided: trials trial_stride >= N*M elements apart, as dc_simulate_strided. */
 int dc_worker_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M,
                       int64_t* out_sum, uint64_t* out_sumsq, double* out_mean, double* out_variance);
+int dc_worker_moments_strided(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t trial_stride,
+                              int64_t* out_sum, uint64_t* out_sumsq, double* out_mean, double* out_variance);
 
 /* Closed-form estimates from (mu, sigma2) of one micro-batch latency (Sections 4.2-4.4, Appendix C.2):
  *   out_edone[k] = sum_{m=1..M} Phi((taus[k] - m*mu) / sqrt(m*sigma2))     expected completed micro-batches per
@@ -200,14 +221,17 @@ int dc_analytic_curves(double mu, double sigma2, int64_t N, int64_t M, const int
 
 /* Optional kernel timing for benchmarks.  enable = 1: every entry point that streams lat brackets its
  * streaming kernel (the single pass over lat) with HIP events on the stream it runs on; enable = 2:
- * also the whole enqueued sequence (two more event records per call); 0: off.  dc_last_kernel_ms waits
- * for those events and returns the elapsed milliseconds of the last call (scan_ms: streaming kernel(s)
- * only; total_ms: all kernels of the call, needs enable = 2).  Either pointer may be NULL.
- * DC_ERR_INVALID_ARG if the requested timing is off or no call has been timed yet.  The events belong to the
- * device that was current when timing was first used; leave timing off while a stream is being captured
- * into a graph (event records would become graph nodes whose times cannot be read back). */
+ * also the whole enqueued sequence (two more event records per call); 0: off.  The setting is per process; the
+ * events belong to the workspace a call runs in (the library's own for the synchronous entry points), so calls on
+ * different streams, each with its own workspace, are timed independently (up to 16 workspaces are remembered).
+ * dc_workspace_kernel_ms waits for the events of the last timed call in workspace_dev and returns the elapsed
+ * milliseconds (scan_ms: streaming kernel(s) only; total_ms: all kernels of the call, needs enable = 2);
+ * dc_last_kernel_ms does the same for the calling thread's last timed call.  Either pointer may be NULL.
+ * DC_ERR_INVALID_ARG if the requested timing is off or no such call has been timed.  Leave timing off while a
+ * stream is being captured into a graph (event records would become graph nodes whose times cannot be read back). */
 int dc_set_kernel_timing(int enable);
 int dc_last_kernel_ms(float* scan_ms, float* total_ms);
+int dc_workspace_kernel_ms(const void* workspace_dev, float* scan_ms, float* total_ms);
 
 /* Name of a status code; a static string, never NULL. */
 const char* dc_status_string(int status);

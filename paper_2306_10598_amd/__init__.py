@@ -21,6 +21,7 @@ DC_MAX_THRESHOLDS = 65536
 
 EXPORTS = (
     "dc_simulate", "dc_workspace_bytes", "dc_simulate_async", "dc_simulate_static", "dc_workspace_status", "dc_select_tau",
+    "dc_simulate_strided", "dc_simulate_strided_async", "dc_worker_moments_strided", "dc_workspace_kernel_ms",
     "dc_speedup_per_step", "dc_speedup_workspace_bytes", "dc_speedup_per_step_async", "dc_select_tau_per_step",
     "dc_moments", "dc_worker_moments", "dc_analytic_curves",
     "dc_set_kernel_timing", "dc_last_kernel_ms", "dc_status_string", "dc_last_device_error", "dc_shutdown",
@@ -56,6 +57,14 @@ def _load():
     lib.dc_simulate_async.restype = ctypes.c_int
     lib.dc_simulate_static.argtypes = [p, i64, i64, i64, p, i64, i64, p, p, p, p]
     lib.dc_simulate_static.restype = ctypes.c_int
+    lib.dc_simulate_strided.argtypes = [p, i64, i64, i64, i64, p, i64, i64, p, p]
+    lib.dc_simulate_strided.restype = ctypes.c_int
+    lib.dc_simulate_strided_async.argtypes = [p, i64, i64, i64, i64, p, i64, i64, p, p, p, sz, p]
+    lib.dc_simulate_strided_async.restype = ctypes.c_int
+    lib.dc_worker_moments_strided.argtypes = [p, i64, i64, i64, i64, p, p, p, p]
+    lib.dc_worker_moments_strided.restype = ctypes.c_int
+    lib.dc_workspace_kernel_ms.argtypes = [p, p, p]
+    lib.dc_workspace_kernel_ms.restype = ctypes.c_int
     lib.dc_workspace_status.argtypes = [p, p]
     lib.dc_workspace_status.restype = ctypes.c_int
     lib.dc_select_tau.argtypes = [p, p, p, i64, i64, i64, i64, i64, p, p, p]
@@ -112,6 +121,21 @@ def _device_writable(t, dtype_name: str, what: str):
     return t
 
 
+def _slab(lat, workers):
+    """(pointer, T, N', M, trial stride in elements) of a contiguous GPU tensor [T][N][M], or of the workers
+    workers[0] .. workers[1]-1 of it when `workers` = (n0, n1) is given: no copy is made."""
+    lat = _device_tensor(lat, "int32", "lat")
+    if lat.dim() != 3:
+        raise TypeError("lat must have shape [T][N][M]")
+    T, N, M = lat.shape
+    if workers is None:
+        return lat.data_ptr(), T, N, M, N * M
+    n0, n1 = int(workers[0]), int(workers[1])
+    if not 0 <= n0 < n1 <= N:
+        raise ValueError("workers must be a range (n0, n1) with 0 <= n0 < n1 <= N")
+    return lat.data_ptr() + 4 * n0 * M, T, n1 - n0, M, N * M
+
+
 def dc_status_string(status: int) -> str:
     return _load().dc_status_string(int(status)).decode()
 
@@ -120,28 +144,27 @@ def dc_workspace_bytes(T: int, N: int, M: int, K: int) -> int:
     return int(_load().dc_workspace_bytes(T, N, M, K))
 
 
-def dc_simulate(lat, taus, comm: int):
-    """out_step[K], out_done[K] (NumPy int64) for a GPU int32 tensor lat[T][N][M] and host thresholds."""
-    lat = _device_tensor(lat, "int32", "lat")
-    if lat.dim() != 3:
-        raise TypeError("lat must have shape [T][N][M]")
-    T, N, M = lat.shape
+def dc_simulate(lat, taus, comm: int, workers=None):
+    """out_step[K], out_done[K] (NumPy int64) for a GPU int32 tensor lat[T][N][M] and host thresholds.
+    workers = (n0, n1): only those workers of every trial (dc_simulate_strided, the tensor is not copied)."""
+    ptr, T, N, M, stride = _slab(lat, workers)
     taus = np.ascontiguousarray(taus, dtype=np.int64)
     K = taus.size
     out_step = np.empty(K, dtype=np.int64)
     out_done = np.empty(K, dtype=np.int64)
-    rc = _load().dc_simulate(lat.data_ptr(), T, N, M, taus.ctypes.data, K, int(comm),
-                             out_step.ctypes.data, out_done.ctypes.data)
+    if workers is None:
+        rc = _load().dc_simulate(ptr, T, N, M, taus.ctypes.data, K, int(comm), out_step.ctypes.data, out_done.ctypes.data)
+    else:
+        rc = _load().dc_simulate_strided(ptr, T, N, M, stride, taus.ctypes.data, K, int(comm),
+                                         out_step.ctypes.data, out_done.ctypes.data)
     _check(rc, "dc_simulate")
     return out_step, out_done
 
 
-def dc_simulate_async(lat, taus_dev, comm: int, out_step_dev, out_done_dev, workspace, stream=None) -> None:
-    """Enqueue the computation on `stream` (a torch.cuda.Stream, or None for the null stream)."""
-    lat = _device_tensor(lat, "int32", "lat")
-    if lat.dim() != 3:
-        raise TypeError("lat must have shape [T][N][M]")
-    T, N, M = lat.shape
+def dc_simulate_async(lat, taus_dev, comm: int, out_step_dev, out_done_dev, workspace, stream=None, workers=None) -> None:
+    """Enqueue the computation on `stream` (a torch.cuda.Stream, or None for the null stream).
+    workers = (n0, n1): only those workers of every trial (dc_simulate_strided_async)."""
+    ptr, T, N, M, stride = _slab(lat, workers)
     taus_dev = _device_tensor(taus_dev, "int64", "taus_dev")
     K = taus_dev.numel()
     out_step_dev = _device_writable(out_step_dev, "int64", "out_step_dev")
@@ -150,9 +173,14 @@ def dc_simulate_async(lat, taus_dev, comm: int, out_step_dev, out_done_dev, work
     if out_step_dev.numel() < K or out_done_dev.numel() < K:
         raise ValueError("output tensors are shorter than the threshold list")
     handle = 0 if stream is None else int(stream.cuda_stream)
-    rc = _load().dc_simulate_async(lat.data_ptr(), T, N, M, taus_dev.data_ptr(), K, int(comm),
-                                   out_step_dev.data_ptr(), out_done_dev.data_ptr(),
-                                   workspace.data_ptr(), workspace.numel(), handle)
+    if workers is None:
+        rc = _load().dc_simulate_async(ptr, T, N, M, taus_dev.data_ptr(), K, int(comm),
+                                       out_step_dev.data_ptr(), out_done_dev.data_ptr(),
+                                       workspace.data_ptr(), workspace.numel(), handle)
+    else:
+        rc = _load().dc_simulate_strided_async(ptr, T, N, M, stride, taus_dev.data_ptr(), K, int(comm),
+                                               out_step_dev.data_ptr(), out_done_dev.data_ptr(),
+                                               workspace.data_ptr(), workspace.numel(), handle)
     _check(rc, "dc_simulate_async")
 
 
@@ -274,19 +302,16 @@ def dc_moments(lat):
     return int(total.value), (int(sq[1]) << 64) | int(sq[0]), float(mean.value), float(var.value)
 
 
-def dc_worker_moments(lat):
+def dc_worker_moments(lat, workers=None):
     """Per worker: (sums, sums of squares) of its iteration time as lists of exact Python ints, and (mean[N],
-    variance[N]) as NumPy float64 arrays."""
-    lat = _device_tensor(lat, "int32", "lat")
-    if lat.dim() != 3:
-        raise TypeError("lat must have shape [T][N][M]")
-    T, N, M = lat.shape
+    variance[N]) as NumPy float64 arrays.  workers = (n0, n1): only those workers (dc_worker_moments_strided)."""
+    ptr, T, N, M, stride = _slab(lat, workers)
     sums = np.empty(N, dtype=np.int64)
     sq = np.empty(2 * N, dtype=np.uint64)
     mean = np.empty(N, dtype=np.float64)
     var = np.empty(N, dtype=np.float64)
-    rc = _load().dc_worker_moments(lat.data_ptr(), T, N, M, sums.ctypes.data, sq.ctypes.data, mean.ctypes.data,
-                                   var.ctypes.data)
+    rc = _load().dc_worker_moments_strided(ptr, T, N, M, stride, sums.ctypes.data, sq.ctypes.data, mean.ctypes.data,
+                                           var.ctypes.data)
     _check(rc, "dc_worker_moments")
     return ([int(v) for v in sums], [(int(sq[2 * n + 1]) << 64) | int(sq[2 * n]) for n in range(N)], mean, var)
 
@@ -315,6 +340,15 @@ def dc_last_kernel_ms(whole: bool = False):
     """(scan_ms, total_ms) of the last timed call; total_ms is None unless whole=True (timing level 2)."""
     a, b = ctypes.c_float(0), ctypes.c_float(0)
     _check(_load().dc_last_kernel_ms(ctypes.byref(a), ctypes.byref(b) if whole else None), "dc_last_kernel_ms")
+    return float(a.value), (float(b.value) if whole else None)
+
+
+def dc_workspace_kernel_ms(workspace, whole: bool = False):
+    """(scan_ms, total_ms) of the last timed call that ran in `workspace`; total_ms is None unless whole=True."""
+    workspace = _device_tensor(workspace, "uint8", "workspace")
+    a, b = ctypes.c_float(0), ctypes.c_float(0)
+    _check(_load().dc_workspace_kernel_ms(workspace.data_ptr(), ctypes.byref(a), ctypes.byref(b) if whole else None),
+           "dc_workspace_kernel_ms")
     return float(a.value), (float(b.value) if whole else None)
 
 

@@ -51,10 +51,11 @@ __device__ __forceinline__ void block_reduce(Acc& a, unsigned long long (*lds)[3
 }  // namespace
 
 // partial[block] = {sum, squares low word, squares high word, OR of values}.  `vec_units` units of 64 KiB
-// (16-byte loads, a wave per unit) cover the first vec_units*16384 elements when lat is 16-byte aligned;
-// the remaining elements [scalar_from, n) are read one by one.
+// (16-byte loads, a wave per unit) cover the elements [head, head + vec_units*16384), where head (0..3) is the
+// number of elements before the first 16-byte boundary; the elements before and after, [0, head) and
+// [scalar_from, n), are read one by one.
 __global__ __launch_bounds__(256)
-void dc_moments_kernel(const int32_t* __restrict__ lat, unsigned long long n, uint32_t vec_units,
+void dc_moments_kernel(const int32_t* __restrict__ lat, unsigned long long n, uint32_t head, uint32_t vec_units,
                        unsigned long long scalar_from, unsigned long long* __restrict__ partial) {
     __shared__ unsigned long long lds[256][3];
     __shared__ uint32_t lds_bits[256];
@@ -63,7 +64,7 @@ void dc_moments_kernel(const int32_t* __restrict__ lat, unsigned long long n, ui
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t total_waves = gridDim.x * 4;
     for (uint32_t u = blockIdx.x * 4 + wave; u < vec_units; u += total_waves) {
-        const u32x4* base = reinterpret_cast<const u32x4*>(lat) + (uint64_t)u * 4096 + lane;
+        const u32x4* base = reinterpret_cast<const u32x4*>(lat + head) + (uint64_t)u * 4096 + lane;
         for (uint32_t i = 0; i < 64; i += 8) {
             u32x4 x[8];
 #pragma unroll
@@ -75,6 +76,7 @@ void dc_moments_kernel(const int32_t* __restrict__ lat, unsigned long long n, ui
     const unsigned long long stride = (unsigned long long)gridDim.x * blockDim.x;
     for (unsigned long long i = scalar_from + (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
         take(a, (uint32_t)lat[i]);
+    if (blockIdx.x == 0 && threadIdx.x < head && threadIdx.x < n) take(a, (uint32_t)lat[threadIdx.x]);
     block_reduce(a, lds, lds_bits);
     if (threadIdx.x == 0) {
         unsigned long long* out = partial + (uint64_t)blockIdx.x * 4;
@@ -142,11 +144,12 @@ namespace dc {
 
 void launch_moments(const int32_t* lat, uint64_t n, uint32_t grid, unsigned long long* partial,
                     unsigned long long* result, uint32_t* status, hipStream_t stream) {
-    const bool aligned = ((uintptr_t)lat & 15u) == 0;
-    const uint64_t units = aligned ? n / 16384 : 0;
+    uint64_t head = (4u - (uint32_t)(((uintptr_t)lat >> 2) & 3u)) & 3u;     // elements before the first 16-byte boundary
+    if (head > n) head = n;
+    const uint64_t units = (n - head) / 16384;
     const uint32_t vec_units = (uint32_t)(units < 0x7FFFFFFFull ? units : 0x7FFFFFFFull);
-    hipLaunchKernelGGL(dc_moments_kernel, dim3(grid), dim3(256), 0, stream, lat, (unsigned long long)n, vec_units,
-                       (unsigned long long)vec_units * 16384ull, partial);
+    hipLaunchKernelGGL(dc_moments_kernel, dim3(grid), dim3(256), 0, stream, lat, (unsigned long long)n, (uint32_t)head,
+                       vec_units, (unsigned long long)(head + (uint64_t)vec_units * 16384ull), partial);
     hipLaunchKernelGGL(dc_moments_final_kernel, dim3(1), dim3(256), 0, stream, partial, grid, result, status);
 }
 

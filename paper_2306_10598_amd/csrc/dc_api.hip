@@ -3,6 +3,7 @@
 // threshold selection.  No computation on latencies happens on the host.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -53,16 +54,31 @@ uint64_t flat_rows_per_unit(int64_t N, int64_t M, uint64_t share = 1) {
     return ((uint64_t)N + pieces - 1) / pieces;
 }
 
-// Returns false when the sizes are outside what the library handles.
-bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::Plan* out) {
-    if (T < 1 || N < 1 || M < 1 || K < 1 || K > DC_MAX_THRESHOLDS) return false;
+// The tensor's shape: T trials of N rows of M elements, consecutive trials `stride` elements apart (0: N*M).
+// Returns false when it is outside what the library handles; else fills T, N, M, elements, stride, extent.
+bool plan_shape(int64_t T, int64_t N, int64_t M, int64_t stride, dc::Plan* p) {
+    if (T < 1 || N < 1 || M < 1) return false;
     const int64_t lim = (int64_t)1 << 31;
     if (T >= lim || N >= lim || M >= lim) return false;
     if ((long double)T * (long double)N * (long double)M >= 4.6e18L) return false;   // < 2^62
+    const uint64_t row_elements = (uint64_t)N * (uint64_t)M;
+    if (stride == 0) stride = (int64_t)row_elements;
+    if (stride < 0 || (uint64_t)stride < row_elements) return false;
+    if ((long double)(T - 1) * (long double)stride + (long double)row_elements >= 4.6e18L) return false;
+    p->T = (uint32_t)T; p->N = (uint32_t)N; p->M = (uint32_t)M;
+    p->elements = (uint64_t)T * row_elements;
+    p->stride = (uint64_t)stride;
+    p->extent = (uint64_t)(T - 1) * (uint64_t)stride + row_elements;
+    return true;
+}
+
+// Returns false when the sizes are outside what the library handles.  allow_vec4: lat is 16-byte aligned.
+bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::Plan* out, int64_t stride = 0) {
+    if (K < 1 || K > DC_MAX_THRESHOLDS) return false;
     dc::Plan p{};
-    p.T = (uint32_t)T; p.N = (uint32_t)N; p.M = (uint32_t)M; p.K = (uint32_t)K;
-    p.elements = (uint64_t)T * (uint64_t)N * (uint64_t)M;
-    p.vec4 = allow_vec4 && vec4_shape(M);
+    if (!plan_shape(T, N, M, stride, &p)) return false;
+    p.K = (uint32_t)K;
+    p.vec4 = allow_vec4 && vec4_shape(M) && (p.stride & 3u) == 0;     // every trial starts on a 16-byte boundary
     uint64_t upt;
     if (p.vec4) {
         const uint64_t rows_per_load = 64 / (M / 4);
@@ -80,7 +96,7 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
         upt = ((uint64_t)N + rows - 1) / rows;
     }
     const uint64_t units = (uint64_t)T * upt;
-    if (units >= (uint64_t)lim) return false;
+    if (units >= ((uint64_t)1 << 31)) return false;
     p.units_per_trial = (uint32_t)upt;
     p.units = (uint32_t)units;
     uint64_t grid = (units + DC_SCAN_WAVES - 1) / DC_SCAN_WAVES;
@@ -106,14 +122,13 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
 }
 
 // Plan of the per-iteration speedup pass: one block per trial, float64 sums per block.
-bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::Plan* out) {
-    if (T < 1 || N < 1 || M < 1 || K < 1 || K > DC_MAX_THRESHOLDS) return false;
-    const int64_t lim = (int64_t)1 << 31;
-    if (T >= lim || N >= lim || M >= lim || N * M >= lim) return false;      // per-trial counts are 32-bit
+bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::Plan* out, int64_t stride = 0) {
+    if (K < 1 || K > DC_MAX_THRESHOLDS) return false;
     dc::Plan p{};
-    p.T = (uint32_t)T; p.N = (uint32_t)N; p.M = (uint32_t)M; p.K = (uint32_t)K;
-    p.elements = (uint64_t)T * (uint64_t)N * (uint64_t)M;
-    p.vec4 = allow_vec4 && vec4_shape(M);
+    if (!plan_shape(T, N, M, stride, &p)) return false;
+    if (N * M >= ((int64_t)1 << 31)) return false;                            // per-trial counts are 32-bit
+    p.K = (uint32_t)K;
+    p.vec4 = allow_vec4 && vec4_shape(M) && (p.stride & 3u) == 0;
     p.grid = (uint32_t)(T < (int64_t)DC_MAX_TRIAL_BLOCKS ? T : DC_MAX_TRIAL_BLOCKS);
     p.grid_wide = p.grid;
     if (p.vec4) {
@@ -137,26 +152,82 @@ bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4
 }
 
 // ---- optional timing ---------------------------------------------------------------------------
-struct Timing {
-    bool enabled = false;
-    bool whole = false;                // also bracket the whole enqueued sequence (two more event records)
-    bool valid = false;
+// Events belong to the workspace that a call runs in, so calls on different streams (each with a workspace of
+// its own, as the interface demands) are timed independently.  A fixed table; the slot used longest ago is taken
+// over when all are in use.
+struct TimingSlot {
+    const void* key = nullptr;         // the workspace
+    int device = -1;
+    bool valid = false, whole = false;
     hipEvent_t begin = nullptr, end = nullptr;
     std::vector<hipEvent_t> scan;      // pairs (before, after) per chunk
     size_t used_pairs = 0;
+    uint64_t stamp = 0;
 };
-Timing g_timing;
-std::mutex g_mutex;                     // guards g_timing and the cached workspace
+constexpr size_t TIMING_SLOTS = 16;
+TimingSlot g_slots[TIMING_SLOTS];
+uint64_t g_slot_clock = 0;
+std::mutex g_timing_mutex;              // guards g_slots' keys, stamps and event creation
+std::atomic<int> g_timing_level{0};     // 0 off, 1 streaming kernel, 2 also the whole sequence
+thread_local TimingSlot* t_last_slot = nullptr;   // the slot of this thread's last timed call
 
-int ensure_events(size_t pairs) {
-    if (!g_timing.begin) {
-        DC_HIP(hipEventCreate(&g_timing.begin));
-        DC_HIP(hipEventCreate(&g_timing.end));
+// The slot of `key` with at least `pairs` event pairs, marked in use by a new call; nullptr on a HIP error (reported
+// through *rc).
+TimingSlot* acquire_slot(const void* key, size_t pairs, int* rc) {
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    int device = 0;
+    (void)hipGetDevice(&device);
+    TimingSlot* slot = nullptr;
+    for (TimingSlot& s : g_slots)
+        if (s.key == key && s.device == device) { slot = &s; break; }
+    if (!slot) {
+        slot = &g_slots[0];
+        for (TimingSlot& s : g_slots)
+            if (s.stamp < slot->stamp) slot = &s;
+        if (slot->device != device && slot->begin) {           // events belong to the device that created them
+            (void)hipEventDestroy(slot->begin); (void)hipEventDestroy(slot->end);
+            for (hipEvent_t e : slot->scan) (void)hipEventDestroy(e);
+            slot->begin = slot->end = nullptr;
+            slot->scan.clear();
+        }
+        slot->key = key;
+        slot->device = device;
     }
-    while (g_timing.scan.size() < 2 * pairs) {
-        hipEvent_t e;
-        DC_HIP(hipEventCreate(&e));
-        g_timing.scan.push_back(e);
+    slot->stamp = ++g_slot_clock;
+    slot->valid = false;
+    slot->whole = g_timing_level.load() >= 2;
+    hipError_t e = hipSuccess;
+    if (!slot->begin) {
+        e = hipEventCreate(&slot->begin);
+        if (e == hipSuccess) e = hipEventCreate(&slot->end);
+    }
+    while (e == hipSuccess && slot->scan.size() < 2 * pairs) {
+        hipEvent_t ev;
+        e = hipEventCreate(&ev);
+        if (e == hipSuccess) slot->scan.push_back(ev);
+    }
+    if (e != hipSuccess) { *rc = device_error(e, "hipEventCreate"); return nullptr; }
+    slot->used_pairs = pairs;
+    t_last_slot = slot;
+    *rc = DC_OK;
+    return slot;
+}
+
+int slot_times(TimingSlot* slot, float* scan_ms, float* total_ms) {
+    if (!slot || !slot->valid || (total_ms && !slot->whole)) return DC_ERR_INVALID_ARG;
+    DC_HIP(hipEventSynchronize(slot->scan[2 * slot->used_pairs - 1]));
+    if (total_ms) {
+        DC_HIP(hipEventSynchronize(slot->end));
+        DC_HIP(hipEventElapsedTime(total_ms, slot->begin, slot->end));
+    }
+    if (scan_ms) {
+        float acc = 0.f;
+        for (size_t c = 0; c < slot->used_pairs; ++c) {
+            float ms = 0.f;
+            DC_HIP(hipEventElapsedTime(&ms, slot->scan[2 * c], slot->scan[2 * c + 1]));
+            acc += ms;
+        }
+        *scan_ms = acc;
     }
     return DC_OK;
 }
@@ -195,9 +266,12 @@ struct Resident {
     uint32_t wide_blocks;   // long rows only: the larger grid for threshold grids that cover much of the data (else = blocks)
 };
 
+std::mutex g_resident_mutex;             // guards g_resident
+
 Resident resident_blocks(const dc::Plan& p, bool trial = false) {
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return {DC_MAX_SCAN_BLOCKS, DC_MAX_SCAN_BLOCKS};
+    std::lock_guard<std::mutex> lock(g_resident_mutex);
     for (size_t i = 0; i < g_resident_used; ++i) {
         const ResidentKey& k = g_resident[i];
         if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == variant_of(p) && k.p2 == p.p2)
@@ -218,7 +292,18 @@ Resident resident_blocks(const dc::Plan& p, bool trial = false) {
     return {(uint32_t)(cus * per_cu), (uint32_t)(cus * wide_per_cu)};
 }
 
+// An error that an earlier, unrelated HIP call of this thread left behind must not be blamed on this call.
+void drop_stale_hip_error() { (void)hipGetLastError(); }
+
+// The status of the launches made since drop_stale_hip_error.
+int launches_ok(const char* what) {
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? DC_OK : device_error(e, what);
+}
+
 // ---- the enqueued sequence ---------------------------------------------------------------------
+// timed: bracket the kernels with the events of the workspace's timing slot.  Takes no lock while it enqueues:
+// calls with different workspaces may run on different threads and streams at the same time.
 int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, int64_t comm, int64_t* out_step_dev,
             int64_t* out_done_dev, unsigned char* ws, hipStream_t stream, bool timed) {
     dc::Plan p = plan;
@@ -252,30 +337,30 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
     uint32_t* hist_part = reinterpret_cast<uint32_t*>(ws + p.off_hist_part);
 
     const uint32_t chunks = (p.K + p.chunk - 1) / p.chunk;
+    TimingSlot* slot = nullptr;
     if (timed) {
-        int rc = ensure_events(chunks);
-        if (rc) return rc;
-        g_timing.used_pairs = chunks;
-        g_timing.valid = false;
-        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.begin, stream));
+        int rc = DC_OK;
+        slot = acquire_slot(ws, chunks, &rc);
+        if (!slot) return rc;
+        if (slot->whole) DC_HIP(hipEventRecord(slot->begin, stream));
     }
+    drop_stale_hip_error();
     dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, hist_total, 3 * p.p2, lat,
-                    (uint64_t)p.T * p.N, p.M, sample_rows, stream);
+                    (uint64_t)p.T * p.N, p.N, p.stride, p.M, sample_rows, stream);
     for (uint32_t c = 0; c < chunks; ++c) {
         const uint32_t chunk0 = c * p.chunk;
         const uint32_t kc = p.K - chunk0 < p.chunk ? p.K - chunk0 : p.chunk;
-        if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c], stream));
+        if (slot) DC_HIP(hipEventRecord(slot->scan[2 * c], stream));
         dc::launch_scan(p, lat, tau_u32 + chunk0, kc, unit_max, hist_part, status, stream);
-        if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c + 1], stream));
+        if (slot) DC_HIP(hipEventRecord(slot->scan[2 * c + 1], stream));
         dc::launch_reduce(p, hist_part, hist_total, unit_max, tau_u32 + chunk0, kc, trial_cnt, trial_sum, status, chunk0,
                           tau_sorted, pos, comm, out_step_dev, out_done_dev, chunk_step, chunk_done, stream);
     }
-    if (timed) {
-        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.end, stream));
-        g_timing.valid = true;
+    if (slot) {
+        if (slot->whole) DC_HIP(hipEventRecord(slot->end, stream));
+        slot->valid = true;
     }
-    DC_HIP(hipGetLastError());
-    return DC_OK;
+    return launches_ok("launch of the ranking, streaming or reduction kernel");
 }
 
 int compute_units() {
@@ -301,29 +386,29 @@ int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* tau
     uint32_t* pos = reinterpret_cast<uint32_t*>(ws + p.off_pos);
     double* partial = reinterpret_cast<double*>(ws + p.off_partial);
     const uint32_t chunks = (p.K + p.chunk - 1) / p.chunk;
+    TimingSlot* slot = nullptr;
     if (timed) {
-        int rc = ensure_events(chunks);
-        if (rc) return rc;
-        g_timing.used_pairs = chunks;
-        g_timing.valid = false;
-        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.begin, stream));
+        int rc = DC_OK;
+        slot = acquire_slot(ws, chunks, &rc);
+        if (!slot) return rc;
+        if (slot->whole) DC_HIP(hipEventRecord(slot->begin, stream));
     }
-    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, nullptr, 0, lat, (uint64_t)p.T * p.N, p.M,
-                    sample_rows, stream);
+    drop_stale_hip_error();
+    dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, nullptr, 0, lat, (uint64_t)p.T * p.N, p.N, p.stride,
+                    p.M, sample_rows, stream);
     for (uint32_t c = 0; c < chunks; ++c) {
         const uint32_t chunk0 = c * p.chunk;
         const uint32_t kc = p.K - chunk0 < p.chunk ? p.K - chunk0 : p.chunk;
-        if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c], stream));
+        if (slot) DC_HIP(hipEventRecord(slot->scan[2 * c], stream));
         dc::launch_trial_scan(p, lat, tau_u32 + chunk0, kc, comm_per_trial_dev, comm, partial, status, stream);
-        if (timed) DC_HIP(hipEventRecord(g_timing.scan[2 * c + 1], stream));
+        if (slot) DC_HIP(hipEventRecord(slot->scan[2 * c + 1], stream));
         dc::launch_speedup_finalize(p, partial, kc, chunk0, pos, status, tau_sorted, out_seff_dev, stream);
     }
-    if (timed) {
-        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.end, stream));
-        g_timing.valid = true;
+    if (slot) {
+        if (slot->whole) DC_HIP(hipEventRecord(slot->end, stream));
+        slot->valid = true;
     }
-    DC_HIP(hipGetLastError());
-    return DC_OK;
+    return launches_ok("launch of the ranking, per-iteration or finishing kernel");
 }
 
 int flags_to_status(uint32_t flags) {
@@ -337,13 +422,14 @@ bool sizes_ok(int64_t T, int64_t N, int64_t M, int64_t K, int64_t comm) {
     return T >= 1 && N >= 1 && M >= 1 && K >= 0 && K <= DC_MAX_THRESHOLDS && comm >= 0;
 }
 
-// cached allocation of the synchronous entry point
+// cached allocation of the synchronous entry points
+std::mutex g_cache_mutex;               // guards the cache and the staging buffer: the synchronous calls are serialised
 unsigned char* g_cache = nullptr;
 size_t g_cache_bytes = 0;
 int g_cache_device = -1;
 std::vector<unsigned char> g_staging;   // host side of the synchronous entry point's result copy
 
-// Grow (never shrink) the cached device allocation of the synchronous entry points.  Caller holds g_mutex.
+// Grow (never shrink) the cached device allocation of the synchronous entry points.  Caller holds g_cache_mutex.
 int ensure_cache(size_t need) {
     int device = 0;
     DC_HIP(hipGetDevice(&device));
@@ -364,12 +450,14 @@ int ensure_cache(size_t need) {
 // with that device current) is what kernels and copies are given.
 static __device__ __align__(256) unsigned char scratch[DC_STATIC_SCRATCH_BYTES];
 constexpr int SCRATCH_DEVICES = 64;
-unsigned char* g_scratch_ptr[SCRATCH_DEVICES] = {};        // guarded by g_mutex
+unsigned char* g_scratch_ptr[SCRATCH_DEVICES] = {};
+std::mutex g_scratch_mutex;             // guards g_scratch_ptr
 
 int scratch_pointer(unsigned char** out) {
     int device = 0;
     DC_HIP(hipGetDevice(&device));
     if (device < 0 || device >= SCRATCH_DEVICES) return DC_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
     if (!g_scratch_ptr[device]) {
         void* ptr = nullptr;
         const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
@@ -384,6 +472,8 @@ int scratch_pointer(unsigned char** out) {
     return DC_OK;
 }
 
+bool timing_on() { return g_timing_level.load() != 0; }
+
 }  // namespace
 
 extern "C" {
@@ -395,20 +485,27 @@ size_t dc_workspace_bytes(int64_t T, int64_t N, int64_t M, int64_t K) {
     return a.bytes > b.bytes ? a.bytes : b.bytes;
 }
 
-int dc_simulate_async(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus_dev, int64_t K,
-                      int64_t comm, int64_t* out_step_dev, int64_t* out_done_dev, void* workspace_dev,
-                      size_t workspace_bytes, void* stream) {
-    if (!sizes_ok(T, N, M, K, comm) || !lat) return DC_ERR_INVALID_ARG;
+int dc_simulate_strided_async(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t trial_stride,
+                              const int64_t* taus_dev, int64_t K, int64_t comm, int64_t* out_step_dev,
+                              int64_t* out_done_dev, void* workspace_dev, size_t workspace_bytes, void* stream) {
+    if (!sizes_ok(T, N, M, K, comm) || !lat || trial_stride < N * M) return DC_ERR_INVALID_ARG;
     if (K == 0) return DC_OK;
     if (!taus_dev || !out_step_dev || !out_done_dev || !workspace_dev) return DC_ERR_INVALID_ARG;
     if (((uintptr_t)lat & 3u) || ((uintptr_t)workspace_dev & 255u)) return DC_ERR_INVALID_ARG;
     dc::Plan p{};
     const bool aligned = ((uintptr_t)lat & 15u) == 0;
-    if (!make_plan(T, N, M, K, aligned, &p)) return DC_ERR_INVALID_ARG;
+    if (!make_plan(T, N, M, K, aligned, &p, trial_stride)) return DC_ERR_INVALID_ARG;
     if (workspace_bytes < p.bytes) return DC_ERR_INVALID_ARG;
-    std::lock_guard<std::mutex> lock(g_mutex);
     return enqueue(p, lat, taus_dev, comm, out_step_dev, out_done_dev, static_cast<unsigned char*>(workspace_dev),
-                   static_cast<hipStream_t>(stream), g_timing.enabled);
+                   static_cast<hipStream_t>(stream), timing_on());
+}
+
+int dc_simulate_async(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus_dev, int64_t K,
+                      int64_t comm, int64_t* out_step_dev, int64_t* out_done_dev, void* workspace_dev,
+                      size_t workspace_bytes, void* stream) {
+    if (T < 1 || N < 1 || M < 1 || N >= ((int64_t)1 << 31) || M >= ((int64_t)1 << 31)) return DC_ERR_INVALID_ARG;
+    return dc_simulate_strided_async(lat, T, N, M, N * M, taus_dev, K, comm, out_step_dev, out_done_dev, workspace_dev,
+                                     workspace_bytes, stream);
 }
 
 int dc_simulate_static(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus_dev, int64_t K,
@@ -424,7 +521,6 @@ int dc_simulate_static(const int32_t* lat, int64_t T, int64_t N, int64_t M, cons
                  p.bytes, (unsigned)DC_STATIC_SCRATCH_BYTES);
         return DC_ERR_INVALID_ARG;
     }
-    std::lock_guard<std::mutex> lock(g_mutex);
     unsigned char* ws = nullptr;
     int rc = scratch_pointer(&ws);
     if (rc) return rc;
@@ -433,7 +529,7 @@ int dc_simulate_static(const int32_t* lat, int64_t T, int64_t N, int64_t M, cons
     if (rc) return rc;
     if (out_status_dev) {
         dc::launch_export_status(reinterpret_cast<const uint32_t*>(ws + p.off_status), out_status_dev, s);
-        DC_HIP(hipGetLastError());
+        return launches_ok("launch of the status kernel");
     }
     return DC_OK;
 }
@@ -446,18 +542,18 @@ int dc_workspace_status(const void* workspace_dev, void* stream) {
     return flags_to_status(flags);
 }
 
-int dc_simulate(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus, int64_t K, int64_t comm,
-                int64_t* out_step, int64_t* out_done) {
-    if (!sizes_ok(T, N, M, K, comm) || !lat) return DC_ERR_INVALID_ARG;
+int dc_simulate_strided(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t trial_stride, const int64_t* taus,
+                        int64_t K, int64_t comm, int64_t* out_step, int64_t* out_done) {
+    if (!sizes_ok(T, N, M, K, comm) || !lat || trial_stride < N * M) return DC_ERR_INVALID_ARG;
     if (K == 0) return DC_OK;
     if (!taus || !out_step || !out_done || ((uintptr_t)lat & 3u)) return DC_ERR_INVALID_ARG;
     for (int64_t k = 0; k < K; ++k)
         if (taus[k] < 0) return DC_ERR_INVALID_ARG;
     dc::Plan p{};
     const bool aligned = ((uintptr_t)lat & 15u) == 0;
-    if (!make_plan(T, N, M, K, aligned, &p)) return DC_ERR_INVALID_ARG;
+    if (!make_plan(T, N, M, K, aligned, &p, trial_stride)) return DC_ERR_INVALID_ARG;
 
-    std::lock_guard<std::mutex> lock(g_mutex);
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
     // cached allocation: thresholds | step | done | workspace (whose first word is the status): the two result
     // arrays are adjacent, so one copy brings both back
     const size_t io_bytes = align256((size_t)K * 8);
@@ -472,7 +568,7 @@ int dc_simulate(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64
 
     hipStream_t stream = nullptr;
     DC_HIP(hipMemcpy(taus_dev, taus, (size_t)K * 8, hipMemcpyHostToDevice));
-    int rc = enqueue(p, lat, taus_dev, comm, step_dev, done_dev, ws, stream, g_timing.enabled);
+    int rc = enqueue(p, lat, taus_dev, comm, step_dev, done_dev, ws, stream, timing_on());
     if (rc) return rc;
     // results and status word in one device-to-host copy (it also waits for the kernels)
     g_staging.resize(2 * io_bytes + 256);
@@ -484,6 +580,12 @@ int dc_simulate(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64
     memcpy(out_step, g_staging.data(), (size_t)K * 8);
     memcpy(out_done, g_staging.data() + io_bytes, (size_t)K * 8);
     return DC_OK;
+}
+
+int dc_simulate(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus, int64_t K, int64_t comm,
+                int64_t* out_step, int64_t* out_done) {
+    if (T < 1 || N < 1 || M < 1 || N >= ((int64_t)1 << 31) || M >= ((int64_t)1 << 31)) return DC_ERR_INVALID_ARG;
+    return dc_simulate_strided(lat, T, N, M, N * M, taus, K, comm, out_step, out_done);
 }
 
 size_t dc_speedup_workspace_bytes(int64_t T, int64_t N, int64_t M, int64_t K) {
@@ -501,10 +603,8 @@ int dc_speedup_per_step_async(const int32_t* lat, int64_t T, int64_t N, int64_t 
     dc::Plan p{};
     if (!make_trial_plan(T, N, M, K, ((uintptr_t)lat & 15u) == 0, &p)) return DC_ERR_INVALID_ARG;
     if (workspace_bytes < p.bytes) return DC_ERR_INVALID_ARG;
-    std::lock_guard<std::mutex> lock(g_mutex);
     return enqueue_speedup(p, lat, taus_dev, comm, comm_per_trial_dev, out_seff_dev,
-                           static_cast<unsigned char*>(workspace_dev), static_cast<hipStream_t>(stream),
-                           g_timing.enabled);
+                           static_cast<unsigned char*>(workspace_dev), static_cast<hipStream_t>(stream), timing_on());
 }
 
 int dc_speedup_per_step(const int32_t* lat, int64_t T, int64_t N, int64_t M, const int64_t* taus, int64_t K,
@@ -520,7 +620,7 @@ int dc_speedup_per_step(const int32_t* lat, int64_t T, int64_t N, int64_t M, con
     dc::Plan p{};
     if (!make_trial_plan(T, N, M, K, ((uintptr_t)lat & 15u) == 0, &p)) return DC_ERR_INVALID_ARG;
 
-    std::lock_guard<std::mutex> lock(g_mutex);
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
     const size_t tau_bytes = align256((size_t)K * 8), comm_bytes = comm_per_trial ? align256((size_t)T * 8) : 0;
     int rc = ensure_cache(2 * tau_bytes + comm_bytes + p.bytes);
     if (rc) return rc;
@@ -531,7 +631,7 @@ int dc_speedup_per_step(const int32_t* lat, int64_t T, int64_t N, int64_t M, con
     hipStream_t stream = nullptr;
     DC_HIP(hipMemcpy(taus_dev, taus, (size_t)K * 8, hipMemcpyHostToDevice));
     if (comm_dev) DC_HIP(hipMemcpy(comm_dev, comm_per_trial, (size_t)T * 8, hipMemcpyHostToDevice));
-    rc = enqueue_speedup(p, lat, taus_dev, comm, comm_dev, seff_dev, ws, stream, g_timing.enabled);
+    rc = enqueue_speedup(p, lat, taus_dev, comm, comm_dev, seff_dev, ws, stream, timing_on());
     if (rc) return rc;
     DC_HIP(hipStreamSynchronize(stream));
     uint32_t flags = 0;
@@ -547,7 +647,7 @@ int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t* out
     if (!lat || T < 1 || N < 1 || M < 1 || ((uintptr_t)lat & 3u)) return DC_ERR_INVALID_ARG;
     if ((long double)T * (long double)N * (long double)M >= 4.6e18L) return DC_ERR_INVALID_ARG;
     const uint64_t n = (uint64_t)T * (uint64_t)N * (uint64_t)M;
-    std::lock_guard<std::mutex> lock(g_mutex);
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
     const uint32_t grid = (uint32_t)compute_units() * 2u;        // 8 waves per compute unit saturate a plain read
     const size_t partial_bytes = align256((size_t)grid * 4 * 8);
     int rc = ensure_cache(256 + 256 + partial_bytes);
@@ -556,25 +656,28 @@ int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t* out
     unsigned long long* result = reinterpret_cast<unsigned long long*>(g_cache + 256);
     unsigned long long* partial = reinterpret_cast<unsigned long long*>(g_cache + 512);
     hipStream_t stream = nullptr;
-    const bool timed = g_timing.enabled;
-    if (timed) {
-        rc = ensure_events(1);
-        if (rc) return rc;
-        g_timing.used_pairs = 1;
-        g_timing.valid = false;
-        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.begin, stream));
-        DC_HIP(hipEventRecord(g_timing.scan[0], stream));
+    TimingSlot* slot = nullptr;
+    if (timing_on()) {
+        slot = acquire_slot(g_cache, 1, &rc);
+        if (!slot) return rc;
+        if (slot->whole) DC_HIP(hipEventRecord(slot->begin, stream));
+        DC_HIP(hipEventRecord(slot->scan[0], stream));
     }
+    drop_stale_hip_error();
     dc::launch_moments(lat, n, grid, partial, result, status, stream);
-    if (timed) {
-        DC_HIP(hipEventRecord(g_timing.scan[1], stream));
-        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.end, stream));
-        g_timing.valid = true;
+    if (slot) {
+        DC_HIP(hipEventRecord(slot->scan[1], stream));
+        if (slot->whole) DC_HIP(hipEventRecord(slot->end, stream));
+        slot->valid = true;
     }
-    DC_HIP(hipGetLastError());
+    rc = launches_ok("launch of the moments kernels");
+    if (rc) return rc;
     unsigned long long host[4] = {0, 0, 0, 0};
     DC_HIP(hipMemcpy(host, result, sizeof(host), hipMemcpyDeviceToHost));
     if (host[3] & 0x80000000ull) return DC_ERR_NEGATIVE_LATENCY;
+    // The sum is kept in 64 bits.  host[3] is the OR of all latencies, hence at least the largest one: when
+    // n * host[3] stays below 2^63 the sum cannot have wrapped; otherwise that cannot be told and the call refuses.
+    if ((unsigned __int128)n * (unsigned __int128)host[3] >= ((unsigned __int128)1 << 63)) return DC_ERR_RANGE;
     if (out_sum) *out_sum = (int64_t)host[0];
     if (out_sumsq) { out_sumsq[0] = host[1]; out_sumsq[1] = host[2]; }
     const unsigned __int128 sq = ((unsigned __int128)host[2] << 64) | host[1];
@@ -593,56 +696,75 @@ int dc_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t* out
     return DC_OK;
 }
 
-int dc_worker_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t* out_sum, uint64_t* out_sumsq,
-                      double* out_mean, double* out_variance) {
-    if (!lat || ((uintptr_t)lat & 3u) || N > (int64_t)DC_MAX_STAT_WORKERS) return DC_ERR_INVALID_ARG;
-    dc::Plan p{};
-    if (!make_trial_plan(T, N, M, 1, ((uintptr_t)lat & 15u) == 0, &p)) return DC_ERR_INVALID_ARG;
-    std::lock_guard<std::mutex> lock(g_mutex);
-    const uint32_t want = (uint32_t)compute_units() * 2u;             // 2 x 60 KiB of LDS always fit
-    if (p.grid > want) p.grid = want;
-    const size_t row_bytes = (size_t)N * 3 * 8;
-    int rc = ensure_cache(256 + align256(row_bytes) + align256((size_t)p.grid * row_bytes));
-    if (rc) return rc;
-    uint32_t* status = reinterpret_cast<uint32_t*>(g_cache);
-    unsigned long long* result = reinterpret_cast<unsigned long long*>(g_cache + 256);
-    unsigned long long* partial = reinterpret_cast<unsigned long long*>(g_cache + 256 + align256(row_bytes));
-    hipStream_t stream = nullptr;
-    const bool timed = g_timing.enabled;
-    if (timed) {
-        rc = ensure_events(1);
-        if (rc) return rc;
-        g_timing.used_pairs = 1;
-        g_timing.valid = false;
-        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.begin, stream));
+int dc_worker_moments_strided(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t trial_stride,
+                              int64_t* out_sum, uint64_t* out_sumsq, double* out_mean, double* out_variance) {
+    if (!lat || ((uintptr_t)lat & 3u) || N < 1 || M < 1 || trial_stride < N * M) return DC_ERR_INVALID_ARG;
+    {
+        dc::Plan whole{};
+        if (!make_trial_plan(T, N, M, 1, false, &whole, trial_stride)) return DC_ERR_INVALID_ARG;
     }
-    dc::launch_worker_totals(p, lat, partial, result, status, stream, timed ? g_timing.scan[0] : nullptr,
-                             timed ? g_timing.scan[1] : nullptr);
-    if (timed) {
-        if (g_timing.whole) DC_HIP(hipEventRecord(g_timing.end, stream));
-        g_timing.valid = true;
-    }
-    DC_HIP(hipGetLastError());
-    uint32_t flags = 0;
-    DC_HIP(hipMemcpy(&flags, status, sizeof(flags), hipMemcpyDeviceToHost));
-    rc = flags_to_status(flags);
-    if (rc) return rc;
-    std::vector<unsigned long long> host((size_t)N * 3);
-    DC_HIP(hipMemcpy(host.data(), result, row_bytes, hipMemcpyDeviceToHost));
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
     const long double tl = (long double)T;
-    for (int64_t n = 0; n < N; ++n) {
-        const unsigned long long sum = host[n], lo = host[N + n], hi = host[2 * N + n];
-        if (out_sum) out_sum[n] = (int64_t)sum;
-        if (out_sumsq) { out_sumsq[2 * n] = lo; out_sumsq[2 * n + 1] = hi; }
-        if (out_mean) out_mean[n] = (double)((long double)sum / tl);
-        if (out_variance) {
-            // (sumsq*T - sum^2) / T^2: sumsq < 2^93 and T < 2^31, so the numerator is exact in 128 bits
-            const unsigned __int128 sq = ((unsigned __int128)hi << 64) | lo;
-            const unsigned __int128 num = sq * (unsigned __int128)T - (unsigned __int128)sum * sum;
-            out_variance[n] = (double)((long double)num / (tl * tl));
+    hipStream_t stream = nullptr;
+    bool first_pass = true;
+    // The accumulators of all workers of a pass live in LDS, so more than DC_MAX_STAT_WORKERS workers are taken in
+    // several passes over lat, each over a range of workers of every trial (a pass reads only its workers' rows).
+    for (int64_t n0 = 0; n0 < N; n0 += (int64_t)DC_MAX_STAT_WORKERS) {
+        const int64_t nc = N - n0 < (int64_t)DC_MAX_STAT_WORKERS ? N - n0 : (int64_t)DC_MAX_STAT_WORKERS;
+        const int32_t* base = lat + n0 * M;
+        dc::Plan p{};
+        if (!make_trial_plan(T, nc, M, 1, ((uintptr_t)base & 15u) == 0, &p, trial_stride)) return DC_ERR_INVALID_ARG;
+        const uint32_t want = (uint32_t)compute_units() * 2u;             // 2 x 60 KiB of LDS always fit
+        if (p.grid > want) p.grid = want;
+        const size_t row_bytes = (size_t)nc * 3 * 8;
+        int rc = ensure_cache(256 + align256(row_bytes) + align256((size_t)p.grid * row_bytes));
+        if (rc) return rc;
+        uint32_t* status = reinterpret_cast<uint32_t*>(g_cache);
+        unsigned long long* result = reinterpret_cast<unsigned long long*>(g_cache + 256);
+        unsigned long long* partial = reinterpret_cast<unsigned long long*>(g_cache + 256 + align256(row_bytes));
+        TimingSlot* slot = nullptr;
+        if (timing_on() && first_pass) {                                   // the first pass is the one that is timed
+            slot = acquire_slot(g_cache, 1, &rc);
+            if (!slot) return rc;
+            if (slot->whole) DC_HIP(hipEventRecord(slot->begin, stream));
+        }
+        first_pass = false;
+        drop_stale_hip_error();
+        dc::launch_worker_totals(p, base, partial, result, status, stream, slot ? slot->scan[0] : nullptr,
+                                 slot ? slot->scan[1] : nullptr);
+        if (slot) {
+            if (slot->whole) DC_HIP(hipEventRecord(slot->end, stream));
+            slot->valid = true;
+        }
+        rc = launches_ok("launch of the per-worker kernels");
+        if (rc) return rc;
+        uint32_t flags = 0;
+        DC_HIP(hipMemcpy(&flags, status, sizeof(flags), hipMemcpyDeviceToHost));
+        rc = flags_to_status(flags);
+        if (rc) return rc;
+        std::vector<unsigned long long> host((size_t)nc * 3);
+        DC_HIP(hipMemcpy(host.data(), result, row_bytes, hipMemcpyDeviceToHost));
+        for (int64_t i = 0; i < nc; ++i) {
+            const int64_t n = n0 + i;
+            const unsigned long long sum = host[i], lo = host[nc + i], hi = host[2 * nc + i];
+            if (out_sum) out_sum[n] = (int64_t)sum;
+            if (out_sumsq) { out_sumsq[2 * n] = lo; out_sumsq[2 * n + 1] = hi; }
+            if (out_mean) out_mean[n] = (double)((long double)sum / tl);
+            if (out_variance) {
+                // (sumsq*T - sum^2) / T^2: sumsq < 2^93 and T < 2^31, so the numerator is exact in 128 bits
+                const unsigned __int128 sq = ((unsigned __int128)hi << 64) | lo;
+                const unsigned __int128 num = sq * (unsigned __int128)T - (unsigned __int128)sum * sum;
+                out_variance[n] = (double)((long double)num / (tl * tl));
+            }
         }
     }
     return DC_OK;
+}
+
+int dc_worker_moments(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t* out_sum, uint64_t* out_sumsq,
+                      double* out_mean, double* out_variance) {
+    if (N < 1 || M < 1 || N >= ((int64_t)1 << 31) || M >= ((int64_t)1 << 31)) return DC_ERR_INVALID_ARG;
+    return dc_worker_moments_strided(lat, T, N, M, N * M, out_sum, out_sumsq, out_mean, out_variance);
 }
 
 namespace {
@@ -682,7 +804,7 @@ int dc_analytic_curves(double mu, double sigma2, int64_t N, int64_t M, const int
     for (int64_t k = 0; k < K; ++k)
         if (taus[k] < 0) return DC_ERR_INVALID_ARG;
 
-    std::lock_guard<std::mutex> lock(g_mutex);
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
     const size_t io = align256((size_t)K * 8);
     int rc = ensure_cache(2 * io);
     if (rc) return rc;
@@ -690,8 +812,10 @@ int dc_analytic_curves(double mu, double sigma2, int64_t N, int64_t M, const int
     double* edone_dev = reinterpret_cast<double*>(g_cache + io);
     hipStream_t stream = nullptr;
     DC_HIP(hipMemcpy(taus_dev, taus, (size_t)K * 8, hipMemcpyHostToDevice));
+    drop_stale_hip_error();
     dc::launch_expected_done(taus_dev, (uint32_t)K, (uint32_t)M, mu, sigma2, edone_dev, stream);
-    DC_HIP(hipGetLastError());
+    rc = launches_ok("launch of the expected-completions kernel");
+    if (rc) return rc;
     DC_HIP(hipMemcpy(out_edone, edone_dev, (size_t)K * 8, hipMemcpyDeviceToHost));
 
     const double et = mean_tmax >= 0.0 ? mean_tmax : et_model;
@@ -742,31 +866,27 @@ int dc_select_tau_per_step(const double* seff, const int64_t* taus, int64_t K, i
 }
 
 int dc_set_kernel_timing(int enable) {
-    std::lock_guard<std::mutex> lock(g_mutex);
-    g_timing.enabled = enable != 0;
-    g_timing.whole = enable >= 2;
-    g_timing.valid = false;
+    g_timing_level.store(enable <= 0 ? 0 : (enable >= 2 ? 2 : 1));
+    t_last_slot = nullptr;
     return DC_OK;
 }
 
 int dc_last_kernel_ms(float* scan_ms, float* total_ms) {
-    std::lock_guard<std::mutex> lock(g_mutex);
-    if (!g_timing.enabled || !g_timing.valid || (total_ms && !g_timing.whole)) return DC_ERR_INVALID_ARG;
-    DC_HIP(hipEventSynchronize(g_timing.scan[2 * g_timing.used_pairs - 1]));
-    if (total_ms) {
-        DC_HIP(hipEventSynchronize(g_timing.end));
-        DC_HIP(hipEventElapsedTime(total_ms, g_timing.begin, g_timing.end));
+    if (!timing_on()) return DC_ERR_INVALID_ARG;
+    return slot_times(t_last_slot, scan_ms, total_ms);
+}
+
+int dc_workspace_kernel_ms(const void* workspace_dev, float* scan_ms, float* total_ms) {
+    if (!workspace_dev || !timing_on()) return DC_ERR_INVALID_ARG;
+    TimingSlot* slot = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_timing_mutex);
+        int device = 0;
+        (void)hipGetDevice(&device);
+        for (TimingSlot& s : g_slots)
+            if (s.key == workspace_dev && s.device == device) slot = &s;
     }
-    if (scan_ms) {
-        float acc = 0.f;
-        for (size_t c = 0; c < g_timing.used_pairs; ++c) {
-            float ms = 0.f;
-            DC_HIP(hipEventElapsedTime(&ms, g_timing.scan[2 * c], g_timing.scan[2 * c + 1]));
-            acc += ms;
-        }
-        *scan_ms = acc;
-    }
-    return DC_OK;
+    return slot_times(slot, scan_ms, total_ms);
 }
 
 const char* dc_status_string(int status) {
@@ -784,13 +904,21 @@ const char* dc_status_string(int status) {
 const char* dc_last_device_error(void) { return g_error_text; }
 
 void dc_shutdown(void) {
-    std::lock_guard<std::mutex> lock(g_mutex);
-    if (g_cache) { (void)hipFree(g_cache); g_cache = nullptr; g_cache_bytes = 0; g_cache_device = -1; }
-    if (g_timing.begin) { (void)hipEventDestroy(g_timing.begin); g_timing.begin = nullptr; }
-    if (g_timing.end) { (void)hipEventDestroy(g_timing.end); g_timing.end = nullptr; }
-    for (hipEvent_t e : g_timing.scan) (void)hipEventDestroy(e);
-    g_timing.scan.clear();
-    g_timing.valid = false;
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        if (g_cache) { (void)hipFree(g_cache); g_cache = nullptr; g_cache_bytes = 0; g_cache_device = -1; }
+    }
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    for (TimingSlot& s : g_slots) {
+        if (s.begin) { (void)hipEventDestroy(s.begin); s.begin = nullptr; }
+        if (s.end) { (void)hipEventDestroy(s.end); s.end = nullptr; }
+        for (hipEvent_t e : s.scan) (void)hipEventDestroy(e);
+        s.scan.clear();
+        s.key = nullptr;
+        s.valid = false;
+        s.stamp = 0;
+    }
+    t_last_slot = nullptr;
 }
 
 }  // extern "C"

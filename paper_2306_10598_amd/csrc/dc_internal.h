@@ -55,6 +55,8 @@ namespace dc {
 struct Plan {
     uint32_t T, N, M, K;
     uint64_t elements;          // T*N*M
+    uint64_t stride;            // elements from one trial to the next (N*M when the tensor is contiguous)
+    uint64_t extent;            // elements from the first one of the tensor to its last: (T-1)*stride + N*M
     bool vec4;                  // 16-byte loads, whole rows per load (M a multiple of 4 up to 128, or 256; lat 16-byte aligned)
     uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; otherwise rows per unit
     uint32_t units_per_trial;
@@ -73,7 +75,8 @@ struct Plan {
 
 void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t* tau_u32, uint32_t* pos,
                  uint32_t* status, unsigned long long* bins, uint32_t bins_words, const int32_t* lat,
-                 uint64_t rows_total, uint32_t M, uint32_t sample_rows, hipStream_t stream);
+                 uint64_t rows_total, uint32_t N, uint64_t trial_stride, uint32_t M, uint32_t sample_rows,
+                 hipStream_t stream);
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
                  uint32_t* hist_part, uint32_t* status, hipStream_t stream);
 void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long* hist_total,

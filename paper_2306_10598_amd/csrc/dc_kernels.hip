@@ -340,7 +340,8 @@ struct Sample {
 
 __device__ __forceinline__ Sample sample_begin(const int64_t* __restrict__ taus, uint32_t K,
                                                const int32_t* __restrict__ lat, unsigned long long rows_total,
-                                               uint32_t M, uint32_t sample_rows) {
+                                               uint32_t N, unsigned long long trial_stride, uint32_t M,
+                                               uint32_t sample_rows) {
     constexpr int PER_WAVE = DC_SAMPLE_ROWS / 4;
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     Sample sm;
@@ -351,7 +352,8 @@ __device__ __forceinline__ Sample sample_begin(const int64_t* __restrict__ taus,
         const uint32_t sidx = wave * PER_WAVE + (uint32_t)q;
         const unsigned long long row = rows_total / sample_rows * sidx + rows_total % sample_rows * sidx / sample_rows;
         sm.x[q] = u32x4{0u, 0u, 0u, 0u};
-        if (sidx < sample_rows && lane < M / 4u) sm.x[q] = *(reinterpret_cast<const u32x4*>(lat + row * M) + lane);
+        const unsigned long long at = row / N * trial_stride + row % N * M;        // row = trial * N + worker
+        if (sidx < sample_rows && lane < M / 4u) sm.x[q] = *(reinterpret_cast<const u32x4*>(lat + at) + lane);
     }
     return sm;
 }
@@ -395,7 +397,8 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
                     int64_t* __restrict__ tau_sorted, uint32_t* __restrict__ tau_u32,
                     uint32_t* __restrict__ pos, uint32_t* __restrict__ status,
                     unsigned long long* __restrict__ bins, uint32_t bins_words,
-                    const int32_t* __restrict__ lat, unsigned long long rows_total, uint32_t M, uint32_t sample_rows) {
+                    const int32_t* __restrict__ lat, unsigned long long rows_total, uint32_t N,
+                    unsigned long long trial_stride, uint32_t M, uint32_t sample_rows) {
     // A block ranks 32 thresholds; the comparisons of each are split over 8 threads.
     constexpr uint32_t TILE = 1024;
     __shared__ int64_t tile[TILE];
@@ -406,7 +409,7 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
     // shapes to use; its loads are issued here and used after the ranking.
     const bool sampling = blockIdx.x == 0 && sample_rows != 0u;
     Sample sm{};
-    if (sampling) sm = sample_begin(taus, K, lat, rows_total, M, sample_rows);
+    if (sampling) sm = sample_begin(taus, K, lat, rows_total, N, trial_stride, M, sample_rows);
     if (gid == 0) { status[0] = 0u; status[2] = 0u; }   // value flags (set by later kernels) and the reduce kernel's ticket
     for (uint32_t i = gid; i < bins_words; i += stride) bins[i] = 0ull;
     const uint32_t jj = threadIdx.x & 31u, part = threadIdx.x >> 5;
@@ -569,7 +572,7 @@ __device__ __forceinline__ void report_range(uint32_t check, uint32_t max_latenc
 // in the loop is one barrier per unit that keeps the block's waves in step.
 template <int L, int SHAPE>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
-void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t units, uint32_t units_per_trial,
+void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride, uint32_t N, uint32_t units, uint32_t units_per_trial,
                          uint32_t run, uint32_t loads_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
                          uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
                          uint32_t* __restrict__ status, uint32_t max_latency, uint32_t lanes_per_row) {
@@ -602,7 +605,7 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t N, uint32_t u
             const uint32_t rows_left = N - row0;
             const uint32_t rows = rows_left < loads_per_unit * R ? rows_left : loads_per_unit * R;
             const uint32_t nfull = rows / R;
-            const u32x4* base = reinterpret_cast<const u32x4*>(lat + ((uint64_t)t * N + row0) * M) + lane;
+            const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)row0 * M) + lane;
             st.lane_max = 0u;
             stream_rows<L>(st, base, nfull, rows - nfull * R, queue, g, lane, shape);
             const uint32_t m = wave_max(st.lane_max);
@@ -906,7 +909,7 @@ __device__ __forceinline__ void flat_count(WaveState& st, uint4 p, uint32_t vm, 
 
 template <int MS>        // 0: rows of at least 4 elements; 1, 2, 3: rows of exactly that many
 __global__ __launch_bounds__(DC_SCAN_THREADS)
-void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint32_t N, uint32_t M, uint32_t units,
+void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint64_t trial_stride, uint32_t N, uint32_t M, uint32_t units,
                          uint32_t units_per_trial, uint32_t run, uint32_t rows_per_unit, const uint32_t* __restrict__ tau_chunk,
                          uint32_t kc, uint32_t p2, uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
                          uint32_t* __restrict__ status, uint32_t max_latency) {
@@ -930,7 +933,7 @@ void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint32
             const uint32_t row0 = j * rows_per_unit;
             const uint32_t rows = (N - row0) < rows_per_unit ? (N - row0) : rows_per_unit;
             st.lane_max = 0u;
-            flat_stream_unit<(MS != 0), DC_FLAT_UNROLL, MS>(st.check, f, ((uint64_t)t * N + row0) * M, rows * M, lane,
+            flat_stream_unit<(MS != 0), DC_FLAT_UNROLL, MS>(st.check, f, (uint64_t)t * trial_stride + (uint64_t)row0 * M, rows * M, lane,
                                     [&](uint4 p, uint32_t vm, uint32_t, uint32_t) { flat_count(st, p, vm, queue, g, lane); });
             const uint32_t m = wave_max(st.lane_max);
             if (lane == 0) unit_max[u] = m;
@@ -1326,7 +1329,7 @@ __device__ __forceinline__ void add_worker_total(unsigned long long* acc, uint32
 
 template <int L>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
-void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N,
+void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride, uint32_t T, uint32_t N,
                                   unsigned long long* __restrict__ partial, uint32_t* __restrict__ status,
                                   uint32_t max_latency, uint32_t lanes_per_row) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -1346,7 +1349,7 @@ void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, u
     const uint32_t hi = (uint32_t)((uint64_t)nfull * (wave + 1) / DC_SCAN_WAVES);
     uint32_t check = 0u;
     for (uint32_t t = blockIdx.x; t < T; t += gridDim.x) {
-        const u32x4* base = reinterpret_cast<const u32x4*>(lat + ((uint64_t)t * N + (uint64_t)lo * R) * M) + lane;
+        const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)lo * R * M) + lane;
         uint32_t i = 0;
         for (; i + U <= hi - lo; i += U) {
             u32x4 x[U];
@@ -1387,8 +1390,8 @@ void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, u
 // Wave w takes units w, w + 4, ... of every trial, so a worker's accumulators always belong to the same wave.
 template <bool SMALL>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
-void dc_worker_totals_flat_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N, uint32_t M,
-                                  uint32_t rows_per_unit, unsigned long long* __restrict__ partial,
+void dc_worker_totals_flat_kernel(const int32_t* __restrict__ lat, uint64_t extent, uint64_t trial_stride, uint32_t T,
+                                  uint32_t N, uint32_t M, uint32_t rows_per_unit, unsigned long long* __restrict__ partial,
                                   uint32_t* __restrict__ status, uint32_t max_latency) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
@@ -1396,7 +1399,7 @@ void dc_worker_totals_flat_kernel(const int32_t* __restrict__ lat, uint32_t T, u
     __syncthreads();
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const FlatTensor f = flat_tensor(lat, (uint64_t)T * N * M, M);
+    const FlatTensor f = flat_tensor(lat, extent, M);
     const uint32_t n_units = (N + rows_per_unit - 1) / rows_per_unit;
     uint32_t check = 0u;
     for (uint32_t t = blockIdx.x; t < T; t += gridDim.x)
@@ -1404,7 +1407,7 @@ void dc_worker_totals_flat_kernel(const int32_t* __restrict__ lat, uint32_t T, u
             const uint32_t row0 = j * rows_per_unit;
             const uint32_t rows = (N - row0) < rows_per_unit ? (N - row0) : rows_per_unit;
             // few waves per compute unit here (the accumulators fill the LDS), so more loads in flight per lane
-            flat_stream_unit<SMALL, DC_SCAN_UNROLL>(check, f, ((uint64_t)t * N + row0) * M, rows * M, lane,
+            flat_stream_unit<SMALL, DC_SCAN_UNROLL>(check, f, (uint64_t)t * trial_stride + (uint64_t)row0 * M, rows * M, lane,
                                                     [&](uint4 p, uint32_t vm, uint32_t pos0, uint32_t row) {
                 const uint32_t val[4] = {p.x, p.y, p.z, p.w};
                 if constexpr (SMALL) {
@@ -1452,12 +1455,14 @@ namespace dc {
 // sample_rows > 0: also sample that many rows of lat ([rows_total][M]) for the choice of the launch shape
 void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t* tau_u32, uint32_t* pos,
                  uint32_t* status, unsigned long long* bins, uint32_t bins_words, const int32_t* lat,
-                 uint64_t rows_total, uint32_t M, uint32_t sample_rows, hipStream_t stream) {
+                 uint64_t rows_total, uint32_t N, uint64_t trial_stride, uint32_t M, uint32_t sample_rows,
+                 hipStream_t stream) {
     const uint32_t threads = 256;                 // 32 thresholds per block
     uint32_t blocks = (K + 31) / 32;
     if (blocks == 0) blocks = 1;
     hipLaunchKernelGGL(dc_prep_kernel, dim3(blocks), dim3(threads), 0, stream, taus, K, tau_sorted, tau_u32, pos,
-                       status, bins, bins_words, lat, (unsigned long long)rows_total, M, sample_rows);
+                       status, bins, bins_words, lat, (unsigned long long)rows_total, N ? N : 1u,
+                       (unsigned long long)trial_stride, M, sample_rows);
 }
 
 size_t scan_lds_bytes(const Plan& p) {
@@ -1504,16 +1509,16 @@ static void launch_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_c
     if (p.grid_wide > p.grid) {                     // the sample decides on the device which of the two launches works
         if constexpr (L == 32 || L == 64) {
             hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 1>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
-                               lat, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max,
+                               lat, p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max,
                                hist_part, status, p.max_latency, p.M / 4);
             hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 2>), dim3(p.grid_wide), dim3(DC_SCAN_THREADS), scan_lds_bytes(p),
-                               stream, lat, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2,
+                               stream, lat, p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2,
                                unit_max, hist_part, status, p.max_latency, p.M / 4);
             return;
         }
     }
     hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 0>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
-                       p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max, hist_part,
+                       p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max, hist_part,
                        status, p.max_latency, p.M / 4);
 }
 
@@ -1521,7 +1526,7 @@ template <int MS>
 static void launch_flat(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                         uint32_t* unit_max, uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
     hipLaunchKernelGGL(dc_scan_flat_kernel<MS>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
-                       (uint64_t)p.elements, p.N, p.M, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2,
+                       p.extent, p.stride, p.N, p.M, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2,
                        unit_max, hist_part, status, p.max_latency);
 }
 
@@ -1678,7 +1683,7 @@ template <int L>
 static void launch_worker_vec4(const Plan& p, const int32_t* lat, unsigned long long* partial, uint32_t* status,
                                hipStream_t stream) {
     hipLaunchKernelGGL(dc_worker_totals_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS), (size_t)p.N * 24, stream,
-                       lat, p.T, p.N, partial, status, p.max_latency, p.M / 4);
+                       lat, p.stride, p.T, p.N, partial, status, p.max_latency, p.M / 4);
 }
 
 // partial: [grid][3][N] u64; result: [3][N] u64 (sum, squares low, squares high per worker)
@@ -1691,10 +1696,12 @@ void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long*
     if (!p.vec4) {
         if (p.M < 4)
             hipLaunchKernelGGL(dc_worker_totals_flat_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS),
-                               (size_t)p.N * 24, stream, lat, p.T, p.N, p.M, p.per_unit, partial, status, p.max_latency);
+                               (size_t)p.N * 24, stream, lat, p.extent, p.stride, p.T, p.N, p.M, p.per_unit, partial, status,
+                               p.max_latency);
         else
             hipLaunchKernelGGL(dc_worker_totals_flat_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS),
-                               (size_t)p.N * 24, stream, lat, p.T, p.N, p.M, p.per_unit, partial, status, p.max_latency);
+                               (size_t)p.N * 24, stream, lat, p.extent, p.stride, p.T, p.N, p.M, p.per_unit, partial, status,
+                               p.max_latency);
     } else {
         switch (p.M / 4) {
             case 1:  launch_worker_vec4<1>(p, lat, partial, status, stream); break;

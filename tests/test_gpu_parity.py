@@ -538,8 +538,104 @@ def test_worker_moments_of_a_workload_and_errors(dev):
     with pytest.raises(dc.DcError) as e:
         dc.dc_worker_moments(to_dev(bad, dev))
     assert e.value.status == dc.DC_ERR_NEGATIVE_LATENCY
-    with pytest.raises(dc.DcError):
-        dc.dc_worker_moments(torch.zeros((1, 2561, 4), dtype=torch.int32, device=dev))
+
+
+def test_worker_moments_of_more_workers_than_one_pass_holds(dev):
+    """The accumulators of 2560 workers fill the LDS; more workers take several passes over their rows."""
+    rng = np.random.default_rng(44)
+    for shape in ((5, 6000, 4), (3, 2561, 7), (2, 5121, 1)):
+        lat = rng.integers(0, (2**31 - 1) // shape[2] + 1, size=shape, dtype=np.int32)
+        sums, squares, mean, var = oracle.worker_moments(lat)
+        gs, gq, gmean, gvar = dc.dc_worker_moments(to_dev(lat, dev))
+        assert gs == sums and gq == squares, shape
+        assert np.allclose(gmean, mean, rtol=1e-14) and np.allclose(gvar, var, rtol=1e-12, atol=0)
+
+
+# ---- a range of workers of a resident tensor, without a copy (trial stride) -----------------------------------
+
+@pytest.mark.parametrize("shape,ranges", [
+    ((9, 64, 32), [(0, 64), (0, 17), (5, 40), (63, 64)]),          # whole rows per load; every start is 16-byte aligned
+    ((7, 50, 128), [(0, 8), (3, 50)]),                             # long rows, two launch shapes
+    ((6, 40, 12), [(0, 9), (7, 33)]),                              # three lanes per row
+    ((8, 33, 7), [(0, 33), (0, 5), (2, 30), (32, 33)]),            # odd rows, odd stride: the kernel for any alignment
+    ((5, 21, 1), [(0, 8), (1, 20)]),
+    ((4, 10, 257), [(0, 3), (4, 9)]),
+    ((3, 2100, 256), [(0, 2048), (52, 2100)]),
+])
+def test_worker_ranges_of_a_resident_tensor(shape, ranges, dev):
+    rng = np.random.default_rng(sum(shape))
+    lat = rng.integers(0, 4000, size=shape, dtype=np.int32)
+    lat_d = to_dev(lat, dev)
+    T, N, M = shape
+    for n0, n1 in ranges:
+        part = np.ascontiguousarray(lat[:, n0:n1, :])
+        top = int(part.sum(axis=2, dtype=np.int64).max())
+        taus = np.concatenate([rng.integers(0, top + 9, size=30), [0, BIG, top]]).astype(np.int64)
+        step, done = dc.dc_simulate(lat_d, taus, 11, workers=(n0, n1))
+        ref_step, ref_done = oracle.simulate(part, taus, 11, "literal")
+        assert np.array_equal(step, ref_step) and np.array_equal(done, ref_done), (shape, n0, n1)
+        sums, squares, _, _ = oracle.worker_moments(part)
+        gs, gq, _, _ = dc.dc_worker_moments(lat_d, workers=(n0, n1))
+        assert gs == sums and gq == squares, (shape, n0, n1)
+        # the stream-ordered form, with negative guard values around the slab's rows to show a stray read
+        taus_d = torch.from_numpy(taus).to(dev)
+        out = torch.zeros((2, taus.size), dtype=torch.int64, device=dev)
+        ws = torch.empty(dc.dc_workspace_bytes(T, n1 - n0, M, taus.size), dtype=torch.uint8, device=dev)
+        guarded = torch.full((T, N, M), -9, dtype=torch.int32, device=dev)
+        guarded[:, n0:n1, :] = lat_d[:, n0:n1, :]
+        dc.dc_simulate_async(guarded, taus_d, 11, out[0], out[1], ws, None, workers=(n0, n1))
+        assert dc.dc_workspace_status(ws, None) == dc.DC_OK
+        assert np.array_equal(out[0].cpu().numpy(), ref_step) and np.array_equal(out[1].cpu().numpy(), ref_done)
+    with pytest.raises(dc.DcError) as e:                          # a stride shorter than a trial
+        dc._check(dc._load().dc_simulate_strided(lat_d.data_ptr(), T, N, M, N * M - 1, None, 0, 0, None, None), "strided")
+    assert e.value.status == dc.DC_ERR_INVALID_ARG
+
+
+def test_two_streams_with_their_own_workspaces(dev):
+    """Calls enqueued alternately on two streams, each with its own workspace: both results against the oracle, and
+    each workspace's kernel times read back separately."""
+    ra = config("extrapolation2048").with_shape(T=64, K=100)
+    rb = config("lognormal64").with_shape(T=3000, K=60)
+    cases = []
+    for r in (ra, rb):
+        lat = host.generate(r)
+        taus = host.tau_grid(r)
+        cases.append({"r": r, "ref": oracle.simulate_threaded(lat, taus, r.comm, "sorted", host.cpu_threads()),
+                      "lat": to_dev(lat, dev), "taus": torch.from_numpy(taus).to(dev),
+                      "out": torch.zeros((2, taus.size), dtype=torch.int64, device=dev),
+                      "ws": torch.empty(dc.dc_workspace_bytes(r.T, r.N, r.M, taus.size), dtype=torch.uint8, device=dev),
+                      "stream": torch.cuda.Stream()})
+    torch.cuda.synchronize()
+    try:
+        dc.dc_set_kernel_timing(2)
+        for _ in range(5):
+            for c in cases:
+                dc.dc_simulate_async(c["lat"], c["taus"], c["r"].comm, c["out"][0], c["out"][1], c["ws"], c["stream"])
+        times = []
+        for c in cases:
+            assert dc.dc_workspace_status(c["ws"], c["stream"]) == dc.DC_OK
+            got = c["out"].cpu().numpy()
+            assert np.array_equal(got[0], c["ref"][0]) and np.array_equal(got[1], c["ref"][1]), c["r"].name
+            scan_ms, total_ms = dc.dc_workspace_kernel_ms(c["ws"], whole=True)
+            assert 0 < scan_ms <= total_ms
+            times.append(scan_ms)
+        assert times[0] != times[1]                                # two tensors of different size: two different clocks
+    finally:
+        dc.dc_set_kernel_timing(False)
+
+
+def test_moments_sum_range(dev):
+    """2^32 latencies of 2^31 - 1: the largest sum that is still shown to fit 63 bits; one trial more is refused."""
+    top = 2**31 - 1
+    lat = torch.full(((1 << 16) + 1, 1 << 8, 1 << 8), top, dtype=torch.int32, device=dev)      # 17 GB
+    n = 1 << 32
+    total, squares, mean, var = dc.dc_moments(lat[: 1 << 16])
+    assert (total, squares) == (n * top, n * top * top) and mean == float(top) and var == 0.0
+    with pytest.raises(dc.DcError) as e:
+        dc.dc_moments(lat)
+    assert e.value.status == dc.DC_ERR_RANGE
+    del lat
+    torch.cuda.empty_cache()
 
 
 @pytest.mark.parametrize("name", ["lognormal64", "extrapolation2048", "heterogeneous2048"])
