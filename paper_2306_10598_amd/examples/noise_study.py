@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Scale sweep with the paper's additive-noise models (Appendix B.1 and C.3) on one GPU.
 
-For each noise family and worker count N it generates synthetic latencies in HBM, runs the library
-(dc_simulate, dc_moments, dc_select_tau, dc_analytic_curves) and prints
+For each noise family it generates ONE tensor of synthetic latencies in HBM with the largest worker count, and for
+each worker count N simulates the first N workers of it in place (dc_simulate's worker range: no copy), runs
+dc_worker_moments, dc_select_tau and dc_analytic_curves and prints
   E[T]/E[T_i]   mean iteration time of N workers over the mean time of one worker (the ratio the appendix tabulates;
                 the appendix does not state its N, so the sweep shows where each tabulated value would fall),
   tau*, S_eff(tau*), the completed fraction at tau*, and the closed-form S_eff at the same tau.
@@ -10,14 +11,14 @@ For each noise family and worker count N it generates synthetic latencies in HBM
 With --local-sgd it sweeps the synchronisation period of Local-SGD with random stragglers (Appendix B.3): throughput of
 Local-SGD, and of Local-SGD with the best drop threshold, relative to synchronising at every step.
 
-  python noise_study.py [--families lognormal normal ...] [--workers 8 64 512 2048] [--variance 0.05] [--delay]
-  python noise_study.py --local-sgd [--periods 1 2 4 8 16 32]
+  python -m paper_2306_10598_amd.examples.noise_study [--families lognormal normal ...] [--workers 8 64 512 2048] [--variance 0.05] [--delay]
+  python -m paper_2306_10598_amd.examples.noise_study --local-sgd [--periods 1 2 4 8 16 32]
 
 With --surrogate it repeats the check of the paper's iteration-time figure: measure every worker's mean and variance
 of its iteration time (dc_worker_moments), redraw each T_n from a normal distribution with those moments, and compare
 the mean iteration time and the speedup curve of the surrogate with those of the original latencies.
 
-  python noise_study.py --surrogate [--workers 200]
+  python -m paper_2306_10598_amd.examples.noise_study --surrogate [--workers 200]
 """
 from __future__ import annotations
 
@@ -25,7 +26,7 @@ import argparse
 import sys
 from pathlib import Path
 
-ROOT = Path(__file__).resolve().parent
+ROOT = Path(__file__).resolve().parents[2]
 if str(ROOT) not in sys.path:
     sys.path.insert(0, str(ROOT))
 
@@ -33,22 +34,36 @@ PAPER_RATIO = {"lognormal": 1.496, "normal": 1.302, "bernoulli": 1.283, "exponen
 BIG = 1 << 40
 
 
-def study(recipe):
+def sweep(recipe, workers):
+    """One tensor with recipe.N workers in HBM; for each n in `workers` (n <= recipe.N) the first n workers of every
+    iteration are simulated in place.  Returns one dict per n:
+      ratio          E[T]/E[T_i]: mean iteration time of n workers over the mean iteration time of one worker
+      tau, seff      the best threshold of the workload's grid rule applied to these n workers, and S_eff there
+      completed      completed fraction of micro-batches at tau
+      analytic_seff  the closed-form S_eff at tau, given the measured mean iteration time"""
     import numpy as np
 
     import paper_2306_10598_amd as dc
-    from dc_workloads import device
+    from dc_workloads import device, spec
     lat = device.generate(recipe)
-    taus = np.append(device.tau_grid(recipe, lat), BIG)
-    step, done = dc.dc_simulate(lat, taus, recipe.comm)
-    _, _, mean, var = dc.dc_moments(lat)
-    T, N, M = recipe.T, recipe.N, recipe.M
-    base = int(step[-1])
-    thr, seff, best = dc.dc_select_tau(step, done, taus, T, N, M, base)
-    mean_tmax = (base - T * recipe.comm) / T
-    _, _, ana, _ = dc.dc_analytic_curves(mean, var, N, M, taus, recipe.comm, mean_tmax)
-    return {"ratio": mean_tmax / (M * mean), "tau": int(taus[best]), "seff": float(seff[best]),
-            "completed": float(done[best]) / (T * N * M), "analytic_seff": float(ana[best])}
+    T, M = recipe.T, recipe.M
+    _, _, mean, var = dc.dc_moments(lat)                         # one micro-batch, all workers alike
+    rows = []
+    for n in workers:
+        totals = lat[:, :n, :].sum(dim=2, dtype=__import__("torch").int64).reshape(-1)     # grid placement only
+        i_lo, i_hi = spec.grid_rank_indices(totals.numel(), recipe.grid)
+        ordered = totals.sort().values
+        taus = np.append(spec.tau_grid((int(ordered[i_lo].item()), int(ordered[i_hi].item())), recipe.K), BIG)
+        step, done = dc.dc_simulate(lat, taus, recipe.comm, workers=(0, n))
+        sums, _, _, _ = dc.dc_worker_moments(lat, workers=(0, n))
+        base = int(step[-1])
+        thr, seff, best = dc.dc_select_tau(step, done, taus, T, n, M, base)
+        mean_tmax = (base - T * recipe.comm) / T
+        one_worker = sum(sums) / (T * n)
+        ana = dc.dc_analytic_curves(mean, var, max(n, 2), M, taus, recipe.comm, mean_tmax)[2]
+        rows.append({"workers": n, "ratio": mean_tmax / one_worker, "tau": int(taus[best]), "seff": float(seff[best]),
+                     "completed": float(done[best]) / (T * n * M), "analytic_seff": float(ana[best])})
+    return rows
 
 
 def local_sgd_study(periods, trials: int) -> None:
@@ -99,7 +114,7 @@ def main() -> int:
     ap.add_argument("--families", nargs="*", default=["lognormal", "normal", "bernoulli", "exponential", "gamma"])
     ap.add_argument("--workers", nargs="*", type=int, default=[8, 32, 128, 512, 2048])
     ap.add_argument("--variance", type=float, default=0.05)
-    ap.add_argument("--elements", type=int, default=1 << 26, help="approximate T*N*M per point")
+    ap.add_argument("--elements", type=int, default=1 << 28, help="approximate T*N*M of the tensor (N = the largest worker count)")
     ap.add_argument("--delay", action="store_true", help="also sweep the simulated-delay model of Appendix B.1")
     ap.add_argument("--local-sgd", action="store_true", help="sweep Local-SGD's synchronisation period instead")
     ap.add_argument("--surrogate", action="store_true", help="per-worker normal surrogate of the iteration time")
@@ -113,14 +128,14 @@ def main() -> int:
         return 0
     from dc_workloads import noise
     print(f"{'noise':<16}{'N':>6}{'T':>8}{'E[T]/E[T_i]':>13}{'paper':>8}{'tau* us':>12}{'S_eff':>8}{'done':>8}{'closed form':>13}")
+    top = max(args.workers)
+    T = max(16, args.elements // (top * 12))
     for family in args.families + (["delay"] if args.delay else []):
-        for N in args.workers:
-            T = max(16, args.elements // (N * 12))
-            r = noise.simulated_delay(T, N) if family == "delay" else noise.additive_noise(family, T, N, args.variance)
-            s = study(r)
-            ref = PAPER_RATIO.get(family) if abs(args.variance - 0.05) < 1e-12 else None
-            print(f"{family:<16}{N:>6}{T:>8}{s['ratio']:>13.3f}{(f'{ref:.3f}' if ref else '-'):>8}{s['tau']:>12}"
-                  f"{s['seff']:>8.3f}{s['completed']:>8.3f}{s['analytic_seff']:>13.3f}")
+        r = noise.simulated_delay(T, top) if family == "delay" else noise.additive_noise(family, T, top, args.variance)
+        ref = PAPER_RATIO.get(family) if abs(args.variance - 0.05) < 1e-12 else None
+        for row in sweep(r, sorted(args.workers)):
+            print(f"{family:<16}{row['workers']:>6}{T:>8}{row['ratio']:>13.3f}{(f'{ref:.3f}' if ref else '-'):>8}{row['tau']:>12}"
+                  f"{row['seff']:>8.3f}{row['completed']:>8.3f}{row['analytic_seff']:>13.3f}")
     return 0
 
 

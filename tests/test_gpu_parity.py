@@ -591,6 +591,34 @@ def test_worker_ranges_of_a_resident_tensor(shape, ranges, dev):
     assert e.value.status == dc.DC_ERR_INVALID_ARG
 
 
+@pytest.mark.parametrize("family", ["normal", "lognormal"])
+def test_noise_study_sweep_against_the_oracle(family, dev):
+    """The scale sweep of paper_2306_10598_amd/examples/noise_study.py (first n workers of one resident tensor, n = 4
+    and 16) against the same quantities from the oracle's outputs on the sliced CPU tensor: E[T]/E[T_i] (Appendix
+    C.3's ratio) and S_eff at the chosen threshold."""
+    from dc_workloads import noise, spec
+    from paper_2306_10598_amd.examples import noise_study
+    r = noise.additive_noise(family, 200, 16, K=24)
+    rows = noise_study.sweep(r, [4, 16])
+    lat = host.generate(r)
+    for row in rows:
+        n = row["workers"]
+        part = np.ascontiguousarray(lat[:, :n, :])
+        totals = host.worker_totals(part)
+        i_lo, i_hi = spec.grid_rank_indices(totals.size, r.grid)
+        ordered = np.sort(totals)
+        taus = np.append(spec.tau_grid((int(ordered[i_lo]), int(ordered[i_hi])), r.K), BIG)
+        step, done = oracle.simulate(part, taus, r.comm, "sorted")
+        _, seff, best = oracle.select_tau(step, done, taus, r.T, n, r.M, int(step[-1]))
+        sums, _, _, _ = oracle.worker_moments(part)
+        mean_tmax = (int(step[-1]) - r.T * r.comm) / r.T
+        assert row["tau"] == int(taus[best])
+        assert row["seff"] == pytest.approx(float(seff[best]), rel=1e-9)
+        assert row["ratio"] == pytest.approx(mean_tmax / (sum(sums) / (r.T * n)), rel=1e-12)
+        assert row["completed"] == pytest.approx(int(done[best]) / (r.T * n * r.M), rel=1e-12)
+    assert rows[1]["ratio"] > rows[0]["ratio"] > 1.0            # the slowest of more workers takes longer (Section 4.2)
+
+
 def test_two_streams_with_their_own_workspaces(dev):
     """Calls enqueued alternately on two streams, each with its own workspace: both results against the oracle, and
     each workspace's kernel times read back separately."""
