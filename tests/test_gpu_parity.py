@@ -15,6 +15,8 @@ from dc_workloads import config, host, spec
 
 pytestmark = pytest.mark.gpu
 
+SPEEDUP_RTOL = 1e-6        # stated bar for float ratios; the two sides differ only in rounding order (~1e-15)
+
 torch = pytest.importorskip("torch")
 BIG = 1 << 40
 
@@ -226,6 +228,46 @@ def test_random_cases_against_the_literal_oracle(seed, dev):
     check(lat, taus, comm, dev, "literal")
 
 
+def test_randomised_entry_points(dev):
+    """A bounded, seeded sweep of random shapes, alignments, value ranges and threshold lists through the four entry
+    points that stream the tensor (sums, per-iteration speedup, moments, per-worker statistics) and through a random
+    range of workers, each against the oracle; stops at the first mismatch."""
+    rng = np.random.default_rng(20260)
+    for case in range(500):
+        M = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 13, 16, 24, 31, 32, 63, 64, 65, 100, 128, 132, 256, 257, 600]))
+        N = int(rng.integers(1, 120))
+        T = int(rng.integers(1, max(2, 40000 // (N * M) + 2)))
+        top = min((2**31 - 1) // M, int(rng.choice([3, 100, 10**4, 10**6, 10**9])))
+        lat = rng.integers(0, top + 1, size=(T, N, M), dtype=np.int64)
+        if rng.random() < 0.3:
+            lat *= rng.random((T, N, M)) < 0.2                       # long runs of zero latency
+        lat = lat.astype(np.int32)
+        words = int(rng.integers(0, 4))                              # 0, 4, 8 or 12 bytes past a 16-byte boundary
+        flat = torch.full((lat.size + words + 4,), -3, dtype=torch.int32, device=dev)
+        view = flat[words:words + lat.size].view(T, N, M)
+        view.copy_(torch.from_numpy(lat))
+        P = np.cumsum(lat.astype(np.int64), axis=2)
+        K = int(rng.choice([1, 2, 5, 33, 130]))
+        pool = np.concatenate([P.reshape(-1), P.reshape(-1) + 1, [1, int(P.max()) + 3, BIG]])
+        taus = np.maximum(rng.choice(pool, size=K), 1).astype(np.int64)
+        comm = int(rng.integers(0, 500))
+        tag = (case, T, N, M, words, K)
+        step, done = dc.dc_simulate(view, taus, comm)
+        ref_step, ref_done = oracle.simulate(lat, taus, comm, "literal")
+        assert np.array_equal(step, ref_step) and np.array_equal(done, ref_done), tag
+        assert np.allclose(dc.dc_speedup_per_step(view, taus, comm), oracle.per_step_speedup(lat, taus, comm),
+                           rtol=SPEEDUP_RTOL, atol=0), tag
+        assert dc.dc_moments(view)[:2] == oracle.moments(lat)[1:3], tag
+        assert dc.dc_worker_moments(view)[:2] == oracle.worker_moments(lat)[:2], tag
+        n0 = int(rng.integers(0, N))
+        n1 = int(rng.integers(n0 + 1, N + 1))
+        part = np.ascontiguousarray(lat[:, n0:n1, :])
+        step, done = dc.dc_simulate(view, taus, comm, workers=(n0, n1))
+        ref_step, ref_done = oracle.simulate(part, taus, comm, "literal")
+        assert np.array_equal(step, ref_step) and np.array_equal(done, ref_done), tag + (n0, n1)
+        assert dc.dc_worker_moments(view, workers=(n0, n1))[:2] == oracle.worker_moments(part)[:2], tag + (n0, n1)
+
+
 # ---- degenerate and adversarial inputs --------------------------------------------------------------
 
 def test_thresholds_spanning_every_completion_time(dev):
@@ -412,7 +454,6 @@ def test_kernel_timing_reports_positive_times(dev):
 
 # ---- Algorithm 2 as printed: mean over iterations of the per-iteration speedup -------------------------
 
-SPEEDUP_RTOL = 1e-6        # stated bar for float ratios; the two sides differ only in rounding order (~1e-15)
 
 
 @pytest.mark.parametrize("name,shape", [
