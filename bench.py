@@ -242,8 +242,11 @@ def bench_analytic(args, r, lat, taus) -> int:
     return 0
 
 
-def scan_kernel_name(M: int, grid: str = "recipe") -> str:
-    """The streaming kernel the library runs for rows of M elements (16-byte aligned tensor), as a profile names it."""
+def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0) -> str:
+    """The streaming kernel the library runs for N rows of M elements per trial (16-byte aligned, contiguous tensor),
+    as a profile names it."""
+    if M <= 16 and N % 4 == 0 and N >= 256:                            # every lane holds whole rows
+        return f"dc_scan_rows_kernel<{M}>"
     if M % 4 == 0 and (M <= 128 or M == 256):
         lanes = M // 4
         known = lanes if lanes & (lanes - 1) == 0 else 0              # one instantiation serves every other lane count
@@ -415,7 +418,7 @@ def main() -> int:
         "config": {"workload": f"{r.name}: T={r.T} N={r.N} M={r.M} K={K} comm={r.comm}us, {r.description}",
                    "grid": args.grid, "tensor_bytes": r.nbytes, "best_tau_us": int(taus[best]),
                    "best_thr_per_us": float(thr[best])},
-        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(r.M, args.grid), "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(r.M, args.grid, r.N), "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "traffic_source": traffic_source,
                      "kernel_ms": scan_avg_ms, "kernel_ms_min": float(np.min(scan_ms)),

@@ -78,9 +78,20 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     dc::Plan p{};
     if (!plan_shape(T, N, M, stride, &p)) return false;
     p.K = (uint32_t)K;
-    p.vec4 = allow_vec4 && vec4_shape(M) && (p.stride & 3u) == 0;     // every trial starts on a 16-byte boundary
+    const bool aligned = allow_vec4 && (p.stride & 3u) == 0;          // every trial starts on a 16-byte boundary
+    p.lane_rows = aligned && M <= 16 && (N & 3) == 0 && N >= (int64_t)DC_LANE_ROWS_MIN_N;
+    p.vec4 = aligned && !p.lane_rows && vec4_shape(M);
     uint64_t upt;
-    if (p.vec4) {
+    if (p.lane_rows) {
+        // chunks of whole rows; about DC_FLAT_UNIT_ELEMENTS elements per unit, the units of a trial of equal size
+        const uint64_t chunk_rows = dc::lane_rows_chunk_rows((uint32_t)M);
+        const uint64_t chunks = ((uint64_t)N + chunk_rows - 1) / chunk_rows;
+        uint64_t want = DC_FLAT_UNIT_ELEMENTS / (chunk_rows * (uint64_t)M);
+        if (want < 1) want = 1;
+        const uint64_t pieces = (chunks + want - 1) / want;
+        p.per_unit = (uint32_t)((chunks + pieces - 1) / pieces);
+        upt = (chunks + p.per_unit - 1) / p.per_unit;
+    } else if (p.vec4) {
         const uint64_t rows_per_load = 64 / (M / 4);
         const uint64_t loads_per_trial = ((uint64_t)N + rows_per_load - 1) / rows_per_load;
 #ifdef DC_UNIT_LOADS

@@ -31,6 +31,9 @@
 #ifndef DC_DENSE_BLOCKS_PER_CU
 #define DC_DENSE_BLOCKS_PER_CU 3
 #endif
+#ifndef DC_LANE_ROWS_MIN_N
+#define DC_LANE_ROWS_MIN_N 256u         // workers per trial from which short rows are streamed with whole rows per lane
+#endif
 #define DC_SAMPLE_ROWS 32               // rows of lat that the sample reads (a multiple of 4: a quarter per wave)
 #ifndef DC_MAX_SCAN_BLOCKS
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
@@ -50,6 +53,10 @@
 
 namespace dc {
 
+// Rows that one wave of the kernel with whole rows per lane takes at a time (a chunk): a lane holds 16 rows of one
+// element, 8 of two, otherwise 4.
+inline uint32_t lane_rows_chunk_rows(uint32_t M) { return M == 1u ? 1024u : M == 2u ? 512u : 256u; }
+
 // Everything the host decides about one call: which streaming kernel, how the tensor is cut
 // into units, and where each array sits in the workspace.
 struct Plan {
@@ -58,7 +65,9 @@ struct Plan {
     uint64_t stride;            // elements from one trial to the next (N*M when the tensor is contiguous)
     uint64_t extent;            // elements from the first one of the tensor to its last: (T-1)*stride + N*M
     bool vec4;                  // 16-byte loads, whole rows per load (M a multiple of 4 up to 128, or 256; lat 16-byte aligned)
-    uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; otherwise rows per unit
+    bool lane_rows;             // every lane holds whole rows (M <= 15 and not a multiple of 4, N a multiple of 4 and at
+                                // least DC_LANE_ROWS_MIN_N, trials 16-byte aligned); never set together with vec4
+    uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; lane_rows: chunks per unit; otherwise rows per unit
     uint32_t units_per_trial;
     uint32_t units;             // T * units_per_trial
     uint32_t run;               // consecutive units that one block takes at a time (a multiple of DC_SCAN_WAVES)

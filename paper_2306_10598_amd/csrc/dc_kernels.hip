@@ -949,6 +949,181 @@ void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint64
 }
 
 // ---------------------------------------------------------------------------------------------
+// dc_scan_rows_kernel: short rows that a lane can own.  M <= 15 and not a multiple of 4, N a multiple of 4, every
+// trial on a 16-byte boundary.
+// The kernels above spread a row over lanes and pay for it with cross-lane sums and, per 16-byte load, one queue
+// slot or one search per element; with rows of a few elements that arithmetic, not HBM, bounds them.  Here a lane
+// holds R whole rows in registers (V 16-byte vectors = R*M elements), so completion times are R*M plain additions,
+// and because they do not decrease along a row (latencies >= 0) the thresholds are met from the row's end
+// backwards: step s bins the (M-1-s)-th completion time of all R rows at once and the wave stops at the first
+// step in which no lane reaches the smallest threshold; with the usual grids that is after one or two steps.
+// A wave reads a chunk of 64 V consecutive vectors with coalesced loads (lane l takes vectors l, l + 64, ...) and,
+// unless a vector holds whole rows anyway (M = 1, 2), passes them through its own stretch of LDS so that lane l ends
+// up with vectors l V, ..., l V + V - 1: for odd M these reads are free of bank conflicts, for even M two-way.
+// ---------------------------------------------------------------------------------------------
+template <int M>
+struct LaneRows {
+    static constexpr bool STAGED = (4 % M) != 0;
+    static constexpr int V = STAGED ? M : 4;          // vectors per lane and chunk
+    static constexpr int R = 4 * V / M;               // rows per lane and chunk
+    static constexpr bool PREFETCH = V <= 8;          // the next chunk's loads are issued before this chunk's arithmetic
+    // A lane's vectors sit SPAN vectors from the next lane's in LDS: an odd number, so that eight lanes reading 16 bytes
+    // each fall on different banks (with SPAN = V and V = 8 or 16 every lane of the wave would meet in one bank).
+    static constexpr int SPAN = STAGED ? (V | 1) : 0;
+    static constexpr uint32_t STAGE_VECTORS = 64u * SPAN;       // per wave
+};
+
+template <int M>
+__device__ __forceinline__ void rows_load(u32x4 (&x)[LaneRows<M>::V], const u32x4* base, uint32_t first, uint32_t nv,
+                                          uint32_t lane) {
+    constexpr int V = LaneRows<M>::V;
+    if (first + 64u * V <= nv) {                       // wave-uniform: the whole chunk lies inside the unit
+#pragma unroll
+        for (int j = 0; j < V; ++j) x[j] = __builtin_nontemporal_load(base + first + 64u * j + lane);
+    } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const uint32_t i = first + 64u * j + lane;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            if (i < nv) z = __builtin_nontemporal_load(base + i);
+            x[j] = z;
+        }
+    }
+}
+
+// One chunk: `left` = vectors of the unit from the chunk's first one on (the chunk holds min(left, 64 V)).
+template <int M, bool FULL>
+__device__ __forceinline__ void rows_chunk(WaveState& st, u32x4 (&x)[LaneRows<M>::V], uint32_t left, u32x4* stage,
+                                           const GridView& g, uint32_t lane) {
+    using S = LaneRows<M>;
+    constexpr int V = S::V, R = S::R;
+    if constexpr (S::STAGED) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const uint32_t i = 64u * j + lane;                       // vector i of the chunk belongs to lane i / V
+            stage[S::SPAN == V ? i : i + i / V] = x[j];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int j = 0; j < V; ++j) x[j] = stage[lane * S::SPAN + j];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // read before the next chunk overwrites it
+    }
+    uint32_t e[4 * V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) { e[4 * j] = x[j].x; e[4 * j + 1] = x[j].y; e[4 * j + 2] = x[j].z; e[4 * j + 3] = x[j].w; }
+    uint32_t worst = st.check;
+#pragma unroll
+    for (int i = 0; i < 4 * V; ++i) worst = umax(worst, e[i]);
+    st.check = worst;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int m = 1; m < M; ++m) e[r * M + m] += e[r * M + m - 1];
+    // which of the lane's rows belong to the unit: all of them in a full chunk; in the last, partial one the lanes
+    // (staged) or vectors (not staged) before the unit's end -- N is a multiple of 4, so no vector is split
+    bool mine[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if constexpr (FULL) mine[r] = true;
+        else if constexpr (S::STAGED) mine[r] = lane * V < left;
+        else mine[r] = 64u * (uint32_t)(r * M / 4) + lane < left;
+    }
+    uint32_t top = st.lane_max;
+#pragma unroll
+    for (int r = 0; r < R; ++r) top = umax(top, e[r * M + M - 1]);   // rows outside the unit are all zero
+    st.lane_max = top;
+    bool taken = false;                                             // wave-uniform: this step went with the one before
+#pragma unroll
+    for (int s = 0; s < M; ++s) {
+        if (taken) { taken = false; continue; }
+        uint32_t val[2 * R], b[2 * R];
+        uint32_t high = 0u;
+#pragma unroll
+        for (int r = 0; r < R; ++r) { val[r] = e[r * M + M - 1 - s]; high = umax(high, val[r]); }
+        const uint64_t reach = __ballot(high >= g.tau0);
+        if (reach == 0) break;                                      // wave-uniform
+        if (s + 1 < M && (uint32_t)__popcll(reach) >= DC_DENSE_LANES) {
+            // most lanes are inside the grid, so the next step would very likely run as well: both at once, twice as
+            // many independent searches in flight (completion times below the grid find bin 0 and count nowhere)
+#pragma unroll
+            for (int r = 0; r < R; ++r) val[R + r] = e[r * M + M - 1 - (s + 1 < M ? s + 1 : s)];
+            bins_of<2 * R>(g, val, b);
+#pragma unroll
+            for (int r = 0; r < 2 * R; ++r) count_bin(g, mine[r % R] ? b[r] : 0u);
+            taken = true;
+        } else {
+            uint32_t v1[R], b1[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) v1[r] = val[r];
+            bins_of<R>(g, v1, b1);
+#pragma unroll
+            for (int r = 0; r < R; ++r) count_bin(g, mine[r] ? b1[r] : 0u);
+        }
+    }
+}
+
+template <int M>
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_scan_rows_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride, uint32_t N, uint32_t units, uint32_t units_per_trial,
+                         uint32_t run, uint32_t chunks_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
+                         uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part, uint32_t* __restrict__ status,
+                         uint32_t max_latency) {
+    using S = LaneRows<M>;
+    constexpr int V = S::V;
+    constexpr uint32_t CHUNK_ROWS = 64u * S::R, CHUNK_VECTORS = 64u * V;
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr size_t STAGE_BYTES = (size_t)DC_SCAN_WAVES * S::STAGE_VECTORS * sizeof(u32x4);
+    const GridView g = stage_grid(reinterpret_cast<uint32_t*>(smem + STAGE_BYTES), tau_chunk, kc, p2);
+
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    u32x4* stage = reinterpret_cast<u32x4*>(smem) + wave * S::STAGE_VECTORS;
+
+    WaveState st{0u, 0u, 0u, 0u};
+    const UnitRuns ur = unit_runs(units, run, gridDim.x);                                  // as in dc_scan_vec4_kernel
+    for (uint32_t r = blockIdx.x; r < ur.padded; r += gridDim.x)                          // block-uniform bounds
+    for (uint32_t round = 0; round < ur.rounds; ++round) {
+        const uint32_t u = r < ur.runs ? r * run + round * DC_SCAN_WAVES + wave : units;
+        if (u < units) {
+            const uint32_t t = u / units_per_trial;
+            const uint32_t j = u - t * units_per_trial;
+            const uint32_t row0 = j * chunks_per_unit * CHUNK_ROWS;
+            const uint32_t rows = (N - row0) < chunks_per_unit * CHUNK_ROWS ? (N - row0) : chunks_per_unit * CHUNK_ROWS;
+            const uint32_t nv = rows / 4u * (uint32_t)M;                                  // rows is a multiple of 4
+            const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)row0 * M);
+            st.lane_max = 0u;
+            u32x4 x[V];
+            rows_load<M>(x, base, 0u, nv, lane);
+            for (uint32_t first = 0; first < nv; first += CHUNK_VECTORS) {
+                const uint32_t left = nv - first;
+                if constexpr (S::PREFETCH) {
+                    u32x4 ahead[V];
+#pragma unroll
+                    for (int q = 0; q < V; ++q) ahead[q] = x[q];
+                    if (left > CHUNK_VECTORS) rows_load<M>(ahead, base, first + CHUNK_VECTORS, nv, lane);
+                    if (left >= CHUNK_VECTORS) rows_chunk<M, true>(st, x, left, stage, g, lane);
+                    else rows_chunk<M, false>(st, x, left, stage, g, lane);
+#pragma unroll
+                    for (int q = 0; q < V; ++q) x[q] = ahead[q];
+                } else {
+                    if (left >= CHUNK_VECTORS) rows_chunk<M, true>(st, x, left, stage, g, lane);
+                    else rows_chunk<M, false>(st, x, left, stage, g, lane);
+                    if (left > CHUNK_VECTORS) rows_load<M>(x, base, first + CHUNK_VECTORS, nv, lane);
+                }
+            }
+            const uint32_t m = wave_max(st.lane_max);
+            if (lane == 0) unit_max[u] = m;
+        }
+        __syncthreads();
+    }
+    report_range(st.check, max_latency, lane, status);
+
+    __syncthreads();
+    uint32_t* out = hist_part + (uint64_t)blockIdx.x * p2;
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = g.hist[i];
+}
+
+// ---------------------------------------------------------------------------------------------
 // The last step of a pass, run by one block of THREADS threads once every sum is in.  Running sums over the bins
 // give, for sorted threshold i of the chunk: not_done[i] = sum_{b>i} hist[b];
 // below[i] = #{t : Tmax_t < tau_i} = sum_{b<=i} cnt[b];  below_sum[i] = sum_{b<=i} sum[b].  Then
@@ -1467,6 +1642,8 @@ void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t*
 
 size_t scan_lds_bytes(const Plan& p) {
     const size_t tables = (size_t)p.p2 * 8;                       // thresholds + histogram
+    if (p.lane_rows)                                              // + cells + every wave's stretch for its chunk
+        return tables + (size_t)p.p2 * 8 + (4u % p.M ? (size_t)DC_SCAN_WAVES * 64u * (p.M | 1u) * sizeof(u32x4) : 0u);
     return tables + (size_t)p.p2 * 8 + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);   // + cells + queues
 }
 
@@ -1481,6 +1658,18 @@ static int resident_vec4(size_t lds) {
 int scan_blocks_per_cu(const Plan& p) {
     const size_t lds = scan_lds_bytes(p);
     int n = 0;
+    if (p.lane_rows) {
+        hipError_t e = hipErrorInvalidValue;
+        switch (p.M) {
+#define DC_ROWS_CASE(m) case m: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_rows_kernel<m>, DC_SCAN_THREADS, lds); break;
+            DC_ROWS_CASE(1) DC_ROWS_CASE(2) DC_ROWS_CASE(3) DC_ROWS_CASE(4) DC_ROWS_CASE(5) DC_ROWS_CASE(6) DC_ROWS_CASE(7)
+            DC_ROWS_CASE(8) DC_ROWS_CASE(9) DC_ROWS_CASE(10) DC_ROWS_CASE(11) DC_ROWS_CASE(12) DC_ROWS_CASE(13)
+            DC_ROWS_CASE(14) DC_ROWS_CASE(15) DC_ROWS_CASE(16)
+#undef DC_ROWS_CASE
+            default: break;
+        }
+        return e == hipSuccess ? n : 0;
+    }
     if (!p.vec4) {
         hipError_t e;
         switch (p.M) {
@@ -1530,8 +1719,27 @@ static void launch_flat(const Plan& p, const int32_t* lat, const uint32_t* tau_c
                        unit_max, hist_part, status, p.max_latency);
 }
 
+template <int M>
+static void launch_rows(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
+                        uint32_t* unit_max, uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
+    hipLaunchKernelGGL(dc_scan_rows_kernel<M>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
+                       p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max,
+                       hist_part, status, p.max_latency);
+}
+
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
                  uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
+    if (p.lane_rows) {
+        switch (p.M) {
+#define DC_ROWS_CASE(m) case m: launch_rows<m>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
+            DC_ROWS_CASE(1) DC_ROWS_CASE(2) DC_ROWS_CASE(3) DC_ROWS_CASE(4) DC_ROWS_CASE(5) DC_ROWS_CASE(6) DC_ROWS_CASE(7)
+            DC_ROWS_CASE(8) DC_ROWS_CASE(9) DC_ROWS_CASE(10) DC_ROWS_CASE(11) DC_ROWS_CASE(12) DC_ROWS_CASE(13)
+            DC_ROWS_CASE(14) DC_ROWS_CASE(15) DC_ROWS_CASE(16)
+#undef DC_ROWS_CASE
+            default: break;                         // make_plan sets lane_rows for these row lengths only
+        }
+        return;
+    }
     if (!p.vec4) {
         switch (p.M) {
             case 1:  launch_flat<1>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;

@@ -172,6 +172,35 @@ def test_any_alignment_any_row_length(words, M, dev):
     assert gs == sums and gq == squares
 
 
+@pytest.mark.parametrize("N", [256, 260, 1024, 2052, 5000])
+@pytest.mark.parametrize("M", list(range(1, 17)))
+def test_short_rows_held_whole_by_a_lane(M, N, dev):
+    """Rows of up to 16 elements with at least 256 workers, a multiple of 4, on an aligned
+    tensor go through the kernel in which every lane owns whole rows: full and partial chunks, one and several units
+    per trial, a narrow grid near the row totals, a grid over every completion time (with 0, repeats and values no
+    completion time reaches), and a worker range of the resident tensor (trials further apart than they are long)."""
+    rng = np.random.default_rng(100 * M + N)
+    T = 3
+    top = min((2**31 - 1) // M, 6000)
+    lat = rng.integers(0, top + 1, size=(T, N, M), dtype=np.int32)
+    lat[0, 0, :] = top                                    # the largest legal row, and the row of trial 1 that decides its maximum
+    lat[1, N - 1, :] = top // 2 + 1
+    lat[1, :N - 1, :] //= 4
+    totals = lat.sum(axis=2, dtype=np.int64)
+    narrow = np.quantile(totals, np.linspace(0.6, 1.0, 33)).astype(np.int64)
+    wide = np.concatenate([[0, 0, 1], rng.integers(0, int(totals.max()) + 50, size=60), [int(totals.max())] * 2, [BIG]])
+    lat_dev = to_dev(lat, dev)
+    for taus in (narrow, wide):
+        step, done = dc.dc_simulate(lat_dev, taus, 9)
+        ref = oracle.simulate(lat, taus, 9, "literal")
+        assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, taus[:4])
+    if N >= 260:
+        a = 4 * int(rng.integers(0, (N - 256) // 4 + 1))
+        step, done = dc.dc_simulate(lat_dev, narrow, 2, workers=(a, a + 256))
+        ref = oracle.simulate(np.ascontiguousarray(lat[:, a:a + 256]), narrow, 2, "literal")
+        assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, a)
+
+
 def test_long_rows_and_many_rows_per_unit(dev):
     """Rows longer than a unit (one row per unit, carries across dozens of loads) and units of thousands of short rows."""
     rng = np.random.default_rng(12)
