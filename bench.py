@@ -6,7 +6,7 @@ dc_simulate_async (thresholds sorted, the streaming scan over lat, reductions, f
 copy of the 2*K result sums to the host, and dc_select_tau.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
-                  [--rows M] [--grid recipe|dense|upper-half] [--path sums|per-step|analytic]
+                  [--rows M] [--grid recipe|dense|upper-half] [--path sums|per-step|analytic|worker-moments]
 
 The result sums are written by the library's last kernel straight into pinned host memory (the output pointers of
 dc_simulate_async may be any memory the device can write), so a step has no separate copy.
@@ -242,6 +242,40 @@ def bench_analytic(args, r, lat, taus) -> int:
     return 0
 
 
+def bench_worker_moments(args, r, lat) -> int:
+    """Per-worker statistics (dc_worker_moments): one read of lat; the roofline is that of its streaming kernel."""
+    import numpy as np
+    import torch
+
+    import paper_2306_10598_amd as dc
+    dc.dc_set_kernel_timing(True)
+    for _ in range(args.warmup):
+        dc.dc_worker_moments(lat)
+    kernel_ms = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sums, squares, mean, var = dc.dc_worker_moments(lat)
+        kernel_ms.append(dc.dc_last_kernel_ms()[0])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dc.dc_set_kernel_timing(False)
+    ms = float(np.mean(kernel_ms))
+    achieved = 4.0 * r.elements / (ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "latencies/s through the per-worker statistics; achieved HBM GB/s vs MI355X peak",
+        "value": float(r.elements) / (wall / args.steps), "unit": "latencies/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * wall / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"{r.name}: T={r.T} N={r.N} M={r.M}", "path": "per-worker sums and sums of squares of the row totals",
+                   "mean_of_worker_means_us": float(mean.mean()), "variance_between_worker_means_us2": float(mean.var())},
+        "roofline": {"bound": "hbm", "kernel": "dc_worker_totals_vec4_kernel" if r.M % 4 == 0 and (r.M <= 128 or r.M == 256)
+                     else "dc_worker_totals_flat_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "kernel_ms": ms,
+                     "algorithmic_bytes": 4.0 * r.elements}}))
+    return 0
+
+
 def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0) -> str:
     """The streaming kernel the library runs for N rows of M elements per trial (16-byte aligned, contiguous tensor),
     as a profile names it."""
@@ -337,10 +371,11 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="heterogeneous2048")
-    ap.add_argument("--path", choices=("sums", "per-step", "analytic"), default="sums",
+    ap.add_argument("--path", choices=("sums", "per-step", "analytic", "worker-moments"), default="sums",
                     help="sums: dc_simulate_async + dc_select_tau (the headline path); "
                          "per-step: dc_speedup_per_step_async, Algorithm 2's mean of per-iteration speedups; "
-                         "analytic: dc_moments + dc_analytic_curves, the closed-form curves")
+                         "analytic: dc_moments + dc_analytic_curves, the closed-form curves; "
+                         "worker-moments: dc_worker_moments, per-worker statistics of the iteration time")
     ap.add_argument("--rows", type=int, default=0,
                     help="run the workload with this many accumulations per worker instead of its own M, the number of "
                          "trials rescaled to keep the tensor's size (not a bench line: for timing other row lengths)")
@@ -395,6 +430,8 @@ def main() -> int:
         return bench_per_step(args, r, lat, taus, taus_dev, stream)
     if args.path == "analytic":
         return bench_analytic(args, r, lat, taus)
+    if args.path == "worker-moments":
+        return bench_worker_moments(args, r, lat)
 
     m = time_sums_path(r, lat, taus, taus_dev, stream, args.steps, args.warmup, timing=2)
     if m is None:

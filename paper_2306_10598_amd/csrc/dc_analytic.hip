@@ -50,10 +50,11 @@ __device__ __forceinline__ void block_reduce(Acc& a, unsigned long long (*lds)[3
 
 }  // namespace
 
-// partial[block] = {sum, squares low word, squares high word, OR of values}.  `vec_units` units of 64 KiB
-// (16-byte loads, a wave per unit) cover the elements [head, head + vec_units*16384), where head (0..3) is the
+// partial[block] = {sum, squares low word, squares high word, OR of values}.  `vec_units` units of 32 KiB
+// (16-byte loads, a wave per unit) cover the elements [head, head + vec_units*8192), where head (0..3) is the
 // number of elements before the first 16-byte boundary; the elements before and after, [0, head) and
-// [scalar_from, n), are read one by one.
+// [scalar_from, n), are read one by one.  The units are dealt as in the threshold pass: a block takes runs of
+// DC_UNIT_RUN consecutive units and its four waves walk a run four adjacent units at a time, in step.
 __global__ __launch_bounds__(256)
 void dc_moments_kernel(const int32_t* __restrict__ lat, unsigned long long n, uint32_t head, uint32_t vec_units,
                        unsigned long long scalar_from, unsigned long long* __restrict__ partial) {
@@ -62,16 +63,22 @@ void dc_moments_kernel(const int32_t* __restrict__ lat, unsigned long long n, ui
     Acc a{0ull, 0, 0u};
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t total_waves = gridDim.x * 4;
-    for (uint32_t u = blockIdx.x * 4 + wave; u < vec_units; u += total_waves) {
-        const u32x4* base = reinterpret_cast<const u32x4*>(lat + head) + (uint64_t)u * 4096 + lane;
-        for (uint32_t i = 0; i < 64; i += 8) {
-            u32x4 x[8];
+    const uint32_t runs = (vec_units + DC_UNIT_RUN - 1u) / DC_UNIT_RUN;
+    const uint32_t padded = (runs + gridDim.x - 1u) / gridDim.x * gridDim.x;     // block-uniform loop bounds
+    for (uint32_t r = blockIdx.x; r < padded; r += gridDim.x)
+    for (uint32_t round = 0; round < DC_UNIT_RUN / 4u; ++round) {
+        const uint32_t u = r < runs ? r * DC_UNIT_RUN + round * 4u + wave : vec_units;
+        if (u < vec_units) {
+            const u32x4* base = reinterpret_cast<const u32x4*>(lat + head) + (uint64_t)u * 2048 + lane;
+            for (uint32_t i = 0; i < 32; i += 8) {
+                u32x4 x[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) x[k] = __builtin_nontemporal_load(base + (uint64_t)(i + k) * 64);
+                for (int k = 0; k < 8; ++k) x[k] = __builtin_nontemporal_load(base + (uint64_t)(i + k) * 64);
 #pragma unroll
-            for (int k = 0; k < 8; ++k) { take(a, x[k].x); take(a, x[k].y); take(a, x[k].z); take(a, x[k].w); }
+                for (int k = 0; k < 8; ++k) { take(a, x[k].x); take(a, x[k].y); take(a, x[k].z); take(a, x[k].w); }
+            }
         }
+        __syncthreads();
     }
     const unsigned long long stride = (unsigned long long)gridDim.x * blockDim.x;
     for (unsigned long long i = scalar_from + (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
@@ -146,10 +153,10 @@ void launch_moments(const int32_t* lat, uint64_t n, uint32_t grid, unsigned long
                     unsigned long long* result, uint32_t* status, hipStream_t stream) {
     uint64_t head = (4u - (uint32_t)(((uintptr_t)lat >> 2) & 3u)) & 3u;     // elements before the first 16-byte boundary
     if (head > n) head = n;
-    const uint64_t units = (n - head) / 16384;
+    const uint64_t units = (n - head) / 8192;
     const uint32_t vec_units = (uint32_t)(units < 0x7FFFFFFFull ? units : 0x7FFFFFFFull);
     hipLaunchKernelGGL(dc_moments_kernel, dim3(grid), dim3(256), 0, stream, lat, (unsigned long long)n, (uint32_t)head,
-                       vec_units, (unsigned long long)(head + (uint64_t)vec_units * 16384ull), partial);
+                       vec_units, (unsigned long long)(head + (uint64_t)vec_units * 8192ull), partial);
     hipLaunchKernelGGL(dc_moments_final_kernel, dim3(1), dim3(256), 0, stream, partial, grid, result, status);
 }
 

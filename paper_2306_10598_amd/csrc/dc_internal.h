@@ -39,6 +39,7 @@
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
 #endif
 #define DC_SCAN_WAVES (DC_SCAN_THREADS / 64)
+#define DC_REDUCE_TRIAL_BLOCKS 256u     // at most this many blocks of the reduce kernel bin the per-trial maxima
 #define DC_REDUCE_SLOTS 64u             // per-block histograms added by one block of the reduce kernel
 #define DC_CHUNK_THRESHOLDS 4095u      // thresholds handled by one pass over lat (LDS-resident grid)
 #define DC_TRIAL_CHUNK_THRESHOLDS 2047u // same for the per-iteration speedup pass (it also keeps float64 sums in LDS)
