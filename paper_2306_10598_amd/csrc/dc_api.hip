@@ -124,7 +124,6 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     p.off_tau_u32 = off;    off += align256((size_t)K * 4);
     p.off_pos = off;        off += align256((size_t)K * 4);
     p.off_bins = off;       off += align256((size_t)3 * p.p2 * 8);
-    p.off_chunk_out = off;  off += align256((size_t)2 * p.chunk * 8);
     p.off_unit_max = off;   off += align256((size_t)p.units * 4);
     p.off_hist_part = off;  off += align256((size_t)p.grid * p.p2 * 4);
     p.bytes = off;
@@ -342,8 +341,6 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
     unsigned long long* hist_total = reinterpret_cast<unsigned long long*>(ws + p.off_bins);
     unsigned long long* trial_cnt = hist_total + p.p2;
     unsigned long long* trial_sum = trial_cnt + p.p2;
-    int64_t* chunk_step = reinterpret_cast<int64_t*>(ws + p.off_chunk_out);
-    int64_t* chunk_done = chunk_step + p.chunk;
     uint32_t* unit_max = reinterpret_cast<uint32_t*>(ws + p.off_unit_max);
     uint32_t* hist_part = reinterpret_cast<uint32_t*>(ws + p.off_hist_part);
 
@@ -365,7 +362,7 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
         dc::launch_scan(p, lat, tau_u32 + chunk0, kc, unit_max, hist_part, status, stream);
         if (slot) DC_HIP(hipEventRecord(slot->scan[2 * c + 1], stream));
         dc::launch_reduce(p, hist_part, hist_total, unit_max, tau_u32 + chunk0, kc, trial_cnt, trial_sum, status, chunk0,
-                          tau_sorted, pos, comm, out_step_dev, out_done_dev, chunk_step, chunk_done, stream);
+                          tau_sorted, pos, comm, out_step_dev, out_done_dev, stream);
     }
     if (slot) {
         if (slot->whole) DC_HIP(hipEventRecord(slot->end, stream));

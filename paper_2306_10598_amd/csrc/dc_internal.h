@@ -78,7 +78,7 @@ struct Plan {
     uint32_t p2;                // power of two > chunk: padded length of the LDS threshold array
     uint32_t max_latency;       // floor((2^31-1)/M)
     // byte offsets into the workspace
-    size_t off_status, off_tau_sorted, off_tau_u32, off_pos, off_bins, off_chunk_out, off_unit_max, off_hist_part;
+    size_t off_status, off_tau_sorted, off_tau_u32, off_pos, off_bins, off_unit_max, off_hist_part;
     size_t off_partial;         // per-iteration speedup pass: float64 [grid][p2]
     size_t bytes;
 };
@@ -93,7 +93,7 @@ void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long*
                    const uint32_t* unit_max, const uint32_t* tau_chunk, uint32_t kc,
                    unsigned long long* trial_cnt, unsigned long long* trial_sum, uint32_t* status, uint32_t chunk0,
                    const int64_t* tau_sorted, const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done,
-                   int64_t* chunk_step, int64_t* chunk_done, hipStream_t stream);
+                   hipStream_t stream);
 void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                        const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
                        hipStream_t stream);

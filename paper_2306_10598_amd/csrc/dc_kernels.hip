@@ -1144,8 +1144,6 @@ struct FinalArgs {
     long long comm;
     long long* out_step;
     long long* out_done;
-    long long* chunk_step;
-    long long* chunk_done;
 };
 
 __device__ __forceinline__ unsigned long long load_device_scope(const unsigned long long* p) {
@@ -1153,22 +1151,28 @@ __device__ __forceinline__ unsigned long long load_device_scope(const unsigned l
 }
 
 template <uint32_t THREADS>
-__device__ __forceinline__ void finalize_chunk(const FinalArgs& f) {
+__device__ __forceinline__ void finalize_chunk(const FinalArgs& f, long long* s_step, long long* s_done) {
     constexpr uint32_t MAX_PER = (DC_CHUNK_THRESHOLDS + 1u + THREADS - 1u) / THREADS;   // p2 <= 4096
     __shared__ unsigned long long s_a[THREADS], s_b[THREADS], s_c[THREADS];
     const uint32_t tid = threadIdx.x;
     const uint32_t per = (f.p2 + THREADS - 1) / THREADS;           // each thread owns a contiguous run of bins
     const uint32_t b0 = tid * per;
     unsigned long long h[MAX_PER], c[MAX_PER], s[MAX_PER];
+    long long tau[MAX_PER];
     unsigned long long th = 0, tc = 0, ts = 0;
+    // everything this step reads from device memory is requested here, in one go: a block that runs alone waits
+    // a few microseconds for every dependent round trip
+    const uint32_t first_pos = tid < f.K ? f.pos[tid] : 0xFFFFFFFFu;
 #pragma unroll
     for (uint32_t i = 0; i < MAX_PER; ++i) {
         const uint32_t b = b0 + i;
         h[i] = i < per && b < f.p2 ? load_device_scope(&f.hist_total[b]) : 0ull;
         c[i] = i < per && b <= f.kc ? load_device_scope(&f.trial_cnt[b]) : 0ull;
         s[i] = i < per && b <= f.kc ? load_device_scope(&f.trial_sum[b]) : 0ull;
-        th += h[i]; tc += c[i]; ts += s[i];
+        tau[i] = i < per && b < f.kc ? f.tau_sorted[f.chunk0 + b] : 0ll;
     }
+#pragma unroll
+    for (uint32_t i = 0; i < MAX_PER; ++i) { th += h[i]; tc += c[i]; ts += s[i]; }
     s_a[tid] = th; s_b[tid] = tc; s_c[tid] = ts;
     __syncthreads();
     for (uint32_t d = 1; d < THREADS; d <<= 1) {                    // inclusive scan over threads
@@ -1186,26 +1190,23 @@ __device__ __forceinline__ void finalize_chunk(const FinalArgs& f) {
         run_h += h[i]; run_c += c[i]; run_s += s[i];                 // inclusive up to bin b
         if (i < per && b < f.kc) {
             const unsigned long long not_done = all_hist - run_h;
-            const long long tau = f.tau_sorted[f.chunk0 + b];
-            const unsigned long long tau_c = tau >= (long long)DC_TAU_CLAMP ? (unsigned long long)DC_TAU_CLAMP
-                                                                           : (unsigned long long)(tau < 0 ? 0 : tau);
-            f.chunk_done[b] = (long long)(f.elements - not_done);
-            f.chunk_step[b] = (long long)(run_s + tau_c * (f.T - run_c) + f.T * (unsigned long long)f.comm);
+            const unsigned long long tau_c = tau[i] >= (long long)DC_TAU_CLAMP ? (unsigned long long)DC_TAU_CLAMP
+                                                                               : (unsigned long long)(tau[i] < 0 ? 0 : tau[i]);
+            s_done[b] = (long long)(f.elements - not_done);          // the chunk's results stay in LDS until they are
+            s_step[b] = (long long)(run_s + tau_c * (f.T - run_c) + f.T * (unsigned long long)f.comm);   // scattered
         }
     }
-    __syncthreads();
     for (uint32_t b = tid; b < f.p2; b += THREADS) {
         f.hist_total[b] = 0ull;
         if (b <= f.kc) { f.trial_cnt[b] = 0ull; f.trial_sum[b] = 0ull; }
     }
-    __threadfence_block();
+    if (tid == 0 && f.chunk0 == 0u && f.kc > 0u && tau[0] < 0) atomicOr(f.status, DC_FLAG_NEGATIVE_TAU);
     __syncthreads();
-    if (tid == 0 && f.chunk0 == 0u && f.tau_sorted[0] < 0) atomicOr(f.status, DC_FLAG_NEGATIVE_TAU);
     for (uint32_t j = tid; j < f.K; j += THREADS) {
-        const uint32_t p = f.pos[j];
+        const uint32_t p = j == tid ? first_pos : f.pos[j];
         if (p >= f.chunk0 && p < f.chunk0 + f.kc) {
-            f.out_step[j] = f.chunk_step[p - f.chunk0];
-            f.out_done[j] = f.chunk_done[p - f.chunk0];
+            f.out_step[j] = s_step[p - f.chunk0];
+            f.out_done[j] = s_done[p - f.chunk0];
         }
     }
 }
@@ -1222,7 +1223,7 @@ void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t narrow_sl
                       uint32_t* __restrict__ status, uint32_t col_blocks, uint32_t hist_blocks,
                       const uint32_t* __restrict__ unit_max, uint32_t units_per_trial,
                       const uint32_t* __restrict__ tau_chunk, FinalArgs f) {
-    extern __shared__ unsigned long long bin_sum[];                       // (b): [p2], then the counts
+    extern __shared__ unsigned long long bin_sum[];                       // (b): [p2], then the counts; (c): 2 [p2] results
     __shared__ unsigned long long part[4][64];
     __shared__ uint32_t is_last;
     const uint32_t lane = threadIdx.x & 63u;
@@ -1296,7 +1297,8 @@ void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t narrow_sl
     if (!is_last) return;
     __threadfence();
     if (threadIdx.x == 0) status[2] = 0u;              // next pass (kernels on a stream run one after the other)
-    finalize_chunk<256>(f);
+    long long* results = reinterpret_cast<long long*>(bin_sum);   // the block's bins, if it had any, are added by now
+    finalize_chunk<256>(f, results, results + p2);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1783,7 +1785,7 @@ void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long*
                    const uint32_t* unit_max, const uint32_t* tau_chunk, uint32_t kc,
                    unsigned long long* trial_cnt, unsigned long long* trial_sum, uint32_t* status, uint32_t chunk0,
                    const int64_t* tau_sorted, const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done,
-                   int64_t* chunk_step, int64_t* chunk_done, hipStream_t stream) {
+                   hipStream_t stream) {
     const uint32_t col_blocks = (p.p2 + 63) / 64;
     const uint32_t slot_groups = (p.grid_wide + DC_REDUCE_SLOTS - 1) / DC_REDUCE_SLOTS;
     const uint32_t hist_blocks = col_blocks * slot_groups;
@@ -1796,8 +1798,7 @@ void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long*
     f.tau_sorted = tau_sorted; f.pos = pos;
     f.T = p.T; f.elements = p.elements; f.comm = (long long)comm;
     f.out_step = (long long*)out_step; f.out_done = (long long*)out_done;
-    f.chunk_step = (long long*)chunk_step; f.chunk_done = (long long*)chunk_done;
-    hipLaunchKernelGGL(dc_reduce_kernel, dim3(hist_blocks + trial_blocks), dim3(256), (size_t)p.p2 * 12, stream, hist_part,
+    hipLaunchKernelGGL(dc_reduce_kernel, dim3(hist_blocks + trial_blocks), dim3(256), (size_t)p.p2 * 16, stream, hist_part,
                        p.grid, p.grid_wide, status, col_blocks, hist_blocks, unit_max, p.units_per_trial, tau_chunk, f);
 }
 
