@@ -1235,9 +1235,15 @@ void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t narrow_sl
         const uint32_t col = (blockIdx.x % col_blocks) * 64 + lane;       // consecutive lanes, consecutive columns
         const uint32_t s0 = (blockIdx.x / col_blocks) * DC_REDUCE_SLOTS;
         const uint32_t s1 = s0 + DC_REDUCE_SLOTS < slots ? s0 + DC_REDUCE_SLOTS : slots;
+        uint32_t v[DC_REDUCE_SLOTS / 4];                                  // all requested before the first is used
+#pragma unroll
+        for (uint32_t q = 0; q < DC_REDUCE_SLOTS / 4; ++q) {
+            const uint32_t s = s0 + grp + 4u * q;
+            v[q] = col < p2 && s < s1 ? hist_part[(uint64_t)s * p2 + col] : 0u;
+        }
         unsigned long long acc = 0ull;
-        if (col < p2)
-            for (uint32_t s = s0 + grp; s < s1; s += 4) acc += hist_part[(uint64_t)s * p2 + col];
+#pragma unroll
+        for (uint32_t q = 0; q < DC_REDUCE_SLOTS / 4; ++q) acc += v[q];
         part[grp][lane] = acc;
         __syncthreads();
         if (grp == 0 && col < p2) {
@@ -1249,9 +1255,11 @@ void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t narrow_sl
         // workload crowd into a few bins, and same-address atomics in device memory serialise), then the
         // bins that were hit go to device memory: at most one addition per bin and block.
         uint32_t* bin_cnt = reinterpret_cast<uint32_t*>(bin_sum + p2);    // [p2]
+        uint32_t* tau_s = bin_cnt + p2;                                   // [p2] the pass's thresholds, for the searches
         for (uint32_t i = threadIdx.x; i < p2; i += 256) {
             bin_sum[i] = 0ull;
             bin_cnt[i] = 0u;
+            tau_s[i] = i < kc ? tau_chunk[i] : 0xFFFFFFFFu;
         }
         __syncthreads();
         // The trial blocks take groups of 256 trials round-robin: with very many trials a bin then receives one
@@ -1261,18 +1269,27 @@ void dc_reduce_kernel(const uint32_t* __restrict__ hist_part, uint32_t narrow_sl
             uint32_t tmax = 0u;
             const uint32_t* um = unit_max + (uint64_t)t * units_per_trial;
             if ((units_per_trial & 3u) == 0u) {                           // unit_max is 256-byte aligned
-                for (uint32_t j = 0; j < units_per_trial; j += 4) {
+                uint32_t j = 0;
+                for (; j + 32u <= units_per_trial; j += 32u) {            // eight independent loads at a time
+                    uint4 v[8];
+#pragma unroll
+                    for (uint32_t q = 0; q < 8; ++q) v[q] = *reinterpret_cast<const uint4*>(um + j + 4u * q);
+#pragma unroll
+                    for (uint32_t q = 0; q < 8; ++q) tmax = umax(umax(tmax, v[q].x), umax(umax(v[q].y, v[q].z), v[q].w));
+                }
+                for (; j < units_per_trial; j += 4u) {
                     const uint4 v = *reinterpret_cast<const uint4*>(um + j);
                     tmax = umax(umax(tmax, v.x), umax(umax(v.y, v.z), v.w));
                 }
             } else {
+#pragma unroll 4
                 for (uint32_t j = 0; j < units_per_trial; ++j) tmax = umax(tmax, um[j]);
             }
             // b = #{i < kc : tau_i <= tmax}; the trial's step time is tmax for thresholds i >= b, tau_i below
             uint32_t lo = 0, hi = kc;
             while (lo < hi) {
                 const uint32_t mid = (lo + hi) >> 1;
-                if (tau_chunk[mid] <= tmax) lo = mid + 1; else hi = mid;
+                if (tau_s[mid] <= tmax) lo = mid + 1; else hi = mid;
             }
             atomicAdd(&bin_cnt[lo], 1u);
             atomicAdd(&bin_sum[lo], (unsigned long long)tmax);
