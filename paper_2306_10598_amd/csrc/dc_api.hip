@@ -268,6 +268,7 @@ uint32_t wanted_blocks_per_cu(const dc::Plan& p) {
 // per load, else which of the kernels for arbitrary rows (built for rows of 1, 2, 3 elements, or for any longer row).
 uint32_t variant_of(const dc::Plan& p) {
     if (p.vec4) return p.M;
+    if (p.lane_rows) return 0x10000u + p.M;
     return p.M < 4 ? p.M : 4u;
 }
 
@@ -325,7 +326,6 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
     p.grid_wide = planned < resident.wide_blocks ? planned : resident.wide_blocks;
     if (p.grid > resident.blocks) p.grid = resident.blocks;
     if (p.grid_wide < p.grid) p.grid_wide = p.grid;
-    const uint32_t sample_rows = p.grid_wide > p.grid ? DC_SAMPLE_ROWS : 0u;
     // Long runs of consecutive units per block stream best in the kernels with whole rows per load (+2-3.5 %), as
     // long as every block still gets several runs; the flat kernel, with its larger units, is 6-11 % faster when
     // every block jumps ahead by the whole grid after each round of four units.
@@ -334,6 +334,7 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
         p.run = DC_UNIT_RUN;
         while (p.run > DC_SCAN_WAVES && (uint64_t)p.units < 4ull * p.run * p.grid) p.run >>= 1;
     }
+    const uint32_t sample_rows = p.grid_wide > p.grid ? DC_SAMPLE_ROWS : 0u;
     uint32_t* status = reinterpret_cast<uint32_t*>(ws + p.off_status);
     int64_t* tau_sorted = reinterpret_cast<int64_t*>(ws + p.off_tau_sorted);
     uint32_t* tau_u32 = reinterpret_cast<uint32_t*>(ws + p.off_tau_u32);
