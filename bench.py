@@ -276,11 +276,15 @@ def bench_worker_moments(args, r, lat) -> int:
     return 0
 
 
-def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0) -> str:
+def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0, T: int = 0) -> str:
     """The streaming kernel the library runs for N rows of M elements per trial (16-byte aligned, contiguous tensor),
     as a profile names it."""
     if M <= 16 and N % 4 == 0 and N >= 256:                            # every lane holds whole rows
-        return f"dc_scan_rows_kernel<{M}>"
+        return f"dc_scan_rows_kernel<{M}, false>"
+    if M <= 16 and N % 4 == 0 and M not in (1, 2, 4):                  # the same over trials of few workers, unless
+        per_load = 64 // (M // 4) if M % 4 == 0 else 0                 # whole rows per load fill their loads well
+        if per_load == 0 or (N * 100 < -(-N // per_load) * per_load * 85 and T * N * M >= 1 << 22):
+            return f"dc_scan_rows_kernel<{M}, true>"
     if M % 4 == 0 and (M <= 128 or M == 256):
         lanes = M // 4
         known = lanes if lanes & (lanes - 1) == 0 else 0              # one instantiation serves every other lane count
@@ -455,7 +459,7 @@ def main() -> int:
         "config": {"workload": f"{r.name}: T={r.T} N={r.N} M={r.M} K={K} comm={r.comm}us, {r.description}",
                    "grid": args.grid, "tensor_bytes": r.nbytes, "best_tau_us": int(taus[best]),
                    "best_thr_per_us": float(thr[best])},
-        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(r.M, args.grid, r.N), "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(r.M, args.grid, r.N, r.T), "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "traffic_source": traffic_source,
                      "kernel_ms": scan_avg_ms, "kernel_ms_min": float(np.min(scan_ms)),

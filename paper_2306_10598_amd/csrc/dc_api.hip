@@ -80,13 +80,29 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     p.K = (uint32_t)K;
     const bool aligned = allow_vec4 && (p.stride & 3u) == 0;          // every trial starts on a 16-byte boundary
     p.lane_rows = aligned && M <= 16 && (N & 3) == 0 && N >= (int64_t)DC_LANE_ROWS_MIN_N;
+    // fewer workers: the same kernel over the tensor as one run of T*N rows, when the tensor is contiguous and a lane's
+    // four rows are consecutive (rows of 1, 2 and 4 elements are dealt to the lanes vector by vector instead)
+    bool span = DC_SPAN_TRIALS != 0 && aligned && !p.lane_rows && M <= 16 && M != 1 && M != 2 && M != 4 && (N & 3) == 0 &&
+                p.stride == (uint64_t)N * (uint64_t)M && (uint64_t)T * (uint64_t)N < ((uint64_t)1 << 31);
+    if (span && (M & 3) == 0) {
+        // rows of 8, 12 and 16 elements also fit the kernel with whole rows per load, which is the faster one
+        // (5.5-5.9 against 4.0-5.4 TB/s on 512 MB with 200 workers) unless the trial's last load is mostly empty
+        const int64_t rows_per_load = 64 / (M / 4);
+        const int64_t loads = (N + rows_per_load - 1) / rows_per_load;
+        span = N * 100 < loads * rows_per_load * 85 && p.elements >= ((uint64_t)1 << 22);   // (below 16 MB either takes 8-9 us)
+    }
+    if (span) { p.lane_rows = true; p.span_rows = (uint32_t)N; }
     p.vec4 = aligned && !p.lane_rows && vec4_shape(M);
     uint64_t upt;
     if (p.lane_rows) {
         // chunks of whole rows; about DC_FLAT_UNIT_ELEMENTS elements per unit, the units of a trial of equal size
         const uint64_t chunk_rows = dc::lane_rows_chunk_rows((uint32_t)M);
-        const uint64_t chunks = ((uint64_t)N + chunk_rows - 1) / chunk_rows;
+        const uint64_t run_rows = span ? (uint64_t)T * (uint64_t)N : (uint64_t)N;
+        const uint64_t chunks = (run_rows + chunk_rows - 1) / chunk_rows;
         uint64_t want = DC_FLAT_UNIT_ELEMENTS / (chunk_rows * (uint64_t)M);
+        // a small tensor is cut into more, shorter units, so that every wave of the chip has one
+        const uint64_t all_chunks = span ? chunks : chunks * (uint64_t)T;
+        if (want > all_chunks / (4ull * DC_MAX_SCAN_BLOCKS)) want = all_chunks / (4ull * DC_MAX_SCAN_BLOCKS);
         if (want < 1) want = 1;
         const uint64_t pieces = (chunks + want - 1) / want;
         p.per_unit = (uint32_t)((chunks + pieces - 1) / pieces);
@@ -106,7 +122,7 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
         p.per_unit = (uint32_t)rows;
         upt = ((uint64_t)N + rows - 1) / rows;
     }
-    const uint64_t units = (uint64_t)T * upt;
+    const uint64_t units = span ? upt : (uint64_t)T * upt;
     if (units >= ((uint64_t)1 << 31)) return false;
     p.units_per_trial = (uint32_t)upt;
     p.units = (uint32_t)units;
@@ -124,7 +140,7 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     p.off_tau_u32 = off;    off += align256((size_t)K * 4);
     p.off_pos = off;        off += align256((size_t)K * 4);
     p.off_bins = off;       off += align256((size_t)3 * p.p2 * 8);
-    p.off_unit_max = off;   off += align256((size_t)p.units * 4);
+    p.off_unit_max = off;   off += align256((size_t)(span && p.T > p.units ? p.T : p.units) * 4);   // or one word per trial
     p.off_hist_part = off;  off += align256((size_t)p.grid * p.p2 * 4);
     p.bytes = off;
     *out = p;
@@ -355,7 +371,8 @@ int enqueue(const dc::Plan& plan, const int32_t* lat, const int64_t* taus_dev, i
     }
     drop_stale_hip_error();
     dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, hist_total, 3 * p.p2, lat,
-                    (uint64_t)p.T * p.N, p.N, p.stride, p.M, sample_rows, stream);
+                    (uint64_t)p.T * p.N, p.N, p.stride, p.M, sample_rows, p.span_rows ? unit_max : nullptr,
+                    p.span_rows ? p.T : 0u, stream);
     for (uint32_t c = 0; c < chunks; ++c) {
         const uint32_t chunk0 = c * p.chunk;
         const uint32_t kc = p.K - chunk0 < p.chunk ? p.K - chunk0 : p.chunk;
@@ -404,7 +421,7 @@ int enqueue_speedup(const dc::Plan& plan, const int32_t* lat, const int64_t* tau
     }
     drop_stale_hip_error();
     dc::launch_prep(taus_dev, p.K, tau_sorted, tau_u32, pos, status, nullptr, 0, lat, (uint64_t)p.T * p.N, p.N, p.stride,
-                    p.M, sample_rows, stream);
+                    p.M, sample_rows, nullptr, 0u, stream);
     for (uint32_t c = 0; c < chunks; ++c) {
         const uint32_t chunk0 = c * p.chunk;
         const uint32_t kc = p.K - chunk0 < p.chunk ? p.K - chunk0 : p.chunk;

@@ -34,6 +34,12 @@
 #ifndef DC_LANE_ROWS_MIN_N
 #define DC_LANE_ROWS_MIN_N 256u         // workers per trial from which short rows are streamed with whole rows per lane
 #endif
+#ifndef DC_SPAN_TRIALS
+#define DC_SPAN_TRIALS 1                // short rows of few workers: stream the tensor as one run of rows (0: never)
+#endif
+#ifndef DC_ROWS_PREFETCH_MAX_V
+#define DC_ROWS_PREFETCH_MAX_V 8        // rows of up to this many elements: the next chunk's loads are in flight during a chunk's arithmetic
+#endif
 #define DC_SAMPLE_ROWS 32               // rows of lat that the sample reads (a multiple of 4: a quarter per wave)
 #ifndef DC_MAX_SCAN_BLOCKS
 #define DC_MAX_SCAN_BLOCKS 2048u        // upper bound of the grid (sizes the per-block histograms in the workspace)
@@ -68,6 +74,8 @@ struct Plan {
     bool vec4;                  // 16-byte loads, whole rows per load (M a multiple of 4 up to 128, or 256; lat 16-byte aligned)
     bool lane_rows;             // every lane holds whole rows (M <= 15 and not a multiple of 4, N a multiple of 4 and at
                                 // least DC_LANE_ROWS_MIN_N, trials 16-byte aligned); never set together with vec4
+    uint32_t span_rows;         // lane_rows with few workers per trial on a contiguous tensor: N, and the units ignore the
+                                // trials (unit_max then holds one maximum per trial); 0 otherwise
     uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; lane_rows: chunks per unit; otherwise rows per unit
     uint32_t units_per_trial;
     uint32_t units;             // T * units_per_trial
@@ -86,7 +94,7 @@ struct Plan {
 void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t* tau_u32, uint32_t* pos,
                  uint32_t* status, unsigned long long* bins, uint32_t bins_words, const int32_t* lat,
                  uint64_t rows_total, uint32_t N, uint64_t trial_stride, uint32_t M, uint32_t sample_rows,
-                 hipStream_t stream);
+                 uint32_t* zero_words, uint32_t zero_count, hipStream_t stream);
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
                  uint32_t* hist_part, uint32_t* status, hipStream_t stream);
 void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long* hist_total,

@@ -398,7 +398,8 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
                     uint32_t* __restrict__ pos, uint32_t* __restrict__ status,
                     unsigned long long* __restrict__ bins, uint32_t bins_words,
                     const int32_t* __restrict__ lat, unsigned long long rows_total, uint32_t N,
-                    unsigned long long trial_stride, uint32_t M, uint32_t sample_rows) {
+                    unsigned long long trial_stride, uint32_t M, uint32_t sample_rows,
+                    uint32_t* __restrict__ zero_words, uint32_t zero_count) {
     // A block ranks 32 thresholds; the comparisons of each are split over 8 threads.
     constexpr uint32_t TILE = 1024;
     __shared__ int64_t tile[TILE];
@@ -412,6 +413,7 @@ void dc_prep_kernel(const int64_t* __restrict__ taus, uint32_t K,
     if (sampling) sm = sample_begin(taus, K, lat, rows_total, N, trial_stride, M, sample_rows);
     if (gid == 0) { status[0] = 0u; status[2] = 0u; }   // value flags (set by later kernels) and the reduce kernel's ticket
     for (uint32_t i = gid; i < bins_words; i += stride) bins[i] = 0ull;
+    for (uint32_t i = gid; i < zero_count; i += stride) zero_words[i] = 0u;      // per-trial maxima built with atomics
     const uint32_t jj = threadIdx.x & 31u, part = threadIdx.x >> 5;
     const uint32_t j = blockIdx.x * 32 + jj;
     const int64_t mine = j < K ? taus[j] : 0;
@@ -949,8 +951,8 @@ void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint64
 }
 
 // ---------------------------------------------------------------------------------------------
-// dc_scan_rows_kernel: short rows that a lane can own.  M <= 15 and not a multiple of 4, N a multiple of 4, every
-// trial on a 16-byte boundary.
+// dc_scan_rows_kernel: short rows that a lane can own.  M <= 16, N a multiple of 4, every trial on a 16-byte
+// boundary.
 // The kernels above spread a row over lanes and pay for it with cross-lane sums and, per 16-byte load, one queue
 // slot or one search per element; with rows of a few elements that arithmetic, not HBM, bounds them.  Here a lane
 // holds R whole rows in registers (V 16-byte vectors = R*M elements), so completion times are R*M plain additions,
@@ -966,7 +968,7 @@ struct LaneRows {
     static constexpr bool STAGED = (4 % M) != 0;
     static constexpr int V = STAGED ? M : 4;          // vectors per lane and chunk
     static constexpr int R = 4 * V / M;               // rows per lane and chunk
-    static constexpr bool PREFETCH = V <= 8;          // the next chunk's loads are issued before this chunk's arithmetic
+    static constexpr bool PREFETCH = V <= DC_ROWS_PREFETCH_MAX_V;   // the next chunk's loads are issued before this chunk's arithmetic
     // A lane's vectors sit SPAN vectors from the next lane's in LDS: an odd number, so that eight lanes reading 16 bytes
     // each fall on different banks (with SPAN = V and V = 8 or 16 every lane of the wave would meet in one bank).
     static constexpr int SPAN = STAGED ? (V | 1) : 0;
@@ -1062,12 +1064,31 @@ __device__ __forceinline__ void rows_chunk(WaveState& st, u32x4 (&x)[LaneRows<M>
     }
 }
 
-template <int M>
+// The lanes' maxima of one chunk, when a chunk may hold rows of several trials (SPAN): trials are runs of at most
+// trial_rows / 4 consecutive lanes, so a running maximum over lanes that restarts where the trial changes (steps up to
+// that length suffice) leaves every trial's maximum in the last of its lanes, which adds it to the trial's word
+// (cleared by the prep kernel) with one atomic maximum.
+__device__ __forceinline__ void add_trial_maxima(uint32_t m, uint32_t t, bool valid, uint32_t lane, uint32_t trial_lanes,
+                                                 uint32_t* trial_max) {
+    const uint32_t key = valid ? t : 0xFFFFFFFFu;
+    for (uint32_t d = 1; d < 64u && d < trial_lanes; d <<= 1) {                  // wave-uniform bounds
+        const uint32_t om = (uint32_t)__shfl_up((int)m, d, 64);
+        const uint32_t ok = (uint32_t)__shfl_up((int)key, d, 64);
+        if (lane >= d && ok == key) m = umax(m, om);
+    }
+    const uint32_t next = (uint32_t)__shfl_down((int)key, 1, 64);
+    if (valid && (lane == 63u || next != key)) atomicMax(&trial_max[t], m);
+}
+
+// SPAN = false: a unit is a run of chunks inside one trial and unit_max[u] receives its maximum.  SPAN = true (few
+// workers per trial, contiguous tensor): the tensor is one run of N = T * trial_rows rows, units and chunks ignore
+// the trials, and unit_max[t] is trial t's maximum, built with atomic maxima.
+template <int M, bool SPAN>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_scan_rows_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride, uint32_t N, uint32_t units, uint32_t units_per_trial,
                          uint32_t run, uint32_t chunks_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
                          uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part, uint32_t* __restrict__ status,
-                         uint32_t max_latency) {
+                         uint32_t max_latency, uint32_t trial_rows) {
     using S = LaneRows<M>;
     constexpr int V = S::V;
     constexpr uint32_t CHUNK_ROWS = 64u * S::R, CHUNK_VECTORS = 64u * V;
@@ -1092,10 +1113,17 @@ void dc_scan_rows_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride,
             const uint32_t nv = rows / 4u * (uint32_t)M;                                  // rows is a multiple of 4
             const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)row0 * M);
             st.lane_max = 0u;
+            uint32_t trial = 0u, within = 0u, trial_recip = 0u;            // SPAN: where the chunk's first row sits
+            if constexpr (SPAN) {
+                trial = row0 / trial_rows;
+                within = row0 - trial * trial_rows;
+                trial_recip = ((1u << 20) + trial_rows - 1u) / trial_rows;
+            }
             u32x4 x[V];
             rows_load<M>(x, base, 0u, nv, lane);
             for (uint32_t first = 0; first < nv; first += CHUNK_VECTORS) {
                 const uint32_t left = nv - first;
+                if constexpr (SPAN) st.lane_max = 0u;
                 if constexpr (S::PREFETCH) {
                     u32x4 ahead[V];
 #pragma unroll
@@ -1110,9 +1138,22 @@ void dc_scan_rows_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride,
                     else rows_chunk<M, false>(st, x, left, stage, g, lane);
                     if (left > CHUNK_VECTORS) rows_load<M>(x, base, first + CHUNK_VECTORS, nv, lane);
                 }
+                if constexpr (SPAN) {
+                    static_assert(!SPAN || (S::STAGED && S::R == 4), "a lane's rows must be consecutive");
+                    // the lane's first row: row `within + 4 lane` of the tensor counted from the head of trial `trial`;
+                    // within + 4 lane < 512 and trial_rows <= 252, so the fixed-point quotient is exact
+                    const uint32_t ahead = within + 4u * lane;
+                    const uint32_t t = trial + ((ahead * trial_recip) >> 20);
+                    add_trial_maxima(st.lane_max, t, row0 + first / (uint32_t)M * 4u + 4u * lane < N, lane, trial_rows / 4u, unit_max);
+                    trial += CHUNK_ROWS / trial_rows;                       // the next chunk starts 256 rows further on
+                    within += CHUNK_ROWS % trial_rows;
+                    if (within >= trial_rows) { within -= trial_rows; ++trial; }
+                }
             }
-            const uint32_t m = wave_max(st.lane_max);
-            if (lane == 0) unit_max[u] = m;
+            if constexpr (!SPAN) {
+                const uint32_t m = wave_max(st.lane_max);
+                if (lane == 0) unit_max[u] = m;
+            }
         }
         __syncthreads();
     }
@@ -1667,13 +1708,15 @@ namespace dc {
 void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t* tau_u32, uint32_t* pos,
                  uint32_t* status, unsigned long long* bins, uint32_t bins_words, const int32_t* lat,
                  uint64_t rows_total, uint32_t N, uint64_t trial_stride, uint32_t M, uint32_t sample_rows,
-                 hipStream_t stream) {
+                 uint32_t* zero_words, uint32_t zero_count, hipStream_t stream) {
     const uint32_t threads = 256;                 // 32 thresholds per block
     uint32_t blocks = (K + 31) / 32;
     if (blocks == 0) blocks = 1;
+    const uint32_t clearing = (zero_count + 4095u) / 4096u;           // blocks beyond the thresholds only clear
+    if (blocks < clearing) blocks = clearing < 64u ? clearing : 64u;
     hipLaunchKernelGGL(dc_prep_kernel, dim3(blocks), dim3(threads), 0, stream, taus, K, tau_sorted, tau_u32, pos,
                        status, bins, bins_words, lat, (unsigned long long)rows_total, N ? N : 1u,
-                       (unsigned long long)trial_stride, M, sample_rows);
+                       (unsigned long long)trial_stride, M, sample_rows, zero_words, zero_count);
 }
 
 size_t scan_lds_bytes(const Plan& p) {
@@ -1697,7 +1740,7 @@ int scan_blocks_per_cu(const Plan& p) {
     if (p.lane_rows) {
         hipError_t e = hipErrorInvalidValue;
         switch (p.M) {
-#define DC_ROWS_CASE(m) case m: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_rows_kernel<m>, DC_SCAN_THREADS, lds); break;
+#define DC_ROWS_CASE(m) case m: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_rows_kernel<m, false>, DC_SCAN_THREADS, lds); break;
             DC_ROWS_CASE(1) DC_ROWS_CASE(2) DC_ROWS_CASE(3) DC_ROWS_CASE(4) DC_ROWS_CASE(5) DC_ROWS_CASE(6) DC_ROWS_CASE(7)
             DC_ROWS_CASE(8) DC_ROWS_CASE(9) DC_ROWS_CASE(10) DC_ROWS_CASE(11) DC_ROWS_CASE(12) DC_ROWS_CASE(13)
             DC_ROWS_CASE(14) DC_ROWS_CASE(15) DC_ROWS_CASE(16)
@@ -1758,9 +1801,17 @@ static void launch_flat(const Plan& p, const int32_t* lat, const uint32_t* tau_c
 template <int M>
 static void launch_rows(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                         uint32_t* unit_max, uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
-    hipLaunchKernelGGL(dc_scan_rows_kernel<M>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
+    if constexpr (LaneRows<M>::STAGED && LaneRows<M>::R == 4) {
+        if (p.span_rows) {                          // the tensor as one run of T * N rows
+            hipLaunchKernelGGL((dc_scan_rows_kernel<M, true>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
+                               lat, 0ull, p.T * p.N, p.units, p.units, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max,
+                               hist_part, status, p.max_latency, p.span_rows);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((dc_scan_rows_kernel<M, false>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
                        p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max,
-                       hist_part, status, p.max_latency);
+                       hist_part, status, p.max_latency, p.N);
 }
 
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
@@ -1816,7 +1867,8 @@ void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long*
     f.T = p.T; f.elements = p.elements; f.comm = (long long)comm;
     f.out_step = (long long*)out_step; f.out_done = (long long*)out_done;
     hipLaunchKernelGGL(dc_reduce_kernel, dim3(hist_blocks + trial_blocks), dim3(256), (size_t)p.p2 * 16, stream, hist_part,
-                       p.grid, p.grid_wide, status, col_blocks, hist_blocks, unit_max, p.units_per_trial, tau_chunk, f);
+                       p.grid, p.grid_wide, status, col_blocks, hist_blocks, unit_max, p.span_rows ? 1u : p.units_per_trial,
+                       tau_chunk, f);
 }
 
 template <int L>

@@ -201,6 +201,65 @@ def test_short_rows_held_whole_by_a_lane(M, N, dev):
         assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, a)
 
 
+@pytest.mark.parametrize("N", [4, 8, 64, 200, 252])
+@pytest.mark.parametrize("M", [3, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
+def test_short_rows_of_few_workers(M, N, dev):
+    """Fewer than 256 workers per trial, a multiple of 4, short rows, contiguous tensor: the lanes of a wave then hold
+    rows of several trials and the trial maxima are built with atomic maxima.  Trials whose maximum sits in their first
+    or last worker, a trial of zeros, a partial last chunk, narrow and all-covering grids."""
+    rng = np.random.default_rng(1000 * M + N)
+    T = 37
+    top = min((2**31 - 1) // M, 6000)
+    lat = rng.integers(0, top + 1, size=(T, N, M), dtype=np.int32)
+    lat[::3] //= 3                                          # neighbouring trials with different maxima
+    lat[1, 0, :] = top
+    lat[2, N - 1, :] = top
+    lat[5] = 0
+    totals = lat.sum(axis=2, dtype=np.int64)
+    narrow = np.quantile(totals, np.linspace(0.6, 1.0, 33)).astype(np.int64)
+    wide = np.concatenate([[0, 0, 1], rng.integers(0, int(totals.max()) + 50, size=60), [int(totals.max())] * 2, [BIG]])
+    lat_dev = to_dev(lat, dev)
+    for taus in (narrow, wide):
+        step, done = dc.dc_simulate(lat_dev, taus, 9)
+        ref = oracle.simulate(lat, taus, 9, "literal")
+        assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, taus[:4])
+
+
+def test_short_rows_of_few_workers_many_trials_and_passes(dev):
+    """The same path over many units and blocks, with more thresholds than one pass holds (every pass repeats the
+    atomic maxima), twice on one workspace (the maxima are cleared per call), then through the entry point without
+    a workspace."""
+    rng = np.random.default_rng(4242)
+    for T, N, M in ((30000, 20, 8), (25000, 12, 16)):      # rows of 8 and 16 elements take this path from 16 MB on
+        lat = rng.integers(0, 5000, size=(T, N, M), dtype=np.int32)
+        lat[rng.integers(0, T, 50), rng.integers(0, N, 50), :] = 30000
+        totals = lat.sum(axis=2, dtype=np.int64)
+        check(lat, rng.integers(int(totals.min()), int(totals.max()) + 10, size=200), 3, dev)
+    T, N, M = 50000, 8, 12
+    lat = rng.integers(0, 5000, size=(T, N, M), dtype=np.int32)
+    lat[rng.integers(0, T, 50), rng.integers(0, N, 50), :] = 30000
+    totals = lat.sum(axis=2, dtype=np.int64)
+    taus = rng.integers(int(totals.min()), int(totals.max()) + 10, size=5000)
+    lat_dev = to_dev(lat, dev)
+    ref = oracle.simulate(lat, taus, 11)
+    for scale in (1, 2):                                    # second call: smaller maxima on the same workspace
+        step, done = dc.dc_simulate(lat_dev // (scale * scale) if scale > 1 else lat_dev, taus, 11)
+        if scale == 1:
+            assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0])
+        else:
+            ref2 = oracle.simulate(lat // 4, taus, 11)
+            assert np.array_equal(done, ref2[1]) and np.array_equal(step, ref2[0])
+    few = np.sort(taus[:100])
+    taus_dev = torch.from_numpy(few).to(dev)
+    out = torch.zeros((2, few.size), dtype=torch.int64, device=dev)
+    flags = torch.zeros(1, dtype=torch.int32, device=dev)
+    dc.dc_simulate_static(lat_dev, taus_dev, 11, out[0], out[1], flags)
+    torch.cuda.synchronize()
+    ref3 = oracle.simulate(lat, few, 11)
+    assert int(flags.item()) == 0
+    assert np.array_equal(out[0].cpu().numpy(), ref3[0]) and np.array_equal(out[1].cpu().numpy(), ref3[1])
+
+
 def test_long_rows_and_many_rows_per_unit(dev):
     """Rows longer than a unit (one row per unit, carries across dozens of loads) and units of thousands of short rows."""
     rng = np.random.default_rng(12)
