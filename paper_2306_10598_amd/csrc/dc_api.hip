@@ -102,7 +102,8 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
         uint64_t want = DC_FLAT_UNIT_ELEMENTS / (chunk_rows * (uint64_t)M);
         // a small tensor is cut into more, shorter units, so that every wave of the chip has one
         const uint64_t all_chunks = span ? chunks : chunks * (uint64_t)T;
-        if (want > all_chunks / (4ull * DC_MAX_SCAN_BLOCKS)) want = all_chunks / (4ull * DC_MAX_SCAN_BLOCKS);
+        if (want > all_chunks / (DC_ROWS_UNITS_PER_WAVE * 4ull * DC_MAX_SCAN_BLOCKS))
+            want = all_chunks / (DC_ROWS_UNITS_PER_WAVE * 4ull * DC_MAX_SCAN_BLOCKS);
         if (want < 1) want = 1;
         const uint64_t pieces = (chunks + want - 1) / want;
         p.per_unit = (uint32_t)((chunks + pieces - 1) / pieces);

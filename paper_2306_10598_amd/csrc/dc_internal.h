@@ -34,6 +34,9 @@
 #ifndef DC_LANE_ROWS_MIN_N
 #define DC_LANE_ROWS_MIN_N 256u         // workers per trial from which short rows are streamed with whole rows per lane
 #endif
+#ifndef DC_ROWS_UNITS_PER_WAVE
+#define DC_ROWS_UNITS_PER_WAVE 1ull     // the kernel with whole rows per lane: units are shortened until a wave gets this many (8: 7-10 % slower on 512 MB)
+#endif
 #ifndef DC_SPAN_TRIALS
 #define DC_SPAN_TRIALS 1                // short rows of few workers: stream the tensor as one run of rows (0: never)
 #endif
