@@ -288,7 +288,7 @@ def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0, T: int = 0) -> st
     if M % 4 == 0 and (M <= 128 or M == 256):
         lanes = M // 4
         known = lanes if lanes & (lanes - 1) == 0 else 0              # one instantiation serves every other lane count
-        shape = 0 if M < 128 else (1 if grid == "recipe" else 2)      # long rows: <L, 1> works on narrow grids, <L, 2> on dense ones
+        shape = 0 if M not in (32, 64, 128, 256) else (1 if grid == "recipe" else 2)   # <L, 1> works on narrow grids, <L, 2> on dense ones
         return f"{SCAN_KERNEL}<{known}, {shape}>"
     return f"dc_scan_flat_kernel<{M if M < 4 else 0}>"
 

@@ -263,23 +263,37 @@ int slot_times(TimingSlot* slot, float* scan_ms, float* total_ms) {
 // The kernel splits the work statically over its waves, so every block must be resident at once (a
 // block that waits for a free slot would run alone at the end), and the same number of blocks must
 // sit on every compute unit.  Queried once per (device, kernel variant, LDS size).
-struct ResidentKey { int device; bool vec4; bool trial; uint32_t M; uint32_t p2; int blocks; int wide_blocks; };
+struct ResidentKey { int device; bool vec4; bool trial; uint32_t M; uint32_t p2; uint32_t wanted; int blocks; int wide_blocks; };
 constexpr size_t RESIDENT_SLOTS = 64;         // a fixed table: the enqueue path never touches the host heap
 ResidentKey g_resident[RESIDENT_SLOTS];
 size_t g_resident_used = 0, g_resident_next = 0;
 
-// Blocks per compute unit that stream best (measured on MI355X with 8 loads in flight per lane): long
-// rows have few completion times inside the threshold grid and want few, fat waves; short rows put a
-// large share of their lanes through the queue and the binning, whose LDS latencies need more waves
-// to hide.  `DC_SCAN_BLOCKS_PER_CU` overrides the choice at build time.
-uint32_t wanted_blocks_per_cu(const dc::Plan& p) {
+// Blocks per compute unit that stream best (measured on MI355X with 8 loads in flight per lane): rows that fill
+// whole 16-lane groups have few completion times inside a narrow threshold grid and want few, fat waves; short rows
+// put a large share of their lanes through the queue and the binning, whose LDS latencies need more waves to hide.
+// Rows of 32 and 64 elements on 4.3 GB: 6.8-6.9 TB/s with 2 blocks, 6.4-6.45 with 8; on 512 MB and 82 MB, where the
+// kernel is over before few waves have ramped up, 4 blocks are best (6.2 against 5.9-6.0 TB/s and 4.5 against 3.8-4.1).
+// `DC_SCAN_BLOCKS_PER_CU` overrides the choice at build time.
+// The second launch and the sample behind the choice cost about 15 us per call, so rows of 32 and 64 elements take
+// them from 1 GiB on and run tensors below that with one launch of 4 blocks per compute unit.
+bool two_launch_shapes(const dc::Plan& p, bool trial) {
+    if (!p.vec4) return false;
+    return p.M >= 128 || (!trial && (p.M == 32 || p.M == 64) && p.elements >= ((uint64_t)1 << 28));
+}
+
+uint32_t wanted_blocks_per_cu(const dc::Plan& p, bool trial) {
 #ifdef DC_SCAN_BLOCKS_PER_CU
     return DC_SCAN_BLOCKS_PER_CU;
 #else
     if (p.vec4 && p.M >= 128) return 2;
+    if (two_launch_shapes(p, trial)) return 2;
+    if (p.vec4 && !trial && (p.M == 32 || p.M == 64)) return 4;
     return 8;
 #endif
 }
+
+// ... and for threshold grids that cover much of the data (the second launch shape)
+uint32_t dense_blocks_per_cu(const dc::Plan& p) { return p.M >= 128 ? DC_DENSE_BLOCKS_PER_CU : 8; }
 
 // Which instantiation a plan runs, as the M field of the key: the row length for the kernels of whole rows
 // per load, else which of the kernels for arbitrary rows (built for rows of 1, 2, 3 elements, or for any longer row).
@@ -302,19 +316,20 @@ Resident resident_blocks(const dc::Plan& p, bool trial = false) {
     std::lock_guard<std::mutex> lock(g_resident_mutex);
     for (size_t i = 0; i < g_resident_used; ++i) {
         const ResidentKey& k = g_resident[i];
-        if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == variant_of(p) && k.p2 == p.p2)
+        if (k.device == device && k.vec4 == p.vec4 && k.trial == trial && k.M == variant_of(p) && k.p2 == p.p2 &&
+            k.wanted == wanted_blocks_per_cu(p, trial))
             return {(uint32_t)k.blocks, (uint32_t)k.wide_blocks};
     }
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1) cus = 256;
     int fit = trial ? dc::trial_scan_blocks_per_cu(p) : dc::scan_blocks_per_cu(p);      // what fits
     if (fit < 1) fit = 1;
-    const int wanted = (int)wanted_blocks_per_cu(p);                                    // what streams best
+    const int wanted = (int)wanted_blocks_per_cu(p, trial);                             // what streams best
     const int per_cu = fit > wanted ? wanted : fit;
     int wide_per_cu = per_cu;
-    if (p.vec4 && p.M >= 128 && per_cu < DC_DENSE_BLOCKS_PER_CU)
-        wide_per_cu = fit > DC_DENSE_BLOCKS_PER_CU ? DC_DENSE_BLOCKS_PER_CU : fit;
-    g_resident[g_resident_next] = {device, p.vec4, trial, variant_of(p), p.p2, cus * per_cu, cus * wide_per_cu};
+    const int dense = (int)dense_blocks_per_cu(p);
+    if (two_launch_shapes(p, trial) && per_cu < dense) wide_per_cu = fit > dense ? dense : fit;
+    g_resident[g_resident_next] = {device, p.vec4, trial, variant_of(p), p.p2, (uint32_t)wanted, cus * per_cu, cus * wide_per_cu};
     g_resident_next = (g_resident_next + 1) % RESIDENT_SLOTS;          // when full, the oldest entry is replaced
     if (g_resident_used < RESIDENT_SLOTS) ++g_resident_used;
     return {(uint32_t)(cus * per_cu), (uint32_t)(cus * wide_per_cu)};

@@ -1775,7 +1775,7 @@ template <int L>
 static void launch_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                         uint32_t* unit_max, uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
     if (p.grid_wide > p.grid) {                     // the sample decides on the device which of the two launches works
-        if constexpr (L == 32 || L == 64) {
+        if constexpr (L == 8 || L == 16 || L == 32 || L == 64) {
             hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 1>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
                                lat, p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max,
                                hist_part, status, p.max_latency, p.M / 4);
