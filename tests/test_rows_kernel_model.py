@@ -1,0 +1,118 @@
+"""The lane bookkeeping of the kernel in which every lane holds whole rows, modelled in NumPy.
+
+`dc_scan_rows_kernel` reads a chunk of 64 V vectors with coalesced loads (lane l takes vectors l, l + 64, ...),
+passes them through a padded stretch of LDS so that lane l ends up with vectors l V ... l V + V - 1, meets the
+thresholds from each row's end backwards, and, when a chunk may hold rows of several trials, finds every lane's trial
+with a fixed-point quotient and the trials' maxima with a running maximum over lanes that restarts where the trial
+changes.  This file writes those steps out for 64 "lanes" and checks them against their plain definitions; the kernel
+itself is compared with the oracle in test_gpu_parity.py.
+"""
+import numpy as np
+import pytest
+
+LANES = np.arange(64)
+
+
+def staged_shape(M: int):
+    """(V vectors per lane and chunk, R rows per lane and chunk, vectors between two lanes' stretches in LDS)."""
+    staged = 4 % M != 0
+    V = M if staged else 4
+    return V, 4 * V // M, (V | 1) if staged else 0
+
+
+@pytest.mark.parametrize("M", [3, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
+def test_staging_gives_every_lane_its_own_rows(M):
+    V, R, span = staged_shape(M)
+    assert R == 4 and span % 2 == 1
+    chunk = np.arange(64 * V)                                   # vector numbers of a chunk stand in for their contents
+    lds = np.full(64 * span, -1)
+    for j in range(V):                                          # write: the vector a lane loaded with instruction j
+        i = 64 * j + LANES
+        at = i if span == V else i + i // V
+        assert np.all(lds[at] == -1)                            # no two vectors share a slot
+        lds[at] = chunk[i]
+    for j in range(V):                                          # read: lane l's j-th vector
+        got = lds[LANES * span + j]
+        assert np.array_equal(got, LANES * V + j)
+    # eight consecutive lanes read 16 bytes each from eight different groups of four banks (32 banks of 4 bytes)
+    for j in range(V):
+        for l0 in range(0, 64, 8):
+            banks = ((np.arange(l0, l0 + 8) * span + j) * 4) % 32
+            assert len(set(banks.tolist())) == 8
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 5, 8, 13, 16])
+def test_backward_steps_count_what_a_search_over_every_element_counts(M):
+    """Binning the (M-1-s)-th completion time of every row for s = 0, 1, ... until no row of the wave reaches the
+    smallest threshold gives the histogram of all completion times at or above it."""
+    rng = np.random.default_rng(M)
+    for trial in range(20):
+        rows = rng.integers(0, 300, size=(256, M))
+        if trial % 4 == 0:
+            rows[rng.integers(0, 256, 40)] = 0                  # rows of zeros: equal completion times
+        p = np.cumsum(rows, axis=1)
+        taus = np.sort(rng.integers(int(p.max() * rng.uniform(0, 1)), int(p.max()) + 2, size=17))
+        want = np.bincount(np.searchsorted(taus, p.ravel(), side="right"), minlength=18)
+        hist = np.zeros(18, dtype=np.int64)
+        steps = 0
+        for s in range(M):
+            val = p[:, M - 1 - s]
+            if not np.any(val >= taus[0]):
+                break                                           # completion times do not decrease along a row
+            steps += 1
+            hist += np.bincount(np.searchsorted(taus, val, side="right"), minlength=18)
+        assert np.array_equal(hist[1:], want[1:])               # bin 0 (below every threshold) is never read
+        assert steps == int(np.max(np.sum(p >= taus[0], axis=1)))   # as many steps as the fullest row has entries in the grid
+
+
+def test_fixed_point_quotient_finds_the_trial_of_every_lane():
+    """trial offset = ((within + 4 lane) * ceil(2^20 / N)) >> 20 must equal (within + 4 lane) // N for every worker
+    count the mode is used for (a multiple of 4 below 256) and every position of a chunk's first row in its trial."""
+    for N in range(4, 256, 4):
+        recip = ((1 << 20) + N - 1) // N
+        ahead = np.arange(0, N + 4 * 63 + 1)
+        assert ahead.max() < 512 and int(ahead.max()) * recip < 2**32
+        assert np.array_equal((ahead * recip) >> 20, ahead // N), N
+
+
+def test_chunk_to_chunk_update_of_the_first_rows_trial():
+    for N in range(4, 256, 4):
+        for row0 in (0, 256 * 7, 256 * 1000 + 0):
+            trial, within = divmod(row0, N)
+            for c in range(40):
+                assert (trial, within) == divmod(row0 + 256 * c, N)
+                trial += 256 // N
+                within += 256 % N
+                if within >= N:
+                    within -= N
+                    trial += 1
+
+
+@pytest.mark.parametrize("N", [4, 8, 12, 64, 100, 200, 252])
+def test_running_maximum_restarts_where_the_trial_changes(N):
+    """Steps of 1, 2, 4, ... lanes, as many as a trial can span, leave each trial's maximum in its last lane."""
+    rng = np.random.default_rng(N)
+    trial_lanes = N // 4
+    for case in range(50):
+        within = int(rng.integers(0, N // 4)) * 4
+        valid_lanes = 64 if case % 3 else int(rng.integers(1, 65))
+        t = (within + 4 * LANES) // N
+        key = np.where(LANES < valid_lanes, t, 0xFFFFFFFF)
+        m = rng.integers(0, 1000, size=64)
+        m[LANES >= valid_lanes] = 0
+        want = {int(k): int(m[key == k].max()) for k in np.unique(key[LANES < valid_lanes])}
+        run = m.copy()
+        d = 1
+        while d < 64 and d < trial_lanes:
+            up = np.concatenate([np.zeros(d, dtype=run.dtype), run[:-d]])
+            up_key = np.concatenate([np.full(d, -1, dtype=np.int64), key[:-d].astype(np.int64)])
+            take = (LANES >= d) & (up_key == key)
+            run = np.where(take, np.maximum(run, up), run)
+            d <<= 1
+        nxt = np.concatenate([key[1:], [-2]])
+        last = (LANES < valid_lanes) & ((LANES == 63) | (nxt != key))
+        got = {}
+        for lane in np.flatnonzero(last):
+            assert int(key[lane]) not in got                    # one addition per trial and chunk
+            got[int(key[lane])] = int(run[lane])
+        assert got == want
