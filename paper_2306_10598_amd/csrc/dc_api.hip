@@ -156,7 +156,10 @@ bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4
     if (N * M >= ((int64_t)1 << 31)) return false;                            // per-trial counts are 32-bit
     p.K = (uint32_t)K;
     p.vec4 = allow_vec4 && vec4_shape(M) && (p.stride & 3u) == 0;
-    p.grid = (uint32_t)(T < (int64_t)DC_MAX_TRIAL_BLOCKS ? T : DC_MAX_TRIAL_BLOCKS);
+    p.wave_trials = p.vec4 && p.stride == (uint64_t)N * (uint64_t)M && (uint64_t)N * (uint64_t)M <= DC_WAVE_TRIAL_ELEMENTS &&
+                    K <= (int64_t)DC_WAVE_TRIAL_THRESHOLDS;
+    const int64_t owners = p.wave_trials ? (T + DC_SCAN_WAVES - 1) / DC_SCAN_WAVES : T;     // blocks that can have a trial
+    p.grid = (uint32_t)(owners < (int64_t)DC_MAX_TRIAL_BLOCKS ? owners : DC_MAX_TRIAL_BLOCKS);
     p.grid_wide = p.grid;
     if (p.vec4) {
         const uint32_t rows_per_load = 64u / (uint32_t)(M / 4);
@@ -277,7 +280,7 @@ size_t g_resident_used = 0, g_resident_next = 0;
 // The second launch and the sample behind the choice cost about 15 us per call, so rows of 32 and 64 elements take
 // them from 1 GiB on and run tensors below that with one launch of 4 blocks per compute unit.
 bool two_launch_shapes(const dc::Plan& p, bool trial) {
-    if (!p.vec4) return false;
+    if (!p.vec4 || p.wave_trials) return false;
     return p.M >= 128 || (!trial && (p.M == 32 || p.M == 64) && p.elements >= ((uint64_t)1 << 28));
 }
 
@@ -285,6 +288,7 @@ uint32_t wanted_blocks_per_cu(const dc::Plan& p, bool trial) {
 #ifdef DC_SCAN_BLOCKS_PER_CU
     return DC_SCAN_BLOCKS_PER_CU;
 #else
+    if (p.wave_trials) return 8;
     if (p.vec4 && p.M >= 128) return 2;
     if (two_launch_shapes(p, trial)) return 2;
     if (p.vec4 && !trial && (p.M == 32 || p.M == 64)) return 4;
@@ -298,6 +302,7 @@ uint32_t dense_blocks_per_cu(const dc::Plan& p) { return p.M >= 128 ? DC_DENSE_B
 // Which instantiation a plan runs, as the M field of the key: the row length for the kernels of whole rows
 // per load, else which of the kernels for arbitrary rows (built for rows of 1, 2, 3 elements, or for any longer row).
 uint32_t variant_of(const dc::Plan& p) {
+    if (p.wave_trials) return 0x20000u + p.M;
     if (p.vec4) return p.M;
     if (p.lane_rows) return 0x10000u + p.M;
     return p.M < 4 ? p.M : 4u;

@@ -37,6 +37,10 @@
 #ifndef DC_ROWS_UNITS_PER_WAVE
 #define DC_ROWS_UNITS_PER_WAVE 1ull     // the kernel with whole rows per lane: units are shortened until a wave gets this many (8: 7-10 % slower on 512 MB)
 #endif
+#ifndef DC_WAVE_TRIAL_ELEMENTS
+#define DC_WAVE_TRIAL_ELEMENTS 16384u   // per-iteration pass: trials of up to this many latencies are taken by single waves
+#endif
+#define DC_WAVE_TRIAL_THRESHOLDS 511u   // ... when one pass holds every threshold with the waves' own histograms in LDS
 #ifndef DC_SPAN_TRIALS
 #define DC_SPAN_TRIALS 1                // short rows of few workers: stream the tensor as one run of rows (0: never)
 #endif
@@ -77,6 +81,7 @@ struct Plan {
     bool vec4;                  // 16-byte loads, whole rows per load (M a multiple of 4 up to 128, or 256; lat 16-byte aligned)
     bool lane_rows;             // every lane holds whole rows (M <= 15 and not a multiple of 4, N a multiple of 4 and at
                                 // least DC_LANE_ROWS_MIN_N, trials 16-byte aligned); never set together with vec4
+    bool wave_trials;           // per-iteration pass: every wave owns a trial (small trials of whole rows per load, K <= 511)
     uint32_t span_rows;         // lane_rows with few workers per trial on a contiguous tensor: N, and the units ignore the
                                 // trials (unit_max then holds one maximum per trial); 0 otherwise
     uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; lane_rows: chunks per unit; otherwise rows per unit

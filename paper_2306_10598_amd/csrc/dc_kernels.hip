@@ -1471,6 +1471,83 @@ void dc_trial_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
     for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = sh.acc[i];
 }
 
+// Small trials (a few KiB to tens of KiB, which is what a few hundred workers with tens of accumulations give): the
+// per-trial step above, with its block-wide barriers, then costs more than reading the trial.  Here every wave owns
+// a trial of its own, with a histogram and running sums of its own in LDS, and ends it without leaving the wave:
+// each lane adds up p2/64 consecutive bins, one wave scan gives the running counts, and the lane forms S_t for its
+// thresholds.  Trials go to the waves of the grid round-robin and a wave adds its trials in ascending order; the
+// block's four sets of sums are added in wave order at the end, so the result does not depend on timing.
+template <int L>
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_trial_scan_wave_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N,
+                               const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
+                               const long long* __restrict__ comm_per_trial, long long comm,
+                               double* __restrict__ partial, uint32_t* __restrict__ status, uint32_t max_latency,
+                               uint32_t lanes_per_row) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
+    uint32_t* tables = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);
+    double* acc_all = reinterpret_cast<double*>(tables + 4 * p2);                       // [waves][p2]
+    uint32_t* hist_all = reinterpret_cast<uint32_t*>(acc_all + DC_SCAN_WAVES * p2);     // [waves][p2]
+    for (uint32_t i = threadIdx.x; i < DC_SCAN_WAVES * p2; i += DC_SCAN_THREADS) { acc_all[i] = 0.0; hist_all[i] = 0u; }
+    GridView g = stage_grid(tables, tau_chunk, kc, p2);                                 // synchronises the block
+
+    const uint32_t lane = threadIdx.x & 63u;
+    const RowShape shape = row_shape<L>(lane, lanes_per_row);
+    const uint32_t R = shape.rows;
+    const uint32_t M = 4 * shape.lanes;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint4* queue = queue_all + wave * QUEUE_ITEMS;
+    double* acc = acc_all + wave * p2;
+    g.hist = hist_all + wave * p2;                                                      // this wave's trial
+    const uint32_t nfull = N / R, tail_rows = N - nfull * R;
+    const double elements_per_trial = (double)N * (double)M;
+    const uint32_t per = (p2 + 63u) / 64u;                                              // bins per lane at the trial's end
+    const uint32_t b0 = lane * per;
+
+    WaveState st{0u, 0u, 0u, 0u};
+    for (uint32_t t = blockIdx.x * DC_SCAN_WAVES + wave; t < T; t += gridDim.x * DC_SCAN_WAVES) {
+        st.lane_max = 0u;
+        const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * N * M) + lane;
+        stream_rows<L>(st, base, nfull, tail_rows, queue, g, lane, shape);
+        while (st.q_count) drain(st, queue, g, lane);
+        const uint32_t tmax = wave_max(st.lane_max);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");                          // the wave's histogram is complete
+        uint32_t mine = 0;
+        for (uint32_t i = 0; i < per; ++i) mine += (b0 + i < p2) ? g.hist[b0 + i] : 0u;
+        const uint32_t incl = segmented_inclusive_scan<64>(mine, lane);
+        const uint32_t all = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        const long long c = comm_per_trial ? comm_per_trial[t] : comm;
+        if (c < 0 && lane == 0) atomicOr(status, DC_FLAG_NEGATIVE_TAU);
+        uint32_t run = incl - mine;                                                     // counted elements in bins below b0
+        for (uint32_t i = 0; i < per; ++i) {
+            const uint32_t b = b0 + i;
+            if (b >= p2) break;
+            const uint32_t h = g.hist[b];
+            g.hist[b] = 0u;                                                             // for the wave's next trial
+            if (b >= kc) continue;
+            run += h;
+            const uint32_t not_done = all - run;                                        // completion times at or above threshold b
+            const uint32_t tau = g.tau[b];
+            const long long capped = (long long)(tau < tmax ? tau : tmax);
+            const long long den = capped + c;
+            if (den <= 0) { atomicOr(status, DC_FLAG_ZERO_STEP); continue; }
+            const double done = elements_per_trial - (double)not_done;
+            acc[b] += (double)((long long)tmax + c) / (double)den * (done / elements_per_trial);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");                          // cleared before the next trial counts
+    }
+    report_range(st.check, max_latency, lane, status);
+    __syncthreads();
+    double* out = partial + (uint64_t)blockIdx.x * p2;
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) {
+        double sum = acc_all[i];
+#pragma unroll
+        for (uint32_t w = 1; w < DC_SCAN_WAVES; ++w) sum += acc_all[w * p2 + i];
+        out[i] = sum;
+    }
+}
+
 // Any M >= 1, any 4-byte alignment: the waves of the block take the trial's units (runs of whole rows) in
 // turn, in step, with the flat pass of dc_scan_flat_kernel.
 template <bool SMALL>
@@ -1881,9 +1958,28 @@ static int resident_trial_vec4(size_t lds) {
 size_t trial_scan_lds_bytes(const Plan& p);
 
 // Blocks of the per-trial kernel that one compute unit holds at a time (0 if the query fails).
+template <int L>
+static int resident_trial_wave(size_t lds) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_wave_kernel<L>, DC_SCAN_THREADS, lds) != hipSuccess) n = 0;
+    return n;
+}
+
 int trial_scan_blocks_per_cu(const Plan& p) {
     const size_t lds = trial_scan_lds_bytes(p);
     int n = 0;
+    if (p.wave_trials) {
+        switch (p.M / 4) {
+            case 1:  return resident_trial_wave<1>(lds);
+            case 2:  return resident_trial_wave<2>(lds);
+            case 4:  return resident_trial_wave<4>(lds);
+            case 8:  return resident_trial_wave<8>(lds);
+            case 16: return resident_trial_wave<16>(lds);
+            case 32: return resident_trial_wave<32>(lds);
+            case 64: return resident_trial_wave<64>(lds);
+            default: return resident_trial_wave<0>(lds);
+        }
+    }
     if (!p.vec4) {
         if ((p.M < 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_flat_kernel<true>, DC_SCAN_THREADS, lds)
                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_flat_kernel<false>, DC_SCAN_THREADS, lds)) != hipSuccess) n = 0;
@@ -1902,6 +1998,8 @@ int trial_scan_blocks_per_cu(const Plan& p) {
 }
 
 size_t trial_scan_lds_bytes(const Plan& p) {
+    if (p.wave_trials)                                                                      // grid + every wave's sums and histogram + queues
+        return (size_t)p.p2 * 16 + (size_t)DC_SCAN_WAVES * p.p2 * 12 + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);
     const size_t tables = (size_t)p.p2 * 16 + (size_t)p.p2 * 8 + (DC_SCAN_WAVES + 1) * 4;   // grid + sums + scratch
     return tables + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);                    // + queues
 }
@@ -1930,6 +2028,23 @@ static void launch_trial_vec4(const Plan& p, const int32_t* lat, const uint32_t*
 void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                        const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
                        hipStream_t stream) {
+    if (p.wave_trials) {
+#define DC_WAVE_CASE(l) hipLaunchKernelGGL(dc_trial_scan_wave_kernel<l>, dim3(p.grid), dim3(DC_SCAN_THREADS), trial_scan_lds_bytes(p), \
+                                           stream, lat, p.T, p.N, tau_chunk, kc, p.p2, (const long long*)comm_per_trial,              \
+                                           (long long)comm, partial, status, p.max_latency, p.M / 4)
+        switch (p.M / 4) {
+            case 1:  DC_WAVE_CASE(1); break;
+            case 2:  DC_WAVE_CASE(2); break;
+            case 4:  DC_WAVE_CASE(4); break;
+            case 8:  DC_WAVE_CASE(8); break;
+            case 16: DC_WAVE_CASE(16); break;
+            case 32: DC_WAVE_CASE(32); break;
+            case 64: DC_WAVE_CASE(64); break;
+            default: DC_WAVE_CASE(0); break;
+        }
+#undef DC_WAVE_CASE
+        return;
+    }
     if (!p.vec4) {
         if (p.M < 4)
             hipLaunchKernelGGL(dc_trial_scan_flat_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS),

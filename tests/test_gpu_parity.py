@@ -580,6 +580,29 @@ def test_per_step_speedup_shapes(M, dev):
     assert np.allclose(got, oracle.per_step_speedup(lat, taus, 11), rtol=SPEEDUP_RTOL, atol=0)
 
 
+@pytest.mark.parametrize("N,M,K", [(8, 16, 40), (64, 12, 100), (64, 32, 511), (200, 64, 128), (7, 256, 33), (33, 4, 512)])
+def test_per_step_speedup_small_trials(N, M, K, dev):
+    """Trials of a few KiB: every wave owns a trial (up to 511 thresholds; 512 go the other way).  More trials than
+    the grid has waves, a trial of zeros, one of the largest legal rows, per-iteration communication times."""
+    rng = np.random.default_rng(N * 1000 + M)
+    T = 9000
+    top = min((2**31 - 1) // M, 5000)
+    lat = rng.integers(0, top + 1, size=(T, N, M), dtype=np.int32)
+    lat[3] = 0
+    lat[T - 1, N - 1, :] = (2**31 - 1) // M
+    totals = lat.sum(axis=2, dtype=np.int64)
+    taus = np.concatenate([[1, BIG], rng.integers(1, int(np.quantile(totals, 0.999)) + 50, size=K - 2)])
+    comm_t = rng.integers(1, 4000, size=T)
+    lat_dev = to_dev(lat, dev)
+    got = dc.dc_speedup_per_step(lat_dev, taus, 0, comm_t)
+    ref = oracle.per_step_speedup(lat, taus, comm_t, threads=8)
+    assert np.allclose(got, ref, rtol=SPEEDUP_RTOL, atol=0)
+    assert np.allclose(got, ref, rtol=1e-11, atol=0)
+    assert np.array_equal(got, dc.dc_speedup_per_step(lat_dev, taus, 0, comm_t))       # fixed summation order
+    got = dc.dc_speedup_per_step(lat_dev, taus, 17)
+    assert np.allclose(got, oracle.per_step_speedup(lat, taus, 17, threads=8), rtol=SPEEDUP_RTOL, atol=0)
+
+
 def test_per_step_speedup_many_trials_and_thresholds(dev):
     """More trials than blocks, more thresholds than one pass holds."""
     rng = np.random.default_rng(9)
