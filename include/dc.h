@@ -167,9 +167,10 @@ int dc_select_tau_per_step(const double* seff, const int64_t* taus, int64_t K, i
 size_t dc_speedup_workspace_bytes(int64_t T, int64_t N, int64_t M, int64_t K);
 
 /* Same, enqueued on `stream` without synchronising or allocating.  taus_dev: DEVICE K int64;
- * comm_per_trial_dev: DEVICE T int64 or NULL; out_seff_dev: DEVICE K doubles; workspace as for
- * dc_simulate_async (at least dc_speedup_workspace_bytes bytes); device-side value errors are read
- * back with dc_workspace_status. */
+ * comm_per_trial_dev: DEVICE T int64 or NULL; out_seff_dev: K doubles in any memory the device can write
+ * (device memory, or pinned host memory: the last kernel then delivers the result without a copy);
+ * workspace as for dc_simulate_async (at least dc_speedup_workspace_bytes bytes); device-side value
+ * errors are read back with dc_workspace_status. */
 int dc_speedup_per_step_async(const int32_t* lat, int64_t T, int64_t N, int64_t M,
                               const int64_t* taus_dev, int64_t K, int64_t comm,
                               const int64_t* comm_per_trial_dev, double* out_seff_dev,

@@ -271,7 +271,7 @@ def dc_speedup_per_step_async(lat, taus_dev, comm: int, comm_per_trial_dev, out_
         raise TypeError("lat must have shape [T][N][M]")
     T, N, M = lat.shape
     taus_dev = _device_tensor(taus_dev, "int64", "taus_dev")
-    out_seff_dev = _device_tensor(out_seff_dev, "float64", "out_seff_dev")
+    out_seff_dev = _device_writable(out_seff_dev, "float64", "out_seff_dev")
     workspace = _device_tensor(workspace, "uint8", "workspace")
     per_ptr = None
     if comm_per_trial_dev is not None:

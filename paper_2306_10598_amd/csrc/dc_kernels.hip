@@ -1597,33 +1597,46 @@ void dc_trial_scan_flat_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
     for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) out[i] = sh.acc[i];
 }
 
-// out_seff[j] = (sum of the per-block sums for j's sorted position) / T.  A block of 256 threads serves 32
-// thresholds; the range of blocks is cut into 8 fixed slices that are summed in order and then
-// combined in slice order, so the grouping of the float additions never changes between calls.
+// out_seff[j] = (sum of the per-block sums for j's sorted position) / T.  A block of 256 threads serves 8
+// thresholds; the range of blocks is cut into 32 fixed slices that are summed in order (eight values requested at a
+// time, added one after the other) and then combined in slice order, so the grouping of the float additions never
+// changes between calls.  (32 thresholds x 8 slices per block left a handful of blocks to read several MB of sums;
+// this shape took a call on 82 MB with 128 thresholds from 94 to 54 us.)
 __global__ __launch_bounds__(256)
 void dc_speedup_finalize_kernel(const double* __restrict__ partial, uint32_t narrow_blocks, uint32_t wide_blocks,
                                 uint32_t* __restrict__ status, const int64_t* __restrict__ tau_sorted, uint32_t p2,
                                 uint32_t kc, uint32_t chunk0, const uint32_t* __restrict__ pos, uint32_t K,
                                 double trials, double* __restrict__ out_seff) {
-    __shared__ double slice_sum[8][32];
+    constexpr uint32_t PER_BLOCK = 8, SLICES = 32;
+    __shared__ double slice_sum[SLICES][PER_BLOCK];
     if (blockIdx.x == 0 && threadIdx.x == 0 && chunk0 == 0u && tau_sorted[0] < 0) atomicOr(status, DC_FLAG_NEGATIVE_TAU);
     // per-block sums were written by the launch of the per-trial kernel that the sample chose
     const uint32_t blocks = wide_blocks > narrow_blocks && status[1] != 0u ? wide_blocks : narrow_blocks;
-    const uint32_t jj = threadIdx.x & 31u, slice = threadIdx.x >> 5;
-    const uint32_t j = blockIdx.x * 32 + jj;
+    const uint32_t jj = threadIdx.x % PER_BLOCK, slice = threadIdx.x / PER_BLOCK;
+    const uint32_t j = blockIdx.x * PER_BLOCK + jj;
     const uint32_t p = j < K ? pos[j] : 0xFFFFFFFFu;
     const bool mine = p >= chunk0 && p < chunk0 + kc;
-    const uint32_t per = (blocks + 7) / 8;
-    const uint32_t b0 = slice * per, b1 = b0 + per < blocks ? b0 + per : blocks;
+    const uint32_t per = (blocks + SLICES - 1) / SLICES;
+    const uint32_t b0 = slice * per < blocks ? slice * per : blocks, b1 = b0 + per < blocks ? b0 + per : blocks;
     double sum = 0.0;
-    if (mine)
-        for (uint32_t b = b0; b < b1; ++b) sum += partial[(uint64_t)b * p2 + (p - chunk0)];
+    if (mine) {
+        const double* col = partial + (p - chunk0);
+        uint32_t b = b0;
+        for (; b + 8u <= b1; b += 8u) {
+            double v[8];
+#pragma unroll
+            for (uint32_t q = 0; q < 8; ++q) v[q] = col[(uint64_t)(b + q) * p2];
+#pragma unroll
+            for (uint32_t q = 0; q < 8; ++q) sum += v[q];
+        }
+        for (; b < b1; ++b) sum += col[(uint64_t)b * p2];
+    }
     slice_sum[slice][jj] = sum;
     __syncthreads();
     if (slice != 0 || !mine) return;
     sum = 0.0;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) sum += slice_sum[q][jj];
+    for (uint32_t q = 0; q < SLICES; ++q) sum += slice_sum[q][jj];
     out_seff[j] = sum / trials;
 }
 
@@ -2070,7 +2083,7 @@ void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_ch
 
 void launch_speedup_finalize(const Plan& p, const double* partial, uint32_t kc, uint32_t chunk0, const uint32_t* pos,
                              uint32_t* status, const int64_t* tau_sorted, double* out_seff, hipStream_t stream) {
-    hipLaunchKernelGGL(dc_speedup_finalize_kernel, dim3((p.K + 31) / 32), dim3(256), 0, stream, partial, p.grid,
+    hipLaunchKernelGGL(dc_speedup_finalize_kernel, dim3((p.K + 7) / 8), dim3(256), 0, stream, partial, p.grid,
                        p.grid_wide, status, tau_sorted, p.p2, kc, chunk0, pos, p.K, (double)p.T, out_seff);
 }
 

@@ -635,7 +635,12 @@ def test_per_step_speedup_errors_and_async(dev):
     torch.cuda.synchronize()
     dc.dc_speedup_per_step_async(lat_d, taus_d, r.comm, None, out, ws, stream)
     assert dc.dc_workspace_status(ws, stream) == dc.DC_OK
-    assert np.allclose(out.cpu().numpy(), oracle.per_step_speedup(lat, taus, r.comm), rtol=SPEEDUP_RTOL, atol=0)
+    ref = oracle.per_step_speedup(lat, taus, r.comm)
+    assert np.allclose(out.cpu().numpy(), ref, rtol=SPEEDUP_RTOL, atol=0)
+    pinned = torch.zeros(taus.size, dtype=torch.float64).pin_memory()      # the result written straight to the host
+    dc.dc_speedup_per_step_async(lat_d, taus_d, r.comm, None, pinned, ws, stream)
+    assert dc.dc_workspace_status(ws, stream) == dc.DC_OK
+    assert np.array_equal(pinned.numpy(), out.cpu().numpy())
 
 
 # ---- analytical side: exact moments, closed-form curves ----------------------------------------------------
