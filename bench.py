@@ -141,8 +141,8 @@ def cpu_baseline(r, taus, target_seconds: float = 12.0):
 def trial_kernel_name(r, K: int) -> str:
     """The streaming kernel of the per-iteration pass for this shape (16-byte aligned, contiguous tensor)."""
     whole_rows = r.M % 4 == 0 and (r.M <= 128 or r.M == 256)
-    if whole_rows and r.N * r.M <= 16384 and K <= 511:
-        return "dc_trial_scan_wave_kernel"                             # every wave owns a trial
+    if r.N * r.M <= 16384 and K <= 511:                                # every wave owns a trial
+        return "dc_trial_scan_wave_kernel" if whole_rows else "dc_trial_scan_wave_flat_kernel"
     return "dc_trial_scan_vec4_kernel" if whole_rows else "dc_trial_scan_flat_kernel"
 
 

@@ -156,7 +156,7 @@ bool make_trial_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4
     if (N * M >= ((int64_t)1 << 31)) return false;                            // per-trial counts are 32-bit
     p.K = (uint32_t)K;
     p.vec4 = allow_vec4 && vec4_shape(M) && (p.stride & 3u) == 0;
-    p.wave_trials = p.vec4 && p.stride == (uint64_t)N * (uint64_t)M && (uint64_t)N * (uint64_t)M <= DC_WAVE_TRIAL_ELEMENTS &&
+    p.wave_trials = p.stride == (uint64_t)N * (uint64_t)M && (uint64_t)N * (uint64_t)M <= DC_WAVE_TRIAL_ELEMENTS &&
                     K <= (int64_t)DC_WAVE_TRIAL_THRESHOLDS;
     const int64_t owners = p.wave_trials ? (T + DC_SCAN_WAVES - 1) / DC_SCAN_WAVES : T;     // blocks that can have a trial
     p.grid = (uint32_t)(owners < (int64_t)DC_MAX_TRIAL_BLOCKS ? owners : DC_MAX_TRIAL_BLOCKS);

@@ -81,7 +81,7 @@ struct Plan {
     bool vec4;                  // 16-byte loads, whole rows per load (M a multiple of 4 up to 128, or 256; lat 16-byte aligned)
     bool lane_rows;             // every lane holds whole rows (M <= 15 and not a multiple of 4, N a multiple of 4 and at
                                 // least DC_LANE_ROWS_MIN_N, trials 16-byte aligned); never set together with vec4
-    bool wave_trials;           // per-iteration pass: every wave owns a trial (small trials of whole rows per load, K <= 511)
+    bool wave_trials;           // per-iteration pass: every wave owns a trial (small trials of a contiguous tensor, K <= 511)
     uint32_t span_rows;         // lane_rows with few workers per trial on a contiguous tensor: N, and the units ignore the
                                 // trials (unit_max then holds one maximum per trial); 0 otherwise
     uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; lane_rows: chunks per unit; otherwise rows per unit

@@ -1477,6 +1477,70 @@ void dc_trial_scan_vec4_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
 // each lane adds up p2/64 consecutive bins, one wave scan gives the running counts, and the lane forms S_t for its
 // thresholds.  Trials go to the waves of the grid round-robin and a wave adds its trials in ascending order; the
 // block's four sets of sums are added in wave order at the end, so the result does not depend on timing.
+struct WaveTrial {
+    double* acc_all;      // [waves][p2]
+    double* acc;          // this wave's
+    uint32_t per, b0;     // bins per lane at a trial's end, and the lane's first
+};
+
+// LDS behind the queues: tau | block histogram (unused here) | cells | sums [waves][p2] | histograms [waves][p2].
+// Returns the grid with the calling wave's histogram; synchronises the block.
+__device__ __forceinline__ GridView stage_wave_trials(unsigned char* smem, const uint32_t* __restrict__ tau_chunk,
+                                                      uint32_t kc, uint32_t p2, uint32_t wave, uint32_t lane, WaveTrial* wt) {
+    uint32_t* tables = reinterpret_cast<uint32_t*>(reinterpret_cast<uint4*>(smem) + DC_SCAN_WAVES * QUEUE_ITEMS);
+    wt->acc_all = reinterpret_cast<double*>(tables + 4 * p2);
+    uint32_t* hist_all = reinterpret_cast<uint32_t*>(wt->acc_all + DC_SCAN_WAVES * p2);
+    for (uint32_t i = threadIdx.x; i < DC_SCAN_WAVES * p2; i += DC_SCAN_THREADS) { wt->acc_all[i] = 0.0; hist_all[i] = 0u; }
+    GridView g = stage_grid(tables, tau_chunk, kc, p2);
+    wt->acc = wt->acc_all + wave * p2;
+    wt->per = (p2 + 63u) / 64u;
+    wt->b0 = lane * wt->per;
+    g.hist = hist_all + wave * p2;
+    return g;
+}
+
+// The wave's trial t is binned: S_t for every threshold of the pass, and the histogram cleared for the next trial.
+__device__ __forceinline__ void finish_wave_trial(const GridView& g, const WaveTrial& wt, uint32_t kc, uint32_t t,
+                                                  uint32_t tmax, const long long* __restrict__ comm_per_trial, long long comm,
+                                                  double elements_per_trial, uint32_t lane, uint32_t* status) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");                          // the wave's histogram is complete
+    uint32_t mine = 0;
+    for (uint32_t i = 0; i < wt.per; ++i) mine += (wt.b0 + i < g.p2) ? g.hist[wt.b0 + i] : 0u;
+    const uint32_t incl = segmented_inclusive_scan<64>(mine, lane);
+    const uint32_t all = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    const long long c = comm_per_trial ? comm_per_trial[t] : comm;
+    if (c < 0 && lane == 0) atomicOr(status, DC_FLAG_NEGATIVE_TAU);
+    uint32_t run = incl - mine;                                                     // counted elements in bins below b0
+    for (uint32_t i = 0; i < wt.per; ++i) {
+        const uint32_t b = wt.b0 + i;
+        if (b >= g.p2) break;
+        const uint32_t h = g.hist[b];
+        g.hist[b] = 0u;
+        if (b >= kc) continue;
+        run += h;
+        const uint32_t not_done = all - run;                                        // completion times at or above threshold b
+        const uint32_t tau = g.tau[b];
+        const long long capped = (long long)(tau < tmax ? tau : tmax);
+        const long long den = capped + c;
+        if (den <= 0) { atomicOr(status, DC_FLAG_ZERO_STEP); continue; }
+        const double done = elements_per_trial - (double)not_done;
+        wt.acc[b] += (double)((long long)tmax + c) / (double)den * (done / elements_per_trial);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");                          // cleared before the next trial counts
+}
+
+// partial[block][i] = the four waves' sums in wave order.  Every thread of the block must call it.
+__device__ __forceinline__ void write_wave_trial_sums(const WaveTrial& wt, uint32_t p2, double* __restrict__ partial) {
+    __syncthreads();
+    double* out = partial + (uint64_t)blockIdx.x * p2;
+    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) {
+        double sum = wt.acc_all[i];
+#pragma unroll
+        for (uint32_t w = 1; w < DC_SCAN_WAVES; ++w) sum += wt.acc_all[w * p2 + i];
+        out[i] = sum;
+    }
+}
+
 template <int L>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_trial_scan_wave_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N,
@@ -1485,25 +1549,16 @@ void dc_trial_scan_wave_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
                                double* __restrict__ partial, uint32_t* __restrict__ status, uint32_t max_latency,
                                uint32_t lanes_per_row) {
     extern __shared__ __align__(16) unsigned char smem[];
-    uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
-    uint32_t* tables = reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS);
-    double* acc_all = reinterpret_cast<double*>(tables + 4 * p2);                       // [waves][p2]
-    uint32_t* hist_all = reinterpret_cast<uint32_t*>(acc_all + DC_SCAN_WAVES * p2);     // [waves][p2]
-    for (uint32_t i = threadIdx.x; i < DC_SCAN_WAVES * p2; i += DC_SCAN_THREADS) { acc_all[i] = 0.0; hist_all[i] = 0u; }
-    GridView g = stage_grid(tables, tau_chunk, kc, p2);                                 // synchronises the block
-
     const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    WaveTrial wt;
+    const GridView g = stage_wave_trials(smem, tau_chunk, kc, p2, wave, lane, &wt);
     const RowShape shape = row_shape<L>(lane, lanes_per_row);
     const uint32_t R = shape.rows;
     const uint32_t M = 4 * shape.lanes;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    uint4* queue = queue_all + wave * QUEUE_ITEMS;
-    double* acc = acc_all + wave * p2;
-    g.hist = hist_all + wave * p2;                                                      // this wave's trial
+    uint4* queue = reinterpret_cast<uint4*>(smem) + wave * QUEUE_ITEMS;
     const uint32_t nfull = N / R, tail_rows = N - nfull * R;
     const double elements_per_trial = (double)N * (double)M;
-    const uint32_t per = (p2 + 63u) / 64u;                                              // bins per lane at the trial's end
-    const uint32_t b0 = lane * per;
 
     WaveState st{0u, 0u, 0u, 0u};
     for (uint32_t t = blockIdx.x * DC_SCAN_WAVES + wave; t < T; t += gridDim.x * DC_SCAN_WAVES) {
@@ -1511,41 +1566,39 @@ void dc_trial_scan_wave_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
         const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * N * M) + lane;
         stream_rows<L>(st, base, nfull, tail_rows, queue, g, lane, shape);
         while (st.q_count) drain(st, queue, g, lane);
-        const uint32_t tmax = wave_max(st.lane_max);
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");                          // the wave's histogram is complete
-        uint32_t mine = 0;
-        for (uint32_t i = 0; i < per; ++i) mine += (b0 + i < p2) ? g.hist[b0 + i] : 0u;
-        const uint32_t incl = segmented_inclusive_scan<64>(mine, lane);
-        const uint32_t all = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-        const long long c = comm_per_trial ? comm_per_trial[t] : comm;
-        if (c < 0 && lane == 0) atomicOr(status, DC_FLAG_NEGATIVE_TAU);
-        uint32_t run = incl - mine;                                                     // counted elements in bins below b0
-        for (uint32_t i = 0; i < per; ++i) {
-            const uint32_t b = b0 + i;
-            if (b >= p2) break;
-            const uint32_t h = g.hist[b];
-            g.hist[b] = 0u;                                                             // for the wave's next trial
-            if (b >= kc) continue;
-            run += h;
-            const uint32_t not_done = all - run;                                        // completion times at or above threshold b
-            const uint32_t tau = g.tau[b];
-            const long long capped = (long long)(tau < tmax ? tau : tmax);
-            const long long den = capped + c;
-            if (den <= 0) { atomicOr(status, DC_FLAG_ZERO_STEP); continue; }
-            const double done = elements_per_trial - (double)not_done;
-            acc[b] += (double)((long long)tmax + c) / (double)den * (done / elements_per_trial);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");                          // cleared before the next trial counts
+        finish_wave_trial(g, wt, kc, t, wave_max(st.lane_max), comm_per_trial, comm, elements_per_trial, lane, status);
     }
     report_range(st.check, max_latency, lane, status);
-    __syncthreads();
-    double* out = partial + (uint64_t)blockIdx.x * p2;
-    for (uint32_t i = threadIdx.x; i < p2; i += DC_SCAN_THREADS) {
-        double sum = acc_all[i];
-#pragma unroll
-        for (uint32_t w = 1; w < DC_SCAN_WAVES; ++w) sum += acc_all[w * p2 + i];
-        out[i] = sum;
+    write_wave_trial_sums(wt, p2, partial);
+}
+
+// The same for rows of any length and tensors of any 4-byte alignment: a trial is one unit of the flat pass.
+template <bool SMALL>
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_trial_scan_wave_flat_kernel(const int32_t* __restrict__ lat, uint32_t T, uint32_t N, uint32_t M,
+                                    const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
+                                    const long long* __restrict__ comm_per_trial, long long comm,
+                                    double* __restrict__ partial, uint32_t* __restrict__ status, uint32_t max_latency) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    WaveTrial wt;
+    const GridView g = stage_wave_trials(smem, tau_chunk, kc, p2, wave, lane, &wt);
+    uint4* queue = reinterpret_cast<uint4*>(smem) + wave * QUEUE_ITEMS;
+    const FlatTensor f = flat_tensor(lat, (uint64_t)T * N * M, M);
+    const uint32_t per_trial = N * M;                                               // at most DC_WAVE_TRIAL_ELEMENTS
+    const double elements_per_trial = (double)N * (double)M;
+
+    WaveState st{0u, 0u, 0u, 0u};
+    for (uint32_t t = blockIdx.x * DC_SCAN_WAVES + wave; t < T; t += gridDim.x * DC_SCAN_WAVES) {
+        st.lane_max = 0u;
+        flat_stream_unit<SMALL>(st.check, f, (uint64_t)t * per_trial, per_trial, lane,
+                                [&](uint4 p, uint32_t vm, uint32_t, uint32_t) { flat_count(st, p, vm, queue, g, lane); });
+        while (st.q_count) drain(st, queue, g, lane);
+        finish_wave_trial(g, wt, kc, t, wave_max(st.lane_max), comm_per_trial, comm, elements_per_trial, lane, status);
     }
+    report_range(st.check, max_latency, lane, status);
+    write_wave_trial_sums(wt, p2, partial);
 }
 
 // Any M >= 1, any 4-byte alignment: the waves of the block take the trial's units (runs of whole rows) in
@@ -1981,6 +2034,11 @@ static int resident_trial_wave(size_t lds) {
 int trial_scan_blocks_per_cu(const Plan& p) {
     const size_t lds = trial_scan_lds_bytes(p);
     int n = 0;
+    if (p.wave_trials && !p.vec4) {
+        if ((p.M < 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_wave_flat_kernel<true>, DC_SCAN_THREADS, lds)
+                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_trial_scan_wave_flat_kernel<false>, DC_SCAN_THREADS, lds)) != hipSuccess) n = 0;
+        return n;
+    }
     if (p.wave_trials) {
         switch (p.M / 4) {
             case 1:  return resident_trial_wave<1>(lds);
@@ -2041,6 +2099,17 @@ static void launch_trial_vec4(const Plan& p, const int32_t* lat, const uint32_t*
 void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                        const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
                        hipStream_t stream) {
+    if (p.wave_trials && !p.vec4) {
+        if (p.M < 4)
+            hipLaunchKernelGGL(dc_trial_scan_wave_flat_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS), trial_scan_lds_bytes(p),
+                               stream, lat, p.T, p.N, p.M, tau_chunk, kc, p.p2, (const long long*)comm_per_trial,
+                               (long long)comm, partial, status, p.max_latency);
+        else
+            hipLaunchKernelGGL(dc_trial_scan_wave_flat_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS), trial_scan_lds_bytes(p),
+                               stream, lat, p.T, p.N, p.M, tau_chunk, kc, p.p2, (const long long*)comm_per_trial,
+                               (long long)comm, partial, status, p.max_latency);
+        return;
+    }
     if (p.wave_trials) {
 #define DC_WAVE_CASE(l) hipLaunchKernelGGL(dc_trial_scan_wave_kernel<l>, dim3(p.grid), dim3(DC_SCAN_THREADS), trial_scan_lds_bytes(p), \
                                            stream, lat, p.T, p.N, tau_chunk, kc, p.p2, (const long long*)comm_per_trial,              \

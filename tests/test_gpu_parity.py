@@ -580,7 +580,8 @@ def test_per_step_speedup_shapes(M, dev):
     assert np.allclose(got, oracle.per_step_speedup(lat, taus, 11), rtol=SPEEDUP_RTOL, atol=0)
 
 
-@pytest.mark.parametrize("N,M,K", [(8, 16, 40), (64, 12, 100), (64, 32, 511), (200, 64, 128), (7, 256, 33), (33, 4, 512)])
+@pytest.mark.parametrize("N,M,K", [(8, 16, 40), (64, 12, 100), (64, 32, 511), (200, 64, 128), (7, 256, 33), (33, 4, 512),
+                                   (64, 13, 100), (200, 5, 64), (9, 1, 20), (40, 3, 511), (17, 257, 50), (30, 2, 77)])
 def test_per_step_speedup_small_trials(N, M, K, dev):
     """Trials of a few KiB: every wave owns a trial (up to 511 thresholds; 512 go the other way).  More trials than
     the grid has waves, a trial of zeros, one of the largest legal rows, per-iteration communication times."""
