@@ -313,7 +313,8 @@ def dc_worker_moments(lat, workers=None):
     rc = _load().dc_worker_moments_strided(ptr, T, N, M, stride, sums.ctypes.data, sq.ctypes.data, mean.ctypes.data,
                                            var.ctypes.data)
     _check(rc, "dc_worker_moments")
-    return ([int(v) for v in sums], [(int(sq[2 * n + 1]) << 64) | int(sq[2 * n]) for n in range(N)], mean, var)
+    low, high = sq[0::2].tolist(), sq[1::2].tolist()           # the 128-bit sums of squares as Python ints
+    return (sums.tolist(), [(h << 64) | l for l, h in zip(low, high)], mean, var)
 
 
 def dc_analytic_curves(mu: float, sigma2: float, N: int, M: int, taus, comm: int, mean_tmax=None):

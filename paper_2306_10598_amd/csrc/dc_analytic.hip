@@ -54,20 +54,20 @@ __device__ __forceinline__ void block_reduce(Acc& a, unsigned long long (*lds)[3
 // (16-byte loads, a wave per unit) cover the elements [head, head + vec_units*8192), where head (0..3) is the
 // number of elements before the first 16-byte boundary; the elements before and after, [0, head) and
 // [scalar_from, n), are read one by one.  The units are dealt as in the threshold pass: a block takes runs of
-// DC_UNIT_RUN consecutive units and its four waves walk a run four adjacent units at a time, in step.
+// `run` consecutive units (a multiple of 4) and its four waves walk a run four adjacent units at a time, in step.
 __global__ __launch_bounds__(256)
-void dc_moments_kernel(const int32_t* __restrict__ lat, unsigned long long n, uint32_t head, uint32_t vec_units,
+void dc_moments_kernel(const int32_t* __restrict__ lat, unsigned long long n, uint32_t head, uint32_t vec_units, uint32_t run,
                        unsigned long long scalar_from, unsigned long long* __restrict__ partial) {
     __shared__ unsigned long long lds[256][3];
     __shared__ uint32_t lds_bits[256];
     Acc a{0ull, 0, 0u};
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t runs = (vec_units + DC_UNIT_RUN - 1u) / DC_UNIT_RUN;
+    const uint32_t runs = (vec_units + run - 1u) / run;
     const uint32_t padded = (runs + gridDim.x - 1u) / gridDim.x * gridDim.x;     // block-uniform loop bounds
     for (uint32_t r = blockIdx.x; r < padded; r += gridDim.x)
-    for (uint32_t round = 0; round < DC_UNIT_RUN / 4u; ++round) {
-        const uint32_t u = r < runs ? r * DC_UNIT_RUN + round * 4u + wave : vec_units;
+    for (uint32_t round = 0; round < run / 4u; ++round) {
+        const uint32_t u = r < runs ? r * run + round * 4u + wave : vec_units;
         if (u < vec_units) {
             const u32x4* base = reinterpret_cast<const u32x4*>(lat + head) + (uint64_t)u * 2048 + lane;
             for (uint32_t i = 0; i < 32; i += 8) {
@@ -155,8 +155,10 @@ void launch_moments(const int32_t* lat, uint64_t n, uint32_t grid, unsigned long
     if (head > n) head = n;
     const uint64_t units = (n - head) / 8192;
     const uint32_t vec_units = (uint32_t)(units < 0x7FFFFFFFull ? units : 0x7FFFFFFFull);
+    uint32_t run = DC_UNIT_RUN;                          // long runs only while every block still gets several of them
+    while (run > 4u && (uint64_t)vec_units < 4ull * run * grid) run >>= 1;
     hipLaunchKernelGGL(dc_moments_kernel, dim3(grid), dim3(256), 0, stream, lat, (unsigned long long)n, (uint32_t)head,
-                       vec_units, (unsigned long long)(head + (uint64_t)vec_units * 8192ull), partial);
+                       vec_units, run, (unsigned long long)(head + (uint64_t)vec_units * 8192ull), partial);
     hipLaunchKernelGGL(dc_moments_final_kernel, dim3(1), dim3(256), 0, stream, partial, grid, result, status);
 }
 
