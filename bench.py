@@ -286,7 +286,7 @@ def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0, T: int = 0) -> st
     as a profile names it."""
     if M <= 16 and N % 4 == 0 and N >= 256:                            # every lane holds whole rows
         return f"dc_scan_rows_kernel<{M}, false>"
-    if M <= 16 and N % 4 == 0 and M not in (1, 2, 4):                  # the same over trials of few workers, unless
+    if M <= 16 and N >= 4 and (T * N) % 4 == 0 and M not in (1, 2, 4): # the same over trials of any worker count, unless
         per_load = 64 // (M // 4) if M % 4 == 0 else 0                 # whole rows per load fill their loads well
         if per_load == 0 or (N * 100 < -(-N // per_load) * per_load * 85 and T * N * M >= 1 << 22):
             return f"dc_scan_rows_kernel<{M}, true>"

@@ -80,10 +80,12 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     p.K = (uint32_t)K;
     const bool aligned = allow_vec4 && (p.stride & 3u) == 0;          // every trial starts on a 16-byte boundary
     p.lane_rows = aligned && M <= 16 && (N & 3) == 0 && N >= (int64_t)DC_LANE_ROWS_MIN_N;
-    // fewer workers: the same kernel over the tensor as one run of T*N rows, when the tensor is contiguous and a lane's
-    // four rows are consecutive (rows of 1, 2 and 4 elements are dealt to the lanes vector by vector instead)
-    bool span = DC_SPAN_TRIALS != 0 && aligned && !p.lane_rows && M <= 16 && M != 1 && M != 2 && M != 4 && (N & 3) == 0 &&
-                p.stride == (uint64_t)N * (uint64_t)M && (uint64_t)T * (uint64_t)N < ((uint64_t)1 << 31);
+    // other worker counts from 4 on: the same kernel over the tensor as one run of T*N rows (a multiple of 4), when the
+    // tensor is contiguous and a lane's four rows are consecutive (rows of 1, 2 and 4 elements are dealt to the lanes
+    // vector by vector instead)
+    bool span = DC_SPAN_TRIALS != 0 && aligned && !p.lane_rows && M <= 16 && M != 1 && M != 2 && M != 4 && N >= 4 &&
+                (((uint64_t)T * (uint64_t)N) & 3u) == 0 && p.stride == (uint64_t)N * (uint64_t)M &&
+                (uint64_t)T * (uint64_t)N < ((uint64_t)1 << 31);
     if (span && (M & 3) == 0) {
         // rows of 8, 12 and 16 elements also fit the kernel with whole rows per load, which is the faster one
         // (5.5-5.9 against 4.0-5.4 TB/s on 512 MB with 200 workers) unless the trial's last load is mostly empty

@@ -3,8 +3,9 @@
 // Pipeline of one call (all on one stream):
 //   dc_prep_kernel       sort the K thresholds by rank, clamp them to 32 bits, clear accumulators; for long rows
 //                        also sample the tensor to choose the streaming kernel's launch shape
-//   dc_scan_vec4_kernel  the single pass over lat: completion times by a segmented wave scan,
-//     / dc_scan_flat     histogram of completion times over the threshold grid, per-unit maxima
+//   dc_scan_vec4_kernel  the single pass over lat: completion times (a segmented wave scan over the lanes of a row;
+//     / dc_scan_rows     plain sums where a lane holds whole short rows; one flat scan for any other row length),
+//     / dc_scan_flat     histogram of completion times over the threshold grid, per-unit or per-trial maxima
 //   dc_reduce_kernel     add the per-block histograms; per-trial maximum -> binned count and sum; the last block
 //                        to finish takes prefix sums over the bins -> out_step, out_done in the caller's order
 //
@@ -996,7 +997,7 @@ __device__ __forceinline__ void rows_load(u32x4 (&x)[LaneRows<M>::V], const u32x
 // One chunk: `left` = vectors of the unit from the chunk's first one on (the chunk holds min(left, 64 V)).
 template <int M, bool FULL>
 __device__ __forceinline__ void rows_chunk(WaveState& st, u32x4 (&x)[LaneRows<M>::V], uint32_t left, u32x4* stage,
-                                           const GridView& g, uint32_t lane) {
+                                           const GridView& g, uint32_t lane, uint32_t (&total)[LaneRows<M>::R]) {
     using S = LaneRows<M>;
     constexpr int V = S::V, R = S::R;
     if constexpr (S::STAGED) {
@@ -1032,7 +1033,7 @@ __device__ __forceinline__ void rows_chunk(WaveState& st, u32x4 (&x)[LaneRows<M>
     }
     uint32_t top = st.lane_max;
 #pragma unroll
-    for (int r = 0; r < R; ++r) top = umax(top, e[r * M + M - 1]);   // rows outside the unit are all zero
+    for (int r = 0; r < R; ++r) { total[r] = e[r * M + M - 1]; top = umax(top, total[r]); }   // rows outside the unit are all zero
     st.lane_max = top;
     bool taken = false;                                             // wave-uniform: this step went with the one before
 #pragma unroll
@@ -1064,12 +1065,15 @@ __device__ __forceinline__ void rows_chunk(WaveState& st, u32x4 (&x)[LaneRows<M>
     }
 }
 
-// The lanes' maxima of one chunk, when a chunk may hold rows of several trials (SPAN): trials are runs of at most
-// trial_rows / 4 consecutive lanes, so a running maximum over lanes that restarts where the trial changes (steps up to
-// that length suffice) leaves every trial's maximum in the last of its lanes, which adds it to the trial's word
-// (cleared by the prep kernel) with one atomic maximum.
-__device__ __forceinline__ void add_trial_maxima(uint32_t m, uint32_t t, bool valid, uint32_t lane, uint32_t trial_lanes,
-                                                 uint32_t* trial_max) {
+// The lanes' maxima of one chunk, when a chunk may hold rows of several trials (SPAN).  A lane's four consecutive rows
+// lie in one trial or, with a trial boundary inside the lane, in two (trials have at least 4 rows).  Key and value
+// of a lane are the trial of its last row and the maximum over its rows in that trial; trials are runs of at most
+// trial_lanes consecutive lanes, so a running maximum over lanes that restarts where the key changes (steps up to that
+// length suffice) leaves every trial's maximum in the last lane with its key, which adds it to the trial's word
+// (cleared by the prep kernel) with one atomic maximum.  A lane with a boundary inside adds the maximum of its rows
+// before the boundary to the previous trial's word itself.
+__device__ __forceinline__ void add_trial_maxima(uint32_t m, uint32_t t, uint32_t m_before, bool valid, uint32_t lane,
+                                                 uint32_t trial_lanes, uint32_t* trial_max) {
     const uint32_t key = valid ? t : 0xFFFFFFFFu;
     for (uint32_t d = 1; d < 64u && d < trial_lanes; d <<= 1) {                  // wave-uniform bounds
         const uint32_t om = (uint32_t)__shfl_up((int)m, d, 64);
@@ -1078,6 +1082,7 @@ __device__ __forceinline__ void add_trial_maxima(uint32_t m, uint32_t t, bool va
     }
     const uint32_t next = (uint32_t)__shfl_down((int)key, 1, 64);
     if (valid && (lane == 63u || next != key)) atomicMax(&trial_max[t], m);
+    if (valid && m_before) atomicMax(&trial_max[t - 1u], m_before);              // zero adds nothing to a maximum
 }
 
 // SPAN = false: a unit is a run of chunks inside one trial and unit_max[u] receives its maximum.  SPAN = true (few
@@ -1117,34 +1122,44 @@ void dc_scan_rows_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride,
             if constexpr (SPAN) {
                 trial = row0 / trial_rows;
                 within = row0 - trial * trial_rows;
-                trial_recip = ((1u << 20) + trial_rows - 1u) / trial_rows;
+                trial_recip = trial_rows < 256u ? ((1u << 20) + trial_rows - 1u) / trial_rows : 0u;
             }
             u32x4 x[V];
             rows_load<M>(x, base, 0u, nv, lane);
             for (uint32_t first = 0; first < nv; first += CHUNK_VECTORS) {
                 const uint32_t left = nv - first;
-                if constexpr (SPAN) st.lane_max = 0u;
+                uint32_t total[S::R];
                 if constexpr (S::PREFETCH) {
                     u32x4 ahead[V];
 #pragma unroll
                     for (int q = 0; q < V; ++q) ahead[q] = x[q];
                     if (left > CHUNK_VECTORS) rows_load<M>(ahead, base, first + CHUNK_VECTORS, nv, lane);
-                    if (left >= CHUNK_VECTORS) rows_chunk<M, true>(st, x, left, stage, g, lane);
-                    else rows_chunk<M, false>(st, x, left, stage, g, lane);
+                    if (left >= CHUNK_VECTORS) rows_chunk<M, true>(st, x, left, stage, g, lane, total);
+                    else rows_chunk<M, false>(st, x, left, stage, g, lane, total);
 #pragma unroll
                     for (int q = 0; q < V; ++q) x[q] = ahead[q];
                 } else {
-                    if (left >= CHUNK_VECTORS) rows_chunk<M, true>(st, x, left, stage, g, lane);
-                    else rows_chunk<M, false>(st, x, left, stage, g, lane);
+                    if (left >= CHUNK_VECTORS) rows_chunk<M, true>(st, x, left, stage, g, lane, total);
+                    else rows_chunk<M, false>(st, x, left, stage, g, lane, total);
                     if (left > CHUNK_VECTORS) rows_load<M>(x, base, first + CHUNK_VECTORS, nv, lane);
                 }
                 if constexpr (SPAN) {
                     static_assert(!SPAN || (S::STAGED && S::R == 4), "a lane's rows must be consecutive");
-                    // the lane's first row: row `within + 4 lane` of the tensor counted from the head of trial `trial`;
-                    // within + 4 lane < 512 and trial_rows <= 252, so the fixed-point quotient is exact
+                    // the lane's rows are rows ahead .. ahead + 3 counted from the head of trial `trial`; ahead + 3 < 512
+                    // and, below 256 rows per trial, the fixed-point quotient is exact; from 256 rows on a chunk holds
+                    // at most one boundary
                     const uint32_t ahead = within + 4u * lane;
-                    const uint32_t t = trial + ((ahead * trial_recip) >> 20);
-                    add_trial_maxima(st.lane_max, t, row0 + first / (uint32_t)M * 4u + 4u * lane < N, lane, trial_rows / 4u, unit_max);
+                    const uint32_t q0 = trial_recip ? (ahead * trial_recip) >> 20 : (ahead >= trial_rows ? 1u : 0u);
+                    const uint32_t q3 = trial_recip ? ((ahead + 3u) * trial_recip) >> 20 : (ahead + 3u >= trial_rows ? 1u : 0u);
+                    const uint32_t before = q3 != q0 ? q3 * trial_rows - ahead : 0u;   // rows of the lane ahead of the boundary (1..3)
+                    uint32_t m_before = 0u, m_after = 0u;
+#pragma unroll
+                    for (uint32_t q = 0; q < 4u; ++q) {
+                        m_before = umax(m_before, q < before ? total[q] : 0u);
+                        m_after = umax(m_after, q < before ? 0u : total[q]);
+                    }
+                    add_trial_maxima(m_after, trial + q3, m_before, row0 + first / (uint32_t)M * 4u + 4u * lane < N, lane,
+                                     (trial_rows + 3u) / 4u + 1u, unit_max);
                     trial += CHUNK_ROWS / trial_rows;                       // the next chunk starts 256 rows further on
                     within += CHUNK_ROWS % trial_rows;
                     if (within >= trial_rows) { within -= trial_rows; ++trial; }

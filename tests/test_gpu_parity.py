@@ -201,14 +201,15 @@ def test_short_rows_held_whole_by_a_lane(M, N, dev):
         assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, a)
 
 
-@pytest.mark.parametrize("N", [4, 8, 64, 200, 252])
+@pytest.mark.parametrize("N", [4, 5, 6, 8, 10, 30, 64, 150, 200, 250, 252, 257, 1022])
 @pytest.mark.parametrize("M", [3, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
 def test_short_rows_of_few_workers(M, N, dev):
-    """Fewer than 256 workers per trial, a multiple of 4, short rows, contiguous tensor: the lanes of a wave then hold
-    rows of several trials and the trial maxima are built with atomic maxima.  Trials whose maximum sits in their first
-    or last worker, a trial of zeros, a partial last chunk, narrow and all-covering grids."""
+    """Worker counts that are below 256 or no multiple of 4, short rows, contiguous tensor with a multiple of 4 rows in
+    all: the lanes of a wave then hold rows of several trials, a trial boundary may fall inside a lane, and the trial
+    maxima are built with atomic maxima.  Trials whose maximum sits in their first or last worker, a trial of zeros, a
+    partial last chunk, narrow and all-covering grids."""
     rng = np.random.default_rng(1000 * M + N)
-    T = 37
+    T = 40
     top = min((2**31 - 1) // M, 6000)
     lat = rng.integers(0, top + 1, size=(T, N, M), dtype=np.int32)
     lat[::3] //= 3                                          # neighbouring trials with different maxima

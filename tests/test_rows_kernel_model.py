@@ -65,18 +65,22 @@ def test_backward_steps_count_what_a_search_over_every_element_counts(M):
         assert steps == int(np.max(np.sum(p >= taus[0], axis=1)))   # as many steps as the fullest row has entries in the grid
 
 
-def test_fixed_point_quotient_finds_the_trial_of_every_lane():
-    """trial offset = ((within + 4 lane) * ceil(2^20 / N)) >> 20 must equal (within + 4 lane) // N for every worker
-    count the mode is used for (a multiple of 4 below 256) and every position of a chunk's first row in its trial."""
-    for N in range(4, 256, 4):
+def test_fixed_point_quotient_finds_the_trial_of_every_row():
+    """trial offset = (x * ceil(2^20 / N)) >> 20 must equal x // N for every worker count below 256 and every row
+    x = within + 4 lane + 0..3 of a chunk counted from the head of the trial of the chunk's first row; from 256
+    workers on the offset is 0 or 1."""
+    for N in range(4, 256):
         recip = ((1 << 20) + N - 1) // N
-        ahead = np.arange(0, N + 4 * 63 + 1)
-        assert ahead.max() < 512 and int(ahead.max()) * recip < 2**32
-        assert np.array_equal((ahead * recip) >> 20, ahead // N), N
+        x = np.arange(0, N + 4 * 63 + 3 + 1)
+        assert x.max() < 512 and int(x.max()) * recip < 2**32
+        assert np.array_equal((x * recip) >> 20, x // N), N
+    for N in (256, 257, 1000, 5001):
+        x = np.arange(0, N + 4 * 63 + 3 + 1)
+        assert np.array_equal((x >= N).astype(np.int64), x // N)
 
 
 def test_chunk_to_chunk_update_of_the_first_rows_trial():
-    for N in range(4, 256, 4):
+    for N in list(range(4, 256)) + [256, 257, 1000]:
         for row0 in (0, 256 * 7, 256 * 1000 + 0):
             trial, within = divmod(row0, N)
             for c in range(40):
@@ -88,19 +92,32 @@ def test_chunk_to_chunk_update_of_the_first_rows_trial():
                     trial += 1
 
 
-@pytest.mark.parametrize("N", [4, 8, 12, 64, 100, 200, 252])
+@pytest.mark.parametrize("N", [4, 5, 6, 7, 8, 10, 12, 30, 64, 100, 150, 200, 250, 252, 257, 1001])
 def test_running_maximum_restarts_where_the_trial_changes(N):
-    """Steps of 1, 2, 4, ... lanes, as many as a trial can span, leave each trial's maximum in its last lane."""
+    """A lane's four rows lie in one trial or in two.  Key = trial of the lane's last row, value = maximum over its rows
+    in that trial; steps of 1, 2, 4, ... lanes, as many as a trial can span, leave each trial's maximum in the last
+    lane with its key; a lane with a boundary inside adds its rows before the boundary to the previous trial itself."""
     rng = np.random.default_rng(N)
-    trial_lanes = N // 4
+    trial_lanes = (N + 3) // 4 + 1
     for case in range(50):
-        within = int(rng.integers(0, N // 4)) * 4
+        within = int(rng.integers(0, N))
         valid_lanes = 64 if case % 3 else int(rng.integers(1, 65))
-        t = (within + 4 * LANES) // N
+        totals = rng.integers(1, 1000, size=(64, 4))
+        totals[LANES >= valid_lanes] = 0
+        rows = within + 4 * LANES[:, None] + np.arange(4)[None, :]           # counted from the head of the first row's trial
+        trial_of = rows // N
+        want = {}
+        for lane in range(valid_lanes):
+            for q in range(4):
+                k = int(trial_of[lane, q])
+                want[k] = max(want.get(k, 0), int(totals[lane, q]))
+        t = trial_of[:, 3]
+        before = np.where(trial_of[:, 0] != t, t * N - rows[:, 0], 0)
+        assert np.all((before >= 0) & (before <= 3))
+        q = np.arange(4)[None, :]
+        m_before = np.where(q < before[:, None], totals, 0).max(axis=1)
+        m = np.where(q < before[:, None], 0, totals).max(axis=1)
         key = np.where(LANES < valid_lanes, t, 0xFFFFFFFF)
-        m = rng.integers(0, 1000, size=64)
-        m[LANES >= valid_lanes] = 0
-        want = {int(k): int(m[key == k].max()) for k in np.unique(key[LANES < valid_lanes])}
         run = m.copy()
         d = 1
         while d < 64 and d < trial_lanes:
@@ -113,6 +130,9 @@ def test_running_maximum_restarts_where_the_trial_changes(N):
         last = (LANES < valid_lanes) & ((LANES == 63) | (nxt != key))
         got = {}
         for lane in np.flatnonzero(last):
-            assert int(key[lane]) not in got                    # one addition per trial and chunk
+            assert int(key[lane]) not in got                    # one addition per key and chunk
             got[int(key[lane])] = int(run[lane])
+        for lane in np.flatnonzero((LANES < valid_lanes) & (m_before > 0)):
+            k = int(t[lane]) - 1
+            got[k] = max(got.get(k, 0), int(m_before[lane]))
         assert got == want
