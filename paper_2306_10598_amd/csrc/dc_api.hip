@@ -527,11 +527,15 @@ bool timing_on() { return g_timing_level.load() != 0; }
 
 extern "C" {
 
+// The largest of the plans that a call with these sizes can end up with: a contiguous 16-byte aligned tensor, an aligned
+// worker range of a larger tensor (trials further apart than they are long), and a tensor that is not 16-byte aligned.
 size_t dc_workspace_bytes(int64_t T, int64_t N, int64_t M, int64_t K) {
-    dc::Plan a{}, b{};
+    dc::Plan a{}, b{}, c{};
     if (!make_plan(T, N, M, K, true, &a)) return 0;
     if (!make_plan(T, N, M, K, false, &b)) return 0;
-    return a.bytes > b.bytes ? a.bytes : b.bytes;
+    size_t bytes = a.bytes > b.bytes ? a.bytes : b.bytes;
+    if (make_plan(T, N, M, K, true, &c, N * M + 4) && c.bytes > bytes) bytes = c.bytes;
+    return bytes;
 }
 
 int dc_simulate_strided_async(const int32_t* lat, int64_t T, int64_t N, int64_t M, int64_t trial_stride,

@@ -722,6 +722,8 @@ def test_worker_moments_of_more_workers_than_one_pass_holds(dev):
     ((5, 21, 1), [(0, 8), (1, 20)]),
     ((4, 10, 257), [(0, 3), (4, 9)]),
     ((3, 2100, 256), [(0, 2048), (52, 2100)]),
+    ((400, 40, 13), [(0, 8), (4, 24), (0, 40)]),                   # short rows: another kernel than the contiguous tensor of that shape takes
+    ((64, 600, 6), [(0, 256), (8, 520), (3, 259)]),
 ])
 def test_worker_ranges_of_a_resident_tensor(shape, ranges, dev):
     rng = np.random.default_rng(sum(shape))
