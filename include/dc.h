@@ -21,10 +21,10 @@
  *   - Every pointer is owned by the caller.  "DEVICE" pointers are HIP device memory of the
  *     current device; "HOST" pointers are ordinary host memory.
  *   - lat must be 4-byte aligned; rows are contiguous with m fastest: element (t,n,m) is at
- *     lat[(t*N + n)*M + m].  The fastest kernels need lat 16-byte aligned and M a multiple of 4
- *     up to 128, or 256 (best when M is a power of two); every other M >= 1 and any 4-byte alignment
- *     takes a kernel that reads the tensor as one flat run of 16-byte vectors, with the same
- *     results at 75-95 % of that speed for M >= 30 and about a third of it for M <= 5.
+ *     lat[(t*N + n)*M + m].  The fastest kernels need lat 16-byte aligned and either M a multiple of 4
+ *     up to 128, or 256 (best when M is a power of two), or M <= 16 with a multiple of 4 rows in all;
+ *     every other M >= 1 and any 4-byte alignment takes a kernel that reads the tensor as one flat run
+ *     of 16-byte vectors, with the same results at 75-90 % of that speed.
  *   - Preconditions on values, checked while streaming: every latency is >= 0
  *     (else DC_ERR_NEGATIVE_LATENCY) and <= floor((2^31-1)/M) (else DC_ERR_RANGE), which
  *     guarantees that no worker's total overflows 31 bits.
