@@ -1114,6 +1114,26 @@ def test_launch_shape_follows_the_threshold_grid(dev):
         assert np.array_equal(out[0, :k].cpu().numpy(), ref_step) and np.array_equal(out[1, :k].cpu().numpy(), ref_done)
 
 
+def test_long_rows_with_more_thresholds_than_one_pass_holds(dev):
+    """Long rows, enough units for both launch shapes, and more thresholds than one pass holds (a full pass's grid
+    leaves room for two blocks per compute unit only, so there is one launch shape): the first pass starts at 0, the
+    later ones ever higher.  Both entry points, against the oracle."""
+    r = config("heterogeneous2048").with_shape(T=700)
+    lat = host.generate(r)
+    lat_d = to_dev(lat, dev)
+    top = int(host.worker_totals(lat).max())
+    rng = np.random.default_rng(31)
+    taus = np.linspace(0, top + 3, 9001).astype(np.int64)[rng.permutation(9001)]
+    step, done = dc.dc_simulate(lat_d, taus, r.comm)
+    ref_step, ref_done = oracle.simulate_threaded(lat, taus, r.comm, "sorted", host.cpu_threads())
+    assert np.array_equal(step, ref_step) and np.array_equal(done, ref_done)
+    few = r.with_shape(T=40)
+    lat_few = np.ascontiguousarray(lat[:40])
+    taus1 = np.maximum(np.linspace(0, top + 3, 4500).astype(np.int64), 1)       # three passes of 2047 thresholds
+    got = dc.dc_speedup_per_step(to_dev(lat_few, dev), taus1, few.comm)
+    assert np.allclose(got, oracle.per_step_speedup(lat_few, taus1, few.comm, threads=host.cpu_threads()), rtol=SPEEDUP_RTOL, atol=0)
+
+
 def test_graph_replay_picks_the_launch_shape_from_the_data(dev):
     """A captured sequence for long rows holds both launch shapes; each replay chooses on the device.  The graph is
     replayed on a tensor whose contents change between replays (scaled so that the same thresholds cover almost
