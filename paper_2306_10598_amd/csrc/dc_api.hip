@@ -79,7 +79,9 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     if (!plan_shape(T, N, M, stride, &p)) return false;
     p.K = (uint32_t)K;
     const bool aligned = allow_vec4 && (p.stride & 3u) == 0;          // every trial starts on a 16-byte boundary
-    p.lane_rows = aligned && M <= 16 && (N & 3) == 0 && N >= (int64_t)DC_LANE_ROWS_MIN_N;
+    const bool rows_length = M < 64 && dc::lane_rows_length((uint32_t)M);
+    const int64_t rows_per_lane = (M > 16 && (M & 3) == 2) ? 2 : 4;
+    p.lane_rows = aligned && rows_length && (N % rows_per_lane) == 0 && N >= (int64_t)DC_LANE_ROWS_MIN_N;
     // other worker counts from 4 on: the same kernel over the tensor as one run of T*N rows (a multiple of 4), when the
     // tensor is contiguous and a lane's four rows are consecutive (rows of 1, 2 and 4 elements are dealt to the lanes
     // vector by vector instead)

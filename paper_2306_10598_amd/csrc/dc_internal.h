@@ -69,7 +69,11 @@ namespace dc {
 
 // Rows that one wave of the kernel with whole rows per lane takes at a time (a chunk): a lane holds 16 rows of one
 // element, 8 of two, otherwise 4.
-inline uint32_t lane_rows_chunk_rows(uint32_t M) { return M == 1u ? 1024u : M == 2u ? 512u : 256u; }
+inline uint32_t lane_rows_chunk_rows(uint32_t M) { return M == 1u ? 1024u : M == 2u ? 512u : (M > 16u && (M & 3u) == 2u) ? 128u : 256u; }
+// 16-byte vectors that a lane holds per chunk when they pass through LDS: its four rows, or two of the longer even rows
+inline uint32_t lane_rows_vectors(uint32_t M) { return (M > 16u && (M & 3u) == 2u) ? M / 2u : M; }
+// row lengths that kernel is built for
+inline bool lane_rows_length(uint32_t M) { return M <= 16u || ((M & 1u) && M <= 25u) || ((M & 3u) == 2u && M <= 34u); }
 
 // Everything the host decides about one call: which streaming kernel, how the tensor is cut
 // into units, and where each array sits in the workspace.

@@ -967,9 +967,10 @@ void dc_scan_flat_kernel(const int32_t* __restrict__ lat, uint64_t total, uint64
 template <int M>
 struct LaneRows {
     static constexpr bool STAGED = (4 % M) != 0;
-    static constexpr int V = STAGED ? M : 4;          // vectors per lane and chunk
+    static constexpr int V = !STAGED ? 4 : (M > 16 && (M & 3) == 2) ? M / 2 : M;   // vectors per lane and chunk
     static constexpr int R = 4 * V / M;               // rows per lane and chunk
     static constexpr bool PREFETCH = V <= DC_ROWS_PREFETCH_MAX_V;   // the next chunk's loads are issued before this chunk's arithmetic
+    static constexpr int PAIRED_STEPS = M <= 16 ? M : 4;            // backward steps that may take the next one along (code size)
     // A lane's vectors sit SPAN vectors from the next lane's in LDS: an odd number, so that eight lanes reading 16 bytes
     // each fall on different banks (with SPAN = V and V = 8 or 16 every lane of the wave would meet in one bank).
     static constexpr int SPAN = STAGED ? (V | 1) : 0;
@@ -1045,7 +1046,7 @@ __device__ __forceinline__ void rows_chunk(WaveState& st, u32x4 (&x)[LaneRows<M>
         for (int r = 0; r < R; ++r) { val[r] = e[r * M + M - 1 - s]; high = umax(high, val[r]); }
         const uint64_t reach = __ballot(high >= g.tau0);
         if (reach == 0) break;                                      // wave-uniform
-        if (s + 1 < M && (uint32_t)__popcll(reach) >= DC_DENSE_LANES) {
+        if (s + 1 < M && s < S::PAIRED_STEPS && (uint32_t)__popcll(reach) >= DC_DENSE_LANES) {
             // most lanes are inside the grid, so the next step would very likely run as well: both at once, twice as
             // many independent searches in flight (completion times below the grid find bin 0 and count nowhere)
 #pragma unroll
@@ -1115,7 +1116,7 @@ void dc_scan_rows_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride,
             const uint32_t j = u - t * units_per_trial;
             const uint32_t row0 = j * chunks_per_unit * CHUNK_ROWS;
             const uint32_t rows = (N - row0) < chunks_per_unit * CHUNK_ROWS ? (N - row0) : chunks_per_unit * CHUNK_ROWS;
-            const uint32_t nv = rows / 4u * (uint32_t)M;                                  // rows is a multiple of 4
+            const uint32_t nv = rows * (uint32_t)M / 4u;                                  // whole vectors: rows is a multiple of R
             const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)row0 * M);
             st.lane_max = 0u;
             uint32_t trial = 0u, within = 0u, trial_recip = 0u;            // SPAN: where the chunk's first row sits
@@ -1880,7 +1881,7 @@ void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t*
 size_t scan_lds_bytes(const Plan& p) {
     const size_t tables = (size_t)p.p2 * 8;                       // thresholds + histogram
     if (p.lane_rows)                                              // + cells + every wave's stretch for its chunk
-        return tables + (size_t)p.p2 * 8 + (4u % p.M ? (size_t)DC_SCAN_WAVES * 64u * (p.M | 1u) * sizeof(u32x4) : 0u);
+        return tables + (size_t)p.p2 * 8 + (4u % p.M ? (size_t)DC_SCAN_WAVES * 64u * (lane_rows_vectors(p.M) | 1u) * sizeof(u32x4) : 0u);
     return tables + (size_t)p.p2 * 8 + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);   // + cells + queues
 }
 
@@ -1902,6 +1903,8 @@ int scan_blocks_per_cu(const Plan& p) {
             DC_ROWS_CASE(1) DC_ROWS_CASE(2) DC_ROWS_CASE(3) DC_ROWS_CASE(4) DC_ROWS_CASE(5) DC_ROWS_CASE(6) DC_ROWS_CASE(7)
             DC_ROWS_CASE(8) DC_ROWS_CASE(9) DC_ROWS_CASE(10) DC_ROWS_CASE(11) DC_ROWS_CASE(12) DC_ROWS_CASE(13)
             DC_ROWS_CASE(14) DC_ROWS_CASE(15) DC_ROWS_CASE(16)
+            DC_ROWS_CASE(17) DC_ROWS_CASE(18) DC_ROWS_CASE(19) DC_ROWS_CASE(21) DC_ROWS_CASE(22) DC_ROWS_CASE(23) DC_ROWS_CASE(25)
+            DC_ROWS_CASE(26) DC_ROWS_CASE(30) DC_ROWS_CASE(34)
 #undef DC_ROWS_CASE
             default: break;
         }
@@ -1959,7 +1962,7 @@ static void launch_flat(const Plan& p, const int32_t* lat, const uint32_t* tau_c
 template <int M>
 static void launch_rows(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                         uint32_t* unit_max, uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
-    if constexpr (LaneRows<M>::STAGED && LaneRows<M>::R == 4) {
+    if constexpr (LaneRows<M>::STAGED && LaneRows<M>::R == 4 && M <= 16) {
         if (p.span_rows) {                          // the tensor as one run of T * N rows
             hipLaunchKernelGGL((dc_scan_rows_kernel<M, true>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
                                lat, 0ull, p.T * p.N, p.units, p.units, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max,
@@ -1980,6 +1983,8 @@ void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, u
             DC_ROWS_CASE(1) DC_ROWS_CASE(2) DC_ROWS_CASE(3) DC_ROWS_CASE(4) DC_ROWS_CASE(5) DC_ROWS_CASE(6) DC_ROWS_CASE(7)
             DC_ROWS_CASE(8) DC_ROWS_CASE(9) DC_ROWS_CASE(10) DC_ROWS_CASE(11) DC_ROWS_CASE(12) DC_ROWS_CASE(13)
             DC_ROWS_CASE(14) DC_ROWS_CASE(15) DC_ROWS_CASE(16)
+            DC_ROWS_CASE(17) DC_ROWS_CASE(18) DC_ROWS_CASE(19) DC_ROWS_CASE(21) DC_ROWS_CASE(22) DC_ROWS_CASE(23) DC_ROWS_CASE(25)
+            DC_ROWS_CASE(26) DC_ROWS_CASE(30) DC_ROWS_CASE(34)
 #undef DC_ROWS_CASE
             default: break;                         // make_plan sets lane_rows for these row lengths only
         }

@@ -173,7 +173,7 @@ def test_any_alignment_any_row_length(words, M, dev):
 
 
 @pytest.mark.parametrize("N", [256, 260, 1024, 2052, 5000])
-@pytest.mark.parametrize("M", list(range(1, 17)))
+@pytest.mark.parametrize("M", list(range(1, 17)) + [17, 18, 19, 21, 22, 23, 25, 26, 30, 34])
 def test_short_rows_held_whole_by_a_lane(M, N, dev):
     """Rows of up to 16 elements with at least 256 workers, a multiple of 4, on an aligned
     tensor go through the kernel in which every lane owns whole rows: full and partial chunks, one and several units
