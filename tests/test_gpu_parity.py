@@ -890,13 +890,14 @@ LITERAL_FULL_EVALS = 2.0e10      # the four-loop oracle runs on the whole tensor
 
 @pytest.mark.parametrize("name,rows", [("tiny", 0), ("lognormal64", 0), ("additive200", 0), ("extrapolation2048", 0),
                                        ("heterogeneous2048", 0), ("heterogeneous2048", 63), ("extrapolation2048", 5),
-                                       ("extrapolation2048", 16), ("additive200", 13), ("lognormal64", 12)])
+                                       ("extrapolation2048", 16), ("additive200", 13), ("lognormal64", 12),
+                                       ("heterogeneous2048", 5)])
 def test_full_size_parity(name, rows, dev):
     """All five workloads at their stated size, in the launch configuration the benchmark times, against the
     sorted-walk oracle on the whole tensor; the three smaller ones also against the four-loop oracle on the whole
     tensor (the two 2048-worker ones on a sampled slab).  The largest runs once more with 63 accumulations per worker
-    (same bytes, more than 2^32 elements through the kernel for arbitrary row lengths); the 4.3 GB one with 5 and 16
-    (every lane holds whole rows), the two middle ones with 13 and 12 (the same over trials of few workers)."""
+    (same bytes, more than 2^32 elements through the kernel for arbitrary row lengths) and with 5 (the same through the
+    kernel in which every lane holds whole rows); the 4.3 GB one with 5 and 16, the two middle ones with 13 and 12 (the same over trials of few workers)."""
     from dc_workloads import device
     r = config(name)
     if rows:
