@@ -75,8 +75,11 @@ def additive_noise(family: str, T: int, N: int, variance: float = 0.05, mean: fl
         q = lambda u: base_us - 1e6 * np.log1p(-u) / prm["rate"]
     else:
         q = lambda u: base_us + 1e6 * gammaincinv(prm["shape"], u) / prm["rate"]
-    return Recipe(f"additive_{family}", T=T, N=N, M=M, K=K, comm=comm_us, grid="pct", value=quantile_tables(q),
-                  seed=seed, description=f"{base_s} s + {family} noise (mean {mean} s, variance {variance} s^2), us", **kw)
+    # a worker's total must stay below 2^31 us: the far tail of the widest log-normal (beyond 1 - 1e-9) is cut there
+    cap = float((2**31 - 1) // M - kw.get("spike_add", 0) - 1)
+    return Recipe(f"additive_{family}", T=T, N=N, M=M, K=K, comm=comm_us, grid="pct",
+                  value=quantile_tables(lambda u: np.minimum(q(u), cap)), seed=seed,
+                  description=f"{base_s} s + {family} noise (mean {mean} s, variance {variance} s^2), us", **kw)
 
 
 def local_sgd(T: int, period: int, scenario: str = "uniform", N: int = 32, step_us: int = 250_000,

@@ -11,7 +11,7 @@ dc_worker_moments, dc_select_tau and dc_analytic_curves and prints
 With --local-sgd it sweeps the synchronisation period of Local-SGD with random stragglers (Appendix B.3): throughput of
 Local-SGD, and of Local-SGD with the best drop threshold, relative to synchronising at every step.
 
-  python -m paper_2306_10598_amd.examples.noise_study [--families lognormal normal ...] [--workers 8 64 512 2048] [--variance 0.05] [--delay]
+  python -m paper_2306_10598_amd.examples.noise_study [--families lognormal normal ...] [--workers 8 64 512 2048] [--variance 0.05 | --variances 0.05 0.1 0.2 0.3] [--delay]
   python -m paper_2306_10598_amd.examples.noise_study --local-sgd [--periods 1 2 4 8 16 32]
 
 With --surrogate it repeats the check of the paper's iteration-time figure: measure every worker's mean and variance
@@ -114,6 +114,8 @@ def main() -> int:
     ap.add_argument("--families", nargs="*", default=["lognormal", "normal", "bernoulli", "exponential", "gamma"])
     ap.add_argument("--workers", nargs="*", type=int, default=[8, 32, 128, 512, 2048])
     ap.add_argument("--variance", type=float, default=0.05)
+    ap.add_argument("--variances", nargs="*", type=float, default=None,
+                    help="sweep the noise variance (s^2) as well, as the appendix's second table does (overrides --variance)")
     ap.add_argument("--elements", type=int, default=1 << 28, help="approximate T*N*M of the tensor (N = the largest worker count)")
     ap.add_argument("--delay", action="store_true", help="also sweep the simulated-delay model of Appendix B.1")
     ap.add_argument("--local-sgd", action="store_true", help="sweep Local-SGD's synchronisation period instead")
@@ -127,15 +129,17 @@ def main() -> int:
         local_sgd_study(args.periods, trials=20000)
         return 0
     from dc_workloads import noise
-    print(f"{'noise':<16}{'N':>6}{'T':>8}{'E[T]/E[T_i]':>13}{'paper':>8}{'tau* us':>12}{'S_eff':>8}{'done':>8}{'closed form':>13}")
+    print(f"{'noise':<16}{'var s^2':>8}{'N':>6}{'T':>8}{'E[T]/E[T_i]':>13}{'paper':>8}{'tau* us':>12}{'S_eff':>8}{'done':>8}{'closed form':>13}")
     top = max(args.workers)
     T = max(16, args.elements // (top * 12))
     for family in args.families + (["delay"] if args.delay else []):
-        r = noise.simulated_delay(T, top) if family == "delay" else noise.additive_noise(family, T, top, args.variance)
-        ref = PAPER_RATIO.get(family) if abs(args.variance - 0.05) < 1e-12 else None
-        for row in sweep(r, sorted(args.workers)):
-            print(f"{family:<16}{row['workers']:>6}{T:>8}{row['ratio']:>13.3f}{(f'{ref:.3f}' if ref else '-'):>8}{row['tau']:>12}"
-                  f"{row['seff']:>8.3f}{row['completed']:>8.3f}{row['analytic_seff']:>13.3f}")
+        for variance in ([args.variance] if args.variances is None or family == "delay" else args.variances):
+            r = noise.simulated_delay(T, top) if family == "delay" else noise.additive_noise(family, T, top, variance)
+            ref = PAPER_RATIO.get(family) if abs(variance - 0.05) < 1e-12 else None
+            shown = "-" if family == "delay" else f"{variance:g}"
+            for row in sweep(r, sorted(args.workers)):
+                print(f"{family:<16}{shown:>8}{row['workers']:>6}{T:>8}{row['ratio']:>13.3f}{(f'{ref:.3f}' if ref else '-'):>8}"
+                      f"{row['tau']:>12}{row['seff']:>8.3f}{row['completed']:>8.3f}{row['analytic_seff']:>13.3f}", flush=True)
     return 0
 
 
