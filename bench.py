@@ -40,8 +40,9 @@ def ensure_built() -> None:
 
 def kernel_source_hash() -> str:
     h = hashlib.sha256()
-    for name in ("dc_kernels.hip", "dc_internal.h", "dc_api.hip"):
-        h.update((ROOT / "paper_2306_10598_amd" / "csrc" / name).read_bytes())
+    for path in sorted((ROOT / "paper_2306_10598_amd" / "csrc").iterdir()):        # every source of the library
+        if path.suffix in (".hip", ".h"):
+            h.update(path.read_bytes())
     return h.hexdigest()[:16]
 
 

@@ -7,18 +7,33 @@ from pathlib import Path
 HERE = Path(__file__).resolve().parent
 ROOT = HERE.parent
 LIB_PATH = HERE / "libdc.so"
-SOURCES = [HERE / "csrc" / "dc_api.hip", HERE / "csrc" / "dc_kernels.hip", HERE / "csrc" / "dc_analytic.hip"]
+SOURCES = [HERE / "csrc" / name for name in ("dc_api.hip", "dc_kernels.hip", "dc_rows.hip", "dc_trial.hip", "dc_workers.hip",
+                                             "dc_analytic.hip")]
+OBJECTS = HERE / "_build"                 # object files of the last build (git-ignored)
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
 ]
 
 
+def _compile(src: Path, verbose: bool) -> Path:
+    obj = OBJECTS / (src.stem + ".o")
+    cmd = ["hipcc", *HIPCC_FLAGS, f"-I{ROOT / 'include'}", f"-I{HERE / 'csrc'}", "-c", str(src), "-o", str(obj)]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return obj
+
+
 def build(verbose: bool = False) -> Path:
-    cmd = ["hipcc", *HIPCC_FLAGS, f"-I{ROOT / 'include'}", f"-I{HERE / 'csrc'}",
-           "-o", str(LIB_PATH), *map(str, SOURCES)]
+    """Compile every translation unit (side by side: the kernels with many instantiations take a minute each) and link."""
+    from concurrent.futures import ThreadPoolExecutor
+    OBJECTS.mkdir(exist_ok=True)
+    with ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
+        objects = list(pool.map(lambda src: _compile(src, verbose), SOURCES))
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(LIB_PATH), *map(str, objects)]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

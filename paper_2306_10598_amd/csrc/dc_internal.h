@@ -1,4 +1,5 @@
-// Shared between dc_api.hip (host logic, C ABI) and dc_kernels.hip (device code).
+// Shared between dc_api.hip (host logic, C ABI) and the translation units with the kernels and their launchers
+// (dc_kernels.hip, dc_rows.hip, dc_trial.hip, dc_workers.hip, dc_analytic.hip).
 #ifndef DC_INTERNAL_H
 #define DC_INTERNAL_H
 
@@ -129,6 +130,9 @@ void launch_expected_done(const int64_t* taus, uint32_t K, uint32_t M, double mu
                           hipStream_t stream);
 void launch_export_status(const uint32_t* status, int32_t* out, hipStream_t stream);
 size_t scan_lds_bytes(const Plan& p);
+int rows_blocks_per_cu(const Plan& p, size_t lds);
+void launch_rows_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
+                      uint32_t* hist_part, uint32_t* status, hipStream_t stream);
 int scan_blocks_per_cu(const Plan& p);
 int trial_scan_blocks_per_cu(const Plan& p);
 

@@ -1,0 +1,201 @@
+// Per-worker statistics of the iteration time: streaming kernels, the sum over blocks, and their launcher.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dc_device.h"
+#include "dc_internal.h"
+
+// ---------------------------------------------------------------------------------------------
+// Per-worker statistics of the compute time T_n = sum_m t_n^(m): sum and sum of squares over iterations
+// ---------------------------------------------------------------------------------------------
+// A block owns whole trials and a wave always the same rows of each trial, so every worker's accumulators
+// in LDS ([3][N]: sum, squares low word, squares high word) have one owner lane and need no atomics.
+
+__device__ __forceinline__ void add_worker_total(unsigned long long* acc, uint32_t N, uint32_t n, uint32_t total) {
+    acc[n] += total;
+    const unsigned long long sq = (unsigned long long)total * total;
+    const unsigned long long before = acc[N + n];
+    acc[N + n] = before + sq;
+    if (before + sq < before) acc[2 * N + n] += 1ull;
+}
+
+template <int L>
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride, uint32_t T, uint32_t N,
+                                  unsigned long long* __restrict__ partial, uint32_t* __restrict__ status,
+                                  uint32_t max_latency, uint32_t lanes_per_row) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
+    for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) acc[i] = 0ull;
+    __syncthreads();
+
+    constexpr int U = DC_SCAN_UNROLL;
+    const uint32_t lane = threadIdx.x & 63u;
+    const RowShape shape = row_shape<L>(lane, lanes_per_row);
+    const uint32_t R = shape.rows, M = 4 * shape.lanes;
+    const uint64_t stride = L ? 64u : shape.active;
+    const bool row_end = shape.ok && shape.pos == shape.lanes - 1;      // this lane ends a row: it holds the total
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t nfull = N / R, tail_rows = N - nfull * R;
+    const uint32_t lo = (uint32_t)((uint64_t)nfull * wave / DC_SCAN_WAVES);
+    const uint32_t hi = (uint32_t)((uint64_t)nfull * (wave + 1) / DC_SCAN_WAVES);
+    uint32_t check = 0u;
+    for (uint32_t t = blockIdx.x; t < T; t += gridDim.x) {
+        const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)lo * R * M) + lane;
+        uint32_t i = 0;
+        for (; i + U <= hi - lo; i += U) {
+            u32x4 x[U];
+            uint32_t incl[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) x[k] = load_rows<L>(base + (uint64_t)(i + k) * stride, shape);
+            completion_times<L, U>(x, incl, lane, shape);
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                check = umax(check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
+                if (row_end) add_worker_total(acc, N, (lo + i + k) * R + shape.row, incl[k]);
+            }
+        }
+        for (; i < hi - lo; ++i) {
+            const u32x4 x[1] = {load_rows<L>(base + (uint64_t)i * stride, shape)};
+            uint32_t incl[1];
+            completion_times<L, 1>(x, incl, lane, shape);
+            check = umax(check, umax(umax(x[0].x, x[0].y), umax(x[0].z, x[0].w)));
+            if (row_end) add_worker_total(acc, N, (lo + i) * R + shape.row, incl[0]);
+        }
+        if (wave == DC_SCAN_WAVES - 1 && tail_rows) {
+            const bool valid = lane < tail_rows * shape.lanes;
+            u32x4 x[1] = {{0u, 0u, 0u, 0u}};
+            if (valid) x[0] = __builtin_nontemporal_load(base + (uint64_t)(hi - lo) * stride);
+            uint32_t incl[1];
+            completion_times<L, 1>(x, incl, lane, shape);
+            check = umax(check, umax(umax(x[0].x, x[0].y), umax(x[0].z, x[0].w)));
+            if (valid && row_end) add_worker_total(acc, N, nfull * R + shape.row, incl[0]);
+        }
+    }
+    report_range(check, max_latency, lane, status);
+    __syncthreads();
+    unsigned long long* out = partial + (uint64_t)blockIdx.x * 3 * N;
+    for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) out[i] = acc[i];
+}
+
+// Any M >= 1, any 4-byte alignment: the flat pass; the lane that holds a row's last element holds its total.
+// Wave w takes units w, w + 4, ... of every trial, so a worker's accumulators always belong to the same wave.
+template <bool SMALL>
+__global__ __launch_bounds__(DC_SCAN_THREADS)
+void dc_worker_totals_flat_kernel(const int32_t* __restrict__ lat, uint64_t extent, uint64_t trial_stride, uint32_t T,
+                                  uint32_t N, uint32_t M, uint32_t rows_per_unit, unsigned long long* __restrict__ partial,
+                                  uint32_t* __restrict__ status, uint32_t max_latency) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
+    for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) acc[i] = 0ull;
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const FlatTensor f = flat_tensor(lat, extent, M);
+    const uint32_t n_units = (N + rows_per_unit - 1) / rows_per_unit;
+    uint32_t check = 0u;
+    for (uint32_t t = blockIdx.x; t < T; t += gridDim.x)
+        for (uint32_t j = wave; j < n_units; j += DC_SCAN_WAVES) {
+            const uint32_t row0 = j * rows_per_unit;
+            const uint32_t rows = (N - row0) < rows_per_unit ? (N - row0) : rows_per_unit;
+            // few waves per compute unit here (the accumulators fill the LDS), so more loads in flight per lane
+            flat_stream_unit<SMALL, DC_SCAN_UNROLL>(check, f, (uint64_t)t * trial_stride + (uint64_t)row0 * M, rows * M, lane,
+                                                    [&](uint4 p, uint32_t vm, uint32_t pos0, uint32_t row) {
+                const uint32_t val[4] = {p.x, p.y, p.z, p.w};
+                if constexpr (SMALL) {
+#pragma unroll
+                    for (uint32_t c = 0; c < 4; ++c) {
+                        const uint32_t e = pos0 + c;                      // < 6: position counted from the first element's row head
+                        if (((vm >> c) & 1u) && e % M == M - 1u) add_worker_total(acc, N, row0 + row + e / M, val[c]);
+                    }
+                } else {
+                    const uint32_t ce = M - pos0;                         // the row of the first element ends at component ce - 1
+                    if (ce <= 4u && ((vm >> (ce - 1u)) & 1u))
+                        add_worker_total(acc, N, row0 + row, ce == 1u ? val[0] : ce == 2u ? val[1] : ce == 3u ? val[2] : val[3]);
+                }
+            });
+        }
+    report_range(check, max_latency, lane, status);
+    __syncthreads();
+    unsigned long long* out = partial + (uint64_t)blockIdx.x * 3 * N;
+    for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) out[i] = acc[i];
+}
+
+// result[3][N] = sums over blocks (the 128-bit squares with carry).  A block of 256 threads takes 32 workers; its
+// eight groups of 32 threads add every eighth block's partial sums (32 consecutive 8-byte words per read), then the
+// eight partial results are added in a fixed order.
+__global__ __launch_bounds__(256)
+void dc_worker_totals_final_kernel(const unsigned long long* __restrict__ partial, uint32_t blocks, uint32_t N,
+                                   unsigned long long* __restrict__ result) {
+    __shared__ unsigned long long part[8][32][3];
+    const uint32_t w = threadIdx.x & 31u, slice = threadIdx.x >> 5;
+    const uint32_t n = blockIdx.x * 32u + w;
+    unsigned long long sum = 0ull;
+    unsigned __int128 sq = 0;
+    if (n < N) {
+        for (uint32_t b = slice; b < blocks; b += 8u) {
+            const unsigned long long* in = partial + (uint64_t)b * 3 * N;
+            sum += in[n];
+            sq += ((unsigned __int128)in[2 * N + n] << 64) | in[N + n];
+        }
+    }
+    part[slice][w][0] = sum;
+    part[slice][w][1] = (unsigned long long)sq;
+    part[slice][w][2] = (unsigned long long)(sq >> 64);
+    __syncthreads();
+    if (slice == 0 && n < N) {
+        for (uint32_t q = 1; q < 8u; ++q) {
+            sum += part[q][w][0];
+            sq += ((unsigned __int128)part[q][w][2] << 64) | part[q][w][1];
+        }
+        result[n] = sum;
+        result[N + n] = (unsigned long long)sq;
+        result[2 * N + n] = (unsigned long long)(sq >> 64);
+    }
+}
+
+__global__ void dc_clear_status_kernel(uint32_t* status) { *status = 0u; }
+
+namespace dc {
+
+template <int L>
+static void launch_worker_vec4(const Plan& p, const int32_t* lat, unsigned long long* partial, uint32_t* status,
+                               hipStream_t stream) {
+    hipLaunchKernelGGL(dc_worker_totals_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS), (size_t)p.N * 24, stream,
+                       lat, p.stride, p.T, p.N, partial, status, p.max_latency, p.M / 4);
+}
+
+// partial: [grid][3][N] u64; result: [3][N] u64 (sum, squares low, squares high per worker)
+// before/after: optional events recorded around the streaming kernel
+void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long* partial,
+                          unsigned long long* result, uint32_t* status, hipStream_t stream, hipEvent_t before,
+                          hipEvent_t after) {
+    hipLaunchKernelGGL(dc_clear_status_kernel, dim3(1), dim3(1), 0, stream, status);
+    if (before) (void)hipEventRecord(before, stream);
+    if (!p.vec4) {
+        if (p.M < 4)
+            hipLaunchKernelGGL(dc_worker_totals_flat_kernel<true>, dim3(p.grid), dim3(DC_SCAN_THREADS),
+                               (size_t)p.N * 24, stream, lat, p.extent, p.stride, p.T, p.N, p.M, p.per_unit, partial, status,
+                               p.max_latency);
+        else
+            hipLaunchKernelGGL(dc_worker_totals_flat_kernel<false>, dim3(p.grid), dim3(DC_SCAN_THREADS),
+                               (size_t)p.N * 24, stream, lat, p.extent, p.stride, p.T, p.N, p.M, p.per_unit, partial, status,
+                               p.max_latency);
+    } else {
+        switch (p.M / 4) {
+            case 1:  launch_worker_vec4<1>(p, lat, partial, status, stream); break;
+            case 2:  launch_worker_vec4<2>(p, lat, partial, status, stream); break;
+            case 4:  launch_worker_vec4<4>(p, lat, partial, status, stream); break;
+            case 8:  launch_worker_vec4<8>(p, lat, partial, status, stream); break;
+            case 16: launch_worker_vec4<16>(p, lat, partial, status, stream); break;
+            case 32: launch_worker_vec4<32>(p, lat, partial, status, stream); break;
+            case 64: launch_worker_vec4<64>(p, lat, partial, status, stream); break;
+            default: launch_worker_vec4<0>(p, lat, partial, status, stream); break;
+        }
+    }
+    if (after) (void)hipEventRecord(after, stream);
+    hipLaunchKernelGGL(dc_worker_totals_final_kernel, dim3((p.N + 31) / 32), dim3(256), 0, stream, partial, p.grid,
+                       p.N, result);
+}
+
+}  // namespace dc
