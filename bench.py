@@ -315,10 +315,14 @@ def time_sums_path(r, lat, taus, taus_dev, stream, steps, warmup, timing: int = 
     host_step, host_done = host_out[0].numpy(), host_out[1].numpy()
     ws = torch.empty(dc.dc_workspace_bytes(r.T, r.N, r.M, K), dtype=torch.uint8, device=lat.device)
 
+    # the same call on the same tensors every step: its arguments are marshalled once (the binding's prepared calls)
+    simulation = dc.PreparedSimulation(lat, taus_dev, r.comm, host_out[0], host_out[1], ws, stream)
+    selection = dc.PreparedSelection(host_step, host_done, taus, r.T, r.N, r.M, 0)
+
     def step():
-        dc.dc_simulate_async(lat, taus_dev, r.comm, host_out[0], host_out[1], ws, stream)
+        simulation.enqueue()
         stream.synchronize()
-        return dc.dc_select_tau(host_step, host_done, taus, r.T, r.N, r.M, 0)
+        return selection.select()
 
     dc.dc_set_kernel_timing(timing)
     try:

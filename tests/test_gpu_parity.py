@@ -497,6 +497,40 @@ def test_async_entry_point_on_a_side_stream(dev):
         dc.dc_simulate_async(lat_d, taus_d, r.comm, out_step, out_done, small, stream)
 
 
+def test_prepared_calls_of_the_binding(dev):
+    """The binding's prepared calls (arguments marshalled once) give what the plain wrappers give, call after call,
+    also on a range of workers, and follow the contents of the tensors they were prepared on."""
+    r = config("lognormal64").with_shape(T=300)
+    lat = host.generate(r)
+    taus = host.tau_grid(r)
+    lat_d, taus_d = to_dev(lat, dev), torch.from_numpy(taus).to(dev)
+    out = torch.zeros((2, taus.size), dtype=torch.int64).pin_memory()
+    step_h, done_h = out[0].numpy(), out[1].numpy()
+    ws = torch.empty(dc.dc_workspace_bytes(r.T, r.N, r.M, taus.size), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    sim = dc.PreparedSimulation(lat_d, taus_d, r.comm, out[0], out[1], ws, stream)
+    sel = dc.PreparedSelection(step_h, done_h, taus, r.T, r.N, r.M)
+    for scale in (1, 2, 1):
+        lat_d.copy_(torch.from_numpy(lat // scale))
+        torch.cuda.synchronize()
+        sim.enqueue()
+        stream.synchronize()
+        ref_step, ref_done = oracle.simulate(lat // scale, taus, r.comm)
+        assert np.array_equal(step_h, ref_step) and np.array_equal(done_h, ref_done)
+        thr, seff, best = sel.select()
+        othr, oseff, obest = oracle.select_tau(ref_step, ref_done, taus, r.T, r.N, r.M)
+        assert best == obest and np.allclose(thr, othr, rtol=1e-6, atol=0)
+        assert np.allclose(seff, oseff, rtol=1e-6, atol=0, equal_nan=True)      # no no-drop baseline given: not a number on both sides
+    part = dc.PreparedSimulation(lat_d, taus_d, r.comm, out[0], out[1], ws, stream, workers=(8, 40))
+    part.enqueue()
+    stream.synchronize()
+    ref_step, ref_done = oracle.simulate(np.ascontiguousarray(lat[:, 8:40]), taus, r.comm)
+    assert np.array_equal(step_h, ref_step) and np.array_equal(done_h, ref_done)
+    with pytest.raises(TypeError):
+        dc.PreparedSelection(list(step_h), done_h, taus, r.T, r.N, r.M)
+
+
 def test_async_entry_point_replays_from_a_graph(dev):
     """The enqueued sequence uses no memset and no allocation, so it can be captured; every replay must
     reproduce the eager result, with other work and synchronisations in between."""
