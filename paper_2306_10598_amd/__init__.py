@@ -235,6 +235,56 @@ class PreparedSelection:
         return self.thr, self.seff, self._best.value
 
 
+class PreparedSpeedup:
+    """dc_speedup_per_step_async with its arguments marshalled once (see PreparedSimulation); select() is Algorithm 2's
+    final argmax on the result, which must then be a pinned host tensor."""
+
+    def __init__(self, lat, taus_dev, comm: int, comm_per_trial_dev, out_seff, workspace, stream=None, taus_host=None):
+        lat = _device_tensor(lat, "int32", "lat")
+        if lat.dim() != 3:
+            raise TypeError("lat must have shape [T][N][M]")
+        T, N, M = lat.shape
+        taus_dev = _device_tensor(taus_dev, "int64", "taus_dev")
+        K = taus_dev.numel()
+        out_seff = _device_writable(out_seff, "float64", "out_seff")
+        workspace = _device_tensor(workspace, "uint8", "workspace")
+        per_ptr = None
+        if comm_per_trial_dev is not None:
+            per = _device_tensor(comm_per_trial_dev, "int64", "comm_per_trial_dev")
+            if per.numel() != T:
+                raise ValueError("comm_per_trial_dev needs one value per trial")
+            per_ptr = per.data_ptr()
+        if out_seff.numel() < K:
+            raise ValueError("output tensor is shorter than the threshold list")
+        handle = 0 if stream is None else int(stream.cuda_stream)
+        self._keep = (lat, taus_dev, comm_per_trial_dev, out_seff, workspace, stream, taus_host)
+        self._fn = _load().dc_speedup_per_step_async
+        self._args = (lat.data_ptr(), T, N, M, taus_dev.data_ptr(), K, int(comm), per_ptr, out_seff.data_ptr(),
+                      workspace.data_ptr(), workspace.numel(), handle)
+        self._select = None
+        if taus_host is not None:
+            if out_seff.is_cuda:
+                raise TypeError("select() reads the result on the host: out_seff must be a pinned host tensor")
+            if not isinstance(taus_host, np.ndarray) or taus_host.dtype != np.int64 or not taus_host.flags.c_contiguous \
+                    or taus_host.size != K:
+                raise TypeError("taus_host must be the K thresholds as a contiguous NumPy int64 array")
+            self._best = ctypes.c_int64(-1)
+            self._select = (out_seff.data_ptr(), taus_host.ctypes.data, K, ctypes.addressof(self._best))
+
+    def enqueue(self) -> None:
+        rc = self._fn(*self._args)
+        if rc != DC_OK:
+            raise DcError(rc, "dc_speedup_per_step_async")
+
+    def select(self) -> int:
+        if self._select is None:
+            raise ValueError("prepared without the host copy of the thresholds")
+        rc = _load().dc_select_tau_per_step(*self._select)
+        if rc != DC_OK:
+            raise DcError(rc, "dc_select_tau_per_step")
+        return self._best.value
+
+
 DC_STATIC_SCRATCH_BYTES = 16 << 20
 
 

@@ -679,6 +679,13 @@ def test_per_step_speedup_errors_and_async(dev):
     dc.dc_speedup_per_step_async(lat_d, taus_d, r.comm, None, pinned, ws, stream)
     assert dc.dc_workspace_status(ws, stream) == dc.DC_OK
     assert np.array_equal(pinned.numpy(), out.cpu().numpy())
+    pinned.zero_()                                                         # the same through the binding's prepared call
+    call = dc.PreparedSpeedup(lat_d, taus_d, r.comm, None, pinned, ws, stream, taus_host=taus)
+    for _ in range(2):
+        call.enqueue()
+        stream.synchronize()
+        assert np.array_equal(pinned.numpy(), out.cpu().numpy())
+        assert call.select() == oracle.per_step_best(ref, taus)
 
 
 # ---- analytical side: exact moments, closed-form curves ----------------------------------------------------
