@@ -41,7 +41,7 @@ def ensure_built() -> None:
 def kernel_source_hash() -> str:
     h = hashlib.sha256()
     for path in sorted((ROOT / "paper_2306_10598_amd" / "csrc").iterdir()):        # every source of the library
-        if path.suffix in (".hip", ".h"):
+        if path.suffix in (".hip", ".h", ".inl"):
             h.update(path.read_bytes())
     return h.hexdigest()[:16]
 

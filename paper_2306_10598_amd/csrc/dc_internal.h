@@ -1,5 +1,5 @@
 // Shared between dc_api.hip (host logic, C ABI) and the translation units with the kernels and their launchers
-// (dc_kernels.hip, dc_rows.hip, dc_trial.hip, dc_workers.hip, dc_analytic.hip).
+// (dc_kernels.hip, dc_rows.hip, dc_rows_long.hip, dc_trial.hip, dc_workers.hip, dc_analytic.hip).
 #ifndef DC_INTERNAL_H
 #define DC_INTERNAL_H
 
@@ -38,6 +38,7 @@
 #ifndef DC_ROWS_UNITS_PER_WAVE
 #define DC_ROWS_UNITS_PER_WAVE 1ull     // the kernel with whole rows per lane: units are shortened until a wave gets this many (8: 7-10 % slower on 512 MB)
 #endif
+#define DC_ROWS_SHORT_MAX 12u            // row lengths up to this are built in dc_rows.hip, longer ones in dc_rows_long.hip
 #ifndef DC_WAVE_TRIAL_ELEMENTS
 #define DC_WAVE_TRIAL_ELEMENTS 16384u   // per-iteration pass: trials of up to this many latencies are taken by single waves
 #endif
