@@ -96,6 +96,10 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
         span = N * 100 < loads * rows_per_load * 85 && p.elements >= ((uint64_t)1 << 22);   // (below 16 MB either takes 8-9 us)
     }
     if (span) { p.lane_rows = true; p.span_rows = (uint32_t)N; }
+    p.chunk = p.K < DC_CHUNK_THRESHOLDS ? p.K : DC_CHUNK_THRESHOLDS;
+    p.p2 = next_pow2_above(p.chunk);
+    // the longest rows of that kernel and a pass of more than 2047 thresholds do not fit a compute unit's LDS together
+    if (p.lane_rows && dc::scan_lds_bytes(p) > DC_LDS_BYTES) { p.lane_rows = false; p.span_rows = 0u; span = false; }
     p.vec4 = aligned && !p.lane_rows && vec4_shape(M);
     uint64_t upt;
     if (p.lane_rows) {
@@ -135,8 +139,6 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     p.grid = (uint32_t)(grid < DC_MAX_SCAN_BLOCKS ? grid : DC_MAX_SCAN_BLOCKS);
     p.grid_wide = p.grid;
     p.run = DC_SCAN_WAVES;                                     // both settled in enqueue(), once the device's limits are known
-    p.chunk = p.K < DC_CHUNK_THRESHOLDS ? p.K : DC_CHUNK_THRESHOLDS;
-    p.p2 = next_pow2_above(p.chunk);
     p.max_latency = (uint32_t)(2147483647ll / M);
 
     size_t off = 0;

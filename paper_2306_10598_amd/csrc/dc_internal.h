@@ -38,6 +38,7 @@
 #ifndef DC_ROWS_UNITS_PER_WAVE
 #define DC_ROWS_UNITS_PER_WAVE 1ull     // the kernel with whole rows per lane: units are shortened until a wave gets this many (8: 7-10 % slower on 512 MB)
 #endif
+#define DC_LDS_BYTES (160u * 1024u)      // LDS of a compute unit (gfx950): the most one block can ask for
 #define DC_ROWS_SHORT_MAX 12u            // row lengths up to this are built in dc_rows.hip, longer ones in dc_rows_long.hip
 #ifndef DC_WAVE_TRIAL_ELEMENTS
 #define DC_WAVE_TRIAL_ELEMENTS 16384u   // per-iteration pass: trials of up to this many latencies are taken by single waves

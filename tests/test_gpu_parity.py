@@ -226,6 +226,18 @@ def test_short_rows_of_few_workers(M, N, dev):
         assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, taus[:4])
 
 
+@pytest.mark.parametrize("M", [16, 23, 25, 34])
+def test_longest_rows_held_by_a_lane_with_a_full_pass_of_thresholds(M, dev):
+    """The largest staging areas of that kernel next to the largest threshold tables (4095 per pass, two passes): what
+    fits a compute unit's LDS runs there, the rest (rows of 25 elements) goes to the kernel for any row length."""
+    rng = np.random.default_rng(M)
+    lat = rng.integers(0, 5000, size=(6, 512, M), dtype=np.int32)
+    totals = lat.sum(axis=2, dtype=np.int64)
+    taus = rng.integers(int(totals.min()) // 2, int(totals.max()) + 10, size=5000)
+    check(lat, taus, 7, dev)
+    check(lat, taus[:2500], 7, dev)
+
+
 def test_short_rows_of_few_workers_many_trials_and_passes(dev):
     """The same path over many units and blocks, with more thresholds than one pass holds (every pass repeats the
     atomic maxima), twice on one workspace (the maxima are cleared per call), then through the entry point without
