@@ -455,7 +455,7 @@ void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t*
     uint32_t blocks = (K + 31) / 32;
     if (blocks == 0) blocks = 1;
     const uint32_t clearing = (zero_count + 4095u) / 4096u;           // blocks beyond the thresholds only clear
-    if (blocks < clearing) blocks = clearing < 64u ? clearing : 64u;
+    if (blocks < clearing) blocks = clearing < 1024u ? clearing : 1024u;
     hipLaunchKernelGGL(dc_prep_kernel, dim3(blocks), dim3(threads), 0, stream, taus, K, tau_sorted, tau_u32, pos,
                        status, bins, bins_words, lat, (unsigned long long)rows_total, N ? N : 1u,
                        (unsigned long long)trial_stride, M, sample_rows, zero_words, zero_count);

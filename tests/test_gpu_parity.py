@@ -243,7 +243,7 @@ def test_short_rows_of_few_workers_many_trials_and_passes(dev):
     atomic maxima), twice on one workspace (the maxima are cleared per call), then through the entry point without
     a workspace."""
     rng = np.random.default_rng(4242)
-    for T, N, M in ((30000, 20, 8), (25000, 12, 16)):      # rows of 8 and 16 elements take this path from 16 MB on
+    for T, N, M in ((30000, 20, 8), (25000, 12, 16), (600000, 4, 5)):   # rows of 8 and 16 elements take this path from 16 MB on; very many tiny trials
         lat = rng.integers(0, 5000, size=(T, N, M), dtype=np.int32)
         lat[rng.integers(0, T, 50), rng.integers(0, N, 50), :] = 30000
         totals = lat.sum(axis=2, dtype=np.int64)
