@@ -477,7 +477,9 @@ def main() -> int:
                      "traffic": traffic, "traffic_source": traffic_source,
                      "kernel_ms": scan_avg_ms, "kernel_ms_min": float(np.min(scan_ms)),
                      "sequence_ms": float(np.mean(seq_ms)),     # all kernels of a call, first to last, on the device
-                     "algorithmic_bytes": algo_bytes},
+                     "algorithmic_bytes": algo_bytes,
+                     "peak_source": "MI355X published HBM3E bandwidth; `device` holds what this GPU reports about its memory"},
+        "device": {"name": torch.cuda.get_device_name(dev), **dc.dc_device_info()},
     }
     del lat
     torch.cuda.empty_cache()

@@ -241,6 +241,12 @@ const char* dc_status_string(int status);
  * DC_ERR_NOMEM ("" if none).  Static storage, valid until the next failing call. */
 const char* dc_last_device_error(void);
 
+/* What the current device reports about itself, for a benchmark that states the roofline it measures against (the
+ * memory roofline of Section 8 of this library's measurements is bytes per second, so clock and bus width are what a
+ * reader needs to check the peak figure): compute units, memory clock in kHz, memory bus width in bits, L2 size in
+ * bytes.  Any pointer may be NULL.  DC_ERR_DEVICE if a query fails. */
+int dc_device_info(int32_t* compute_units, int32_t* memory_clock_khz, int32_t* memory_bus_bits, int32_t* l2_bytes);
+
 /* Frees everything the library holds (cached workspace, events).  Safe to call twice. */
 void dc_shutdown(void);
 

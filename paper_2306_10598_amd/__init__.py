@@ -24,7 +24,7 @@ EXPORTS = (
     "dc_simulate_strided", "dc_simulate_strided_async", "dc_worker_moments_strided", "dc_workspace_kernel_ms",
     "dc_speedup_per_step", "dc_speedup_workspace_bytes", "dc_speedup_per_step_async", "dc_select_tau_per_step",
     "dc_moments", "dc_worker_moments", "dc_analytic_curves",
-    "dc_set_kernel_timing", "dc_last_kernel_ms", "dc_status_string", "dc_last_device_error", "dc_shutdown",
+    "dc_set_kernel_timing", "dc_last_kernel_ms", "dc_status_string", "dc_last_device_error", "dc_device_info", "dc_shutdown",
 )
 
 _lib = None
@@ -91,6 +91,8 @@ def _load():
     lib.dc_status_string.restype = ctypes.c_char_p
     lib.dc_last_device_error.argtypes = []
     lib.dc_last_device_error.restype = ctypes.c_char_p
+    lib.dc_device_info.argtypes = [p, p, p, p]
+    lib.dc_device_info.restype = ctypes.c_int
     lib.dc_shutdown.argtypes = []
     lib.dc_shutdown.restype = None
     _lib = lib
@@ -452,6 +454,13 @@ def dc_workspace_kernel_ms(workspace, whole: bool = False):
     _check(_load().dc_workspace_kernel_ms(workspace.data_ptr(), ctypes.byref(a), ctypes.byref(b) if whole else None),
            "dc_workspace_kernel_ms")
     return float(a.value), (float(b.value) if whole else None)
+
+
+def dc_device_info() -> dict:
+    """Compute units, memory clock (kHz), memory bus width (bits) and L2 size (bytes) of the current device."""
+    v = [ctypes.c_int32(0) for _ in range(4)]
+    _check(_load().dc_device_info(*[ctypes.byref(x) for x in v]), "dc_device_info")
+    return {"compute_units": v[0].value, "memory_clock_khz": v[1].value, "memory_bus_bits": v[2].value, "l2_bytes": v[3].value}
 
 
 def dc_shutdown() -> None:

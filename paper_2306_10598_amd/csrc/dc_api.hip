@@ -960,6 +960,16 @@ const char* dc_status_string(int status) {
 
 const char* dc_last_device_error(void) { return g_error_text; }
 
+int dc_device_info(int32_t* compute_units, int32_t* memory_clock_khz, int32_t* memory_bus_bits, int32_t* l2_bytes) {
+    int device = 0, v = 0;
+    DC_HIP(hipGetDevice(&device));
+    if (compute_units) { DC_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device)); *compute_units = v; }
+    if (memory_clock_khz) { DC_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMemoryClockRate, device)); *memory_clock_khz = v; }
+    if (memory_bus_bits) { DC_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMemoryBusWidth, device)); *memory_bus_bits = v; }
+    if (l2_bytes) { DC_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeL2CacheSize, device)); *l2_bytes = v; }
+    return DC_OK;
+}
+
 void dc_shutdown(void) {
     {
         std::lock_guard<std::mutex> lock(g_cache_mutex);
