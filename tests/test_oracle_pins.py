@@ -277,6 +277,22 @@ def test_per_step_speedup_pins():
         oracle.per_step_speedup(np.zeros((1, 1, 2), dtype=np.int32), [5], 0)      # 0/0 step time
 
 
+def test_threaded_forms_agree_with_the_single_threaded_ones():
+    """The oracle's helpers that spread trials over threads (used for the large comparisons) return what one thread
+    returns: exactly for the integer sums, to rounding for the float mean over iterations."""
+    rng = np.random.default_rng(77)
+    lat = rng.integers(0, 4000, size=(53, 7, 9), dtype=np.int32)
+    totals = lat.sum(axis=2, dtype=np.int64)
+    taus = np.maximum(rng.integers(0, int(totals.max()) + 9, size=31), 1)
+    comm = rng.integers(0, 300, size=53)
+    for method in ("sorted", "literal"):
+        one = oracle.simulate(lat, taus, 40, method)
+        many = oracle.simulate_threaded(lat, taus, 40, method, 5)
+        assert np.array_equal(one[0], many[0]) and np.array_equal(one[1], many[1])
+    assert np.allclose(oracle.per_step_speedup(lat, taus, comm, threads=5), oracle.per_step_speedup(lat, taus, comm), rtol=1e-13)
+    assert np.allclose(oracle.per_step_speedup(lat, taus, 12, threads=64), oracle.per_step_speedup(lat, taus, 12), rtol=1e-13)
+
+
 def test_per_step_best_on_hand_worked_values(golden_dir):
     """The final argmax of Algorithm 2 on speedups worked by hand from Section 4.4's ratio.
 
