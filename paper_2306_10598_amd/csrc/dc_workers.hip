@@ -40,28 +40,73 @@ void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint64_t tria
     const uint32_t lo = (uint32_t)((uint64_t)nfull * wave / DC_SCAN_WAVES);
     const uint32_t hi = (uint32_t)((uint64_t)nfull * (wave + 1) / DC_SCAN_WAVES);
     uint32_t check = 0u;
-    for (uint32_t t = blockIdx.x; t < T; t += gridDim.x) {
-        const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)lo * R * M) + lane;
-        uint32_t i = 0;
-        for (; i + U <= hi - lo; i += U) {
-            u32x4 x[U];
-            uint32_t incl[U];
+    const uint32_t len = hi - lo;                                   // the wave's loads per trial
+    if (len >= 4u * (uint32_t)U) {
+        for (uint32_t t = blockIdx.x; t < T; t += gridDim.x) {
+            const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)lo * R * M) + lane;
+            uint32_t i = 0;
+            for (; i + U <= len; i += U) {
+                u32x4 x[U];
+                uint32_t incl[U];
 #pragma unroll
-            for (int k = 0; k < U; ++k) x[k] = load_rows<L>(base + (uint64_t)(i + k) * stride, shape);
+                for (int k = 0; k < U; ++k) x[k] = load_rows<L>(base + (uint64_t)(i + k) * stride, shape);
+                completion_times<L, U>(x, incl, lane, shape);
+#pragma unroll
+                for (int k = 0; k < U; ++k) {
+                    check = umax(check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
+                    if (row_end) add_worker_total(acc, N, (lo + i + k) * R + shape.row, incl[k]);
+                }
+            }
+            if (i < len) {                                          // the rest of the trial's loads as one batch
+                const uint32_t n = len - i;                         // wave-uniform
+                u32x4 x[U];
+                uint32_t incl[U];
+#pragma unroll
+                for (int k = 0; k < U; ++k) {
+                    x[k] = u32x4{0u, 0u, 0u, 0u};
+                    if ((uint32_t)k < n) x[k] = load_rows<L>(base + (uint64_t)(i + k) * stride, shape);
+                }
+                completion_times<L, U>(x, incl, lane, shape);
+#pragma unroll
+                for (int k = 0; k < U; ++k) {
+                    check = umax(check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
+                    if ((uint32_t)k < n && row_end) add_worker_total(acc, N, (lo + i + k) * R + shape.row, incl[k]);
+                }
+            }
+        }
+    } else {
+        // Few loads per trial (64 workers of 32 accumulations: two per wave; 200 of 64: twelve): the wave's loads
+        // over all of the block's trials are taken U at a time whatever the trial they belong to, which keeps as
+        // many loads in flight as long trials do.  A worker's row is always the same lane's, so two items of a
+        // batch that belong to one worker are added one after the other by that lane.
+        const uint32_t my_trials = blockIdx.x < T ? (T - blockIdx.x + gridDim.x - 1u) / gridDim.x : 0u;
+        const uint64_t items = (uint64_t)my_trials * len;
+        uint32_t at_trial = 0u, at_load = 0u;                       // the next item: which of the block's trials, which load
+        for (uint64_t k0 = 0; k0 < items; k0 += U) {
+            const uint32_t n = items - k0 < (uint64_t)U ? (uint32_t)(items - k0) : (uint32_t)U;      // wave-uniform
+            u32x4 x[U];
+            uint32_t incl[U], load_of[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                x[k] = u32x4{0u, 0u, 0u, 0u};
+                load_of[k] = at_load;
+                if ((uint32_t)k < n) {
+                    const uint64_t t = (uint64_t)blockIdx.x + (uint64_t)at_trial * gridDim.x;
+                    const u32x4* p = reinterpret_cast<const u32x4*>(lat + t * trial_stride + (uint64_t)(lo + at_load) * R * M) + lane;
+                    x[k] = load_rows<L>(p, shape);
+                    if (++at_load == len) { at_load = 0u; ++at_trial; }
+                }
+            }
             completion_times<L, U>(x, incl, lane, shape);
 #pragma unroll
             for (int k = 0; k < U; ++k) {
                 check = umax(check, umax(umax(x[k].x, x[k].y), umax(x[k].z, x[k].w)));
-                if (row_end) add_worker_total(acc, N, (lo + i + k) * R + shape.row, incl[k]);
+                if ((uint32_t)k < n && row_end) add_worker_total(acc, N, (lo + load_of[k]) * R + shape.row, incl[k]);
             }
         }
-        for (; i < hi - lo; ++i) {
-            const u32x4 x[1] = {load_rows<L>(base + (uint64_t)i * stride, shape)};
-            uint32_t incl[1];
-            completion_times<L, 1>(x, incl, lane, shape);
-            check = umax(check, umax(umax(x[0].x, x[0].y), umax(x[0].z, x[0].w)));
-            if (row_end) add_worker_total(acc, N, (lo + i) * R + shape.row, incl[0]);
-        }
+    }
+    for (uint32_t t = blockIdx.x; t < T; t += gridDim.x) {          // the trial's last, partial load
+        const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)lo * R * M) + lane;
         if (wave == DC_SCAN_WAVES - 1 && tail_rows) {
             const bool valid = lane < tail_rows * shape.lanes;
             u32x4 x[1] = {{0u, 0u, 0u, 0u}};
