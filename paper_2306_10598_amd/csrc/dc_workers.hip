@@ -166,30 +166,57 @@ void dc_worker_totals_flat_kernel(const int32_t* __restrict__ lat, uint64_t exte
     for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) out[i] = acc[i];
 }
 
-// result[3][N] = sums over blocks (the 128-bit squares with carry).  A block of 256 threads takes 32 workers; its
-// eight groups of 32 threads add every eighth block's partial sums (32 consecutive 8-byte words per read), then the
-// eight partial results are added in a fixed order.
-__global__ __launch_bounds__(256)
+// result[3][N] = sums over blocks (the 128-bit squares with carry).  A block of 1024 threads takes 32 workers; each of
+// its 32 groups of 32 threads adds every 32nd block's partial sums (32 consecutive 8-byte words per read, eight rows
+// requested together: one thread after the other through 64 rows had taken 23 us, more than the streaming kernel on
+// a small tensor), then the 32 partial results are added in two fixed stages.
+#define DC_FINAL_SLICES 32
+#define DC_FINAL_BATCH 8
+__global__ __launch_bounds__(32 * DC_FINAL_SLICES)
 void dc_worker_totals_final_kernel(const unsigned long long* __restrict__ partial, uint32_t blocks, uint32_t N,
                                    unsigned long long* __restrict__ result) {
-    __shared__ unsigned long long part[8][32][3];
+    __shared__ unsigned long long part[DC_FINAL_SLICES][32][3];
     const uint32_t w = threadIdx.x & 31u, slice = threadIdx.x >> 5;
     const uint32_t n = blockIdx.x * 32u + w;
     unsigned long long sum = 0ull;
     unsigned __int128 sq = 0;
     if (n < N) {
-        for (uint32_t b = slice; b < blocks; b += 8u) {
-            const unsigned long long* in = partial + (uint64_t)b * 3 * N;
-            sum += in[n];
-            sq += ((unsigned __int128)in[2 * N + n] << 64) | in[N + n];
+        for (uint32_t b0 = slice; b0 < blocks; b0 += DC_FINAL_SLICES * DC_FINAL_BATCH) {
+            unsigned long long s[DC_FINAL_BATCH], lo[DC_FINAL_BATCH], hi[DC_FINAL_BATCH];
+#pragma unroll
+            for (int k = 0; k < DC_FINAL_BATCH; ++k) {
+                const uint32_t b = b0 + (uint32_t)k * DC_FINAL_SLICES;
+                s[k] = lo[k] = hi[k] = 0ull;
+                if (b < blocks) {
+                    const unsigned long long* in = partial + (uint64_t)b * 3 * N;
+                    s[k] = in[n];
+                    lo[k] = in[N + n];
+                    hi[k] = in[2 * N + n];
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < DC_FINAL_BATCH; ++k) {
+                sum += s[k];
+                sq += ((unsigned __int128)hi[k] << 64) | lo[k];
+            }
         }
     }
     part[slice][w][0] = sum;
     part[slice][w][1] = (unsigned long long)sq;
     part[slice][w][2] = (unsigned long long)(sq >> 64);
     __syncthreads();
+    if (slice < 4u) {                                               // 32 -> 4: slices slice, slice + 4, ...
+        for (uint32_t q = slice + 4u; q < DC_FINAL_SLICES; q += 4u) {
+            sum += part[q][w][0];
+            sq += ((unsigned __int128)part[q][w][2] << 64) | part[q][w][1];
+        }
+        part[slice][w][0] = sum;
+        part[slice][w][1] = (unsigned long long)sq;
+        part[slice][w][2] = (unsigned long long)(sq >> 64);
+    }
+    __syncthreads();
     if (slice == 0 && n < N) {
-        for (uint32_t q = 1; q < 8u; ++q) {
+        for (uint32_t q = 1; q < 4u; ++q) {
             sum += part[q][w][0];
             sq += ((unsigned __int128)part[q][w][2] << 64) | part[q][w][1];
         }
@@ -239,8 +266,8 @@ void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long*
         }
     }
     if (after) (void)hipEventRecord(after, stream);
-    hipLaunchKernelGGL(dc_worker_totals_final_kernel, dim3((p.N + 31) / 32), dim3(256), 0, stream, partial, p.grid,
-                       p.N, result);
+    hipLaunchKernelGGL(dc_worker_totals_final_kernel, dim3((p.N + 31) / 32), dim3(32 * DC_FINAL_SLICES), 0, stream,
+                       partial, p.grid, p.N, result);
 }
 
 }  // namespace dc
