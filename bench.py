@@ -287,13 +287,15 @@ def bench_worker_moments(args, r, lat) -> int:
 def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0, T: int = 0) -> str:
     """The streaming kernel the library runs for N rows of M elements per trial (16-byte aligned, contiguous tensor),
     as a profile names it."""
-    longer = (M % 2 == 1 and M <= 25) or (M % 4 == 2 and M <= 34)      # rows of 17 to 34 elements that a lane can still hold
+    longer = M == 17 or (M % 4 == 2 and M <= 34)                       # rows of 17 to 34 elements that a lane can still hold
     if (M <= 16 or longer) and N % (2 if M > 16 and M % 2 == 0 else 4) == 0 and N >= 256:   # every lane holds whole rows
         return f"dc_scan_rows_kernel<{M}, false>"
     if M <= 16 and N >= 4 and (T * N) % 4 == 0 and M not in (1, 2, 4): # the same over trials of any worker count, unless
         per_load = 64 // (M // 4) if M % 4 == 0 else 0                 # whole rows per load fill their loads well
         if per_load == 0 or (N * 100 < -(-N // per_load) * per_load * 85 and T * N * M >= 1 << 22):
             return f"dc_scan_rows_kernel<{M}, true>"
+    if 19 <= M <= 63 and M % 4 != 0 and not longer and (N * M) % 4 == 0 and N >= 32:   # one row per lane
+        return "dc_scan_row_lane_kernel"
     if M % 4 == 0 and (M <= 128 or M == 256):
         lanes = M // 4
         known = lanes if lanes & (lanes - 1) == 0 else 0              # one instantiation serves every other lane count

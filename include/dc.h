@@ -22,9 +22,10 @@
  *     current device; "HOST" pointers are ordinary host memory.
  *   - lat must be 4-byte aligned; rows are contiguous with m fastest: element (t,n,m) is at
  *     lat[(t*N + n)*M + m].  The fastest kernels need lat 16-byte aligned and either M a multiple of 4
- *     up to 128, or 256 (best when M is a power of two), or M <= 16 with a multiple of 4 rows in all;
- *     every other M >= 1 and any 4-byte alignment takes a kernel that reads the tensor as one flat run
- *     of 16-byte vectors, with the same results at 75-90 % of that speed.
+ *     up to 128, or 256 (best when M is a power of two), or M <= 16 with a multiple of 4 rows in all,
+ *     or M <= 63 with N*M a multiple of 4 and at least 32 workers; every other M >= 1 and any 4-byte
+ *     alignment takes a kernel that reads the tensor as one flat run of 16-byte vectors, with the same
+ *     results at 75-90 % of that speed.
  *   - Preconditions on values, checked while streaming: every latency is >= 0
  *     (else DC_ERR_NEGATIVE_LATENCY) and <= floor((2^31-1)/M) (else DC_ERR_RANGE), which
  *     guarantees that no worker's total overflows 31 bits.

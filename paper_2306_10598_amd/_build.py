@@ -7,7 +7,7 @@ from pathlib import Path
 HERE = Path(__file__).resolve().parent
 ROOT = HERE.parent
 LIB_PATH = HERE / "libdc.so"
-SOURCES = [HERE / "csrc" / name for name in ("dc_api.hip", "dc_kernels.hip", "dc_rows.hip", "dc_rows_long.hip", "dc_trial.hip", "dc_workers.hip",
+SOURCES = [HERE / "csrc" / name for name in ("dc_api.hip", "dc_kernels.hip", "dc_rows.hip", "dc_rows_long.hip", "dc_row_lane.hip", "dc_trial.hip", "dc_workers.hip",
                                              "dc_analytic.hip")]
 OBJECTS = HERE / "_build"                 # object files of the last build (git-ignored)
 

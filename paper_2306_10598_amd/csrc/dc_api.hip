@@ -96,10 +96,15 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
         span = N * 100 < loads * rows_per_load * 85 && p.elements >= ((uint64_t)1 << 22);   // (below 16 MB either takes 8-9 us)
     }
     if (span) { p.lane_rows = true; p.span_rows = (uint32_t)N; }
+    // rows of 19 to 63 elements that are no multiple of 4 (and not of that kernel's lengths): one row per lane, chunks of 64 rows
+    p.row_lane = aligned && !p.lane_rows && dc::row_lane_length((uint32_t)M) && (((uint64_t)N * (uint64_t)M) & 3u) == 0 &&
+                 N >= (int64_t)DC_ROW_LANE_MIN_N;
+    if (p.row_lane) p.lane_rows = true;
     p.chunk = p.K < DC_CHUNK_THRESHOLDS ? p.K : DC_CHUNK_THRESHOLDS;
     p.p2 = next_pow2_above(p.chunk);
-    // the longest rows of that kernel and a pass of more than 2047 thresholds do not fit a compute unit's LDS together
-    if (p.lane_rows && dc::scan_lds_bytes(p) > DC_LDS_BYTES) { p.lane_rows = false; p.span_rows = 0u; span = false; }
+    // a plan whose staging areas and threshold tables would not fit a compute unit's LDS together (none of the row
+    // lengths built at present) goes to the kernel for any row length
+    if (p.lane_rows && dc::scan_lds_bytes(p) > DC_LDS_BYTES) { p.lane_rows = p.row_lane = false; p.span_rows = 0u; span = false; }
     p.vec4 = aligned && !p.lane_rows && vec4_shape(M);
     uint64_t upt;
     if (p.lane_rows) {

@@ -61,6 +61,11 @@
 #define DC_TRIAL_CHUNK_THRESHOLDS 2047u // same for the per-iteration speedup pass (it also keeps float64 sums in LDS)
 #define DC_MAX_TRIAL_BLOCKS 2048u      // upper bound of that pass's grid (sizes its per-block sums in the workspace)
 #define DC_MAX_STAT_WORKERS 2560u        // per-worker statistics keep 24 bytes per worker in LDS
+#define DC_ROWS_ODD_MAX 17u             // longest odd row of which a lane holds four in registers, and the longest row of
+#define DC_ROWS_EVEN_MAX 34u            // 4k+2 elements of which it holds two (the instantiations of dc_scan_rows_kernel)
+#define DC_ROW_LANE_MIN_M 19u           // shortest row of the kernel with one row per lane
+#define DC_ROW_LANE_MAX_M 63u           // longest row of the kernel with one row per lane (16 KiB of LDS per wave)
+#define DC_ROW_LANE_MIN_N 32u           // fewer workers leave most of a wave's 64 rows empty
 #define DC_TAU_CLAMP 0x80000000u       // thresholds at or above 2^31 exceed every completion time
 
 #define DC_FLAG_NEGATIVE_TAU 1u
@@ -70,13 +75,19 @@
 
 namespace dc {
 
+// row lengths that kernel is built for
+inline bool lane_rows_length(uint32_t M) { return M <= 16u || ((M & 1u) && M <= DC_ROWS_ODD_MAX) || ((M & 3u) == 2u && M <= DC_ROWS_EVEN_MAX); }
+// longer rows that are no multiple of 4: one row per lane, read word by word from the wave's copy of the chunk in LDS
+inline bool row_lane_length(uint32_t M) { return M >= DC_ROW_LANE_MIN_M && M <= DC_ROW_LANE_MAX_M && (M & 3u) != 0u && !lane_rows_length(M); }
+
 // Rows that one wave of the kernel with whole rows per lane takes at a time (a chunk): a lane holds 16 rows of one
 // element, 8 of two, otherwise 4.
-inline uint32_t lane_rows_chunk_rows(uint32_t M) { return M == 1u ? 1024u : M == 2u ? 512u : (M > 16u && (M & 3u) == 2u) ? 128u : 256u; }
+inline uint32_t lane_rows_chunk_rows(uint32_t M) {
+    if (row_lane_length(M)) return 64u;                 // one row per lane
+    return M == 1u ? 1024u : M == 2u ? 512u : (M > 16u && (M & 3u) == 2u) ? 128u : 256u;
+}
 // 16-byte vectors that a lane holds per chunk when they pass through LDS: its four rows, or two of the longer even rows
 inline uint32_t lane_rows_vectors(uint32_t M) { return (M > 16u && (M & 3u) == 2u) ? M / 2u : M; }
-// row lengths that kernel is built for
-inline bool lane_rows_length(uint32_t M) { return M <= 16u || ((M & 1u) && M <= 25u) || ((M & 3u) == 2u && M <= 34u); }
 
 // Everything the host decides about one call: which streaming kernel, how the tensor is cut
 // into units, and where each array sits in the workspace.
@@ -86,8 +97,11 @@ struct Plan {
     uint64_t stride;            // elements from one trial to the next (N*M when the tensor is contiguous)
     uint64_t extent;            // elements from the first one of the tensor to its last: (T-1)*stride + N*M
     bool vec4;                  // 16-byte loads, whole rows per load (M a multiple of 4 up to 128, or 256; lat 16-byte aligned)
-    bool lane_rows;             // every lane holds whole rows (M <= 15 and not a multiple of 4, N a multiple of 4 and at
-                                // least DC_LANE_ROWS_MIN_N, trials 16-byte aligned); never set together with vec4
+    bool lane_rows;             // every lane holds whole rows (the row lengths of lane_rows_length: N a multiple of the
+                                // rows per lane and at least DC_LANE_ROWS_MIN_N, trials 16-byte aligned; or span_rows; or
+                                // row_lane); never set together with vec4
+    bool row_lane;              // lane_rows with one row per lane (dc_scan_row_lane_kernel: the row lengths of
+                                // row_lane_length, N*M a multiple of 4, at least DC_ROW_LANE_MIN_N workers)
     bool wave_trials;           // per-iteration pass: every wave owns a trial (small trials of a contiguous tensor, K <= 511)
     uint32_t span_rows;         // lane_rows with few workers per trial on a contiguous tensor: N, and the units ignore the
                                 // trials (unit_max then holds one maximum per trial); 0 otherwise
@@ -117,6 +131,9 @@ void launch_reduce(const Plan& p, const uint32_t* hist_part, unsigned long long*
                    unsigned long long* trial_cnt, unsigned long long* trial_sum, uint32_t* status, uint32_t chunk0,
                    const int64_t* tau_sorted, const uint32_t* pos, int64_t comm, int64_t* out_step, int64_t* out_done,
                    hipStream_t stream);
+int row_lane_blocks_per_cu(size_t lds);
+void launch_row_lane_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
+                          uint32_t* hist_part, uint32_t* status, hipStream_t stream);
 void launch_trial_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc,
                        const int64_t* comm_per_trial, int64_t comm, double* partial, uint32_t* status,
                        hipStream_t stream);

@@ -463,6 +463,7 @@ void launch_prep(const int64_t* taus, uint32_t K, int64_t* tau_sorted, uint32_t*
 
 size_t scan_lds_bytes(const Plan& p) {
     const size_t tables = (size_t)p.p2 * 8;                       // thresholds + histogram
+    if (p.row_lane) return tables + (size_t)p.p2 * 8 + (size_t)DC_SCAN_WAVES * 256u * p.M;   // + cells + every wave's 64 rows
     if (p.lane_rows)                                              // + cells + every wave's stretch for its chunk
         return tables + (size_t)p.p2 * 8 + (4u % p.M ? (size_t)DC_SCAN_WAVES * 64u * (lane_rows_vectors(p.M) | 1u) * sizeof(u32x4) : 0u);
     return tables + (size_t)p.p2 * 8 + (size_t)DC_SCAN_WAVES * QUEUE_ITEMS * sizeof(uint4);   // + cells + queues
@@ -479,6 +480,7 @@ static int resident_vec4(size_t lds) {
 int scan_blocks_per_cu(const Plan& p) {
     const size_t lds = scan_lds_bytes(p);
     int n = 0;
+    if (p.row_lane) return row_lane_blocks_per_cu(lds);
     if (p.lane_rows) return rows_blocks_per_cu(p, lds);
     if (!p.vec4) {
         hipError_t e;
@@ -531,6 +533,7 @@ static void launch_flat(const Plan& p, const int32_t* lat, const uint32_t* tau_c
 
 void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
                  uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
+    if (p.row_lane) { launch_row_lane_scan(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); return; }
     if (p.lane_rows) { launch_rows_scan(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); return; }
     if (!p.vec4) {
         switch (p.M) {

@@ -226,10 +226,46 @@ def test_short_rows_of_few_workers(M, N, dev):
         assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, taus[:4])
 
 
-@pytest.mark.parametrize("M", [16, 23, 25, 34])
+@pytest.mark.parametrize("N", [32, 36, 64, 100, 256, 1000, 2052])
+@pytest.mark.parametrize("M", [19, 21, 23, 25, 27, 29, 31, 33, 35, 38, 42, 45, 47, 49, 50, 55, 62, 63])
+def test_rows_of_a_few_dozen_elements_one_per_lane(M, N, dev):
+    """Rows of 19 to 63 elements that are no multiple of 4 (nor 22, 26, 30, 34), N*M a multiple of 4, at least 32 workers, aligned tensor:
+    the kernel in which a lane owns one row and reads it word by word from the wave's copy of the chunk.  Full and
+    partial chunks of 64 rows, one and several units per trial, a narrow grid near the row totals, a grid over every
+    completion time (with 0, repeats and values no completion time reaches), a threshold list of two passes, and a
+    worker range of the resident tensor."""
+    rng = np.random.default_rng(100 * M + N)
+    T = 5
+    top = min((2**31 - 1) // M, 6000)
+    lat = rng.integers(0, top + 1, size=(T, N, M), dtype=np.int32)
+    lat[0, 0, :] = top                                    # the largest legal row, and the row of trial 1 that decides its maximum
+    lat[1, N - 1, :] = top // 2 + 1
+    lat[1, :N - 1, :] //= 4
+    lat[3] = 0
+    totals = lat.sum(axis=2, dtype=np.int64)
+    narrow = np.quantile(totals, np.linspace(0.6, 1.0, 33)).astype(np.int64)
+    wide = np.concatenate([[0, 0, 1], rng.integers(0, int(totals.max()) + 50, size=60), [int(totals.max())] * 2, [BIG]])
+    lat_dev = to_dev(lat, dev)
+    for taus in (narrow, wide):
+        step, done = dc.dc_simulate(lat_dev, taus, 9)
+        ref = oracle.simulate(lat, taus, 9, "literal")
+        assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, taus[:4])
+    if N == 256:
+        many = rng.integers(int(totals.min()) // 2, int(totals.max()) + 10, size=5000)
+        step, done = dc.dc_simulate(lat_dev, many, 3)
+        ref = oracle.simulate(lat, many, 3, "sorted")
+        assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N)
+    if N >= 100:
+        a = 4 * int(rng.integers(0, (N - 64) // 4 + 1))
+        step, done = dc.dc_simulate(lat_dev, narrow, 2, workers=(a, a + 64))
+        ref = oracle.simulate(np.ascontiguousarray(lat[:, a:a + 64]), narrow, 2, "literal")
+        assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, a)
+
+
+@pytest.mark.parametrize("M", [16, 23, 25, 34, 63])
 def test_longest_rows_held_by_a_lane_with_a_full_pass_of_thresholds(M, dev):
-    """The largest staging areas of that kernel next to the largest threshold tables (4095 per pass, two passes): what
-    fits a compute unit's LDS runs there, the rest (rows of 25 elements) goes to the kernel for any row length."""
+    """The largest staging areas of the kernels with whole rows per lane (rows of 16 and 34 elements: four and two rows
+    per lane; 23 and 25: one) next to the largest threshold tables (4095 per pass, two passes)."""
     rng = np.random.default_rng(M)
     lat = rng.integers(0, 5000, size=(6, 512, M), dtype=np.int32)
     totals = lat.sum(axis=2, dtype=np.int64)
@@ -942,15 +978,16 @@ LITERAL_FULL_EVALS = 2.0e10      # the four-loop oracle runs on the whole tensor
 
 
 @pytest.mark.parametrize("name,rows", [("tiny", 0), ("lognormal64", 0), ("additive200", 0), ("extrapolation2048", 0),
-                                       ("heterogeneous2048", 0), ("heterogeneous2048", 63), ("extrapolation2048", 5),
+                                       ("heterogeneous2048", 0), ("heterogeneous2048", 65), ("heterogeneous2048", 63),
+                                       ("extrapolation2048", 5),
                                        ("extrapolation2048", 16), ("additive200", 13), ("lognormal64", 12),
                                        ("heterogeneous2048", 5)])
 def test_full_size_parity(name, rows, dev):
     """All five workloads at their stated size, in the launch configuration the benchmark times, against the
     sorted-walk oracle on the whole tensor; the three smaller ones also against the four-loop oracle on the whole
-    tensor (the two 2048-worker ones on a sampled slab).  The largest runs once more with 63 accumulations per worker
-    (same bytes, more than 2^32 elements through the kernel for arbitrary row lengths) and with 5 (the same through the
-    kernel in which every lane holds whole rows); the 4.3 GB one with 5 and 16, the two middle ones with 13 and 12 (the same over trials of few workers)."""
+    tensor (the two 2048-worker ones on a sampled slab).  The largest runs once more with 65 accumulations per worker
+    (same bytes, more than 2^32 elements through the kernel for arbitrary row lengths), with 63 (the kernel with one
+    row per lane) and with 5 (the kernel in which every lane holds several whole rows); the 4.3 GB one with 5 and 16, the two middle ones with 13 and 12 (the same over trials of few workers)."""
     from dc_workloads import device
     r = config(name)
     if rows:

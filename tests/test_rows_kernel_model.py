@@ -136,3 +136,64 @@ def test_running_maximum_restarts_where_the_trial_changes(N):
             k = int(t[lane]) - 1
             got[k] = max(got.get(k, 0), int(m_before[lane]))
         assert got == want
+
+
+# ---------------------------------------------------------------------------------------------
+# dc_scan_row_lane_kernel: one row per lane, read word by word from the wave's copy of a chunk of 64 rows
+# ---------------------------------------------------------------------------------------------
+ROW_LANE_LENGTHS = [19, 21, 23, 25, 27, 29, 31, 33, 35, 37, 38, 39, 41, 42, 43, 45, 46, 47, 49, 50, 51, 53, 54, 55,
+                    57, 58, 59, 61, 62, 63]
+
+
+@pytest.mark.parametrize("M", ROW_LANE_LENGTHS)
+def test_row_lane_chunks_are_whole_vectors_and_lanes_read_distinct_banks(M):
+    """A chunk starts at a multiple of 64 rows, so its first element is a multiple of 4 whatever M; the last chunk of
+    a trial holds N mod 64 rows, whole vectors iff N*M is a multiple of 4.  NB vectors per lane hold a chunk.  Lane l
+    reads word l*M + m: 32 different banks per half wave for odd M, pairs of lanes for M = 2 mod 4."""
+    nb = 8 if M <= 32 else 12 if M <= 48 else 16
+    assert 64 * M % 4 == 0 and 64 * M // 4 <= 64 * nb
+    for N in range(32, 200):
+        if N * M % 4:
+            continue
+        for c0 in range(0, N, 64):
+            here = min(64, N - c0)
+            assert (c0 * M) % 4 == 0 and (here * M) % 4 == 0
+    for m in (0, 1, M - 1):
+        for half in (LANES[:32], LANES[32:]):
+            banks = (half * M + m) % 32
+            distinct = len(set(banks.tolist()))
+            assert distinct == (32 if M % 2 else 16)
+
+
+@pytest.mark.parametrize("M", [19, 27, 38, 45, 63])
+def test_row_lane_backward_walk_counts_every_completion_time_in_the_grid(M):
+    """total = sum of the row; val starts at the total and loses the row's elements from the end, one step at a time or
+    four at once when 48 lanes are inside the grid; the walk stops at the first step in which no lane reaches the
+    smallest threshold.  What it bins equals the histogram of all completion times at or above that threshold."""
+    rng = np.random.default_rng(M)
+    for trial in range(12):
+        here = 64 if trial % 3 else int(rng.integers(1, 64))          # a partial chunk: lanes beyond it own no row
+        rows = rng.integers(0, 300, size=(64, M))
+        if trial % 4 == 0:
+            rows[rng.integers(0, 64, 10)] = 0
+        mine = LANES < here
+        p = np.cumsum(rows, axis=1)
+        top = int(p[mine].max())
+        taus = np.sort(rng.integers(int(top * rng.choice([0.0, 0.3, 0.9])), top + 2, size=17))
+        if trial == 5:
+            taus[0] = 0                                                # every completion time is inside the grid
+        want = np.bincount(np.searchsorted(taus, p[mine].ravel(), side="right"), minlength=18)
+        hist = np.zeros(18, dtype=np.int64)
+        val = np.where(mine, rows.sum(axis=1), 0)
+        s = 0
+        while s < M:
+            reach = mine & (val >= taus[0])
+            if not reach.any():
+                break
+            width = 4 if s + 4 <= M and reach.sum() >= 48 else 1
+            for k in range(width):
+                b = np.searchsorted(taus, val, side="right")
+                np.add.at(hist, b[mine], 1)
+                val = np.where(mine, val - rows[:, M - 1 - s - k], val)
+            s += width
+        assert np.array_equal(hist[1:], want[1:])                      # bin 0 (below every threshold) is never read
