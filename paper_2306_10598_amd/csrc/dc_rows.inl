@@ -13,8 +13,8 @@
 namespace {
 
 // ---------------------------------------------------------------------------------------------
-// dc_scan_rows_kernel: short rows that a lane can own.  M <= 16, N a multiple of 4, every trial on a 16-byte
-// boundary.
+// dc_scan_rows_kernel: short rows of which a lane can hold several.  M <= 17 or 18, 22, 26, 30, 34 (the lengths of
+// dc::lane_rows_length), N a multiple of the rows per lane, every trial on a 16-byte boundary.
 // The kernels above spread a row over lanes and pay for it with cross-lane sums and, per 16-byte load, one queue
 // slot or one search per element; with rows of a few elements that arithmetic, not HBM, bounds them.  Here a lane
 // holds R whole rows in registers (V 16-byte vectors = R*M elements), so completion times are R*M plain additions,
@@ -23,7 +23,8 @@ namespace {
 // step in which no lane reaches the smallest threshold; with the usual grids that is after one or two steps.
 // A wave reads a chunk of 64 V consecutive vectors with coalesced loads (lane l takes vectors l, l + 64, ...) and,
 // unless a vector holds whole rows anyway (M = 1, 2), passes them through its own stretch of LDS so that lane l ends
-// up with vectors l V, ..., l V + V - 1: for odd M these reads are free of bank conflicts, for even M two-way.
+// up with vectors l V, ..., l V + V - 1; a lane's stretch is padded to an odd number of vectors, which keeps these
+// reads free of bank conflicts for every M.
 // ---------------------------------------------------------------------------------------------
 template <int M>
 struct LaneRows {
