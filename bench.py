@@ -284,18 +284,24 @@ def bench_worker_moments(args, r, lat) -> int:
     return 0
 
 
-def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0, T: int = 0) -> str:
-    """The streaming kernel the library runs for N rows of M elements per trial (16-byte aligned, contiguous tensor),
-    as a profile names it."""
-    longer = M == 17 or (M % 4 == 2 and M <= 34)                       # rows of 17 to 34 elements that a lane can still hold
-    if (M <= 16 or longer) and N % (2 if M > 16 and M % 2 == 0 else 4) == 0 and N >= 256:   # every lane holds whole rows
+def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0, T: int = 0, K: int = 1) -> str:
+    """The streaming kernel the library runs for N rows of M elements per trial and K thresholds (16-byte aligned,
+    contiguous tensor), as a profile names it."""
+    p2 = 4
+    while p2 <= min(K, 4095):
+        p2 *= 2
+    two_blocks = lambda stage_bytes: 16 * p2 + stage_bytes + 1024 <= 80 * 1024     # what two blocks per compute unit leave each
+    per_lane = M // 2 if M > 16 and M % 4 == 2 else M                  # 16-byte vectors of a lane's rows
+    rows_fit = two_blocks(0 if 4 % M == 0 else 4 * 64 * (per_lane | 1) * 16)
+    several = (M <= 15 and M != 12) or M == 17 or (M % 4 == 2 and M <= 30)         # row lengths of which a lane holds several
+    if several and rows_fit and N % (2 if M > 16 and M % 2 == 0 else 4) == 0 and N >= 256:
         return f"dc_scan_rows_kernel<{M}, false>"
-    if M <= 16 and N >= 4 and (T * N) % 4 == 0 and M not in (1, 2, 4): # the same over trials of any worker count, unless
-        per_load = 64 // (M // 4) if M % 4 == 0 else 0                 # whole rows per load fill their loads well
-        if per_load == 0 or (N * 100 < -(-N // per_load) * per_load * 85 and T * N * M >= 1 << 22):
+    if M <= 16 and rows_fit and N >= 4 and (T * N) % 4 == 0 and M not in (1, 2, 4):
+        per_load = 64 // (M // 4) if M % 4 == 0 else 0                 # the same over trials of any worker count, unless
+        if per_load == 0 or (N * 100 < -(-N // per_load) * per_load * 85 and T * N * M >= 1 << 22):   # whole rows per load fill their loads well
             return f"dc_scan_rows_kernel<{M}, true>"
-    if 19 <= M <= 63 and M % 4 != 0 and not longer and (N * M) % 4 == 0 and N >= 32:   # one row per lane
-        return "dc_scan_row_lane_kernel"
+    if 25 <= M <= 63 and M % 4 != 0 and not several and (N * M) % 4 == 0 and N >= 32 and two_blocks(1024 * M):
+        return f"dc_scan_row_lane_kernel<{8 if M <= 32 else 12 if M <= 48 else 16}>"          # one row per lane
     if M % 4 == 0 and (M <= 128 or M == 256):
         lanes = M // 4
         known = lanes if lanes & (lanes - 1) == 0 else 0              # one instantiation serves every other lane count
@@ -474,7 +480,7 @@ def main() -> int:
         "config": {"workload": f"{r.name}: T={r.T} N={r.N} M={r.M} K={K} comm={r.comm}us, {r.description}",
                    "grid": args.grid, "tensor_bytes": r.nbytes, "best_tau_us": int(taus[best]),
                    "best_thr_per_us": float(thr[best])},
-        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(r.M, args.grid, r.N, r.T), "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(r.M, args.grid, r.N, r.T, K), "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "traffic_source": traffic_source,
                      "kernel_ms": scan_avg_ms, "kernel_ms_min": float(np.min(scan_ms)),

@@ -102,9 +102,14 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     if (p.row_lane) p.lane_rows = true;
     p.chunk = p.K < DC_CHUNK_THRESHOLDS ? p.K : DC_CHUNK_THRESHOLDS;
     p.p2 = next_pow2_above(p.chunk);
-    // a plan whose staging areas and threshold tables would not fit a compute unit's LDS together (none of the row
-    // lengths built at present) goes to the kernel for any row length
-    if (p.lane_rows && dc::scan_lds_bytes(p) > DC_LDS_BYTES) { p.lane_rows = p.row_lane = false; p.span_rows = 0u; span = false; }
+    // these kernels need two blocks per compute unit to hide their LDS round trips (one block: 4.0-4.5 against 5.8-6.2
+    // TB/s of the other kernels): a plan whose staging areas and threshold tables leave room for one only (rows of 16,
+    // 17 or 63 elements with more than 511 thresholds in a pass, shorter ones with more) goes to the other kernels
+    if (p.lane_rows && dc::scan_lds_bytes(p) + 1024u > DC_LDS_BYTES / 2) {      // (+ the kernels' few static words)
+        p.lane_rows = p.row_lane = false;
+        p.span_rows = 0u;
+        span = false;
+    }
     p.vec4 = aligned && !p.lane_rows && vec4_shape(M);
     uint64_t upt;
     if (p.lane_rows) {

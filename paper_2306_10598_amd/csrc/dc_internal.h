@@ -62,8 +62,8 @@
 #define DC_MAX_TRIAL_BLOCKS 2048u      // upper bound of that pass's grid (sizes its per-block sums in the workspace)
 #define DC_MAX_STAT_WORKERS 2560u        // per-worker statistics keep 24 bytes per worker in LDS
 #define DC_ROWS_ODD_MAX 17u             // longest odd row of which a lane holds four in registers, and the longest row of
-#define DC_ROWS_EVEN_MAX 34u            // 4k+2 elements of which it holds two (the instantiations of dc_scan_rows_kernel)
-#define DC_ROW_LANE_MIN_M 19u           // shortest row of the kernel with one row per lane
+#define DC_ROWS_EVEN_MAX 30u            // 4k+2 elements of which it holds two (the instantiations of dc_scan_rows_kernel)
+#define DC_ROW_LANE_MIN_M 25u           // shortest row of the kernel with one row per lane
 #define DC_ROW_LANE_MAX_M 63u           // longest row of the kernel with one row per lane (16 KiB of LDS per wave)
 #define DC_ROW_LANE_MIN_N 32u           // fewer workers leave most of a wave's 64 rows empty
 #define DC_TAU_CLAMP 0x80000000u       // thresholds at or above 2^31 exceed every completion time
@@ -76,7 +76,11 @@
 namespace dc {
 
 // row lengths that kernel is built for
-inline bool lane_rows_length(uint32_t M) { return M <= 16u || ((M & 1u) && M <= DC_ROWS_ODD_MAX) || ((M & 3u) == 2u && M <= DC_ROWS_EVEN_MAX); }
+// (rows of 12 and 16 elements only over trials of few workers: with long delays in the data the kernel with whole rows
+// per load streams them 10-35 % faster, without them 5 % slower)
+inline bool lane_rows_length(uint32_t M) {
+    return (M <= 15u && M != 12u) || ((M & 1u) && M <= DC_ROWS_ODD_MAX) || ((M & 3u) == 2u && M <= DC_ROWS_EVEN_MAX);
+}
 // longer rows that are no multiple of 4: one row per lane, read word by word from the wave's copy of the chunk in LDS
 inline bool row_lane_length(uint32_t M) { return M >= DC_ROW_LANE_MIN_M && M <= DC_ROW_LANE_MAX_M && (M & 3u) != 0u && !lane_rows_length(M); }
 

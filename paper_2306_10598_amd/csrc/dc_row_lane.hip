@@ -1,5 +1,5 @@
-// dc_scan_row_lane_kernel: rows of 19 to 63 elements whose length is no multiple of 4 (apart from the lengths of
-// 4k+2 elements up to 34 that dc_scan_rows_kernel is built for), on 16-byte aligned trials with N*M a multiple of 4.
+// dc_scan_row_lane_kernel: rows of 19 to 63 elements whose length is no multiple of 4 (apart from 22, 26 and 30,
+// which dc_scan_rows_kernel is built for), on 16-byte aligned trials with N*M a multiple of 4.
 //
 // Neither of the other fast kernels suits such rows: a 16-byte load never holds whole rows, and a lane that keeps
 // four whole rows in registers needs a hundred of them and more.  Here a lane owns ONE row and keeps only its running
@@ -10,7 +10,7 @@
 // decrease along a row (latencies >= 0) the thresholds are met from the row's end backwards,
 // P[M-2-s] = P[M-1-s] - lat[M-1-s] with the latency read from LDS again, and the wave stops at the first step in
 // which no lane reaches the smallest threshold: one or two steps with the usual grids.  When most lanes are inside
-// the grid four steps go at once.  About three lane-operations per element instead of the 17 of the kernel for
+// the grid, or the walk goes on after two steps, four steps go at once.  About three lane-operations per element instead of the 17 of the kernel for
 // arbitrary rows.  NB = 16-byte vectors a lane holds for one chunk (at least M / 4).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -97,7 +97,9 @@ void dc_scan_row_lane_kernel(const int32_t* __restrict__ lat, uint64_t trial_str
                 while (s < M) {
                     const uint64_t reach = __ballot(mine && val >= g.tau0);
                     if (reach == 0) break;                                  // wave-uniform
-                    if (s + 4u <= M && (uint32_t)__popcll(reach) >= DC_DENSE_LANES) {
+                    // four steps at once when most lanes are inside the grid, and from the third step on in any case: a
+                    // walk that goes on after two steps is that of a few rows with long delays, which may go far
+                    if (s + 4u <= M && ((uint32_t)__popcll(reach) >= DC_DENSE_LANES || s >= 2u)) {
                         uint32_t x0 = 0u, x1 = 0u, x2 = 0u, x3 = 0u;
                         if (mine) { x0 = row[M - 1u - s]; x1 = row[M - 2u - s]; x2 = row[M - 3u - s]; x3 = row[M - 4u - s]; }
                         uint32_t v[4], b[4];

@@ -9,7 +9,7 @@ int rows_blocks_per_cu_long(const Plan& p, size_t lds) {
     hipError_t e = hipErrorInvalidValue;
     switch (p.M) {
 #define DC_ROWS_CASE(m) case m: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dc_scan_rows_kernel<m, false>, DC_SCAN_THREADS, lds); break;
-        DC_ROWS_CASE(13) DC_ROWS_CASE(14) DC_ROWS_CASE(15) DC_ROWS_CASE(16) DC_ROWS_CASE(17) DC_ROWS_CASE(18) DC_ROWS_CASE(22) DC_ROWS_CASE(26) DC_ROWS_CASE(30) DC_ROWS_CASE(34)
+        DC_ROWS_CASE(13) DC_ROWS_CASE(14) DC_ROWS_CASE(15) DC_ROWS_CASE(16) DC_ROWS_CASE(17) DC_ROWS_CASE(18) DC_ROWS_CASE(22) DC_ROWS_CASE(26) DC_ROWS_CASE(30)
 #undef DC_ROWS_CASE
         default: break;
     }
@@ -20,7 +20,7 @@ void launch_rows_scan_long(const Plan& p, const int32_t* lat, const uint32_t* ta
                       uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
     switch (p.M) {
 #define DC_ROWS_CASE(m) case m: launch_rows<m>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
-        DC_ROWS_CASE(13) DC_ROWS_CASE(14) DC_ROWS_CASE(15) DC_ROWS_CASE(16) DC_ROWS_CASE(17) DC_ROWS_CASE(18) DC_ROWS_CASE(22) DC_ROWS_CASE(26) DC_ROWS_CASE(30) DC_ROWS_CASE(34)
+        DC_ROWS_CASE(13) DC_ROWS_CASE(14) DC_ROWS_CASE(15) DC_ROWS_CASE(16) DC_ROWS_CASE(17) DC_ROWS_CASE(18) DC_ROWS_CASE(22) DC_ROWS_CASE(26) DC_ROWS_CASE(30)
 #undef DC_ROWS_CASE
         default: break;                             // make_plan sets lane_rows for these row lengths only
     }
