@@ -108,9 +108,10 @@ __device__ __forceinline__ void rows_chunk(WaveState& st, u32x4 (&x)[LaneRows<M>
         for (int r = 0; r < R; ++r) { val[r] = e[r * M + M - 1 - s]; high = umax(high, val[r]); }
         const uint64_t reach = __ballot(high >= g.tau0);
         if (reach == 0) break;                                      // wave-uniform
-        if (s + 1 < M && s < S::PAIRED_STEPS && (uint32_t)__popcll(reach) >= DC_DENSE_LANES) {
-            // most lanes are inside the grid, so the next step would very likely run as well: both at once, twice as
-            // many independent searches in flight (completion times below the grid find bin 0 and count nowhere)
+        if (s + 1 < M && s < S::PAIRED_STEPS && ((uint32_t)__popcll(reach) >= DC_DENSE_LANES || s >= 2)) {
+            // most lanes are inside the grid, so the next step would very likely run as well -- or the walk goes on
+            // after two steps, which is that of a few rows with long delays and may go far: both steps at once, twice
+            // as many independent searches in flight (completion times below the grid find bin 0 and count nowhere)
 #pragma unroll
             for (int r = 0; r < R; ++r) val[R + r] = e[r * M + M - 1 - (s + 1 < M ? s + 1 : s)];
             bins_of<2 * R>(g, val, b);
