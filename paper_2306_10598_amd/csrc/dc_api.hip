@@ -136,12 +136,28 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
         p.per_unit = M >= 128 ? (uint32_t)(32 / rows_per_load < 16 ? 16 : 32 / rows_per_load) : 64u;
 #endif
         upt = (loads_per_trial + p.per_unit - 1) / p.per_unit;
+        // Small trials (8 workers of 32 accumulations are one load): a unit per trial would leave a wave a load or
+        // two at a time and a maximum to reduce after each (2.0-2.8 TB/s on 4.3 GB).  When the trials follow each
+        // other without a gap and each is a whole number of loads, a unit is a run of whole trials instead.
+        // (As many trials per unit as fill a unit, but no more than leave every wave of the largest grid a unit: 82 MB
+        // of 8 KiB trials are over sooner with a unit per trial.)
+        if (p.stride == (uint64_t)N * (uint64_t)M && (uint64_t)N % rows_per_load == 0) {
+            uint64_t several = p.per_unit / loads_per_trial;
+            const uint64_t cap = (uint64_t)T / ((uint64_t)DC_SCAN_WAVES * DC_MAX_SCAN_BLOCKS);
+            if (several > cap) several = cap;
+            if (several >= 2) {
+                p.trials_per_unit = (uint32_t)several;
+                upt = 1;
+            }
+        }
     } else {
         const uint64_t rows = flat_rows_per_unit(N, M);
         p.per_unit = (uint32_t)rows;
         upt = ((uint64_t)N + rows - 1) / rows;
     }
-    const uint64_t units = span ? upt : (uint64_t)T * upt;
+    const uint64_t units = span ? upt
+                         : p.trials_per_unit ? ((uint64_t)T + p.trials_per_unit - 1) / p.trials_per_unit
+                                             : (uint64_t)T * upt;
     if (units >= ((uint64_t)1 << 31)) return false;
     p.units_per_trial = (uint32_t)upt;
     p.units = (uint32_t)units;
@@ -157,7 +173,7 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     p.off_tau_u32 = off;    off += align256((size_t)K * 4);
     p.off_pos = off;        off += align256((size_t)K * 4);
     p.off_bins = off;       off += align256((size_t)3 * p.p2 * 8);
-    p.off_unit_max = off;   off += align256((size_t)(span && p.T > p.units ? p.T : p.units) * 4);   // or one word per trial
+    p.off_unit_max = off;   off += align256((size_t)((span || p.trials_per_unit) && p.T > p.units ? p.T : p.units) * 4);   // or one word per trial
     p.off_hist_part = off;  off += align256((size_t)p.grid * p.p2 * 4);
     p.bytes = off;
     *out = p;

@@ -283,10 +283,12 @@ __device__ __forceinline__ void completion_times(const u32x4 (&x)[U], uint32_t (
     }
 }
 
+// U loads of whole rows: completion times, the lane's running maximum, and the completion times that reach the
+// threshold grid on their way into the histogram.  incl[k] returns the completion time of the lane's last element
+// in load k.
 template <int L, int U>
-__device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U], uint4* queue, const GridView& g,
-                                              uint32_t lane, const RowShape& shape) {
-    uint32_t incl[U];
+__device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U], uint32_t (&incl)[U], uint4* queue,
+                                              const GridView& g, uint32_t lane, const RowShape& shape) {
     completion_times<L, U>(x, incl, lane, shape);
     bool active[U];
     uint64_t mask[U];
@@ -313,6 +315,13 @@ __device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U]
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) enqueue_active(st, x[k], incl[k], active[k], mask[k], queue, g, lane);
+}
+
+template <int L, int U>
+__device__ __forceinline__ void process_loads(WaveState& st, const u32x4 (&x)[U], uint4* queue, const GridView& g,
+                                              uint32_t lane, const RowShape& shape) {
+    uint32_t incl[U];
+    process_loads<L, U>(st, x, incl, queue, g, lane, shape);
 }
 
 
@@ -397,6 +406,48 @@ __device__ __forceinline__ void stream_rows(WaveState& st, const u32x4* base, ui
         st.lane_max = umax(st.lane_max, incl);
         const bool active = valid && incl >= g.tau0;
         enqueue_active(st, x, incl, active, __ballot(active), queue, g, lane);
+    }
+}
+
+// Small trials of a contiguous tensor whose worker count is a multiple of the rows per load: a trial is
+// loads_per_trial whole loads and the next trial follows at once, so one wave streams `nloads` loads of several
+// consecutive trials as one run, eight in flight whatever trial they belong to, and keeps the running maximum per
+// trial: after a trial's last load the wave's maximum goes to trial_max[that trial] (counted from the run's first).
+template <int L>
+__device__ __forceinline__ void stream_small_trials(WaveState& st, const u32x4* base, uint32_t nloads,
+                                                    uint32_t loads_per_trial, uint32_t* trial_max, uint4* queue,
+                                                    const GridView& g, uint32_t lane, const RowShape& shape) {
+    constexpr int U = DC_SCAN_UNROLL;
+    const uint64_t stride = L ? 64u : shape.active;   // 16-byte vectors per load
+    uint32_t in_trial = 0u, t = 0u;                    // loads of the current trial so far; its number (wave-uniform)
+    uint32_t cur = 0u;                                 // the lane's maximum inside the current trial
+    uint32_t i = 0;
+    for (; i + U <= nloads; i += U) {
+        u32x4 x[U];
+        uint32_t incl[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) x[k] = load_rows<L>(base + (uint64_t)(i + k) * stride, shape);
+        process_loads<L, U>(st, x, incl, queue, g, lane, shape);
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            cur = umax(cur, incl[k]);
+            if (++in_trial == loads_per_trial) {
+                const uint32_t m = wave_max(cur);
+                if (lane == 0) trial_max[t] = m;
+                ++t; in_trial = 0u; cur = 0u;
+            }
+        }
+    }
+    for (; i < nloads; ++i) {
+        const u32x4 x[1] = {load_rows<L>(base + (uint64_t)i * stride, shape)};
+        uint32_t incl[1];
+        process_loads<L, 1>(st, x, incl, queue, g, lane, shape);
+        cur = umax(cur, incl[0]);
+        if (++in_trial == loads_per_trial) {
+            const uint32_t m = wave_max(cur);
+            if (lane == 0) trial_max[t] = m;
+            ++t; in_trial = 0u; cur = 0u;
+        }
     }
 }
 

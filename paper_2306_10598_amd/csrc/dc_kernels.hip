@@ -156,7 +156,8 @@ __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride, uint32_t N, uint32_t units, uint32_t units_per_trial,
                          uint32_t run, uint32_t loads_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
                          uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
-                         uint32_t* __restrict__ status, uint32_t max_latency, uint32_t lanes_per_row) {
+                         uint32_t* __restrict__ status, uint32_t max_latency, uint32_t lanes_per_row, uint32_t T,
+                         uint32_t trials_per_unit) {
     extern __shared__ __align__(16) unsigned char smem[];
     if (!launch_is_chosen<SHAPE>(status)) return;
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
@@ -179,7 +180,15 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride,
     for (uint32_t r = blockIdx.x; r < ur.padded; r += gridDim.x)
     for (uint32_t round = 0; round < ur.rounds; ++round) {
         const uint32_t u = r < ur.runs ? r * run + round * DC_SCAN_WAVES + wave : units;
-        if (u < units) {
+        if (u < units && trials_per_unit > 1u) {
+            // small trials (contiguous tensor, N a multiple of R): the unit is a run of whole trials, unit_max holds
+            // one maximum per trial
+            const uint32_t t0 = u * trials_per_unit;
+            const uint32_t trials = T - t0 < trials_per_unit ? T - t0 : trials_per_unit;
+            const uint32_t loads_per_trial = N / R;
+            const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t0 * trial_stride) + lane;
+            stream_small_trials<L>(st, base, trials * loads_per_trial, loads_per_trial, unit_max + t0, queue, g, lane, shape);
+        } else if (u < units) {
             const uint32_t t = u / units_per_trial;
             const uint32_t j = u - t * units_per_trial;
             const uint32_t row0 = j * loads_per_unit * R;
@@ -511,16 +520,16 @@ static void launch_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_c
         if constexpr (L == 8 || L == 16 || L == 32 || L == 64) {
             hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 1>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
                                lat, p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max,
-                               hist_part, status, p.max_latency, p.M / 4);
+                               hist_part, status, p.max_latency, p.M / 4, p.T, p.trials_per_unit);
             hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 2>), dim3(p.grid_wide), dim3(DC_SCAN_THREADS), scan_lds_bytes(p),
                                stream, lat, p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2,
-                               unit_max, hist_part, status, p.max_latency, p.M / 4);
+                               unit_max, hist_part, status, p.max_latency, p.M / 4, p.T, p.trials_per_unit);
             return;
         }
     }
     hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 0>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
                        p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max, hist_part,
-                       status, p.max_latency, p.M / 4);
+                       status, p.max_latency, p.M / 4, p.T, p.trials_per_unit);
 }
 
 template <int MS>

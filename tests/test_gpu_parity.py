@@ -226,6 +226,38 @@ def test_short_rows_of_few_workers(M, N, dev):
         assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, taus[:4])
 
 
+@pytest.mark.parametrize("loads", [1, 2, 3, 5, 8, 16])
+@pytest.mark.parametrize("M", [4, 8, 16, 20, 32, 48, 64, 100, 128, 256])
+def test_small_trials_streamed_several_per_unit(M, loads, dev):
+    """Trials of a few KiB on a contiguous tensor whose worker count is a whole number of 1 KiB loads: a wave streams
+    several consecutive trials as one run and keeps a maximum per trial.  Trial counts that leave the last unit short,
+    a trial whose maximum is its first worker's and one whose maximum is its last worker's next to trials of small
+    values, a trial of zeros, narrow and all-covering grids; the same tensor through a worker range (trials apart)."""
+    rng = np.random.default_rng(1000 * M + loads)
+    rows_per_load = 64 // (M // 4)
+    N = loads * rows_per_load
+    T = int(rng.integers(200, 400)) | 1
+    top = min((2**31 - 1) // M, 5000)
+    lat = rng.integers(0, top + 1, size=(T, N, M), dtype=np.int32)
+    lat[::3] //= 3                                          # neighbouring trials with different maxima
+    lat[1, 0, :] = top
+    lat[2, N - 1, :] = top
+    lat[T - 1, N - 1, :] = top
+    lat[5] = 0
+    totals = lat.sum(axis=2, dtype=np.int64)
+    narrow = np.quantile(totals, np.linspace(0.6, 1.0, 33)).astype(np.int64)
+    wide = np.concatenate([[0, 0, 1], rng.integers(0, int(totals.max()) + 50, size=60), [int(totals.max())] * 2, [BIG]])
+    lat_dev = to_dev(lat, dev)
+    for taus in (narrow, wide):
+        step, done = dc.dc_simulate(lat_dev, taus, 9)
+        ref = oracle.simulate(lat, taus, 9, "literal")
+        assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, T, taus[:4])
+    if N >= 2:
+        step, done = dc.dc_simulate(lat_dev, narrow, 2, workers=(0, N // 2))
+        ref = oracle.simulate(np.ascontiguousarray(lat[:, :N // 2]), narrow, 2, "literal")
+        assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, T)
+
+
 @pytest.mark.parametrize("N", [32, 36, 64, 100, 256, 1000, 2052])
 @pytest.mark.parametrize("M", [25, 27, 29, 31, 33, 34, 35, 38, 42, 45, 47, 49, 50, 55, 62, 63])
 def test_rows_of_a_few_dozen_elements_one_per_lane(M, N, dev):
