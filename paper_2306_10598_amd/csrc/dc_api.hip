@@ -127,8 +127,8 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
         p.per_unit = (uint32_t)((chunks + pieces - 1) / pieces);
         upt = (chunks + p.per_unit - 1) / p.per_unit;
     } else if (p.vec4) {
-        const uint64_t rows_per_load = 64 / (M / 4);
-        const uint64_t loads_per_trial = ((uint64_t)N + rows_per_load - 1) / rows_per_load;
+        uint64_t rows_per_load = 64 / (M / 4);
+        uint64_t loads_per_trial = ((uint64_t)N + rows_per_load - 1) / rows_per_load;
 #ifdef DC_UNIT_LOADS
         p.per_unit = DC_UNIT_LOADS;
 #else
@@ -141,7 +141,23 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
         // other without a gap and each is a whole number of loads, a unit is a run of whole trials instead.
         // (As many trials per unit as fill a unit, but no more than leave every wave of the largest grid a unit: 82 MB
         // of 8 KiB trials are over sooner with a unit per trial.)
-        if (p.stride == (uint64_t)N * (uint64_t)M && (uint64_t)N % rows_per_load == 0) {
+        // A worker count that is no whole number of loads (8 workers of 20 accumulations: 12 rows fit a load) can still
+        // be one of shorter loads: the largest divisor of N below what fits, if it keeps half of the lanes busy or
+        // holds the whole trial.
+        const bool contiguous = p.stride == (uint64_t)N * (uint64_t)M;
+        if (contiguous && M < 128 && (uint64_t)N % rows_per_load != 0) {
+            uint64_t r = rows_per_load < (uint64_t)N ? rows_per_load : (uint64_t)N;
+            while (r > 1 && (uint64_t)N % r) --r;
+            const uint64_t loads = (uint64_t)N / r;
+            if ((r * (uint64_t)(M / 4) >= 32 || r == (uint64_t)N) && 2 * loads <= p.per_unit &&
+                (uint64_t)T / ((uint64_t)DC_SCAN_WAVES * DC_MAX_SCAN_BLOCKS) >= 2) {
+                p.rows_per_load = (uint32_t)r;
+                rows_per_load = r;
+                loads_per_trial = loads;
+                upt = (loads_per_trial + p.per_unit - 1) / p.per_unit;
+            }
+        }
+        if (contiguous && (uint64_t)N % rows_per_load == 0) {
             uint64_t several = p.per_unit / loads_per_trial;
             const uint64_t cap = (uint64_t)T / ((uint64_t)DC_SCAN_WAVES * DC_MAX_SCAN_BLOCKS);
             if (several > cap) several = cap;
@@ -313,6 +329,7 @@ size_t g_resident_used = 0, g_resident_next = 0;
 // them from 1 GiB on and run tensors below that with one launch of 4 blocks per compute unit.
 bool two_launch_shapes(const dc::Plan& p, bool trial) {
     if (!p.vec4 || p.wave_trials) return false;
+    if (p.rows_per_load) return false;               // those plans run the instantiation for any row length, built for one shape
     return p.M >= 128 || (!trial && (p.M == 32 || p.M == 64) && p.elements >= ((uint64_t)1 << 28));
 }
 
@@ -335,7 +352,7 @@ uint32_t dense_blocks_per_cu(const dc::Plan& p) { return p.M >= 128 ? DC_DENSE_B
 // per load, else which of the kernels for arbitrary rows (built for rows of 1, 2, 3 elements, or for any longer row).
 uint32_t variant_of(const dc::Plan& p) {
     if (p.wave_trials) return 0x20000u + p.M;
-    if (p.vec4) return p.M;
+    if (p.vec4) return p.rows_per_load ? 0x40000u + p.M : p.M;
     if (p.lane_rows) return 0x10000u + p.M;
     return p.M < 4 ? p.M : 4u;
 }

@@ -70,11 +70,12 @@ struct RowShape {
     bool ok;             // this lane takes part
 };
 
+// rows_per_load (L = 0 only): fewer whole rows per load than fit, 0 = as many as fit
 template <int L>
-__device__ __forceinline__ RowShape row_shape(uint32_t lane, uint32_t lanes_per_row) {
+__device__ __forceinline__ RowShape row_shape(uint32_t lane, uint32_t lanes_per_row, uint32_t rows_per_load = 0u) {
     RowShape r;
     r.lanes = L ? (uint32_t)L : lanes_per_row;
-    r.rows = 64u / r.lanes;
+    r.rows = (L == 0 && rows_per_load) ? rows_per_load : 64u / r.lanes;
     r.active = r.rows * r.lanes;
     r.pos = lane % r.lanes;
     r.row = lane / r.lanes;

@@ -109,6 +109,8 @@ struct Plan {
     bool wave_trials;           // per-iteration pass: every wave owns a trial (small trials of a contiguous tensor, K <= 511)
     uint32_t span_rows;         // lane_rows with few workers per trial on a contiguous tensor: N, and the units ignore the
                                 // trials (unit_max then holds one maximum per trial); 0 otherwise
+    uint32_t rows_per_load;     // vec4: whole rows per 1 KiB load when fewer than fit are taken, so that a small trial is a
+                                // whole number of loads (8 workers of 20 accumulations: 8 rows of the 12 that fit); else 0
     uint32_t trials_per_unit;   // vec4 with small trials on a contiguous tensor whose N is a multiple of the rows per load:
                                 // a unit is this many whole trials and unit_max holds one maximum per trial; else 0
     uint32_t per_unit;          // vec4: loads (1 KiB, 64/L rows) per unit; lane_rows: chunks per unit; otherwise rows per unit

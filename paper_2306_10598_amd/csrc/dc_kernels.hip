@@ -157,14 +157,14 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride,
                          uint32_t run, uint32_t loads_per_unit, const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
                          uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
                          uint32_t* __restrict__ status, uint32_t max_latency, uint32_t lanes_per_row, uint32_t T,
-                         uint32_t trials_per_unit) {
+                         uint32_t trials_per_unit, uint32_t rows_per_load) {
     extern __shared__ __align__(16) unsigned char smem[];
     if (!launch_is_chosen<SHAPE>(status)) return;
     uint4* queue_all = reinterpret_cast<uint4*>(smem);                                  // [waves][QUEUE_ITEMS]
     const GridView g = stage_grid(reinterpret_cast<uint32_t*>(queue_all + DC_SCAN_WAVES * QUEUE_ITEMS), tau_chunk, kc, p2);
 
     const uint32_t lane = threadIdx.x & 63u;
-    const RowShape shape = row_shape<L>(lane, lanes_per_row);
+    const RowShape shape = row_shape<L>(lane, lanes_per_row, rows_per_load);
     const uint32_t R = shape.rows;                 // rows per load
     const uint32_t M = 4 * shape.lanes;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction
@@ -501,7 +501,7 @@ int scan_blocks_per_cu(const Plan& p) {
         }
         return e == hipSuccess ? n : 0;
     }
-    switch (p.M / 4) {
+    switch (p.rows_per_load ? 0u : p.M / 4) {     // fewer rows per load than fit: the instantiation for any row length
         case 1:  return resident_vec4<1>(lds);
         case 2:  return resident_vec4<2>(lds);
         case 4:  return resident_vec4<4>(lds);
@@ -520,16 +520,16 @@ static void launch_vec4(const Plan& p, const int32_t* lat, const uint32_t* tau_c
         if constexpr (L == 8 || L == 16 || L == 32 || L == 64) {
             hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 1>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream,
                                lat, p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max,
-                               hist_part, status, p.max_latency, p.M / 4, p.T, p.trials_per_unit);
+                               hist_part, status, p.max_latency, p.M / 4, p.T, p.trials_per_unit, p.rows_per_load);
             hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 2>), dim3(p.grid_wide), dim3(DC_SCAN_THREADS), scan_lds_bytes(p),
                                stream, lat, p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2,
-                               unit_max, hist_part, status, p.max_latency, p.M / 4, p.T, p.trials_per_unit);
+                               unit_max, hist_part, status, p.max_latency, p.M / 4, p.T, p.trials_per_unit, p.rows_per_load);
             return;
         }
     }
     hipLaunchKernelGGL((dc_scan_vec4_kernel<L, 0>), dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat,
                        p.stride, p.N, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max, hist_part,
-                       status, p.max_latency, p.M / 4, p.T, p.trials_per_unit);
+                       status, p.max_latency, p.M / 4, p.T, p.trials_per_unit, p.rows_per_load);
 }
 
 template <int MS>
@@ -553,7 +553,7 @@ void launch_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, u
         }
         return;
     }
-    switch (p.M / 4) {
+    switch (p.rows_per_load ? 0u : p.M / 4) {
         case 1:  launch_vec4<1>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
         case 2:  launch_vec4<2>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;
         case 4:  launch_vec4<4>(p, lat, tau_chunk, kc, unit_max, hist_part, status, stream); break;

@@ -226,17 +226,18 @@ def test_short_rows_of_few_workers(M, N, dev):
         assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, taus[:4])
 
 
-@pytest.mark.parametrize("loads", [1, 2, 3, 5, 8, 16])
-@pytest.mark.parametrize("M", [4, 8, 16, 20, 32, 48, 64, 100, 128, 256])
-def test_small_trials_streamed_several_per_unit(M, loads, dev):
-    """Trials of a few KiB on a contiguous tensor whose worker count is a whole number of 1 KiB loads: a wave streams
-    several consecutive trials as one run and keeps a maximum per trial.  Trial counts that leave the last unit short,
-    a trial whose maximum is its first worker's and one whose maximum is its last worker's next to trials of small
-    values, a trial of zeros, narrow and all-covering grids; the same tensor through a worker range (trials apart)."""
-    rng = np.random.default_rng(1000 * M + loads)
-    rows_per_load = 64 // (M // 4)
-    N = loads * rows_per_load
-    T = int(rng.integers(200, 400)) | 1
+@pytest.mark.parametrize("M,N", [(4, 64), (16, 16), (16, 48), (20, 12), (20, 36), (32, 8), (32, 24), (64, 4), (64, 12),
+                                 (100, 2), (100, 6), (128, 2), (128, 8), (256, 1), (256, 4),          # whole loads per trial
+                                 (20, 8), (20, 16), (24, 8), (28, 8), (32, 4), (36, 8), (44, 12), (48, 8), (64, 2), (64, 6),
+                                 (20, 4), (24, 4), (36, 32), (20, 64), (20, 100)])
+def test_small_trials_streamed_several_per_unit(M, N, dev):
+    """Many trials of a few KiB on a contiguous tensor: a wave streams several consecutive trials as one run and keeps
+    a maximum per trial.  Worker counts that are a whole number of 1 KiB loads, and worker counts that are not (a load
+    then holds fewer rows than fit: 8 of 20 elements instead of 12).  A trial count that leaves the last unit short,
+    trials whose maximum is their first or their last worker's next to trials of small values, a trial of zeros,
+    narrow and all-covering grids; the same tensor through a worker range (trials apart: a unit per trial)."""
+    rng = np.random.default_rng(1000 * M + N)
+    T = 2 * 8192 * int(rng.integers(1, 3)) + int(rng.integers(1, 300))       # enough trials for units of several
     top = min((2**31 - 1) // M, 5000)
     lat = rng.integers(0, top + 1, size=(T, N, M), dtype=np.int32)
     lat[::3] //= 3                                          # neighbouring trials with different maxima
@@ -250,11 +251,11 @@ def test_small_trials_streamed_several_per_unit(M, loads, dev):
     lat_dev = to_dev(lat, dev)
     for taus in (narrow, wide):
         step, done = dc.dc_simulate(lat_dev, taus, 9)
-        ref = oracle.simulate(lat, taus, 9, "literal")
+        ref = oracle.simulate(lat, taus, 9, "sorted")
         assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, T, taus[:4])
     if N >= 2:
         step, done = dc.dc_simulate(lat_dev, narrow, 2, workers=(0, N // 2))
-        ref = oracle.simulate(np.ascontiguousarray(lat[:, :N // 2]), narrow, 2, "literal")
+        ref = oracle.simulate(np.ascontiguousarray(lat[:, :N // 2]), narrow, 2, "sorted")
         assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, T)
 
 
