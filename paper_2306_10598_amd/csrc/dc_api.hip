@@ -96,7 +96,7 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
         span = N * 100 < loads * rows_per_load * 85 && p.elements >= ((uint64_t)1 << 22);   // (below 16 MB either takes 8-9 us)
     }
     if (span) { p.lane_rows = true; p.span_rows = (uint32_t)N; }
-    // rows of 19 to 63 elements that are no multiple of 4 (and not of that kernel's lengths): one row per lane, chunks of 64 rows
+    // rows of 25 to 63 elements that are no multiple of 4 (and not of that kernel's lengths): one row per lane, chunks of 64 rows
     p.row_lane = aligned && !p.lane_rows && dc::row_lane_length((uint32_t)M) && (((uint64_t)N * (uint64_t)M) & 3u) == 0 &&
                  N >= (int64_t)DC_ROW_LANE_MIN_N;
     if (p.row_lane) p.lane_rows = true;

@@ -1,5 +1,5 @@
-// dc_scan_row_lane_kernel: rows of 19 to 63 elements whose length is no multiple of 4 (apart from 22, 26 and 30,
-// which dc_scan_rows_kernel is built for), on 16-byte aligned trials with N*M a multiple of 4.
+// dc_scan_row_lane_kernel: rows of 25 to 63 elements whose length is no multiple of 4 (apart from 26 and 30, which
+// dc_scan_rows_kernel is built for), on 16-byte aligned trials with N*M a multiple of 4.
 //
 // Neither of the other fast kernels suits such rows: a 16-byte load never holds whole rows, and a lane that keeps
 // four whole rows in registers needs a hundred of them and more.  Here a lane owns ONE row and keeps only its running

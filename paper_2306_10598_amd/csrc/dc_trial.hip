@@ -21,11 +21,29 @@ struct TrialShared {
     uint32_t* block_max;  // [1] the trial's largest worker total
 };
 
+// a / b for finite a >= 0 and b >= 1: the hardware reciprocal refined twice, the quotient corrected once.  Within an ulp
+// of the exact quotient at a quarter of the instructions of an IEEE division, which a trial's end pays per threshold
+// (small trials spend most of their time there).
+__device__ __forceinline__ double quotient(double a, double b) {
+    double r = __builtin_amdgcn_rcp(b);
+    r = __builtin_fma(__builtin_fma(-b, r, 1.0), r, r);
+    r = __builtin_fma(__builtin_fma(-b, r, 1.0), r, r);
+    const double q = a * r;
+    return __builtin_fma(__builtin_fma(-b, q, a), r, q);
+}
+
+// S_t(tau) = (Tmax + c) / (min(tau, Tmax) + c) * done / (N M)  (Algorithm 2, Appendix C.1): the iteration's speedup
+// at one threshold, from its step time without drops, its step time den with them, and its completed count.
+__device__ __forceinline__ double trial_speedup(long long step, long long den, double done, double per_element) {
+    return quotient((double)step, (double)den) * (done * per_element);
+}
+
 // After every wave has binned its share of trial t: prefix sums over the histogram, S_t per threshold.
 __device__ __forceinline__ void finish_trial(const GridView& g, const TrialShared& sh, uint32_t kc, uint32_t t,
                                              const long long* __restrict__ comm_per_trial, long long comm,
                                              double elements_per_trial, uint32_t* status) {
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const double per_element = 1.0 / elements_per_trial;
     __syncthreads();                                           // histogram and block_max complete
     const uint32_t tmax = *sh.block_max;
     const uint32_t per = (g.p2 + DC_SCAN_THREADS - 1) / DC_SCAN_THREADS;
@@ -55,7 +73,7 @@ __device__ __forceinline__ void finish_trial(const GridView& g, const TrialShare
         const long long den = capped + c;
         if (den <= 0) { atomicOr(status, DC_FLAG_ZERO_STEP); continue; }
         const double done = elements_per_trial - (double)not_done;
-        sh.acc[b] += (double)((long long)tmax + c) / (double)den * (done / elements_per_trial);
+        sh.acc[b] += trial_speedup((long long)tmax + c, den, done, per_element);
     }
     __syncthreads();                                           // everyone has read the histogram
     for (uint32_t i = threadIdx.x; i < g.p2; i += DC_SCAN_THREADS) g.hist[i] = 0u;
@@ -151,6 +169,7 @@ __device__ __forceinline__ void finish_wave_trial(const GridView& g, const WaveT
                                                   uint32_t tmax, const long long* __restrict__ comm_per_trial, long long comm,
                                                   double elements_per_trial, uint32_t lane, uint32_t* status) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");                          // the wave's histogram is complete
+    const double per_element = 1.0 / elements_per_trial;
     uint32_t mine = 0;
     for (uint32_t i = 0; i < wt.per; ++i) mine += (wt.b0 + i < g.p2) ? g.hist[wt.b0 + i] : 0u;
     const uint32_t incl = segmented_inclusive_scan<64>(mine, lane);
@@ -171,7 +190,7 @@ __device__ __forceinline__ void finish_wave_trial(const GridView& g, const WaveT
         const long long den = capped + c;
         if (den <= 0) { atomicOr(status, DC_FLAG_ZERO_STEP); continue; }
         const double done = elements_per_trial - (double)not_done;
-        wt.acc[b] += (double)((long long)tmax + c) / (double)den * (done / elements_per_trial);
+        wt.acc[b] += trial_speedup((long long)tmax + c, den, done, per_element);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");                          // cleared before the next trial counts
 }
@@ -208,12 +227,50 @@ void dc_trial_scan_wave_kernel(const int32_t* __restrict__ lat, uint32_t T, uint
     const double elements_per_trial = (double)N * (double)M;
 
     WaveState st{0u, 0u, 0u, 0u};
-    for (uint32_t t = blockIdx.x * DC_SCAN_WAVES + wave; t < T; t += gridDim.x * DC_SCAN_WAVES) {
-        st.lane_max = 0u;
-        const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * N * M) + lane;
-        stream_rows<L>(st, base, nfull, tail_rows, queue, g, lane, shape);
-        while (st.q_count) drain(st, queue, g, lane);
-        finish_wave_trial(g, wt, kc, t, wave_max(st.lane_max), comm_per_trial, comm, elements_per_trial, lane, status);
+    const uint32_t step = gridDim.x * DC_SCAN_WAVES;                                // from one of the wave's trials to its next
+    constexpr int U = DC_SCAN_UNROLL;
+    if (tail_rows == 0u && 2u * nfull <= (uint32_t)U) {
+        // Trials of one to four loads: the loads of the wave's next U / nfull trials are requested together (a trial at
+        // a time leaves one load in flight and a trial's end to wait for: 1.4 TB/s on 1 KiB trials), then the trials
+        // are binned and finished one after the other, in the same order as below.
+        const uint64_t stride = L ? 64u : shape.active;                             // 16-byte vectors per load
+        const uint32_t batch = (uint32_t)U / nfull * nfull;                         // loads per batch: whole trials
+        for (uint32_t t0 = blockIdx.x * DC_SCAN_WAVES + wave; t0 < T; t0 += step * ((uint32_t)U / nfull)) {
+            u32x4 x[U];
+            uint32_t tl = t0, jl = 0u;                                              // wave-uniform
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                x[k] = u32x4{0u, 0u, 0u, 0u};
+                if ((uint32_t)k < batch && tl < T) {
+                    x[k] = load_rows<L>(reinterpret_cast<const u32x4*>(lat + (uint64_t)tl * N * M) + lane + (uint64_t)jl * stride, shape);
+                    if (++jl == nfull) { jl = 0u; tl += step; }
+                }
+            }
+            uint32_t t = t0, j = 0u;
+            st.lane_max = 0u;
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                if ((uint32_t)k < batch && t < T) {
+                    const u32x4 one[1] = {x[k]};
+                    process_loads<L, 1>(st, one, queue, g, lane, shape);
+                    if (++j == nfull) {
+                        while (st.q_count) drain(st, queue, g, lane);
+                        finish_wave_trial(g, wt, kc, t, wave_max(st.lane_max), comm_per_trial, comm, elements_per_trial, lane, status);
+                        st.lane_max = 0u;
+                        j = 0u;
+                        t += step;
+                    }
+                }
+            }
+        }
+    } else {
+        for (uint32_t t = blockIdx.x * DC_SCAN_WAVES + wave; t < T; t += step) {
+            st.lane_max = 0u;
+            const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * N * M) + lane;
+            stream_rows<L>(st, base, nfull, tail_rows, queue, g, lane, shape);
+            while (st.q_count) drain(st, queue, g, lane);
+            finish_wave_trial(g, wt, kc, t, wave_max(st.lane_max), comm_per_trial, comm, elements_per_trial, lane, status);
+        }
     }
     report_range(st.check, max_latency, lane, status);
     write_wave_trial_sums(wt, p2, partial);

@@ -726,6 +726,30 @@ def test_per_step_speedup_small_trials(N, M, K, dev):
     assert np.allclose(got, oracle.per_step_speedup(lat, taus, 17, threads=8), rtol=SPEEDUP_RTOL, atol=0)
 
 
+@pytest.mark.parametrize("N,M,K", [(8, 32, 40), (16, 32, 33), (24, 32, 20), (32, 32, 25), (4, 256, 64), (3, 256, 30),
+                                   (64, 4, 30), (12, 20, 25), (2, 128, 50), (128, 8, 20)])
+def test_per_step_speedup_trials_of_a_few_loads(N, M, K, dev):
+    """Trials of one to four 1 KiB loads, many more than the grid has waves: a wave requests the loads of its next
+    few trials together and finishes the trials one after the other.  A trial count that leaves the last batch short,
+    a trial of zeros, one of the largest legal rows, per-iteration communication times, identical bits on a repeat."""
+    rng = np.random.default_rng(N * 1000 + M)
+    T = 8 * 8192 + int(rng.integers(5000, 9000))
+    top = min((2**31 - 1) // M, 5000)
+    lat = rng.integers(0, top + 1, size=(T, N, M), dtype=np.int32)
+    lat[3] = 0
+    lat[T - 1, N - 1, :] = (2**31 - 1) // M
+    totals = lat.sum(axis=2, dtype=np.int64)
+    taus = np.concatenate([[1, BIG], rng.integers(1, int(np.quantile(totals, 0.999)) + 50, size=K - 2)])
+    comm_t = rng.integers(1, 4000, size=T)
+    lat_dev = to_dev(lat, dev)
+    got = dc.dc_speedup_per_step(lat_dev, taus, 0, comm_t)
+    ref = oracle.per_step_speedup(lat, taus, comm_t, threads=8)
+    assert np.allclose(got, ref, rtol=1e-11, atol=0)
+    assert np.array_equal(got, dc.dc_speedup_per_step(lat_dev, taus, 0, comm_t))       # fixed summation order
+    got = dc.dc_speedup_per_step(lat_dev, taus, 17)
+    assert np.allclose(got, oracle.per_step_speedup(lat, taus, 17, threads=8), rtol=SPEEDUP_RTOL, atol=0)
+
+
 def test_per_step_speedup_many_trials_and_thresholds(dev):
     """More trials than blocks, more thresholds than one pass holds."""
     rng = np.random.default_rng(9)
