@@ -23,22 +23,28 @@ template <int L>
 __global__ __launch_bounds__(DC_SCAN_THREADS)
 void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride, uint32_t T, uint32_t N,
                                   unsigned long long* __restrict__ partial, uint32_t* __restrict__ status,
-                                  uint32_t max_latency, uint32_t lanes_per_row) {
+                                  uint32_t max_latency, uint32_t lanes_per_row, uint32_t trials_by_wave,
+                                  uint32_t rows_per_load) {
+    // trials_by_wave: a trial is fewer whole loads than the block has waves (8 workers of 32 accumulations are one), so
+    // every wave takes whole trials of its own, the block's trials w, w + 4, ..., and keeps accumulators of its own
+    // ([waves][3][N] in LDS, added up at the end); otherwise the waves share a trial's loads and one set of accumulators
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
-    for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) acc[i] = 0ull;
+    unsigned long long* acc_all = reinterpret_cast<unsigned long long*>(smem);
+    const uint32_t sets = trials_by_wave ? DC_SCAN_WAVES : 1u;
+    for (uint32_t i = threadIdx.x; i < sets * 3 * N; i += DC_SCAN_THREADS) acc_all[i] = 0ull;
     __syncthreads();
 
     constexpr int U = DC_SCAN_UNROLL;
     const uint32_t lane = threadIdx.x & 63u;
-    const RowShape shape = row_shape<L>(lane, lanes_per_row);
+    const RowShape shape = row_shape<L>(lane, lanes_per_row, rows_per_load);
     const uint32_t R = shape.rows, M = 4 * shape.lanes;
     const uint64_t stride = L ? 64u : shape.active;
     const bool row_end = shape.ok && shape.pos == shape.lanes - 1;      // this lane ends a row: it holds the total
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t nfull = N / R, tail_rows = N - nfull * R;
-    const uint32_t lo = (uint32_t)((uint64_t)nfull * wave / DC_SCAN_WAVES);
-    const uint32_t hi = (uint32_t)((uint64_t)nfull * (wave + 1) / DC_SCAN_WAVES);
+    const uint32_t lo = trials_by_wave ? 0u : (uint32_t)((uint64_t)nfull * wave / DC_SCAN_WAVES);
+    const uint32_t hi = trials_by_wave ? nfull : (uint32_t)((uint64_t)nfull * (wave + 1) / DC_SCAN_WAVES);
+    unsigned long long* acc = acc_all + (trials_by_wave ? wave * 3u * N : 0u);
     uint32_t check = 0u;
     const uint32_t len = hi - lo;                                   // the wave's loads per trial
     if (len >= 4u * (uint32_t)U) {
@@ -79,7 +85,11 @@ void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint64_t tria
         // over all of the block's trials are taken U at a time whatever the trial they belong to, which keeps as
         // many loads in flight as long trials do.  A worker's row is always the same lane's, so two items of a
         // batch that belong to one worker are added one after the other by that lane.
-        const uint32_t my_trials = blockIdx.x < T ? (T - blockIdx.x + gridDim.x - 1u) / gridDim.x : 0u;
+        const uint32_t block_trials = blockIdx.x < T ? (T - blockIdx.x + gridDim.x - 1u) / gridDim.x : 0u;
+        // the trials whose loads this wave takes: all of the block's, or every fourth from the wave's own number on
+        const uint32_t my_trials = !trials_by_wave ? block_trials
+                                 : block_trials > wave ? (block_trials - wave + DC_SCAN_WAVES - 1u) / DC_SCAN_WAVES : 0u;
+        const uint32_t first_trial = trials_by_wave ? wave : 0u, trial_step = trials_by_wave ? DC_SCAN_WAVES : 1u;
         const uint64_t items = (uint64_t)my_trials * len;
         uint32_t at_trial = 0u, at_load = 0u;                       // the next item: which of the block's trials, which load
         for (uint64_t k0 = 0; k0 < items; k0 += U) {
@@ -91,7 +101,7 @@ void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint64_t tria
                 x[k] = u32x4{0u, 0u, 0u, 0u};
                 load_of[k] = at_load;
                 if ((uint32_t)k < n) {
-                    const uint64_t t = (uint64_t)blockIdx.x + (uint64_t)at_trial * gridDim.x;
+                    const uint64_t t = (uint64_t)blockIdx.x + (uint64_t)(first_trial + at_trial * trial_step) * gridDim.x;
                     const u32x4* p = reinterpret_cast<const u32x4*>(lat + t * trial_stride + (uint64_t)(lo + at_load) * R * M) + lane;
                     x[k] = load_rows<L>(p, shape);
                     if (++at_load == len) { at_load = 0u; ++at_trial; }
@@ -120,7 +130,22 @@ void dc_worker_totals_vec4_kernel(const int32_t* __restrict__ lat, uint64_t tria
     report_range(check, max_latency, lane, status);
     __syncthreads();
     unsigned long long* out = partial + (uint64_t)blockIdx.x * 3 * N;
-    for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) out[i] = acc[i];
+    if (!trials_by_wave) {
+        for (uint32_t i = threadIdx.x; i < 3 * N; i += DC_SCAN_THREADS) out[i] = acc_all[i];
+        return;
+    }
+    for (uint32_t n = threadIdx.x; n < N; n += DC_SCAN_THREADS) {  // the waves' sums, the squares in 128 bits
+        unsigned long long sum = 0ull;
+        unsigned __int128 sq = 0;
+        for (uint32_t w = 0; w < DC_SCAN_WAVES; ++w) {
+            const unsigned long long* a = acc_all + w * 3u * N;
+            sum += a[n];
+            sq += ((unsigned __int128)a[2u * N + n] << 64) | a[N + n];
+        }
+        out[n] = sum;
+        out[N + n] = (unsigned long long)sq;
+        out[2u * N + n] = (unsigned long long)(sq >> 64);
+    }
 }
 
 // Any M >= 1, any 4-byte alignment: the flat pass; the lane that holds a row's last element holds its total.
@@ -232,9 +257,13 @@ namespace dc {
 
 template <int L>
 static void launch_worker_vec4(const Plan& p, const int32_t* lat, unsigned long long* partial, uint32_t* status,
-                               hipStream_t stream) {
-    hipLaunchKernelGGL(dc_worker_totals_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS), (size_t)p.N * 24, stream,
-                       lat, p.stride, p.T, p.N, partial, status, p.max_latency, p.M / 4);
+                               hipStream_t stream, uint32_t rows_override) {
+    // a trial of fewer whole loads than a block has waves: every wave takes whole trials (and accumulators) of its own
+    const uint32_t rows_per_load = rows_override ? rows_override : 64u / (p.M / 4u);
+    const uint32_t by_wave = (p.N % rows_per_load == 0u && p.N / rows_per_load < DC_SCAN_WAVES) ? 1u : 0u;
+    hipLaunchKernelGGL(dc_worker_totals_vec4_kernel<L>, dim3(p.grid), dim3(DC_SCAN_THREADS),
+                       (size_t)p.N * 24 * (by_wave ? DC_SCAN_WAVES : 1u), stream, lat, p.stride, p.T, p.N, partial, status,
+                       p.max_latency, p.M / 4, by_wave, rows_override);
 }
 
 // partial: [grid][3][N] u64; result: [3][N] u64 (sum, squares low, squares high per worker)
@@ -254,15 +283,25 @@ void launch_worker_totals(const Plan& p, const int32_t* lat, unsigned long long*
                                (size_t)p.N * 24, stream, lat, p.extent, p.stride, p.T, p.N, p.M, p.per_unit, partial, status,
                                p.max_latency);
     } else {
-        switch (p.M / 4) {
-            case 1:  launch_worker_vec4<1>(p, lat, partial, status, stream); break;
-            case 2:  launch_worker_vec4<2>(p, lat, partial, status, stream); break;
-            case 4:  launch_worker_vec4<4>(p, lat, partial, status, stream); break;
-            case 8:  launch_worker_vec4<8>(p, lat, partial, status, stream); break;
-            case 16: launch_worker_vec4<16>(p, lat, partial, status, stream); break;
-            case 32: launch_worker_vec4<32>(p, lat, partial, status, stream); break;
-            case 64: launch_worker_vec4<64>(p, lat, partial, status, stream); break;
-            default: launch_worker_vec4<0>(p, lat, partial, status, stream); break;
+        // A small trial whose worker count is no whole number of full loads is taken as shorter loads (a divisor of N
+        // rows each, if that keeps half of the lanes busy or holds the whole trial), so that no wave is left with a
+        // partial load per trial: the instantiation for any row length.
+        uint32_t rows_override = 0u;
+        const uint32_t fit = 64u / (p.M / 4u);
+        if (p.N % fit != 0u && p.N < 8u * fit) {
+            uint32_t r = fit < p.N ? fit : p.N;
+            while (r > 1u && p.N % r) --r;
+            if (r * (p.M / 4u) >= 32u || r == p.N) rows_override = r;
+        }
+        switch (rows_override ? 0u : p.M / 4) {
+            case 1:  launch_worker_vec4<1>(p, lat, partial, status, stream, 0u); break;
+            case 2:  launch_worker_vec4<2>(p, lat, partial, status, stream, 0u); break;
+            case 4:  launch_worker_vec4<4>(p, lat, partial, status, stream, 0u); break;
+            case 8:  launch_worker_vec4<8>(p, lat, partial, status, stream, 0u); break;
+            case 16: launch_worker_vec4<16>(p, lat, partial, status, stream, 0u); break;
+            case 32: launch_worker_vec4<32>(p, lat, partial, status, stream, 0u); break;
+            case 64: launch_worker_vec4<64>(p, lat, partial, status, stream, 0u); break;
+            default: launch_worker_vec4<0>(p, lat, partial, status, stream, rows_override); break;
         }
     }
     if (after) (void)hipEventRecord(after, stream);

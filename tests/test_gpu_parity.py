@@ -828,7 +828,12 @@ def test_moments_of_a_workload_and_errors(dev):
 
 @pytest.mark.parametrize("shape", [(30, 64, 32), (7, 200, 64), (3, 2048, 256), (5, 2047, 128), (40, 33, 12),
                                    (9, 10, 100), (6, 9, 300), (11, 5, 1), (4, 2560, 16), (11, 50, 7), (20, 100, 3),
-                                   (6, 170, 2), (4, 9, 257), (3, 2, 5000)])
+                                   (6, 170, 2), (4, 9, 257), (3, 2, 5000),
+                                   # trials of one to three whole loads (a wave takes whole trials), few and many trials
+                                   (3, 8, 32), (5000, 8, 32), (4099, 16, 32), (3001, 24, 32), (2500, 4, 64), (2222, 2, 128),
+                                   (2601, 12, 20), (2048, 3, 256), (1234, 64, 4), (700, 96, 8),
+                                   # worker counts that are no whole number of full loads: shorter loads
+                                   (3000, 32, 20), (2000, 8, 20), (1500, 16, 24), (1800, 4, 32), (900, 40, 36), (1100, 6, 64)])
 def test_worker_moments_are_exact(shape, dev):
     rng = np.random.default_rng(sum(shape))
     top = (2**31 - 1) // shape[2]
