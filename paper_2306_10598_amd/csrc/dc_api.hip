@@ -96,9 +96,15 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
         span = N * 100 < loads * rows_per_load * 85 && p.elements >= ((uint64_t)1 << 22);   // (below 16 MB either takes 8-9 us)
     }
     if (span) { p.lane_rows = true; p.span_rows = (uint32_t)N; }
-    // rows of 25 to 63 elements that are no multiple of 4 (and not of that kernel's lengths): one row per lane, chunks of 64 rows
-    p.row_lane = aligned && !p.lane_rows && dc::row_lane_length((uint32_t)M) && (((uint64_t)N * (uint64_t)M) & 3u) == 0 &&
-                 N >= (int64_t)DC_ROW_LANE_MIN_N;
+    // rows of 17 to 63 elements that are no multiple of 4 and that the kernel above does not take: one row per lane,
+    // chunks of 64 rows -- from 25 elements on, and shorter ones with fewer than 256 workers (where the kernel above is
+    // not available and the flat pass would take a unit per small trial: 3.5-5.7 against 5.4-6.6 TB/s at 64 and 128
+    // workers), when the trial's chunks are at least 85 % full (200 workers = 3 chunks and 8 rows: the flat pass wins)
+    const uint64_t row_chunks = ((uint64_t)N + 63) / 64;
+    p.row_lane = aligned && !p.lane_rows && dc::row_lane_length((uint32_t)M) &&
+                 (M >= (int64_t)DC_ROW_LANE_MIN_M_MANY || N < (int64_t)DC_LANE_ROWS_MIN_N) &&
+                 (((uint64_t)N * (uint64_t)M) & 3u) == 0 && N >= (int64_t)DC_ROW_LANE_MIN_N &&
+                 (uint64_t)N * 100 >= row_chunks * 64 * 85;
     if (p.row_lane) p.lane_rows = true;
     p.chunk = p.K < DC_CHUNK_THRESHOLDS ? p.K : DC_CHUNK_THRESHOLDS;
     p.p2 = next_pow2_above(p.chunk);
@@ -114,7 +120,7 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     uint64_t upt;
     if (p.lane_rows) {
         // chunks of whole rows; about DC_FLAT_UNIT_ELEMENTS elements per unit, the units of a trial of equal size
-        const uint64_t chunk_rows = dc::lane_rows_chunk_rows((uint32_t)M);
+        const uint64_t chunk_rows = dc::lane_rows_chunk_rows((uint32_t)M, p.row_lane);
         const uint64_t run_rows = span ? (uint64_t)T * (uint64_t)N : (uint64_t)N;
         const uint64_t chunks = (run_rows + chunk_rows - 1) / chunk_rows;
         uint64_t want = DC_FLAT_UNIT_ELEMENTS / (chunk_rows * (uint64_t)M);

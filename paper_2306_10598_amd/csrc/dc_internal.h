@@ -63,7 +63,8 @@
 #define DC_MAX_STAT_WORKERS 2560u        // per-worker statistics keep 24 bytes per worker in LDS
 #define DC_ROWS_ODD_MAX 17u             // longest odd row of which a lane holds four in registers, and the longest row of
 #define DC_ROWS_EVEN_MAX 30u            // 4k+2 elements of which it holds two (the instantiations of dc_scan_rows_kernel)
-#define DC_ROW_LANE_MIN_M 25u           // shortest row of the kernel with one row per lane
+#define DC_ROW_LANE_MIN_M 17u           // shortest row of the kernel with one row per lane ...
+#define DC_ROW_LANE_MIN_M_MANY 25u      // ... with 256 workers or more (shorter ones are kernel 3's or stream faster in the flat pass)
 #define DC_ROW_LANE_MAX_M 63u           // longest row of the kernel with one row per lane (16 KiB of LDS per wave)
 #define DC_ROW_LANE_MIN_N 32u           // fewer workers leave most of a wave's 64 rows empty
 #define DC_TAU_CLAMP 0x80000000u       // thresholds at or above 2^31 exceed every completion time
@@ -82,12 +83,12 @@ inline bool lane_rows_length(uint32_t M) {
     return (M <= 15u && M != 12u) || ((M & 1u) && M <= DC_ROWS_ODD_MAX) || ((M & 3u) == 2u && M <= DC_ROWS_EVEN_MAX);
 }
 // longer rows that are no multiple of 4: one row per lane, read word by word from the wave's copy of the chunk in LDS
-inline bool row_lane_length(uint32_t M) { return M >= DC_ROW_LANE_MIN_M && M <= DC_ROW_LANE_MAX_M && (M & 3u) != 0u && !lane_rows_length(M); }
+inline bool row_lane_length(uint32_t M) { return M >= DC_ROW_LANE_MIN_M && M <= DC_ROW_LANE_MAX_M && (M & 3u) != 0u; }
 
-// Rows that one wave of the kernel with whole rows per lane takes at a time (a chunk): a lane holds 16 rows of one
-// element, 8 of two, otherwise 4.
-inline uint32_t lane_rows_chunk_rows(uint32_t M) {
-    if (row_lane_length(M)) return 64u;                 // one row per lane
+// Rows that one wave of the kernels with whole rows per lane takes at a time (a chunk): a lane holds 16 rows of one
+// element, 8 of two, otherwise 4 (2 of the longer even rows); one_row: the kernel in which it holds one.
+inline uint32_t lane_rows_chunk_rows(uint32_t M, bool one_row) {
+    if (one_row) return 64u;
     return M == 1u ? 1024u : M == 2u ? 512u : (M > 16u && (M & 3u) == 2u) ? 128u : 256u;
 }
 // 16-byte vectors that a lane holds per chunk when they pass through LDS: its four rows, or two of the longer even rows

@@ -192,7 +192,7 @@ void dc_scan_vec4_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride,
             const uint32_t t = u / units_per_trial;
             const uint32_t j = u - t * units_per_trial;
             const uint32_t row0 = j * loads_per_unit * R;
-            const uint32_t rows_left = N - row0;
+            const uint32_t rows_left = row0 < N ? N - row0 : 0u;          // (a unit past the trial's end is empty)
             const uint32_t rows = rows_left < loads_per_unit * R ? rows_left : loads_per_unit * R;
             const uint32_t nfull = rows / R;
             const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)row0 * M) + lane;

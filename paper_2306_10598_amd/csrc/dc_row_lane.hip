@@ -1,5 +1,5 @@
-// dc_scan_row_lane_kernel: rows of 25 to 63 elements whose length is no multiple of 4 (apart from 26 and 30, which
-// dc_scan_rows_kernel is built for), on 16-byte aligned trials with N*M a multiple of 4.
+// dc_scan_row_lane_kernel: rows of 17 to 63 elements whose length is no multiple of 4 (where dc_scan_rows_kernel does
+// not take them), on 16-byte aligned trials with N*M a multiple of 4.
 //
 // Neither of the other fast kernels suits such rows: a 16-byte load never holds whole rows, and a lane that keeps
 // four whole rows in registers needs a hundred of them and more.  Here a lane owns ONE row and keeps only its running
@@ -54,7 +54,8 @@ void dc_scan_row_lane_kernel(const int32_t* __restrict__ lat, uint64_t trial_str
             const uint32_t t = u / units_per_trial;
             const uint32_t j = u - t * units_per_trial;
             const uint32_t row0 = j * chunks_per_unit * 64u;
-            const uint32_t rows = (N - row0) < chunks_per_unit * 64u ? (N - row0) : chunks_per_unit * 64u;
+            const uint32_t rows_left = row0 < N ? N - row0 : 0u;          // (a unit past the trial's end is empty)
+            const uint32_t rows = rows_left < chunks_per_unit * 64u ? rows_left : chunks_per_unit * 64u;
             // row0 is a multiple of 64 and the trial starts on a 16-byte boundary, so every chunk does
             const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)row0 * M);
             uint32_t lane_max = 0u;

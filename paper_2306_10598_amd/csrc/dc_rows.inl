@@ -178,7 +178,8 @@ void dc_scan_rows_kernel(const int32_t* __restrict__ lat, uint64_t trial_stride,
             const uint32_t t = u / units_per_trial;
             const uint32_t j = u - t * units_per_trial;
             const uint32_t row0 = j * chunks_per_unit * CHUNK_ROWS;
-            const uint32_t rows = (N - row0) < chunks_per_unit * CHUNK_ROWS ? (N - row0) : chunks_per_unit * CHUNK_ROWS;
+            const uint32_t rows_left = row0 < N ? N - row0 : 0u;          // (a unit past the trial's end is empty)
+            const uint32_t rows = rows_left < chunks_per_unit * CHUNK_ROWS ? rows_left : chunks_per_unit * CHUNK_ROWS;
             const uint32_t nv = rows * (uint32_t)M / 4u;                                  // whole vectors: rows is a multiple of R
             const u32x4* base = reinterpret_cast<const u32x4*>(lat + (uint64_t)t * trial_stride + (uint64_t)row0 * M);
             st.lane_max = 0u;

@@ -259,10 +259,10 @@ def test_small_trials_streamed_several_per_unit(M, N, dev):
         assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, T)
 
 
-@pytest.mark.parametrize("N", [32, 36, 64, 100, 256, 1000, 2052])
-@pytest.mark.parametrize("M", [25, 27, 29, 31, 33, 34, 35, 38, 42, 45, 47, 49, 50, 55, 62, 63])
+@pytest.mark.parametrize("N", [32, 36, 64, 100, 120, 128, 192, 256, 1000, 2052])
+@pytest.mark.parametrize("M", [17, 18, 21, 22, 25, 26, 27, 29, 30, 31, 33, 34, 35, 38, 42, 45, 47, 49, 50, 55, 62, 63])
 def test_rows_of_a_few_dozen_elements_one_per_lane(M, N, dev):
-    """Rows of 25 to 63 elements that are no multiple of 4 (nor 26, 30), N*M a multiple of 4, at least 32 workers, aligned tensor:
+    """Rows of 25 to 63 elements that are no multiple of 4 (nor 26, 30), and from 17 on with fewer than 256 workers, N*M a multiple of 4, at least 32 workers, aligned tensor:
     the kernel in which a lane owns one row and reads it word by word from the wave's copy of the chunk.  Full and
     partial chunks of 64 rows, one and several units per trial, a narrow grid near the row totals, a grid over every
     completion time (with 0, repeats and values no completion time reaches), 700 thresholds (tables that leave the
