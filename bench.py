@@ -290,7 +290,7 @@ def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0, T: int = 0, K: in
     p2 = 4
     while p2 <= min(K, 4095):
         p2 *= 2
-    two_blocks = lambda stage_bytes: 16 * p2 + stage_bytes + 1024 <= 80 * 1024     # what two blocks per compute unit leave each
+    two_blocks = lambda stage_bytes: 16 * p2 + stage_bytes + 1024 <= (80 if p2 <= 1024 else 160) * 1024   # two blocks per compute unit, one with large tables
     per_lane = M // 2 if M > 16 and M % 4 == 2 else M                  # 16-byte vectors of a lane's rows
     rows_fit = two_blocks(0 if 4 % M == 0 else 4 * 64 * (per_lane | 1) * 16)
     several = (M <= 15 and M != 12) or M == 17 or (M % 4 == 2 and M <= 30)         # row lengths of which a lane holds several

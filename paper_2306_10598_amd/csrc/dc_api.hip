@@ -108,10 +108,13 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     if (p.row_lane) p.lane_rows = true;
     p.chunk = p.K < DC_CHUNK_THRESHOLDS ? p.K : DC_CHUNK_THRESHOLDS;
     p.p2 = next_pow2_above(p.chunk);
-    // these kernels need two blocks per compute unit to hide their LDS round trips (one block: 4.0-4.5 against 5.8-6.2
-    // TB/s of the other kernels): a plan whose staging areas and threshold tables leave room for one only (rows of 16,
-    // 17 or 63 elements with more than 511 thresholds in a pass, shorter ones with more) goes to the other kernels
-    if (p.lane_rows && dc::scan_lds_bytes(p) + 1024u > DC_LDS_BYTES / 2) {      // (+ the kernels' few static words)
+    // These kernels need two blocks per compute unit to hide their LDS round trips (one block: 4.0-4.5 against 5.7-6.2
+    // TB/s of the other kernels with 512 thresholds): a plan whose staging areas and threshold tables leave room for
+    // one only (rows of 16 or 17 elements with 512 thresholds or more in a pass) goes to the other kernels -- as long as
+    // those still run many blocks themselves.  From 2048 table entries on (1024 thresholds in a pass) the tables alone
+    // take 32 KiB and more, the kernel for any row length is down to four blocks and fewer, and one block of these
+    // kernels is the faster choice again on thin-tailed data by 15-60 %, on heavy-tailed data level.
+    if (p.lane_rows && dc::scan_lds_bytes(p) + 1024u > (p.p2 <= 1024u ? DC_LDS_BYTES / 2 : DC_LDS_BYTES)) {   // (+ the kernels' few static words)
         p.lane_rows = p.row_lane = false;
         p.span_rows = 0u;
         span = false;
