@@ -6,7 +6,8 @@ dc_simulate_async (thresholds sorted, the streaming scan over lat, reductions, f
 copy of the 2*K result sums to the host, and dc_select_tau.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
-                  [--rows M] [--grid recipe|dense|upper-half] [--path sums|per-step|analytic|worker-moments]
+                  [--rows M] [--workers N] [--thresholds K] [--grid recipe|dense|upper-half]
+                  [--path sums|per-step|analytic|worker-moments]
 
 The result sums are written by the library's last kernel straight into pinned host memory (the output pointers of
 dc_simulate_async may be any memory the device can write), so a step has no separate copy.
@@ -306,7 +307,8 @@ def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0, T: int = 0, K: in
     if M % 4 == 0 and (M <= 128 or M == 256):
         lanes = M // 4
         known = lanes if lanes & (lanes - 1) == 0 else 0              # one instantiation serves every other lane count
-        shape = 0 if M not in (32, 64, 128, 256) else (1 if grid == "recipe" else 2)   # <L, 1> works on narrow grids, <L, 2> on dense ones
+        two = M in (128, 256) or (M in (32, 64) and T * N * M >= 1 << 28)   # two launch shapes; the smaller M only from 1 GiB on
+        shape = 0 if not two else (1 if grid == "recipe" else 2)     # <L, 1> works on narrow grids, <L, 2> on dense ones
         return f"{SCAN_KERNEL}<{known}, {shape}>"
     return f"dc_scan_flat_kernel<{M if M < 4 else 0}>"
 
@@ -405,6 +407,11 @@ def main() -> int:
     ap.add_argument("--rows", type=int, default=0,
                     help="run the workload with this many accumulations per worker instead of its own M, the number of "
                          "trials rescaled to keep the tensor's size (not a bench line: for timing other row lengths)")
+    ap.add_argument("--workers", type=int, default=0,
+                    help="run the workload with this many workers instead of its own N, the number of trials rescaled to "
+                         "keep the tensor's size (not a bench line: for timing small trials)")
+    ap.add_argument("--thresholds", type=int, default=0,
+                    help="run the workload with this many thresholds on its grid rule instead of its own K (not a bench line)")
     ap.add_argument("--grid", choices=("recipe", "dense", "upper-half"), default="recipe",
                     help="recipe: the workload's own threshold grid; dense: K thresholds from 0 to the largest worker total "
                          "(every completion time falls inside the grid); upper-half: from half the largest total to it "
@@ -441,6 +448,10 @@ def main() -> int:
     r = config(args.workload)
     if args.rows > 0 and args.rows != r.M:
         r = r.with_shape(T=max(1, r.T * r.M // args.rows), M=args.rows)
+    if args.workers > 0 and args.workers != r.N:
+        r = r.with_shape(T=max(1, r.T * r.N // args.workers), N=args.workers)
+    if args.thresholds > 0:
+        r = r.with_shape(K=args.thresholds)
 
     lat = device.generate(r)                                   # resident in HBM before timing starts
     taus = device.tau_grid(r, lat)
@@ -470,7 +481,7 @@ def main() -> int:
     scan_avg_ms = float(np.mean(scan_ms))
     algo_bytes = 4.0 * r.elements                              # every latency read once, nothing written back
     achieved = algo_bytes / (scan_avg_ms * 1e-3) / 1e9
-    plain = args.rows <= 0 and args.grid == "recipe"
+    plain = args.rows <= 0 and args.workers <= 0 and args.thresholds <= 0 and args.grid == "recipe"
     traffic, traffic_source = recorded_traffic(r.name) if plain else (None, "not the workload's own shape or grid")
     line = {
         "metric": METRIC, "value": evals / (wall / args.steps), "unit": "evals/s",
