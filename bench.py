@@ -301,8 +301,9 @@ def scan_kernel_name(M: int, grid: str = "recipe", N: int = 0, T: int = 0, K: in
         per_load = 64 // (M // 4) if M % 4 == 0 else 0                 # the same over trials of any worker count, unless
         if per_load == 0 or (N * 100 < -(-N // per_load) * per_load * 85 and T * N * M >= 1 << 22):   # whole rows per load fill their loads well
             return f"dc_scan_rows_kernel<{M}, true>"
-    if (17 <= M <= 63 and M % 4 != 0 and (M >= 25 or N < 256) and (N * M) % 4 == 0 and N >= 32
-            and N * 100 >= -(-N // 64) * 64 * 85 and two_blocks(1024 * M)):
+    inside = (N * M) % 4 == 0 and N >= 32 and N * 100 >= -(-N // 64) * 64 * 85      # chunks of 64 rows inside the trials,
+    over = 4 <= N < 64 and (T * N * M) % 4 == 0                                    # or over small trials of a contiguous tensor
+    if 17 <= M <= 63 and M % 4 != 0 and (M >= 25 or N < 256) and (inside or over) and two_blocks(1024 * M):
         return f"dc_scan_row_lane_kernel<{8 if M <= 32 else 12 if M <= 48 else 16}>"          # one row per lane
     if M % 4 == 0 and (M <= 128 or M == 256):
         lanes = M // 4

@@ -99,12 +99,20 @@ bool make_plan(int64_t T, int64_t N, int64_t M, int64_t K, bool allow_vec4, dc::
     // rows of 17 to 63 elements that are no multiple of 4 and that the kernel above does not take: one row per lane,
     // chunks of 64 rows -- from 25 elements on, and shorter ones with fewer than 256 workers (where the kernel above is
     // not available and the flat pass would take a unit per small trial: 3.5-5.7 against 5.4-6.6 TB/s at 64 and 128
-    // workers), when the trial's chunks are at least 85 % full (200 workers = 3 chunks and 8 rows: the flat pass wins)
+    // workers).  The chunks stay inside the trials when those fill them to 85 % at least (200 workers = 3 chunks and 8
+    // rows do not: the flat pass then wins on data with long delays, 4.9 against 4.0 TB/s at 21 elements); trials of
+    // fewer than 64 workers on a contiguous tensor are taken as one run of rows as above (8 workers of 45 elements:
+    // 2.4 -> 6.3 TB/s).
     const uint64_t row_chunks = ((uint64_t)N + 63) / 64;
-    p.row_lane = aligned && !p.lane_rows && dc::row_lane_length((uint32_t)M) &&
-                 (M >= (int64_t)DC_ROW_LANE_MIN_M_MANY || N < (int64_t)DC_LANE_ROWS_MIN_N) &&
-                 (((uint64_t)N * (uint64_t)M) & 3u) == 0 && N >= (int64_t)DC_ROW_LANE_MIN_N &&
-                 (uint64_t)N * 100 >= row_chunks * 64 * 85;
+    const bool row_lane_ok = aligned && !p.lane_rows && dc::row_lane_length((uint32_t)M) &&
+                             (M >= (int64_t)DC_ROW_LANE_MIN_M_MANY || N < (int64_t)DC_LANE_ROWS_MIN_N);
+    const bool row_lane_inside = row_lane_ok && (((uint64_t)N * (uint64_t)M) & 3u) == 0 && N >= (int64_t)DC_ROW_LANE_MIN_N &&
+                                 (uint64_t)N * 100 >= row_chunks * 64 * 85;
+    const bool row_lane_span = DC_SPAN_TRIALS != 0 && row_lane_ok && !row_lane_inside && N >= 4 && N < 64 &&
+                               p.stride == (uint64_t)N * (uint64_t)M && (p.elements & 3u) == 0 &&
+                               (uint64_t)T * (uint64_t)N < ((uint64_t)1 << 31);
+    p.row_lane = row_lane_inside || row_lane_span;
+    if (row_lane_span) { span = true; p.span_rows = (uint32_t)N; }
     if (p.row_lane) p.lane_rows = true;
     p.chunk = p.K < DC_CHUNK_THRESHOLDS ? p.K : DC_CHUNK_THRESHOLDS;
     p.p2 = next_pow2_above(p.chunk);

@@ -463,6 +463,26 @@ __device__ __forceinline__ bool launch_is_chosen(const uint32_t* status) {
     return (dense != 0u) == (SHAPE == 2);
 }
 
+// The lanes' maxima of one chunk, when a chunk may hold rows of several trials (SPAN).  A lane's consecutive rows (four, or one)
+// lie in one trial or, with a trial boundary inside the lane, in two (trials have at least 4 rows).  Key and value
+// of a lane are the trial of its last row and the maximum over its rows in that trial; trials are runs of at most
+// trial_lanes consecutive lanes, so a running maximum over lanes that restarts where the key changes (steps up to that
+// length suffice) leaves every trial's maximum in the last lane with its key, which adds it to the trial's word
+// (cleared by the prep kernel) with one atomic maximum.  A lane with a boundary inside adds the maximum of its rows
+// before the boundary to the previous trial's word itself.
+__device__ __forceinline__ void add_trial_maxima(uint32_t m, uint32_t t, uint32_t m_before, bool valid, uint32_t lane,
+                                                 uint32_t trial_lanes, uint32_t* trial_max) {
+    const uint32_t key = valid ? t : 0xFFFFFFFFu;
+    for (uint32_t d = 1; d < 64u && d < trial_lanes; d <<= 1) {                  // wave-uniform bounds
+        const uint32_t om = (uint32_t)__shfl_up((int)m, d, 64);
+        const uint32_t ok = (uint32_t)__shfl_up((int)key, d, 64);
+        if (lane >= d && ok == key) m = umax(m, om);
+    }
+    const uint32_t next = (uint32_t)__shfl_down((int)key, 1, 64);
+    if (valid && (lane == 63u || next != key)) atomicMax(&trial_max[t], m);
+    if (valid && m_before) atomicMax(&trial_max[t - 1u], m_before);              // zero adds nothing to a maximum
+}
+
 // How the units are dealt to the blocks: runs of `run` consecutive units (a multiple of the waves per block),
 // round-robin over the blocks.
 struct UnitRuns {

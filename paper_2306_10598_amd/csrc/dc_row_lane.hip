@@ -34,7 +34,11 @@ void dc_scan_row_lane_kernel(const int32_t* __restrict__ lat, uint64_t trial_str
                              uint32_t units_per_trial, uint32_t run, uint32_t chunks_per_unit,
                              const uint32_t* __restrict__ tau_chunk, uint32_t kc, uint32_t p2,
                              uint32_t* __restrict__ unit_max, uint32_t* __restrict__ hist_part,
-                             uint32_t* __restrict__ status, uint32_t max_latency) {
+                             uint32_t* __restrict__ status, uint32_t max_latency, uint32_t trial_rows) {
+    // trial_rows = 0: a unit is a run of chunks inside one trial and unit_max[u] receives its maximum.  Otherwise (few
+    // workers per trial, or a worker count that fills its last chunk badly; contiguous tensor): the tensor is one run
+    // of N = T * trial_rows rows, units and chunks ignore the trials, and unit_max[t] is trial t's maximum, built with
+    // atomic maxima (cleared by the prep kernel).
     extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t stage_words = 64u * M;                                   // per wave; 256 M bytes, a multiple of 16
     const GridView g = stage_grid(reinterpret_cast<uint32_t*>(smem) + DC_SCAN_WAVES * stage_words, tau_chunk, kc, p2);
@@ -92,6 +96,10 @@ void dc_scan_row_lane_kernel(const int32_t* __restrict__ lat, uint64_t trial_str
                 }
                 st.check = umax(st.check, worst);
                 lane_max = umax(lane_max, total);
+                if (trial_rows) {                                           // the lane's row is row0 + c0 + lane of the whole run
+                    const uint32_t trial = (row0 + c0 + lane) / trial_rows;
+                    add_trial_maxima(total, trial, 0u, mine, lane, trial_rows, unit_max);
+                }
                 // backwards from the row's end; val = P[M-1-s] (0 in lanes without a row, which count nowhere)
                 uint32_t val = total;
                 uint32_t s = 0;
@@ -121,8 +129,10 @@ void dc_scan_row_lane_kernel(const int32_t* __restrict__ lat, uint64_t trial_str
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // read before the next chunk overwrites it
             }
-            const uint32_t m = wave_max(lane_max);
-            if (lane == 0) unit_max[u] = m;
+            if (!trial_rows) {
+                const uint32_t m = wave_max(lane_max);
+                if (lane == 0) unit_max[u] = m;
+            }
         }
         __syncthreads();
     }
@@ -143,9 +153,12 @@ int row_lane_blocks_per_cu(size_t lds) {
 
 void launch_row_lane_scan(const Plan& p, const int32_t* lat, const uint32_t* tau_chunk, uint32_t kc, uint32_t* unit_max,
                           uint32_t* hist_part, uint32_t* status, hipStream_t stream) {
+    // over trials of few workers the tensor is one run of T * N rows (one "trial" of that many rows, all units its)
+    const uint32_t rows = p.span_rows ? p.T * p.N : p.N;
+    const uint32_t units_per_trial = p.span_rows ? p.units : p.units_per_trial;
 #define DC_RL(nb) hipLaunchKernelGGL(dc_scan_row_lane_kernel<nb>, dim3(p.grid), dim3(DC_SCAN_THREADS), scan_lds_bytes(p), stream, lat, \
-                       p.stride, p.N, p.M, p.units, p.units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max, \
-                       hist_part, status, p.max_latency)
+                       p.span_rows ? 0ull : p.stride, rows, p.M, p.units, units_per_trial, p.run, p.per_unit, tau_chunk, kc, p.p2, unit_max, \
+                       hist_part, status, p.max_latency, p.span_rows)
     if (p.M <= 32) DC_RL(8); else if (p.M <= 48) DC_RL(12); else DC_RL(16);
 #undef DC_RL
 }

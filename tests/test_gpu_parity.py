@@ -297,6 +297,32 @@ def test_rows_of_a_few_dozen_elements_one_per_lane(M, N, dev):
         assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, a)
 
 
+@pytest.mark.parametrize("N", [4, 5, 6, 10, 30, 50, 63, 100, 200, 250, 264])
+@pytest.mark.parametrize("M", [17, 18, 21, 26, 33, 45, 50, 63])
+def test_rows_of_a_few_dozen_elements_of_few_workers(M, N, dev):
+    """Worker counts that fill the chunks of 64 rows badly, or not at all: on a contiguous tensor whose size is a
+    multiple of 4 elements the kernel with one row per lane runs its chunks over the trials, a lane finds its row's
+    trial by division and the trials' maxima are built with atomic maxima (otherwise the kernel for arbitrary rows
+    takes the tensor).  Trials whose maximum sits in their first or last worker, a trial of zeros, a partial last
+    chunk, narrow and all-covering grids, twice on one workspace."""
+    rng = np.random.default_rng(1000 * M + N)
+    T = 41 if (N * M) % 4 == 0 else 40
+    top = min((2**31 - 1) // M, 6000)
+    lat = rng.integers(0, top + 1, size=(T, N, M), dtype=np.int32)
+    lat[::3] //= 3                                          # neighbouring trials with different maxima
+    lat[1, 0, :] = top
+    lat[2, N - 1, :] = top
+    lat[5] = 0
+    totals = lat.sum(axis=2, dtype=np.int64)
+    narrow = np.quantile(totals, np.linspace(0.6, 1.0, 33)).astype(np.int64)
+    wide = np.concatenate([[0, 0, 1], rng.integers(0, int(totals.max()) + 50, size=60), [int(totals.max())] * 2, [BIG]])
+    lat_dev = to_dev(lat, dev)
+    for taus in (narrow, wide, narrow):
+        step, done = dc.dc_simulate(lat_dev, taus, 9)
+        ref = oracle.simulate(lat, taus, 9, "literal")
+        assert np.array_equal(done, ref[1]) and np.array_equal(step, ref[0]), (M, N, taus[:4])
+
+
 @pytest.mark.parametrize("M", [15, 16, 17, 25, 30, 34, 62, 63])
 def test_longest_rows_held_by_a_lane_with_a_full_pass_of_thresholds(M, dev):
     """Row lengths with the largest staging areas of the kernels with whole rows per lane, with the largest threshold
