@@ -197,3 +197,32 @@ def test_row_lane_backward_walk_counts_every_completion_time_in_the_grid(M):
                 val = np.where(mine, val - rows[:, M - 1 - s - k], val)
             s += width
         assert np.array_equal(hist[1:], want[1:])                      # bin 0 (below every threshold) is never read
+
+
+@pytest.mark.parametrize("N", [4, 5, 7, 8, 13, 31, 32, 50, 63])
+def test_row_lane_maxima_over_small_trials(N):
+    """The kernel with one row per lane over trials of fewer than 64 workers: lane l of a chunk holds row first + l of
+    the whole run, its trial is that row number divided by N, and a running maximum over lanes that restarts where the
+    trial changes (steps of 1, 2, 4, ... lanes below N) leaves each trial's maximum in the last lane of the trial."""
+    rng = np.random.default_rng(N)
+    for case in range(60):
+        first = 64 * int(rng.integers(0, 1000))                 # chunks start at multiples of 64 rows
+        here = 64 if case % 3 else int(rng.integers(1, 65))
+        totals = rng.integers(0, 1000, size=64)
+        valid = LANES < here
+        trial = (first + LANES) // N
+        want = {}
+        for lane in range(here):
+            want[int(trial[lane])] = max(want.get(int(trial[lane]), 0), int(totals[lane]))
+        key = np.where(valid, trial, -1)
+        run = totals.copy()
+        d = 1
+        while d < 64 and d < N:
+            up = np.concatenate([np.zeros(d, dtype=run.dtype), run[:-d]])
+            up_key = np.concatenate([np.full(d, -2, dtype=np.int64), key[:-d]])
+            run = np.where((LANES >= d) & (up_key == key), np.maximum(run, up), run)
+            d <<= 1
+        nxt = np.concatenate([key[1:], [-3]])
+        last = valid & ((LANES == 63) | (nxt != key))
+        got = {int(key[lane]): int(run[lane]) for lane in np.flatnonzero(last)}
+        assert len(got) == int(np.count_nonzero(last)) and got == want
